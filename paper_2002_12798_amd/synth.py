@@ -1,0 +1,155 @@
+"""Seeded synthetic inputs and the layout-operator chains of the workloads.
+
+This module holds data only: tensor shapes, value distributions, seeds and the
+operator lists (which operator, with which arguments, in which order).  It does
+no index arithmetic of the method itself, so both the CPU oracle and the HIP
+library can take their inputs from it without sharing any of their logic.
+
+Tensors are returned as numpy arrays of *opaque element bits* (uint16 for
+bf16/fp16, uint32 for fp32): layout operators move bits, they never interpret
+them.
+
+A chain is a list of operator tuples applied left to right:
+    ("transpose", perm)                      numpy/torch permute convention
+    ("reshape", shape)
+    ("slice", axis, begin, end, step)        half-open [begin, end)
+    ("pad", lo, hi, fill_bits)               per-dimension low/high padding
+    ("concat", axis)                         joins all sources; only first
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BASE_SEED = 200212798
+
+
+def _rng(cfg_index: int, tensor_index: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(BASE_SEED + cfg_index + 100 * tensor_index))
+
+
+def f32_bits(x: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 storage bits, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def uniform_f32(shape, cfg_index, tensor_index=0) -> np.ndarray:
+    return _rng(cfg_index, tensor_index).uniform(-1.0, 1.0, size=shape).astype(np.float32)
+
+
+def normal_f32(shape, cfg_index, tensor_index=0, std=1.0) -> np.ndarray:
+    g = _rng(cfg_index, tensor_index).standard_normal(size=shape, dtype=np.float32)
+    return (g * np.float32(std)).astype(np.float32)
+
+
+def random_bits(shape, elem_size: int, seed: int) -> np.ndarray:
+    """Arbitrary bit patterns (NaN payloads, -0, subnormals included)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    dt = {2: np.uint16, 4: np.uint32}[elem_size]
+    return rng.integers(0, np.iinfo(dt).max, size=shape, dtype=dt, endpoint=True)
+
+
+def iota(shape, elem_size: int) -> np.ndarray:
+    """0,1,2,... in row-major order (needs prod(shape) to fit the element)."""
+    dt = {2: np.uint16, 4: np.uint32}[elem_size]
+    n = int(np.prod(shape))
+    return np.arange(n, dtype=np.uint64).astype(dt).reshape(shape)
+
+
+class Workload:
+    """One workload: its sources, its operator chain and (for the fused GEMM)
+    the weight operand."""
+
+    def __init__(self, name, elem_size, src_shapes, ops, make_sources, gemm_n=None, make_w=None,
+                 batch_axis=None):
+        self.name = name
+        self.elem_size = elem_size
+        self.src_shapes = [tuple(s) for s in src_shapes]
+        self.ops = ops
+        self._make_sources = make_sources
+        self.gemm_n = gemm_n
+        self._make_w = make_w
+        self.batch_axis = batch_axis
+
+    def sources(self):
+        return self._make_sources()
+
+    def weight(self):
+        return self._make_w() if self._make_w else None
+
+
+def _cfg0():
+    shp = (8, 16, 32, 32)
+    ops = [("transpose", (0, 2, 3, 1)), ("reshape", (8, 1024, 16)),
+           ("slice", 1, 128, 896, 1), ("pad", (0, 0, 0), (0, 0, 4), 0)]
+    return Workload("cfg0", 4, [shp], ops, lambda: [f32_bits(uniform_f32(shp, 0))])
+
+
+def _cfg1(n=32):
+    shp = (n, 256, 56, 56)
+    ops = [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]
+    return Workload("cfg1" if n == 32 else f"cfg1_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 1))])
+
+
+def _cfg2_fwd(b=16):
+    shp = (b, 512, 2304)
+    ops = [("reshape", (b, 512, 3, 12, 64)), ("transpose", (2, 0, 3, 1, 4))]
+    return Workload("cfg2_fwd" if b == 16 else f"cfg2_fwd_b{b}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 2))])
+
+
+def _cfg2_rev(b=16):
+    shp = (b, 12, 512, 64)
+    ops = [("transpose", (0, 2, 1, 3)), ("reshape", (b, 512, 768))]
+    return Workload("cfg2_rev" if b == 16 else f"cfg2_rev_b{b}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 2, 1))])
+
+
+def _cfg3(n=32):
+    chans = (64, 96, 128, 32)
+    shps = [(n, c, 28, 28) for c in chans]
+    ops = [("concat", 1), ("transpose", (0, 2, 3, 1))]
+    return Workload("cfg3" if n == 32 else f"cfg3_n{n}", 2, shps, ops,
+                    lambda: [f32_to_f16_bits(uniform_f32(s, 3, j)) for j, s in enumerate(shps)])
+
+
+def _cfg4():
+    shp = (16, 16, 512, 64)
+    ops = [("transpose", (0, 2, 1, 3)), ("reshape", (8192, 1024))]
+    return Workload("cfg4", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 4))],
+                    gemm_n=4096,
+                    make_w=lambda: f32_to_bf16_bits(normal_f32((1024, 4096), 4, 1, std=0.02)))
+
+
+_FACTORIES = {
+    "cfg0": _cfg0, "cfg1": _cfg1, "cfg2_fwd": _cfg2_fwd, "cfg2_rev": _cfg2_rev,
+    "cfg3": _cfg3, "cfg4": _cfg4,
+}
+
+WORKLOAD_NAMES = tuple(_FACTORIES)
+
+
+def workload(name: str, **kw) -> Workload:
+    return _FACTORIES[name](**kw)
+
+
+def split_qkv_ops(t: int, b: int = 16):
+    """Secondary reading of the head split: one chain per Q/K/V output, ending
+    in a slice of the leading axis and a reshape that drops it."""
+    return [("reshape", (b, 512, 3, 12, 64)), ("transpose", (2, 0, 3, 1, 4)),
+            ("slice", 0, t, t + 1, 1), ("reshape", (b, 12, 512, 64))]
