@@ -1,0 +1,189 @@
+/*
+ * amap - composed access maps for chains of layout operators, and their
+ * single-kernel execution on gfx950.
+ *
+ * Model (paper Section 2, equations "load" and "store"): every tensor access
+ * is an element-wise load v = t[f(i)] or store t[f(i)] = v inside a loop nest
+ * i, with f(i) = C i + b.  A layout operator (transpose, reshape, slice, pad,
+ * concat) is one load/store pair whose load feeds its store directly
+ * (Section 2.1).  Data-movement elimination reverses the store map, composes
+ * it with the load map (eq. 3) and rewrites every consumer load to read the
+ * original tensor through the composed function (eq. 4), so the intermediate
+ * tensor and the copy that defined it disappear.
+ *
+ * An amap_t is such a composed function for a whole chain: it maps every
+ * index of the chain's final tensor ("dst") either to (source tensor id,
+ * element offset in that source) or to a constant fill pattern.  Reshape
+ * makes the function quasi-affine (floor-div / mod by constants) and pad /
+ * concat make it piecewise, so the normal form is a list of disjoint pieces,
+ * each a loop nest with an affine store address into dst and an affine load
+ * address into one source (or a constant).
+ *
+ * All tensors are dense, row-major, offset 0.  Elements are opaque bit
+ * patterns of 2 or 4 bytes; data movement never interprets them.
+ *
+ * Conventions: every call returns an amap_status and never aborts; on error
+ * the out-parameter is left untouched.  amap_t objects are immutable after
+ * creation, live in host memory, may be shared between threads, and are
+ * released by the caller with amap_free.  The library never owns tensor
+ * memory.  Pointers named src / dst / A_src / W / out in the device entry
+ * points are DEVICE pointers; everything else is a host pointer.
+ */
+#ifndef AMAP_H
+#define AMAP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AMAP_MAX_RANK 8
+
+typedef struct amap amap_t;
+
+typedef enum {
+    AMAP_OK = 0,
+    AMAP_E_INVALID = 1,      /* null pointer, bad rank / axis / perm / element size / source id */
+    AMAP_E_SHAPE = 2,        /* reshape volume mismatch, slice or pad out of range, concat extents */
+    AMAP_E_UNSUPPORTED = 3,  /* e.g. reverse of a map that is not a bijection */
+    AMAP_E_NOMEM = 4,
+    AMAP_E_ALIAS = 5,        /* dst overlaps a source */
+    AMAP_E_HIP = 6           /* the HIP runtime reported an error at launch */
+} amap_status;
+
+typedef enum { AMAP_B16 = 2, AMAP_B32 = 4 } amap_elem; /* element size in bytes */
+
+/* ---- map construction (host only) --------------------------------------
+ * Each builder returns a NEW map for "operator applied to the tensor that m
+ * describes": the operator's own index function (its f in v = in[f(i)]) is
+ * composed with m (eq. 4 with identity store maps) and normalised.  Inputs
+ * are unchanged. */
+
+/* The identity map of source tensor number src_id with the given shape. */
+amap_status amap_source(int src_id, int rank, const int64_t *shape, amap_elem es, amap_t **out);
+
+/* out axis k = in axis perm[k] (numpy / torch permute convention). */
+amap_status amap_transpose(const amap_t *m, const int32_t *perm, amap_t **out);
+
+/* Row-major reshape; the volume must be preserved. */
+amap_status amap_reshape(const amap_t *m, int rank, const int64_t *shape, amap_t **out);
+
+/* Keep indices begin, begin+step, ... < end of one axis.
+ * Needs 0 <= begin < end <= extent and step >= 1. */
+amap_status amap_slice(const amap_t *m, int axis, int64_t begin, int64_t end, int64_t step,
+                       amap_t **out);
+
+/* lo[k] / hi[k] >= 0 fill elements before / after axis k; fill_bits is the
+ * constant (its low 16 bits for 2-byte elements). */
+amap_status amap_pad(const amap_t *m, const int64_t *lo, const int64_t *hi, uint32_t fill_bits,
+                     amap_t **out);
+
+/* Join n maps along axis; all other extents and the element size must agree.
+ * The maps may read different sources, or the same ones. */
+amap_status amap_concat(const amap_t *const *ms, int n, int axis, amap_t **out);
+
+/* The paper's "reverse" (Section 2.1): for a map that is a bijection between
+ * dst and one source, the map from that source's index space back to dst,
+ * expressed as a map whose source 0 has dst's shape. */
+amap_status amap_inverse(const amap_t *m, amap_t **out);
+
+/* One-shot form: fold a linear operator list over n_src sources.  A CONCAT
+ * may only come first and joins all n_src sources; otherwise n_src must be 1. */
+typedef struct {
+    int rank;
+    const int64_t *shape;
+    amap_elem es;
+} amap_src_desc;
+
+typedef enum { AMAP_TRANSPOSE = 0, AMAP_RESHAPE = 1, AMAP_SLICE = 2, AMAP_PAD = 3, AMAP_CONCAT = 4 } amap_op_kind;
+
+typedef struct {
+    amap_op_kind kind;
+    int axis;           /* SLICE, CONCAT */
+    int n;              /* TRANSPOSE: rank; RESHAPE: new rank; PAD: rank; SLICE: 3 */
+    const int64_t *a;   /* TRANSPOSE: perm[n]; RESHAPE: shape[n]; SLICE: {begin,end,step}; PAD: lo[n] */
+    const int64_t *b;   /* PAD: hi[n] */
+    uint32_t fill_bits; /* PAD */
+} amap_op;
+
+amap_status amap_compose(const amap_src_desc *srcs, int n_src, const amap_op *ops, int n_ops,
+                         amap_t **out);
+
+void amap_free(amap_t *m);
+
+/* ---- inspection (host only) -------------------------------------------- */
+
+typedef enum {
+    AMAP_K_PROGRAM = 0, /* element-wise interpreter of the operator program (any map)      */
+    AMAP_K_ELEMENT = 1, /* element-wise over the strided pieces                             */
+    AMAP_K_ROWS = 2,    /* both sides share their contiguous dimension: vector row copy     */
+    AMAP_K_TILE = 3,    /* contiguous dimension permuted: LDS-staged tile transpose         */
+    AMAP_K_WAVE = 4     /* small permute: in-register / cross-lane transpose, no LDS        */
+} amap_kernel_id;
+
+typedef struct {
+    int rank;                        /* of dst */
+    int64_t shape[AMAP_MAX_RANK];    /* of dst */
+    int elem_size;
+    int n_src;                       /* length of the src[] array amap_execute expects */
+    int strided;                     /* 1 if the normal form is a list of affine pieces */
+    int n_pieces;                    /* copy + fill pieces (0 if not strided) */
+    int n_fill_pieces;
+    int kernel_id;                   /* amap_kernel_id the planner chose for the largest piece */
+    int vec_bytes;                   /* smallest access width planned over all pieces, both sides */
+    int64_t min_read_bytes;          /* distinct source elements needed x elem size */
+    int64_t write_bytes;             /* volume(dst) x elem size */
+    int64_t fill_bytes;              /* part of write_bytes that is constant fill */
+} amap_info;
+
+amap_status amap_describe(const amap_t *m, amap_info *out);
+
+/* Shape of source src_id as recorded in the map (rank returned in *rank). */
+amap_status amap_source_shape(const amap_t *m, int src_id, int *rank, int64_t *shape);
+
+/* Evaluate the map on HOST memory: dst[i] = src[g(i)] or the fill.  For tests
+ * of the composer on machines without a GPU; the device path never calls it.
+ * mode 0: as the map is represented (pieces if strided, else the program);
+ * mode 1: operator program; mode 2: pieces (AMAP_E_UNSUPPORTED if not strided). */
+amap_status amap_eval_host(const amap_t *m, const void *const *src, void *dst, int mode);
+
+/* Diagnostic: number of dst elements written by no piece / by more than one
+ * piece of a strided map (both 0 for a well-formed map; out-of-range
+ * addresses count as overwritten).  Costs one byte of host memory per dst
+ * element. */
+amap_status amap_check_cover(const amap_t *m, int64_t *unwritten, int64_t *overwritten);
+
+/* ---- execution (device pointers; asynchronous on `stream`) --------------
+ * `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ * No allocation, no synchronisation, no host access to device memory. */
+
+/* dst[i] = src[src_id][g(i)] or fill, for every index i of dst: the rewritten
+ * load v' = t_l[g'(i')] of eq. 4 executed for the whole chain by one kernel
+ * per group of pieces (one launch for every map in the five workloads).
+ * src has n_src entries, indexed by source id.  dst must not overlap any
+ * source (AMAP_E_ALIAS).  dst is fully overwritten. */
+amap_status amap_execute(const void *const *src, void *dst, const amap_t *map, void *stream);
+
+/* Same, with the kernel family forced (amap_kernel_id) instead of planned:
+ * for A/B measurements and for tests of every family on every map.
+ * AMAP_E_UNSUPPORTED if that family cannot execute the map. */
+amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t *map,
+                                void *stream, int kernel_id);
+
+/* out[M,N] = bf16( A[M,K] x W[K,N] ) with A[m,k] = A_src[g(m,k)] loaded through
+ * the map in the operand-load prologue (the consumer load of eq. 4); A is never
+ * materialised.  A_map: dst shape [M,K], 2-byte elements (bf16), one source,
+ * no fill pieces.  W: [K,N] row-major bf16.  out: [M,N] row-major bf16,
+ * fp32 accumulation, round-to-nearest-even on output.
+ * Needs M % 256 == 0, N % 256 == 0, K % 64 == 0 and 8-element aligned
+ * contiguous runs along k in the map, else AMAP_E_UNSUPPORTED. */
+amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
+                            void *out, void *stream);
+
+const char *amap_status_str(amap_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMAP_H */

@@ -1,0 +1,258 @@
+"""ctypes binding to libamap.so: argument marshalling only.
+
+Every function here has the name of the C entry point it wraps (include/amap.h)
+and does no index arithmetic and no data movement of its own.  If the shared
+library is missing the import of this module fails: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libamap.so")
+
+AMAP_OK, AMAP_E_INVALID, AMAP_E_SHAPE, AMAP_E_UNSUPPORTED, AMAP_E_NOMEM, AMAP_E_ALIAS, AMAP_E_HIP = range(7)
+AMAP_TRANSPOSE, AMAP_RESHAPE, AMAP_SLICE, AMAP_PAD, AMAP_CONCAT = range(5)
+AMAP_K_PROGRAM, AMAP_K_ELEMENT, AMAP_K_ROWS, AMAP_K_TILE, AMAP_K_WAVE = range(5)
+KERNEL_NAMES = {0: "program", 1: "element", 2: "rows", 3: "tile", 4: "wave"}
+AMAP_MAX_RANK = 8
+
+EXPORTS = [
+    "amap_source", "amap_transpose", "amap_reshape", "amap_slice", "amap_pad", "amap_concat",
+    "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
+    "amap_eval_host", "amap_check_cover", "amap_execute", "amap_execute_kernel",
+    "amap_gemm_fused", "amap_status_str",
+]
+
+
+class AmapError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {_status_str(status)} (status {status})")
+
+
+class amap_src_desc(C.Structure):
+    _fields_ = [("rank", C.c_int), ("shape", C.POINTER(C.c_int64)), ("es", C.c_int)]
+
+
+class amap_op(C.Structure):
+    _fields_ = [("kind", C.c_int), ("axis", C.c_int), ("n", C.c_int),
+                ("a", C.POINTER(C.c_int64)), ("b", C.POINTER(C.c_int64)), ("fill_bits", C.c_uint32)]
+
+
+class amap_info(C.Structure):
+    _fields_ = [("rank", C.c_int), ("shape", C.c_int64 * AMAP_MAX_RANK), ("elem_size", C.c_int),
+                ("n_src", C.c_int), ("strided", C.c_int), ("n_pieces", C.c_int),
+                ("n_fill_pieces", C.c_int), ("kernel_id", C.c_int), ("vec_bytes", C.c_int),
+                ("min_read_bytes", C.c_int64), ("write_bytes", C.c_int64), ("fill_bytes", C.c_int64)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+
+_L = C.CDLL(LIB_PATH)
+_vp = C.c_void_p
+_pp = C.POINTER(C.c_void_p)
+_i64p = C.POINTER(C.c_int64)
+_i32p = C.POINTER(C.c_int32)
+
+_L.amap_source.argtypes = [C.c_int, C.c_int, _i64p, C.c_int, _pp]
+_L.amap_transpose.argtypes = [_vp, _i32p, _pp]
+_L.amap_reshape.argtypes = [_vp, C.c_int, _i64p, _pp]
+_L.amap_slice.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int64, _pp]
+_L.amap_pad.argtypes = [_vp, _i64p, _i64p, C.c_uint32, _pp]
+_L.amap_concat.argtypes = [_pp, C.c_int, C.c_int, _pp]
+_L.amap_inverse.argtypes = [_vp, _pp]
+_L.amap_compose.argtypes = [C.POINTER(amap_src_desc), C.c_int, C.POINTER(amap_op), C.c_int, _pp]
+_L.amap_free.argtypes = [_vp]
+_L.amap_free.restype = None
+_L.amap_describe.argtypes = [_vp, C.POINTER(amap_info)]
+_L.amap_source_shape.argtypes = [_vp, C.c_int, C.POINTER(C.c_int), _i64p]
+_L.amap_eval_host.argtypes = [_vp, _pp, _vp, C.c_int]
+_L.amap_check_cover.argtypes = [_vp, _i64p, _i64p]
+_L.amap_execute.argtypes = [_pp, _vp, _vp, _vp]
+_L.amap_execute_kernel.argtypes = [_pp, _vp, _vp, _vp, C.c_int]
+_L.amap_gemm_fused.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp]
+_L.amap_status_str.argtypes = [C.c_int]
+_L.amap_status_str.restype = C.c_char_p
+
+raw = _L  # the raw CDLL, for callers that pre-marshal their arguments
+
+
+def _status_str(s):
+    return _L.amap_status_str(int(s)).decode()
+
+
+def amap_status_str(s):
+    return _status_str(s)
+
+
+def _i64(v):
+    return (C.c_int64 * len(v))(*[int(x) for x in v])
+
+
+def _check(st, what):
+    if st != AMAP_OK:
+        raise AmapError(st, what)
+
+
+class Map:
+    """Owner of one amap_t*; frees it when collected."""
+
+    def __init__(self, handle):
+        self._h = C.c_void_p(handle)
+
+    @property
+    def handle(self):
+        return self._h
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            _L.amap_free(h)
+
+
+def _new(fn, what, *args):
+    out = C.c_void_p()
+    _check(fn(*args, C.byref(out)), what)
+    return Map(out.value)
+
+
+def amap_source(src_id, shape, es):
+    return _new(_L.amap_source, "amap_source", int(src_id), len(shape), _i64(shape), int(es))
+
+
+def amap_transpose(m, perm):
+    if len(perm) != amap_describe(m).rank:
+        raise AmapError(AMAP_E_INVALID, "amap_transpose")
+    return _new(_L.amap_transpose, "amap_transpose", m.handle, (C.c_int32 * len(perm))(*[int(p) for p in perm]))
+
+
+def amap_reshape(m, shape):
+    return _new(_L.amap_reshape, "amap_reshape", m.handle, len(shape), _i64(shape))
+
+
+def amap_slice(m, axis, begin, end, step=1):
+    return _new(_L.amap_slice, "amap_slice", m.handle, int(axis), int(begin), int(end), int(step))
+
+
+def amap_pad(m, lo, hi, fill_bits=0):
+    r = amap_describe(m).rank
+    if len(lo) != r or len(hi) != r:
+        raise AmapError(AMAP_E_INVALID, "amap_pad")
+    return _new(_L.amap_pad, "amap_pad", m.handle, _i64(lo), _i64(hi), int(fill_bits) & 0xFFFFFFFF)
+
+
+def amap_concat(ms, axis):
+    arr = (C.c_void_p * len(ms))(*[m.handle for m in ms])
+    return _new(_L.amap_concat, "amap_concat", arr, len(ms), int(axis))
+
+
+def amap_inverse(m):
+    return _new(_L.amap_inverse, "amap_inverse", m.handle)
+
+
+def marshal_chain(src_shapes, es, ops):
+    """Build the ctypes arguments of amap_compose for an operator list
+    (tuples as in synth.py).  Returned tuple keeps every buffer alive."""
+    keep = []
+    srcs = (amap_src_desc * len(src_shapes))()
+    for i, s in enumerate(src_shapes):
+        buf = _i64(s)
+        keep.append(buf)
+        srcs[i].rank, srcs[i].shape, srcs[i].es = len(s), buf, int(es)
+    cops = (amap_op * max(1, len(ops)))()
+    for k, op in enumerate(ops):
+        o = cops[k]
+        kind = op[0]
+        if kind == "transpose":
+            a = _i64(op[1])
+            o.kind, o.n, o.a = AMAP_TRANSPOSE, len(op[1]), a
+        elif kind == "reshape":
+            a = _i64(op[1])
+            o.kind, o.n, o.a = AMAP_RESHAPE, len(op[1]), a
+        elif kind == "slice":
+            a = _i64([op[2], op[3], op[4] if len(op) > 4 else 1])
+            o.kind, o.axis, o.n, o.a = AMAP_SLICE, int(op[1]), 3, a
+        elif kind == "pad":
+            a, b = _i64(op[1]), _i64(op[2])
+            keep.append(b)
+            o.kind, o.n, o.a, o.b = AMAP_PAD, len(op[1]), a, b
+            o.fill_bits = (int(op[3]) if len(op) > 3 else 0) & 0xFFFFFFFF
+        elif kind == "concat":
+            a = None
+            o.kind, o.axis = AMAP_CONCAT, int(op[1])
+        else:
+            raise AmapError(AMAP_E_INVALID, f"unknown operator {kind}")
+        keep.append(a)
+    return srcs, len(src_shapes), cops, len(ops), keep
+
+
+def amap_compose(src_shapes, es, ops):
+    srcs, n_src, cops, n_ops, keep = marshal_chain(src_shapes, es, ops)
+    m = _new(_L.amap_compose, "amap_compose", srcs, n_src, cops, n_ops)
+    del keep
+    return m
+
+
+def amap_describe(m):
+    info = amap_info()
+    _check(_L.amap_describe(m.handle, C.byref(info)), "amap_describe")
+    return info
+
+
+def dst_shape(m):
+    info = amap_describe(m)
+    return tuple(info.shape[k] for k in range(info.rank))
+
+
+def amap_source_shape(m, src_id):
+    rank = C.c_int()
+    shape = (C.c_int64 * AMAP_MAX_RANK)()
+    _check(_L.amap_source_shape(m.handle, int(src_id), C.byref(rank), shape), "amap_source_shape")
+    return tuple(shape[k] for k in range(rank.value))
+
+
+def amap_check_cover(m):
+    un, ov = C.c_int64(), C.c_int64()
+    _check(_L.amap_check_cover(m.handle, C.byref(un), C.byref(ov)), "amap_check_cover")
+    return un.value, ov.value
+
+
+def amap_eval_host(m, srcs, mode=0):
+    """Host evaluator on numpy arrays (composer tests without a GPU)."""
+    import numpy as np
+    info = amap_describe(m)
+    dt = {2: np.uint16, 4: np.uint32}[info.elem_size]
+    arrs = [None if s is None else np.ascontiguousarray(s).view(dt) for s in srcs]
+    for i, a in enumerate(arrs):
+        if a is not None and a.size != int(np.prod(amap_source_shape(m, i))):
+            raise AmapError(AMAP_E_SHAPE, "amap_eval_host: source size")
+    ptrs = (C.c_void_p * max(1, info.n_src))(*[None if a is None else a.ctypes.data for a in arrs])
+    out = np.empty(dst_shape(m), dtype=dt)
+    _check(_L.amap_eval_host(m.handle, ptrs, out.ctypes.data, int(mode)), "amap_eval_host")
+    return out
+
+
+def _ptr_array(ptrs):
+    return (C.c_void_p * max(1, len(ptrs)))(*[int(p) if p else None for p in ptrs])
+
+
+def amap_execute(src_ptrs, dst_ptr, m, stream=0, kernel_id=None):
+    """src_ptrs: device addresses (ints) indexed by source id; dst_ptr: device address."""
+    arr = _ptr_array(src_ptrs)
+    if kernel_id is None:
+        _check(_L.amap_execute(arr, C.c_void_p(dst_ptr), m.handle, C.c_void_p(stream)), "amap_execute")
+    else:
+        _check(_L.amap_execute_kernel(arr, C.c_void_p(dst_ptr), m.handle, C.c_void_p(stream), int(kernel_id)),
+               "amap_execute_kernel")
+
+
+def amap_execute_kernel(src_ptrs, dst_ptr, m, stream, kernel_id):
+    amap_execute(src_ptrs, dst_ptr, m, stream, kernel_id)
+
+
+def amap_gemm_fused(a_src_ptr, a_map, w_ptr, n, out_ptr, stream=0):
+    _check(_L.amap_gemm_fused(C.c_void_p(a_src_ptr), a_map.handle, C.c_void_p(w_ptr), int(n),
+                              C.c_void_p(out_ptr), C.c_void_p(stream)), "amap_gemm_fused")

@@ -1,0 +1,132 @@
+// Host-side inspection and the host evaluator of a map.  The evaluator exists
+// so that the composer can be tested on machines without a GPU; the device
+// entry points never call it.
+#include <cstring>
+#include <vector>
+
+#include "amap_map.hpp"
+
+using namespace amap_detail;
+
+namespace {
+
+template <class F>
+void for_each_index(const std::vector<int64_t> &shape, F &&f) {
+    if (volume_of(shape) == 0) return;
+    const int rank = (int)shape.size();
+    int64_t idx[kMaxRank] = {0};
+    for (;;) {
+        f(idx);
+        int k = rank - 1;
+        for (; k >= 0; --k) {
+            if (++idx[k] < shape[k]) break;
+            idx[k] = 0;
+        }
+        if (k < 0) return;
+    }
+}
+
+// visit (dst offset, src offset) of every iteration of a kernel-form piece
+template <class F>
+void for_each_iteration(const KPiece &p, F &&f) {
+    const int nd = (int)p.dims.size();
+    std::vector<int64_t> i(nd, 0);
+    int64_t d = p.dbase, s = p.sbase;
+    for (;;) {
+        f(d, s);
+        int k = nd - 1;
+        for (; k >= 0; --k) {
+            d += p.dims[k].ds;
+            s += p.dims[k].ss;
+            if (++i[k] < p.dims[k].extent) break;
+            d -= p.dims[k].ds * p.dims[k].extent;
+            s -= p.dims[k].ss * p.dims[k].extent;
+            i[k] = 0;
+        }
+        if (k < 0) return;
+    }
+}
+
+inline void put(void *dst, int64_t off, const void *src, int64_t soff, int es) {
+    std::memcpy((char *)dst + off * es, (const char *)src + soff * es, (size_t)es);
+}
+
+}  // namespace
+
+extern "C" amap_status amap_eval_host(const amap_t *m, const void *const *src, void *dst, int mode) {
+    if (!m || !dst || mode < 0 || mode > 2) return AMAP_E_INVALID;
+    if (volume_of(m->shape) == 0) return AMAP_OK;
+    if (!src) return AMAP_E_INVALID;
+    const int es = m->elem;
+    const bool use_pieces = mode == 2 || (mode == 0 && m->strided);
+    if (use_pieces) {
+        if (!m->strided) return AMAP_E_UNSUPPORTED;
+        for (const KPiece &p : m->kpieces) {
+            if (p.fill) {
+                uint32_t f32 = p.fill_bits;
+                uint16_t f16 = (uint16_t)p.fill_bits;
+                const void *f = es == 2 ? (const void *)&f16 : (const void *)&f32;
+                for_each_iteration(p, [&](int64_t d, int64_t) { put(dst, d, f, 0, es); });
+            } else {
+                if (!src[p.src]) return AMAP_E_INVALID;
+                const void *s = src[p.src];
+                for_each_iteration(p, [&](int64_t d, int64_t so) { put(dst, d, s, so, es); });
+            }
+        }
+        return AMAP_OK;
+    }
+    int64_t L = 0;
+    amap_status st = AMAP_OK;
+    for_each_index(m->shape, [&](const int64_t *idx) {
+        int sid = -1;
+        int64_t off = 0;
+        uint32_t fill = 0;
+        if (eval_program(m->prog.get(), idx, &sid, &off, &fill)) {
+            if (!src[sid])
+                st = AMAP_E_INVALID;
+            else
+                put(dst, L, src[sid], off, es);
+        } else {
+            uint16_t f16 = (uint16_t)fill;
+            put(dst, L, es == 2 ? (const void *)&f16 : (const void *)&fill, 0, es);
+        }
+        ++L;
+    });
+    return st;
+}
+
+extern "C" amap_status amap_source_shape(const amap_t *m, int src_id, int *rank, int64_t *shape) {
+    if (!m || !rank || !shape || src_id < 0 || src_id >= (int)m->src_shapes.size()) return AMAP_E_INVALID;
+    const auto &s = m->src_shapes[src_id];
+    if (s.empty()) return AMAP_E_INVALID;
+    *rank = (int)s.size();
+    for (size_t k = 0; k < s.size(); ++k) shape[k] = s[k];
+    return AMAP_OK;
+}
+
+// Number of dst elements written zero times / more than once by the pieces:
+// both must be 0 for a well-formed strided map (every dst element has exactly
+// one writer).  Diagnostic for tests; costs one byte per dst element.
+extern "C" amap_status amap_check_cover(const amap_t *m, int64_t *unwritten, int64_t *overwritten) {
+    if (!m || !unwritten || !overwritten) return AMAP_E_INVALID;
+    if (!m->strided) return AMAP_E_UNSUPPORTED;
+    const int64_t vol = volume_of(m->shape);
+    std::vector<uint8_t> cnt((size_t)vol, 0);
+    int64_t over = 0, bad = 0;
+    for (const KPiece &p : m->kpieces) {
+        int64_t svol = p.fill ? 0 : volume_of(m->src_shapes[p.src]);
+        for_each_iteration(p, [&](int64_t d, int64_t s) {
+            if (d < 0 || d >= vol || (!p.fill && (s < 0 || s >= svol))) {
+                ++bad;
+                return;
+            }
+            if (cnt[(size_t)d] == 1) ++over;
+            if (cnt[(size_t)d] < 2) ++cnt[(size_t)d];
+        });
+    }
+    int64_t un = 0;
+    for (uint8_t c : cnt) un += c == 0;
+    *unwritten = un;
+    *overwritten = over + bad;
+    return AMAP_OK;
+}

@@ -1,0 +1,209 @@
+"""Host composer vs the oracle (CPU only): the composed map, evaluated on the
+host, must reproduce the un-optimised operator-by-operator program bit for bit.
+Distinct source elements (iota) turn the output into the address table, so a
+mismatch points at an index."""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2002_12798_amd import binding as B
+from paper_2002_12798_amd import synth
+from tests import chains
+
+
+def _iota_sources(shapes, es):
+    srcs, base = [], 1
+    for s in shapes:
+        n = int(np.prod(s))
+        dt = np.uint16 if es == 2 else np.uint32
+        srcs.append(((np.arange(n, dtype=np.uint64) + base) % (65521 if es == 2 else 4294967291)).astype(dt).reshape(s))
+        base += n
+    return srcs
+
+
+def _check_map(m, srcs, want, expect_strided=None):
+    info = B.amap_describe(m)
+    assert B.dst_shape(m) == want.shape
+    got_prog = B.amap_eval_host(m, srcs, mode=1)
+    assert np.array_equal(got_prog, want), "operator program"
+    if expect_strided is not None:
+        assert bool(info.strided) == expect_strided
+    if info.strided:
+        got = B.amap_eval_host(m, srcs, mode=2)
+        assert np.array_equal(got, want), "strided pieces"
+        assert B.amap_check_cover(m) == (0, 0)
+        assert info.write_bytes == want.nbytes
+        assert info.min_read_bytes + info.fill_bytes == want.nbytes
+
+
+@pytest.mark.parametrize("name", synth.WORKLOAD_NAMES)
+def test_workload_maps_small_values(name):
+    w = synth.workload(name)
+    srcs = w.sources()
+    want = oracle.run_chain(srcs, w.ops)
+    m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
+    _check_map(m, srcs, want, expect_strided=True)
+
+
+def test_workload_piece_counts_and_bytes():
+    exp = {  # name: (pieces, fill pieces, min read bytes, write bytes, fill bytes)
+        "cfg0": (2, 1, 393216, 491520, 24576 * 4),
+        "cfg1": (5, 4, 51380224, 55115776, 1867776 * 2),
+        "cfg2_fwd": (1, 0, 37748736, 37748736, 0),
+        "cfg2_rev": (1, 0, 12582912, 12582912, 0),
+        "cfg3": (4, 0, 16056320, 16056320, 0),
+        "cfg4": (1, 0, 16777216, 16777216, 0),
+    }
+    for name, (np_, nf, rd, wr, fb) in exp.items():
+        w = synth.workload(name)
+        info = B.amap_describe(B.amap_compose(w.src_shapes, w.elem_size, w.ops))
+        assert (info.n_pieces, info.n_fill_pieces) == (np_, nf), name
+        assert (info.min_read_bytes, info.write_bytes, info.fill_bytes) == (rd, wr, fb), name
+
+
+def test_builders_equal_one_shot():
+    w = synth.workload("cfg3")
+    ms = [B.amap_source(i, s, 2) for i, s in enumerate(w.src_shapes)]
+    m = B.amap_transpose(B.amap_concat(ms, 1), (0, 2, 3, 1))
+    srcs = w.sources()
+    assert np.array_equal(B.amap_eval_host(m, srcs), oracle.run_chain(srcs, w.ops))
+
+
+@pytest.mark.parametrize("seed", range(300))
+def test_random_chains(seed):
+    src_shapes, ops = chains.random_chain(seed)
+    es = 2 if seed % 2 else 4
+    srcs = _iota_sources(src_shapes, es)
+    want = oracle.run_chain(srcs, ops)
+    m = B.amap_compose(src_shapes, es, ops)
+    _check_map(m, srcs, want)
+
+
+def test_random_chains_mostly_strided():
+    n = sum(bool(B.amap_describe(B.amap_compose(s, 4, o)).strided)
+            for s, o in (chains.random_chain(k) for k in range(300)))
+    assert n >= 270, n
+
+
+def test_tree_of_builders_with_per_branch_ops():
+    rng = np.random.default_rng(5)
+    for trial in range(40):
+        base = chains.random_shape(rng, max_rank=3, max_extent=6)
+        ax = int(rng.integers(len(base)))
+        maps, outs, srcs = [], [], []
+        for j in range(int(rng.integers(2, 4))):
+            # each branch: its own source, one random op that keeps the rank and the off-axis extents
+            s = list(base)
+            s[ax] = int(rng.integers(2, 6))
+            x = _iota_sources([s], 4)[0] + 1000 * j
+            m = B.amap_source(j, s, 4)
+            b = int(rng.integers(0, s[ax] - 1))
+            m = B.amap_slice(m, ax, b, s[ax], 1)
+            y = oracle.slice_(x, ax, b, s[ax], 1)
+            maps.append(m)
+            outs.append(y)
+            srcs.append(x)
+        m = B.amap_concat(maps, ax)
+        want = oracle.concat(outs, ax)
+        perm = tuple(int(v) for v in rng.permutation(len(base)))
+        m = B.amap_transpose(m, perm)
+        want = oracle.transpose(want, perm)
+        _check_map(m, srcs, want, expect_strided=True)
+
+
+def test_same_source_twice():
+    x = _iota_sources([(3, 4)], 4)[0]
+    s = B.amap_source(0, (3, 4), 4)
+    m = B.amap_concat([s, B.amap_transpose(B.amap_reshape(s, (4, 3)), (1, 0))], 1)
+    want = oracle.concat([x, oracle.transpose(oracle.reshape(x, (4, 3)), (1, 0))], 1)
+    assert np.array_equal(B.amap_eval_host(m, [x]), want)
+
+
+def test_misaligned_reshape_after_slice_splits_pieces():
+    x = _iota_sources([(4, 32)], 4)[0]
+    ops = [("reshape", (128,)), ("slice", 0, 5, 101, 1), ("reshape", (8, 12))]
+    m = B.amap_compose([(4, 32)], 4, ops)
+    _check_map(m, [x], oracle.run_chain([x], ops), expect_strided=True)
+    ops = [("slice", 1, 3, 31, 1), ("reshape", (16, 7)), ("transpose", (1, 0))]
+    m = B.amap_compose([(4, 32)], 4, ops)
+    _check_map(m, [x], oracle.run_chain([x], ops), expect_strided=True)
+
+
+def test_pad_then_flatten_and_step_slices():
+    x = _iota_sources([(2, 3, 5, 6)], 2)[0]
+    ops = [("pad", (0, 0, 1, 1), (0, 0, 1, 1), 7), ("reshape", (6, 56)), ("slice", 1, 3, 50, 3)]
+    m = B.amap_compose([(2, 3, 5, 6)], 2, ops)
+    _check_map(m, [x], oracle.run_chain([x], ops))
+    ops = [("reshape", (6, 30)), ("slice", 1, 1, 29, 2), ("reshape", (6, 2, 7)), ("slice", 2, 1, 7, 4)]
+    m = B.amap_compose([(2, 3, 5, 6)], 2, ops)
+    _check_map(m, [x], oracle.run_chain([x], ops))
+
+
+def test_inverse_closed_forms():
+    for name in ["cfg2_fwd", "cfg2_rev", "cfg4"]:
+        w = synth.workload(name)
+        m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
+        inv = B.amap_inverse(m)
+        assert B.dst_shape(inv) == w.src_shapes[0]
+        x = synth.random_bits(w.src_shapes[0], 2, 3)
+        y = B.amap_eval_host(m, [x])
+        assert np.array_equal(B.amap_eval_host(inv, [y], mode=2), x)
+    # small: program and pieces of the inverse agree; inverse of inverse is the map
+    x = _iota_sources([(4, 6, 10)], 4)[0]
+    ops = [("transpose", (2, 0, 1)), ("reshape", (5, 8, 6)), ("transpose", (1, 2, 0))]
+    m = B.amap_compose([(4, 6, 10)], 4, ops)
+    y = oracle.run_chain([x], ops)
+    inv = B.amap_inverse(m)
+    assert np.array_equal(B.amap_eval_host(inv, [y], mode=1), x)
+    assert np.array_equal(B.amap_eval_host(inv, [y], mode=2), x)
+    assert np.array_equal(B.amap_eval_host(B.amap_inverse(inv), [x]), y)
+    # transpose o transpose^-1 = identity, via the map algebra alone
+    t = B.amap_transpose(B.amap_source(0, (3, 4, 5), 4), (2, 0, 1))
+    ti = B.amap_inverse(t)
+    xs = _iota_sources([(3, 4, 5)], 4)[0]
+    assert np.array_equal(B.amap_eval_host(ti, [B.amap_eval_host(t, [xs])]), xs)
+
+
+def test_inverse_refuses_non_bijections():
+    s = B.amap_source(0, (4, 6), 4)
+    for m in [B.amap_slice(s, 1, 0, 3, 1), B.amap_pad(s, (0, 1), (0, 0), 0),
+              B.amap_concat([s, s], 0)]:
+        with pytest.raises(B.AmapError) as e:
+            B.amap_inverse(m)
+        assert e.value.status == B.AMAP_E_UNSUPPORTED
+
+
+def test_error_paths():
+    s = B.amap_source(0, (4, 6), 4)
+    cases = [
+        (lambda: B.amap_source(0, (), 4), B.AMAP_E_INVALID),
+        (lambda: B.amap_source(0, (1,) * 9, 4), B.AMAP_E_INVALID),
+        (lambda: B.amap_source(0, (2, 3), 3), B.AMAP_E_INVALID),
+        (lambda: B.amap_source(-1, (2, 3), 4), B.AMAP_E_INVALID),
+        (lambda: B.amap_transpose(s, (0, 0)), B.AMAP_E_INVALID),
+        (lambda: B.amap_transpose(s, (0, 2)), B.AMAP_E_INVALID),
+        (lambda: B.amap_reshape(s, (5, 5)), B.AMAP_E_SHAPE),
+        (lambda: B.amap_slice(s, 2, 0, 1, 1), B.AMAP_E_INVALID),
+        (lambda: B.amap_slice(s, 1, 3, 3, 1), B.AMAP_E_SHAPE),
+        (lambda: B.amap_slice(s, 1, 0, 7, 1), B.AMAP_E_SHAPE),
+        (lambda: B.amap_slice(s, 1, 0, 6, 0), B.AMAP_E_SHAPE),
+        (lambda: B.amap_pad(s, (0, -1), (0, 0)), B.AMAP_E_SHAPE),
+        (lambda: B.amap_concat([s, B.amap_source(1, (5, 7), 4)], 0), B.AMAP_E_SHAPE),
+        (lambda: B.amap_concat([s, B.amap_source(1, (4, 6), 2)], 0), B.AMAP_E_INVALID),
+        (lambda: B.amap_concat([s, B.amap_source(0, (4, 7), 4)], 1), B.AMAP_E_SHAPE),
+        (lambda: B.amap_compose([(2, 3), (2, 3)], 4, [("transpose", (1, 0))]), B.AMAP_E_INVALID),
+        (lambda: B.amap_compose([(2, 3)], 4, [("transpose", (1, 0)), ("concat", 0)]), B.AMAP_E_INVALID),
+    ]
+    for fn, status in cases:
+        with pytest.raises(B.AmapError) as e:
+            fn()
+        assert e.value.status == status, (fn, e.value.status)
+    assert B.amap_status_str(B.AMAP_E_ALIAS) == "dst overlaps a source"
+
+
+def test_empty_tensor():
+    m = B.amap_compose([(3, 0, 4)], 4, [("transpose", (2, 0, 1)), ("reshape", (0, 7))])
+    info = B.amap_describe(m)
+    assert info.write_bytes == 0 and info.n_pieces == 0
+    out = B.amap_eval_host(m, [np.zeros((3, 0, 4), np.uint32)])
+    assert out.shape == (0, 7)
