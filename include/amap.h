@@ -154,6 +154,13 @@ amap_status amap_eval_host(const amap_t *m, const void *const *src, void *dst, i
  * element. */
 amap_status amap_check_cover(const amap_t *m, int64_t *unwritten, int64_t *overwritten);
 
+/* Diagnostic: replay on the host, lane by lane, the launches that
+ * amap_execute_kernel(.., kernel_id) would make (kernel_id -1 = planned) and
+ * count out-of-bounds accesses, dst elements with no or several writers, and
+ * dst elements routed from the wrong source element.  Moves no tensor data;
+ * lets the device indexing be verified on a machine without a GPU. */
+amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64_t *n_errors);
+
 /* ---- execution (device pointers; asynchronous on `stream`) --------------
  * `stream` is a hipStream_t passed as void* (NULL = the default stream).
  * No allocation, no synchronisation, no host access to device memory. */

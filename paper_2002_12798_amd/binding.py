@@ -21,7 +21,7 @@ AMAP_MAX_RANK = 8
 EXPORTS = [
     "amap_source", "amap_transpose", "amap_reshape", "amap_slice", "amap_pad", "amap_concat",
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
-    "amap_eval_host", "amap_check_cover", "amap_execute", "amap_execute_kernel",
+    "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_kernel",
     "amap_gemm_fused", "amap_status_str",
 ]
 
@@ -71,6 +71,7 @@ _L.amap_describe.argtypes = [_vp, C.POINTER(amap_info)]
 _L.amap_source_shape.argtypes = [_vp, C.c_int, C.POINTER(C.c_int), _i64p]
 _L.amap_eval_host.argtypes = [_vp, _pp, _vp, C.c_int]
 _L.amap_check_cover.argtypes = [_vp, _i64p, _i64p]
+_L.amap_plan_selfcheck.argtypes = [_vp, C.c_int, _i64p]
 _L.amap_execute.argtypes = [_pp, _vp, _vp, _vp]
 _L.amap_execute_kernel.argtypes = [_pp, _vp, _vp, _vp, C.c_int]
 _L.amap_gemm_fused.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp]
@@ -218,6 +219,12 @@ def amap_check_cover(m):
     un, ov = C.c_int64(), C.c_int64()
     _check(_L.amap_check_cover(m.handle, C.byref(un), C.byref(ov)), "amap_check_cover")
     return un.value, ov.value
+
+
+def amap_plan_selfcheck(m, kernel_id=-1):
+    n = C.c_int64()
+    _check(_L.amap_plan_selfcheck(m.handle, int(kernel_id), C.byref(n)), "amap_plan_selfcheck")
+    return n.value
 
 
 def amap_eval_host(m, srcs, mode=0):

@@ -14,6 +14,7 @@
 #include <numeric>
 
 #include "amap_map.hpp"
+#include "amap_plan.hpp"
 
 using namespace amap_detail;
 
@@ -143,6 +144,16 @@ void finalise(amap &m) {
 
 }  // namespace amap_detail
 
+// every builder ends here: derive the kernel-form pieces and the launch plan
+static void finish(amap &m) {
+    finalise(m);
+    attach_plan(m);
+}
+
+namespace amap_detail {
+
+}  // namespace amap_detail
+
 // ---------------------------------------------------------------- helpers
 
 static amap *clone_header(const amap *m) {
@@ -203,7 +214,7 @@ extern "C" amap_status amap_source(int src_id, int rank, const int64_t *shape, a
             if (shape[k] > 1) p.it.push_back({shape[k], k, 1, R[k]});
         m->pieces.push_back(std::move(p));
     }
-    finalise(*m);
+    finish(*m);
     *out = m;
     return AMAP_OK;
     GUARD_END
@@ -240,7 +251,7 @@ extern "C" amap_status amap_transpose(const amap_t *m, const int32_t *perm, amap
             r->pieces.push_back(std::move(q));
         }
     }
-    finalise(*r);
+    finish(*r);
     *out = hold.release();
     return AMAP_OK;
     GUARD_END
@@ -369,7 +380,7 @@ extern "C" amap_status amap_slice(const amap_t *m, int axis, int64_t begin, int6
             r->pieces.clear();
         }
     }
-    finalise(*r);
+    finish(*r);
     *out = hold.release();
     return AMAP_OK;
     GUARD_END
@@ -439,7 +450,7 @@ extern "C" amap_status amap_pad(const amap_t *m, const int64_t *lo, const int64_
             r->pieces.clear();
         }
     }
-    finalise(*r);
+    finish(*r);
     *out = hold.release();
     return AMAP_OK;
     GUARD_END
@@ -494,7 +505,7 @@ extern "C" amap_status amap_concat(const amap_t *const *ms, int n, int axis, ama
         r->strided = false;
         r->pieces.clear();
     }
-    finalise(*r);
+    finish(*r);
     *out = hold.release();
     return AMAP_OK;
     GUARD_END
@@ -687,7 +698,7 @@ extern "C" amap_status amap_reshape(const amap_t *m, int rank, const int64_t *sh
             r->pieces.clear();
         }
     }
-    finalise(*r);
+    finish(*r);
     *out = hold.release();
     return AMAP_OK;
     GUARD_END
@@ -765,7 +776,7 @@ extern "C" amap_status amap_inverse(const amap_t *m, amap_t **out) {
         r2->kids.push_back(t);
         r->prog = r2;
     }
-    finalise(*r);
+    finish(*r);
     *out = hold.release();
     return AMAP_OK;
     GUARD_END

@@ -1,0 +1,100 @@
+// Plain-data descriptors shared by the host planner and the gfx950 kernels.
+// A launch carries up to kMaxPiecesPerLaunch pieces by value in its kernel
+// arguments, so executing a map needs no device allocation and no copy.
+#pragma once
+
+#include <cstdint>
+
+namespace amap_dev {
+
+constexpr int kMaxLoops = 8;             // loops per piece after merging
+constexpr int kMaxPiecesPerLaunch = 12;  // keeps the argument block under 4 KiB
+constexpr int kThreads = 256;            // 4 wavefronts per workgroup
+constexpr int kRowsUnroll = 4;           // vectors per lane in the row kernel
+
+// n / d for n < 2^31:  q = (umulhi(n, mul) + n) >> shift
+struct FastDiv {
+    uint32_t mul, shift;
+};
+
+inline FastDiv make_fastdiv(uint32_t d) {
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    uint64_t m = ((1ull << 32) * ((1ull << l) - d)) / d + 1;
+    return FastDiv{(uint32_t)m, l};
+}
+
+inline uint32_t fastdiv_host(uint32_t n, FastDiv f) {
+    return (uint32_t)((((uint64_t)n * f.mul) >> 32) + n) >> f.shift;
+}
+
+struct Loop {
+    uint32_t extent;
+    int32_t ds, ss;  // element strides on the dst / source side
+    FastDiv fd;      // division by extent
+};
+
+enum PieceKind : uint32_t {
+    PK_ROWS = 0,  // one lane per vector, dst order (also fill pieces and the element-wise form)
+    PK_TILE = 1,  // P x Q tile, register micro-transpose, staged through LDS
+    PK_WAVE = 2   // P x Q tile per wavefront, register micro-transpose, no LDS
+};
+
+struct DevPiece {
+    uint32_t kind;
+    uint32_t first_block;  // first workgroup of this piece within the launch
+    uint32_t n_blocks;
+    uint32_t n_units;      // ROWS: vectors in the piece
+    const void *src;       // device pointer of the piece's source (patched in at launch); null = fill
+    uint32_t fill;         // fill pattern replicated to 32 bits
+    uint32_t dbase, sbase; // element offsets
+    uint32_t vlog;         // log2(elements per vector)
+    uint32_t nloops;
+    // ROWS: loops[0..nloops) innermost first; loop 0 counts vectors.
+    // TILE/WAVE: loops[0..nq) = Q chain innermost first (ds used, contiguous in the source),
+    //            loops[nq..nloops) = batch loops.
+    Loop loops[kMaxLoops];
+    uint32_t nq;
+    uint32_t eP, EQ;       // extents in elements along P (dst-contiguous) and the merged Q chain
+    int32_t ssP;           // source stride of P
+    uint32_t tilesP, tilesQ;
+    FastDiv fdTP, fdTQ;
+    uint32_t lqlog;        // log2(lanes along Q); lanes along P = 64 >> lqlog
+    uint32_t nwplog;       // log2(wavefronts along P); wavefronts along Q = 4 >> nwplog
+};
+
+struct LaunchArgs {
+    uint32_t n_pieces;
+    uint32_t pad_;
+    DevPiece p[kMaxPiecesPerLaunch];
+};
+
+static_assert(sizeof(LaunchArgs) <= 4000, "kernel argument block too large");
+
+// ---- operator program for the element-wise interpreter ----
+constexpr int kMaxInstr = 24;
+enum InstrKind : int32_t { I_SOURCE = 0, I_TRANSPOSE, I_RESHAPE, I_SLICE, I_PAD, I_CONCAT };
+
+struct Instr {
+    int32_t kind;
+    int32_t rank;  // rank of the index the instruction receives
+    int32_t a;     // SOURCE: src id; SLICE/CONCAT: axis; RESHAPE: child rank
+    int32_t b;     // PAD: fill bits; CONCAT: number of children
+    int32_t v[8];  // SOURCE: shape; TRANSPOSE: perm; RESHAPE: own shape; SLICE: {begin, step}; PAD: lo; CONCAT: child extents
+    int32_t w[8];  // RESHAPE/PAD: child shape; CONCAT: jump targets
+};
+
+struct Program {
+    int32_t n;
+    int32_t rank;          // dst rank
+    int32_t shape[8];      // dst shape
+    Instr ins[kMaxInstr];
+};
+
+static_assert(sizeof(Program) <= 2048, "program too large");
+
+struct SrcTable {
+    const void *p[16];
+};
+
+}  // namespace amap_dev

@@ -1,0 +1,136 @@
+// Index arithmetic of the piece kernels, written once and compiled both for
+// the GPU (used by the kernels) and for the host (used by the plan checker,
+// which replays every lane of every launch on the CPU and verifies that all
+// addresses are in bounds and that every dst element has exactly one writer).
+#pragma once
+
+#include "amap_device.hpp"
+
+#if defined(__HIPCC__)
+#define AMAP_HD __host__ __device__ __forceinline__
+#else
+#define AMAP_HD inline
+#endif
+
+namespace amap_dev {
+
+AMAP_HD uint32_t fdiv(uint32_t n, FastDiv f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (__umulhi(n, f.mul) + n) >> f.shift;
+#else
+    return (uint32_t)((((uint64_t)n * f.mul) >> 32) + n) >> f.shift;
+#endif
+}
+
+// ---- row kernel: vector r of the piece (dst order) -> element offsets
+AMAP_HD void rows_offsets(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_t &soff) {
+    uint32_t d = P.dbase, s = P.sbase;
+    for (uint32_t k = 0; k < P.nloops; ++k) {
+        const uint32_t q = fdiv(r, P.loops[k].fd);
+        const uint32_t dig = r - q * P.loops[k].extent;
+        d += dig * (uint32_t)P.loops[k].ds;
+        s += dig * (uint32_t)P.loops[k].ss;
+        r = q;
+    }
+    doff = d;
+    soff = s;
+}
+
+// ---- tile kernels
+struct TileGeom {
+    uint32_t tp, tq;      // tile coordinates along P and Q
+    uint32_t db, sb;      // element offsets of the tile's batch point (dst / source)
+    uint32_t TP, TQ;      // tile extents in elements
+    uint32_t ncvlog;      // log2(vectors along P per tile row)
+    uint32_t lqlog, lplog, nwplog;
+};
+
+AMAP_HD TileGeom tile_geometry(const DevPiece &P, uint32_t vlog, uint32_t t) {
+    TileGeom G;
+    uint32_t q = fdiv(t, P.fdTP);
+    G.tp = t - q * P.tilesP;
+    t = q;
+    q = fdiv(t, P.fdTQ);
+    G.tq = t - q * P.tilesQ;
+    t = q;
+    G.db = P.dbase;
+    G.sb = P.sbase;
+    for (uint32_t k = P.nq; k < P.nloops; ++k) {
+        q = fdiv(t, P.loops[k].fd);
+        const uint32_t dig = t - q * P.loops[k].extent;
+        G.db += dig * (uint32_t)P.loops[k].ds;
+        G.sb += dig * (uint32_t)P.loops[k].ss;
+        t = q;
+    }
+    G.lqlog = P.lqlog;
+    G.lplog = 6 - P.lqlog;
+    G.nwplog = P.nwplog;
+    G.TP = ((1u << G.nwplog) << G.lplog) << vlog;
+    G.TQ = ((4u >> G.nwplog) << G.lqlog) << vlog;
+    G.ncvlog = G.nwplog + G.lplog;
+    return G;
+}
+
+// what one lane loads: V vectors along Q at P indices p .. p+V-1, Q position w0
+struct TileLane {
+    bool valid;
+    uint32_t pvl;   // vector index along P inside the tile
+    uint32_t r0;    // first row (Q position) inside the tile
+    uint32_t p, w0; // the same in piece coordinates (elements)
+    uint32_t soff;  // source element offset of the first vector
+};
+
+AMAP_HD TileLane tile_lane(const DevPiece &P, const TileGeom &G, uint32_t vlog, uint32_t tid) {
+    TileLane L;
+    const uint32_t wave = tid >> 6, lane = tid & 63;
+    const uint32_t wp = wave & ((1u << G.nwplog) - 1), wq = wave >> G.nwplog;
+    const uint32_t lq = lane & ((1u << G.lqlog) - 1), lp = lane >> G.lqlog;
+    L.pvl = (wp << G.lplog) + lp;
+    L.r0 = ((wq << G.lqlog) + lq) << vlog;
+    L.p = G.tp * G.TP + (L.pvl << vlog);
+    L.w0 = G.tq * G.TQ + L.r0;
+    L.valid = L.p < P.eP && L.w0 < P.EQ;
+    L.soff = G.sb + L.p * (uint32_t)P.ssP + L.w0;
+    return L;
+}
+
+// dst offset contributed by position w of the merged Q chain
+AMAP_HD uint32_t q_chain_offset(const DevPiece &P, uint32_t w) {
+    uint32_t off = 0;
+    for (uint32_t k = 0; k + 1 < P.nq; ++k) {
+        const uint32_t q = fdiv(w, P.loops[k].fd);
+        off += (w - q * P.loops[k].extent) * (uint32_t)P.loops[k].ds;
+        w = q;
+    }
+    return off + w * (uint32_t)P.loops[P.nq - 1].ds;
+}
+
+// LDS slot (in vectors) of the vector at (row, column cv) of the tile.  The tile
+// is kept in dst order; the column is XOR-swizzled with the lane coordinate
+// that produced the row, so the column-wise writes of the load phase spread
+// over the banks while the row-wise reads of the store phase stay contiguous.
+AMAP_HD uint32_t tile_lds_slot(const TileGeom &G, uint32_t vlog, uint32_t row, uint32_t cv) {
+    const uint32_t lqv = (row >> vlog) & ((1u << G.lqlog) - 1);
+    const uint32_t ncv = 1u << G.ncvlog;
+    const uint32_t swz = (G.nwplog ? (lqv << G.lplog) : lqv) & (ncv - 1);
+    return (row << G.ncvlog) + (cv ^ swz);
+}
+
+// store phase of the LDS tile: vector vi of the tile in dst order
+struct TileStore {
+    bool ok;
+    uint32_t slot;
+    uint32_t doff;
+};
+
+AMAP_HD TileStore tile_store(const DevPiece &P, const TileGeom &G, uint32_t vlog, uint32_t vi) {
+    TileStore S;
+    const uint32_t row = vi >> G.ncvlog, cv = vi & ((1u << G.ncvlog) - 1);
+    const uint32_t w = G.tq * G.TQ + row, pp = G.tp * G.TP + (cv << vlog);
+    S.ok = w < P.EQ && pp < P.eP;
+    S.slot = tile_lds_slot(G, vlog, row, cv);
+    S.doff = S.ok ? G.db + q_chain_offset(P, w) + pp : 0;
+    return S;
+}
+
+}  // namespace amap_dev

@@ -1,0 +1,402 @@
+// gfx950 kernels that execute a composed access map, and the device entry
+// points amap_execute / amap_execute_kernel.
+//
+// Every kernel performs the rewritten load of the paper's eq. 4,
+//     dst[i] = src[g(i)]      (or the fill constant outside every copy piece),
+// for all i of the final tensor of a chain, without materialising any
+// intermediate tensor.  Data are moved as opaque integers of 2..16 bytes.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "amap_index.hpp"
+#include "amap_plan.hpp"
+
+using namespace amap_dev;
+using namespace amap_detail;
+
+namespace {
+
+// VB-byte global / LDS accesses (VB = 4, 8, 16 go through dword vectors)
+template <int VB>
+__device__ __forceinline__ void ld(uint32_t (&r)[VB / 4], const void *p) {
+    if constexpr (VB == 16) {
+        uint4 v = *reinterpret_cast<const uint4 *>(p);
+        r[0] = v.x, r[1] = v.y, r[2] = v.z, r[3] = v.w;
+    } else if constexpr (VB == 8) {
+        uint2 v = *reinterpret_cast<const uint2 *>(p);
+        r[0] = v.x, r[1] = v.y;
+    } else {
+        r[0] = *reinterpret_cast<const uint32_t *>(p);
+    }
+}
+template <int VB>
+__device__ __forceinline__ void st(void *p, const uint32_t (&r)[VB / 4]) {
+    if constexpr (VB == 16) {
+        *reinterpret_cast<uint4 *>(p) = make_uint4(r[0], r[1], r[2], r[3]);
+    } else if constexpr (VB == 8) {
+        *reinterpret_cast<uint2 *>(p) = make_uint2(r[0], r[1]);
+    } else {
+        *reinterpret_cast<uint32_t *>(p) = r[0];
+    }
+}
+
+// ------------------------------------------------------------------ rows
+// One lane per vector of VB bytes, vectors enumerated in dst order, so the
+// stores of a wavefront are contiguous; loads are contiguous per source run.
+template <int VB>
+__device__ __forceinline__ void rows_move(const DevPiece &P, char *dst, int es, const uint32_t (&doff)[kRowsUnroll],
+                                          const uint32_t (&soff)[kRowsUnroll], const bool (&ok)[kRowsUnroll]) {
+    if constexpr (VB == 2) {
+        uint16_t v[kRowsUnroll];
+#pragma unroll
+        for (int u = 0; u < kRowsUnroll; ++u)
+            v[u] = P.src && ok[u] ? *reinterpret_cast<const uint16_t *>((const char *)P.src + (size_t)soff[u] * es)
+                                  : (uint16_t)P.fill;
+#pragma unroll
+        for (int u = 0; u < kRowsUnroll; ++u)
+            if (ok[u]) *reinterpret_cast<uint16_t *>(dst + (size_t)doff[u] * es) = v[u];
+    } else {
+        uint32_t v[kRowsUnroll][VB / 4];
+#pragma unroll
+        for (int u = 0; u < kRowsUnroll; ++u) {
+            if (P.src && ok[u]) {
+                ld<VB>(v[u], (const char *)P.src + (size_t)soff[u] * es);
+            } else {
+#pragma unroll
+                for (int k = 0; k < VB / 4; ++k) v[u][k] = P.fill;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kRowsUnroll; ++u)
+            if (ok[u]) st<VB>(dst + (size_t)doff[u] * es, v[u]);
+    }
+}
+
+template <int ES>
+__device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t blk, uint32_t tid) {
+    uint32_t doff[kRowsUnroll], soff[kRowsUnroll];
+    bool ok[kRowsUnroll];
+    const uint32_t base = blk * (kThreads * kRowsUnroll) + tid;
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) {
+        const uint32_t r = base + u * kThreads;
+        ok[u] = r < P.n_units;
+        rows_offsets(P, r, doff[u], soff[u]);
+    }
+    switch (ES << P.vlog) {
+    case 16: rows_move<16>(P, dst, ES, doff, soff, ok); break;
+    case 8: rows_move<8>(P, dst, ES, doff, soff, ok); break;
+    case 4: rows_move<4>(P, dst, ES, doff, soff, ok); break;
+    default:
+        if constexpr (ES == 2) rows_move<2>(P, dst, ES, doff, soff, ok);
+        break;
+    }
+}
+
+// ------------------------------------------------------------------ tile
+// Register micro-transpose: in[i] holds V elements along Q for P index i;
+// out[j] holds V elements along P for Q index j.
+template <int ES, int V>
+__device__ __forceinline__ void micro_transpose(const uint32_t (&in)[V][ES * V / 4], uint32_t (&out)[V][ES * V / 4]) {
+    if constexpr (ES == 4) {
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+#pragma unroll
+            for (int j = 0; j < V; ++j) out[j][i] = in[i][j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j)
+#pragma unroll
+            for (int i2 = 0; i2 < V / 2; ++i2) {
+                const uint32_t a = in[2 * i2][j / 2], b = in[2 * i2 + 1][j / 2];
+                out[j][i2] = (j & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+            }
+    }
+}
+
+template <int ES, int V, bool USE_LDS>
+__device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
+    constexpr int VB = ES * V;
+    constexpr int NW = VB / 4;
+    constexpr uint32_t VLOG = V == 8 ? 3 : V == 4 ? 2 : V == 2 ? 1 : 0;
+    const TileGeom G = tile_geometry(P, VLOG, t);
+    const TileLane L = tile_lane(P, G, VLOG, tid);
+
+    uint32_t in[V][NW], out[V][NW];
+    if (L.valid) {
+        const char *s = (const char *)P.src + (size_t)L.soff * ES;
+        const size_t pitch = (size_t)P.ssP * ES;
+#pragma unroll
+        for (int i = 0; i < V; ++i) ld<VB>(in[i], s + i * pitch);
+    } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+#pragma unroll
+            for (int k = 0; k < NW; ++k) in[i][k] = 0;
+    }
+    micro_transpose<ES, V>(in, out);
+
+    if constexpr (!USE_LDS) {
+        if (L.valid) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const uint32_t doff = G.db + q_chain_offset(P, L.w0 + j) + L.p;
+                st<VB>(dst + (size_t)doff * ES, out[j]);
+            }
+        }
+    } else {
+        if (L.valid) {
+#pragma unroll
+            for (int j = 0; j < V; ++j)
+                st<VB>(smem + (size_t)tile_lds_slot(G, VLOG, L.r0 + j, L.pvl) * VB, out[j]);
+        }
+        __syncthreads();
+        const uint32_t nvec = G.TQ << G.ncvlog;
+        for (uint32_t vi = tid; vi < nvec; vi += kThreads) {
+            const TileStore S = tile_store(P, G, VLOG, vi);
+            if (S.ok) {
+                uint32_t v[NW];
+                ld<VB>(v, smem + (size_t)S.slot * VB);
+                st<VB>(dst + (size_t)S.doff * ES, v);
+            }
+        }
+    }
+}
+
+template <int ES, bool USE_LDS>
+__device__ __forceinline__ void tile_dispatch(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
+    if constexpr (ES == 2) {
+        switch (P.vlog) {
+        case 3: tile_body<2, 8, USE_LDS>(P, dst, t, tid, smem); break;
+        case 2: tile_body<2, 4, USE_LDS>(P, dst, t, tid, smem); break;
+        default: tile_body<2, 2, USE_LDS>(P, dst, t, tid, smem); break;
+        }
+    } else {
+        switch (P.vlog) {
+        case 2: tile_body<4, 4, USE_LDS>(P, dst, t, tid, smem); break;
+        case 1: tile_body<4, 2, USE_LDS>(P, dst, t, tid, smem); break;
+        default: tile_body<4, 1, USE_LDS>(P, dst, t, tid, smem); break;
+        }
+    }
+}
+
+// One launch executes up to kMaxPiecesPerLaunch pieces: each workgroup finds
+// its piece from the block ranges and runs that piece's body.
+template <int ES>
+__global__ __launch_bounds__(kThreads) void amap_pieces_kernel(const LaunchArgs args, char *dst) {
+    extern __shared__ uint4 smem_v[];
+    const uint32_t b = blockIdx.x;
+    uint32_t pi = 0;
+    for (uint32_t k = 1; k < args.n_pieces; ++k)
+        if (b >= args.p[k].first_block) pi = k;
+    const DevPiece &P = args.p[pi];
+    const uint32_t local = b - P.first_block;
+    if (P.kind == PK_ROWS)
+        rows_body<ES>(P, dst, local, threadIdx.x);
+    else if (P.kind == PK_TILE)
+        tile_dispatch<ES, true>(P, dst, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
+    else
+        tile_dispatch<ES, false>(P, dst, local, threadIdx.x, nullptr);
+}
+
+// ------------------------------------------------------------------ program
+// Element-wise interpreter of the operator program: applies the index
+// function of every operator of the chain in turn (eq. 4 evaluated lazily).
+// Handles any map, at one dst element per lane.
+template <int ES>
+__global__ __launch_bounds__(kThreads) void amap_program_kernel(const Program prog, const SrcTable srcs, char *dst,
+                                                               uint32_t total) {
+    const uint32_t L = blockIdx.x * kThreads + threadIdx.x;
+    if (L >= total) return;
+    int32_t idx[8], tmp[8];
+    {
+        uint32_t r = L;
+        for (int k = prog.rank - 1; k >= 0; --k) {
+            idx[k] = (int32_t)(r % (uint32_t)prog.shape[k]);
+            r /= (uint32_t)prog.shape[k];
+        }
+    }
+    int pc = 0;
+    uint32_t value = 0;
+    for (;;) {
+        const Instr &I = prog.ins[pc];
+        if (I.kind == I_SOURCE) {
+            uint32_t off = 0;
+            for (int k = 0; k < I.rank; ++k) off = off * (uint32_t)I.v[k] + (uint32_t)idx[k];
+            const char *s = (const char *)srcs.p[I.a];
+            value = ES == 2 ? *reinterpret_cast<const uint16_t *>(s + (size_t)off * 2)
+                            : *reinterpret_cast<const uint32_t *>(s + (size_t)off * 4);
+            break;
+        } else if (I.kind == I_TRANSPOSE) {
+            for (int k = 0; k < I.rank; ++k) tmp[I.v[k]] = idx[k];
+            for (int k = 0; k < I.rank; ++k) idx[k] = tmp[k];
+            ++pc;
+        } else if (I.kind == I_RESHAPE) {
+            uint32_t r = 0;
+            for (int k = 0; k < I.rank; ++k) r = r * (uint32_t)I.v[k] + (uint32_t)idx[k];
+            for (int k = I.a - 1; k >= 0; --k) {
+                idx[k] = (int32_t)(r % (uint32_t)I.w[k]);
+                r /= (uint32_t)I.w[k];
+            }
+            ++pc;
+        } else if (I.kind == I_SLICE) {
+            idx[I.a] = I.v[0] + idx[I.a] * I.v[1];
+            ++pc;
+        } else if (I.kind == I_PAD) {
+            bool inside = true;
+            for (int k = 0; k < I.rank; ++k) {
+                idx[k] -= I.v[k];
+                inside = inside && idx[k] >= 0 && idx[k] < I.w[k];
+            }
+            if (!inside) {
+                value = (uint32_t)I.b;
+                break;
+            }
+            ++pc;
+        } else {  // I_CONCAT
+            int32_t x = idx[I.a];
+            int m = 0;
+            while (m + 1 < I.b && x >= I.v[m]) {
+                x -= I.v[m];
+                ++m;
+            }
+            idx[I.a] = x;
+            pc = I.w[m];
+        }
+    }
+    if (ES == 2)
+        *reinterpret_cast<uint16_t *>(dst + (size_t)L * 2) = (uint16_t)value;
+    else
+        *reinterpret_cast<uint32_t *>(dst + (size_t)L * 4) = value;
+}
+
+// ------------------------------------------------------------------ host side
+
+bool overlaps(const void *a, int64_t an, const void *b, int64_t bn) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + (uintptr_t)bn && b0 < a0 + (uintptr_t)an;
+}
+
+amap_status check_pointers(const amap *m, const void *const *src, const void *dst) {
+    const int es = m->elem;
+    const int64_t dbytes = volume_of(m->shape) * es;
+    if (!dst || ((uintptr_t)dst & 15)) return AMAP_E_INVALID;
+    for (size_t i = 0; i < m->src_shapes.size(); ++i) {
+        if (m->src_shapes[i].empty()) continue;
+        if (!src[i] || ((uintptr_t)src[i] & 15)) return AMAP_E_INVALID;
+        if (overlaps(dst, dbytes, src[i], volume_of(m->src_shapes[i]) * es)) return AMAP_E_ALIAS;
+    }
+    return AMAP_OK;
+}
+
+amap_status launch_strided(const amap *m, const Plan &plan, const void *const *src, void *dst, hipStream_t stream) {
+    for (size_t i = 0; i < plan.launches.size(); ++i) {
+        LaunchArgs args = plan.launches[i];
+        for (uint32_t k = 0; k < args.n_pieces; ++k) {
+            const uintptr_t id = (uintptr_t)args.p[k].src;
+            args.p[k].src = id ? src[id - 1] : nullptr;
+        }
+        if (m->elem == 2)
+            hipLaunchKernelGGL(amap_pieces_kernel<2>, dim3(plan.grid[i]), dim3(kThreads), plan.lds_bytes[i], stream, args,
+                               (char *)dst);
+        else
+            hipLaunchKernelGGL(amap_pieces_kernel<4>, dim3(plan.grid[i]), dim3(kThreads), plan.lds_bytes[i], stream, args,
+                               (char *)dst);
+        if (hipGetLastError() != hipSuccess) return AMAP_E_HIP;
+    }
+    return AMAP_OK;
+}
+
+amap_status launch_program(const amap *m, const Plan &plan, const void *const *src, void *dst, hipStream_t stream) {
+    if (!plan.program_ok) return AMAP_E_UNSUPPORTED;
+    SrcTable t;
+    std::memset(&t, 0, sizeof(t));
+    for (int i = 0; i < plan.n_prog_src; ++i) t.p[i] = src[i];
+    const uint32_t total = (uint32_t)volume_of(m->shape);
+    const uint32_t grid = (total + kThreads - 1) / kThreads;
+    if (m->elem == 2)
+        hipLaunchKernelGGL(amap_program_kernel<2>, dim3(grid), dim3(kThreads), 0, stream, plan.prog, t, (char *)dst, total);
+    else
+        hipLaunchKernelGGL(amap_program_kernel<4>, dim3(grid), dim3(kThreads), 0, stream, plan.prog, t, (char *)dst, total);
+    return hipGetLastError() == hipSuccess ? AMAP_OK : AMAP_E_HIP;
+}
+
+}  // namespace
+
+extern "C" amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t *map, void *stream,
+                                           int kernel_id) {
+    if (!map || kernel_id < -1 || kernel_id > AMAP_K_WAVE) return AMAP_E_INVALID;
+    if (volume_of(map->shape) == 0) return AMAP_OK;
+    if (!src) return AMAP_E_INVALID;
+    amap_status st = check_pointers(map, src, dst);
+    if (st != AMAP_OK) return st;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    try {
+        if (kernel_id < 0) {
+            const Plan *plan = plan_of(*map);
+            if (!plan || !plan->fits32) return AMAP_E_UNSUPPORTED;
+            if (plan->strided_ok) return launch_strided(map, *plan, src, dst, s);
+            return launch_program(map, *plan, src, dst, s);
+        }
+        Plan forced;
+        if (kernel_id == AMAP_K_PROGRAM) {
+            plan_strided(*map, -1, forced);  // sets fits32
+            if (!forced.fits32 || !plan_program(*map, forced)) return AMAP_E_UNSUPPORTED;
+            return launch_program(map, forced, src, dst, s);
+        }
+        if (!plan_strided(*map, kernel_id, forced)) return AMAP_E_UNSUPPORTED;
+        return launch_strided(map, forced, src, dst, s);
+    } catch (...) {
+        return AMAP_E_NOMEM;
+    }
+}
+
+extern "C" amap_status amap_execute(const void *const *src, void *dst, const amap_t *map, void *stream) {
+    return amap_execute_kernel(src, dst, map, stream, -1);
+}
+
+extern "C" amap_status amap_describe(const amap_t *m, amap_info *out) {
+    if (!m || !out) return AMAP_E_INVALID;
+    amap_info o;
+    std::memset(&o, 0, sizeof(o));
+    o.rank = (int)m->shape.size();
+    for (int k = 0; k < o.rank; ++k) o.shape[k] = m->shape[k];
+    o.elem_size = m->elem;
+    o.n_src = (int)m->src_shapes.size();
+    o.strided = m->strided ? 1 : 0;
+    o.write_bytes = volume_of(m->shape) * m->elem;
+    if (m->strided) {
+        o.n_pieces = (int)m->kpieces.size();
+        for (const KPiece &p : m->kpieces) {
+            if (p.fill) {
+                ++o.n_fill_pieces;
+                o.fill_bytes += p.volume() * m->elem;
+            } else {
+                o.min_read_bytes += p.volume() * m->elem;
+            }
+        }
+    } else {
+        // count the data elements by walking the program over dst
+        int64_t idx[kMaxRank] = {0};
+        const int rank = o.rank;
+        int64_t data = 0, vol = volume_of(m->shape);
+        for (int64_t L = 0; L < vol; ++L) {
+            int sid;
+            int64_t off;
+            uint32_t fill;
+            data += eval_program(m->prog.get(), idx, &sid, &off, &fill) ? 1 : 0;
+            for (int k = rank - 1; k >= 0; --k) {
+                if (++idx[k] < m->shape[k]) break;
+                idx[k] = 0;
+            }
+        }
+        o.min_read_bytes = data * m->elem;
+        o.fill_bytes = (vol - data) * m->elem;
+    }
+    const Plan *plan = plan_of(*m);
+    o.kernel_id = plan ? plan->main_kernel : AMAP_K_PROGRAM;
+    o.vec_bytes = plan ? plan->min_vec_bytes : m->elem;
+    *out = o;
+    return AMAP_OK;
+}

@@ -1,0 +1,391 @@
+// Host planner: chooses, for every strided piece, the kernel family and the
+// tile geometry, and packs the pieces into launches.
+//
+// Vocabulary (per piece, loops in linearised form):
+//   P  = the loop with dst stride 1 (the dst-contiguous direction),
+//   Q  = the loop with source stride 1 (the source-contiguous direction),
+//        extended to the chain of loops that continue it contiguously in the
+//        source, so that a tile can span several short source rows;
+//   batch = all other loops.
+// P == Q: both sides are contiguous along the same loop -> vector row copy.
+// P != Q: the composed map permutes the contiguous dimension -> the tile is
+//   read along Q, transposed in registers in V x V blocks, and written along P
+//   (through LDS for long dst runs, straight from registers for small P).
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+
+#include "amap_plan.hpp"
+
+using namespace amap_dev;
+
+namespace amap_detail {
+
+static int env_int(const char *name, int def) {
+    const char *v = std::getenv(name);
+    return v && *v ? std::atoi(v) : def;
+}
+
+static uint32_t pow2ceil(uint64_t x) {
+    uint32_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+static uint32_t ilog2(uint32_t x) {
+    uint32_t l = 0;
+    while ((1u << l) < x) ++l;
+    return l;
+}
+
+// largest power of two <= vmax dividing every number in xs
+static uint32_t common_pow2(uint32_t vmax, std::initializer_list<int64_t> xs, const std::vector<int64_t> &more) {
+    uint32_t v = vmax;
+    auto fit = [&](int64_t x) {
+        if (x < 0) x = -x;
+        while (v > 1 && x % v != 0) v >>= 1;
+    };
+    for (int64_t x : xs) fit(x);
+    for (int64_t x : more) fit(x);
+    return v;
+}
+
+static uint32_t replicate_fill(uint32_t bits, int es) {
+    if (es == 2) return (bits & 0xFFFFu) | (bits << 16);
+    return bits;
+}
+
+static void fill_rows(DevPiece &dp, const KPiece &kp, uint32_t V) {
+    dp.kind = PK_ROWS;
+    dp.vlog = ilog2(V);
+    dp.nloops = (uint32_t)kp.dims.size();
+    int64_t vol = 1;
+    for (size_t k = 0; k < kp.dims.size(); ++k) {
+        const KDim &d = kp.dims[kp.dims.size() - 1 - k];  // innermost first
+        Loop &l = dp.loops[k];
+        l.extent = (uint32_t)d.extent;
+        l.ds = (int32_t)d.ds;
+        l.ss = (int32_t)d.ss;
+        if (k == 0 && V > 1) {
+            l.extent = (uint32_t)(d.extent / V);
+            l.ds = (int32_t)V;
+            l.ss = kp.fill ? 0 : (int32_t)V;
+        }
+        l.fd = make_fastdiv(l.extent);
+        vol *= l.extent;
+    }
+    dp.n_units = (uint32_t)vol;
+    dp.n_blocks = (uint32_t)((vol + kThreads * kRowsUnroll - 1) / (kThreads * kRowsUnroll));
+}
+
+// returns the family used (amap_kernel_id) or -1 if the forced family cannot run the piece
+static int plan_piece(const amap &m, const KPiece &kp, int family, DevPiece &dp, uint32_t &lds, int &vec_bytes) {
+    const int es = m.elem;
+    const uint32_t vmax = 16 / es;
+    std::memset(&dp, 0, sizeof(dp));
+    dp.src = kp.fill ? nullptr : reinterpret_cast<const void *>((uintptr_t)(kp.src + 1));
+    dp.fill = replicate_fill(kp.fill_bits, es);
+    dp.dbase = (uint32_t)kp.dbase;
+    dp.sbase = (uint32_t)kp.sbase;
+    lds = 0;
+    const int n = (int)kp.dims.size();
+    int iP = -1, iQ = -1;
+    for (int k = 0; k < n; ++k) {
+        if (kp.dims[k].ds == 1) iP = k;
+        if (!kp.fill && kp.dims[k].ss == 1) iQ = k;
+    }
+    std::vector<int64_t> ds_others, ss_others;
+    for (int k = 0; k < n; ++k) {
+        if (k != iP) ds_others.push_back(kp.dims[k].ds);
+        if (k != iQ && !kp.fill) ss_others.push_back(kp.dims[k].ss);
+    }
+    const bool rows_ok = iP >= 0 && (kp.fill || iP == iQ);
+    const bool tile_shape = !kp.fill && iP >= 0 && iQ >= 0 && iP != iQ;
+    uint32_t Vt = 1;
+    if (tile_shape) {
+        Vt = common_pow2(vmax, {kp.dims[iP].extent, kp.dims[iQ].extent, kp.dbase, kp.sbase}, ds_others);
+        Vt = common_pow2(Vt, {}, ss_others);
+    }
+    const bool tile_ok = tile_shape && Vt * es >= 4;
+
+    int fam = family;
+    if (fam < 0) {
+        if (rows_ok)
+            fam = AMAP_K_ROWS;
+        else if (tile_ok)
+            fam = (int64_t)kp.dims[iP].extent * es <= env_int("AMAP_WAVE_MAX_P_BYTES", 64) ? AMAP_K_WAVE : AMAP_K_TILE;
+        else
+            fam = AMAP_K_ELEMENT;
+    }
+    if (kp.fill && (fam == AMAP_K_TILE || fam == AMAP_K_WAVE)) fam = AMAP_K_ROWS;  // constants need no transpose
+
+    if (fam == AMAP_K_ELEMENT) {
+        fill_rows(dp, kp, 1);
+        vec_bytes = es;
+        return fam;
+    }
+    if (fam == AMAP_K_ROWS) {
+        if (!rows_ok) return -1;
+        std::vector<int64_t> all = ds_others;
+        all.insert(all.end(), ss_others.begin(), ss_others.end());
+        uint32_t V = common_pow2(vmax, {kp.dims[iP].extent, kp.dbase, kp.fill ? 0 : kp.sbase}, all);
+        fill_rows(dp, kp, V);
+        vec_bytes = (int)V * es;
+        return fam;
+    }
+    if (fam != AMAP_K_TILE && fam != AMAP_K_WAVE) return -1;
+    if (!tile_ok) return -1;
+
+    // ---- tile geometry
+    const uint32_t V = Vt;
+    dp.kind = fam == AMAP_K_TILE ? PK_TILE : PK_WAVE;
+    dp.vlog = ilog2(V);
+    dp.eP = (uint32_t)kp.dims[iP].extent;
+    dp.ssP = (int32_t)kp.dims[iP].ss;
+    std::vector<int> chain{iQ};
+    int64_t EQ = kp.dims[iQ].extent;
+    for (bool grown = true; grown && chain.size() < 3;) {
+        grown = false;
+        for (int k = 0; k < n; ++k) {
+            if (k == iP || std::find(chain.begin(), chain.end(), k) != chain.end()) continue;
+            if (kp.dims[k].ss == EQ && EQ * kp.dims[k].extent < (1ll << 31)) {
+                chain.push_back(k);
+                EQ *= kp.dims[k].extent;
+                grown = true;
+                break;
+            }
+        }
+    }
+    dp.EQ = (uint32_t)EQ;
+    dp.nq = (uint32_t)chain.size();
+    uint32_t nl = 0;
+    for (int k : chain) {
+        Loop &l = dp.loops[nl++];
+        l.extent = (uint32_t)kp.dims[k].extent;
+        l.ds = (int32_t)kp.dims[k].ds;
+        l.ss = (int32_t)kp.dims[k].ss;
+        l.fd = make_fastdiv(l.extent);
+    }
+    int64_t batch = 1;
+    for (int k = n - 1; k >= 0; --k) {
+        if (k == iP || std::find(chain.begin(), chain.end(), k) != chain.end()) continue;
+        Loop &l = dp.loops[nl++];
+        l.extent = (uint32_t)kp.dims[k].extent;
+        l.ds = (int32_t)kp.dims[k].ds;
+        l.ss = (int32_t)kp.dims[k].ss;
+        l.fd = make_fastdiv(l.extent);
+        batch *= l.extent;
+    }
+    dp.nloops = nl;
+    const uint64_t pv = dp.eP / V, qv = (uint64_t)EQ / V;  // vectors along P / Q
+    uint32_t LP = std::min<uint32_t>(64, pow2ceil(pv)), LQ = std::min<uint32_t>(64, pow2ceil(qv));
+    while (LP * LQ > 64) {
+        if (LP > LQ)
+            LP >>= 1;
+        else
+            LQ >>= 1;
+    }
+    if (LP * LQ < 64) LQ = 64 / LP;
+    int lq_env = env_int("AMAP_TILE_LQLOG", -1);
+    if (lq_env >= 0 && lq_env <= 6) {
+        LQ = 1u << lq_env;
+        LP = 64 / LQ;
+    }
+    const uint64_t remP = (pv + LP - 1) / LP, remQ = (qv + LQ - 1) / LQ;
+    uint32_t NWP;
+    if (remP >= 2 && remQ >= 2)
+        NWP = 2;
+    else if (remQ < 2)
+        NWP = std::min<uint32_t>(4, pow2ceil(remP));
+    else
+        NWP = 1;
+    int nwp_env = env_int("AMAP_TILE_NWPLOG", -1);
+    if (nwp_env >= 0 && nwp_env <= 2) NWP = 1u << nwp_env;
+    dp.lqlog = ilog2(LQ);
+    dp.nwplog = ilog2(NWP);
+    const uint32_t TP = NWP * LP * V, TQ = (4 / NWP) * LQ * V;
+    dp.tilesP = (dp.eP + TP - 1) / TP;
+    dp.tilesQ = (uint32_t)((EQ + TQ - 1) / TQ);
+    dp.fdTP = make_fastdiv(dp.tilesP);
+    dp.fdTQ = make_fastdiv(dp.tilesQ);
+    int64_t nb = (int64_t)dp.tilesP * dp.tilesQ * batch;
+    if (nb >= (1ll << 31)) return -1;
+    dp.n_blocks = (uint32_t)nb;
+    if (dp.kind == PK_TILE) lds = TP * TQ * es;
+    vec_bytes = (int)V * es;
+    return fam;
+}
+
+bool plan_strided(const amap &m, int family, Plan &out) {
+    out.launches.clear();
+    out.grid.clear();
+    out.lds_bytes.clear();
+    out.strided_ok = false;
+    out.fits32 = volume_of(m.shape) < (1ll << 31);
+    for (const auto &s : m.src_shapes)
+        if (!s.empty() && volume_of(s) >= (1ll << 31)) out.fits32 = false;
+    if (!m.strided || !out.fits32) return false;
+    int64_t best_vol = -1;
+    out.min_vec_bytes = 16;
+    LaunchArgs cur;
+    std::memset(&cur, 0, sizeof(cur));
+    uint32_t blocks = 0, lds_max = 0;
+    auto flush = [&]() {
+        if (cur.n_pieces == 0) return;
+        out.launches.push_back(cur);
+        out.grid.push_back(blocks);
+        out.lds_bytes.push_back(lds_max);
+        std::memset(&cur, 0, sizeof(cur));
+        blocks = 0;
+        lds_max = 0;
+    };
+    for (const KPiece &kp : m.kpieces) {
+        if ((int)kp.dims.size() > kMaxLoops) return false;
+        DevPiece dp;
+        uint32_t lds = 0;
+        int vb = 0;
+        int fam = plan_piece(m, kp, family, dp, lds, vb);
+        if (fam < 0) return false;
+        if (cur.n_pieces == (uint32_t)kMaxPiecesPerLaunch || (uint64_t)blocks + dp.n_blocks >= (1u << 31)) flush();
+        dp.first_block = blocks;
+        blocks += dp.n_blocks;
+        lds_max = std::max(lds_max, lds);
+        cur.p[cur.n_pieces++] = dp;
+        out.min_vec_bytes = std::min(out.min_vec_bytes, vb);
+        if (kp.volume() > best_vol) {
+            best_vol = kp.volume();
+            out.main_kernel = fam;
+        }
+    }
+    flush();
+    out.strided_ok = true;
+    return true;
+}
+
+// ---------------------------------------------------------------- program
+
+namespace {
+
+struct Flattener {
+    Program &P;
+    bool ok = true;
+    int64_t max_src = -1;
+
+    int alloc() {
+        if (P.n >= kMaxInstr) {
+            ok = false;
+            return -1;
+        }
+        std::memset(&P.ins[P.n], 0, sizeof(Instr));
+        return P.n++;
+    }
+
+    void concat_group(const PNode *n, size_t lo, size_t hi) {
+        // one CONCAT instruction over at most 8 children or groups of children
+        int at = alloc();
+        if (at < 0) return;
+        const size_t count = hi - lo;
+        const size_t per = (count + 7) / 8;  // children per slot
+        Instr &I = P.ins[at];
+        I.kind = I_CONCAT;
+        I.rank = (int32_t)n->shape.size();
+        I.a = n->axis;
+        std::vector<std::pair<size_t, size_t>> slots;
+        for (size_t s = lo; s < hi; s += per) slots.push_back({s, std::min(hi, s + per)});
+        P.ins[at].b = (int32_t)slots.size();
+        for (size_t t = 0; t < slots.size(); ++t) {
+            int64_t ext = 0;
+            for (size_t c = slots[t].first; c < slots[t].second; ++c) ext += n->kids[c]->shape[n->axis];
+            P.ins[at].v[t] = (int32_t)ext;
+        }
+        for (size_t t = 0; t < slots.size() && ok; ++t) {
+            P.ins[at].w[t] = P.n;
+            if (slots[t].second - slots[t].first == 1)
+                emit(n->kids[slots[t].first].get());
+            else
+                concat_group(n, slots[t].first, slots[t].second);
+        }
+    }
+
+    void emit(const PNode *n) {
+        while (ok) {
+            if (n->kind == PNode::CONCAT) {
+                concat_group(n, 0, n->kids.size());
+                return;
+            }
+            int at = alloc();
+            if (at < 0) return;
+            Instr &I = P.ins[at];
+            const int rank = (int)n->shape.size();
+            I.rank = rank;
+            switch (n->kind) {
+            case PNode::SOURCE:
+                I.kind = I_SOURCE;
+                I.a = n->src_id;
+                for (int k = 0; k < rank; ++k) I.v[k] = (int32_t)n->shape[k];
+                max_src = std::max<int64_t>(max_src, n->src_id);
+                return;
+            case PNode::TRANSPOSE:
+                I.kind = I_TRANSPOSE;
+                for (int k = 0; k < rank; ++k) I.v[k] = n->perm[k];
+                break;
+            case PNode::RESHAPE: {
+                I.kind = I_RESHAPE;
+                const auto &cs = n->kids[0]->shape;
+                I.a = (int32_t)cs.size();
+                for (int k = 0; k < rank; ++k) I.v[k] = (int32_t)n->shape[k];
+                for (size_t k = 0; k < cs.size(); ++k) I.w[k] = (int32_t)cs[k];
+                break;
+            }
+            case PNode::SLICE:
+                I.kind = I_SLICE;
+                I.a = n->axis;
+                I.v[0] = (int32_t)n->begin;
+                I.v[1] = (int32_t)n->step;
+                break;
+            case PNode::PAD: {
+                I.kind = I_PAD;
+                I.b = (int32_t)n->fill;
+                const auto &cs = n->kids[0]->shape;
+                for (int k = 0; k < rank; ++k) {
+                    I.v[k] = (int32_t)n->lo[k];
+                    I.w[k] = (int32_t)cs[k];
+                }
+                break;
+            }
+            default:
+                ok = false;
+                return;
+            }
+            n = n->kids[0].get();
+        }
+    }
+};
+
+}  // namespace
+
+bool plan_program(const amap &m, Plan &out) {
+    out.program_ok = false;
+    if (!m.prog || !out.fits32) return false;
+    std::memset(&out.prog, 0, sizeof(out.prog));
+    out.prog.rank = (int32_t)m.shape.size();
+    for (size_t k = 0; k < m.shape.size(); ++k) out.prog.shape[k] = (int32_t)m.shape[k];
+    Flattener f{out.prog};
+    f.emit(m.prog.get());
+    if (!f.ok || f.max_src >= 16) return false;
+    out.n_prog_src = (int)f.max_src + 1;
+    out.program_ok = true;
+    return true;
+}
+
+void attach_plan(amap &m) {
+    auto p = std::make_shared<Plan>();
+    plan_strided(m, -1, *p);
+    plan_program(m, *p);
+    if (!p->strided_ok) {
+        p->main_kernel = AMAP_K_PROGRAM;
+        p->min_vec_bytes = m.elem;
+    }
+    m.plan = p;
+}
+
+}  // namespace amap_detail

@@ -1,0 +1,173 @@
+// Host replay of a launch plan: walks every workgroup and every lane of every
+// launch with the same index functions the kernels use (amap_index.hpp),
+// checks that every address is in bounds, that LDS slots stay inside the
+// tile, and that the routing  dst element <- source element  equals the map's
+// pieces with exactly one writer per dst element.  It moves no tensor data and
+// is never called by the device entry points; tests run it on machines
+// without a GPU before any kernel is launched.
+#include <cstring>
+#include <vector>
+
+#include "amap_index.hpp"
+#include "amap_plan.hpp"
+
+using namespace amap_dev;
+using namespace amap_detail;
+
+namespace {
+
+constexpr int64_t kUnwritten = -1, kFill = -2;
+
+struct Replay {
+    const amap &m;
+    std::vector<int64_t> got;      // per dst element: source id * 2^40 + source offset, kFill, kUnwritten
+    std::vector<int64_t> src_vol;  // by source id
+    int64_t errors = 0;
+
+    explicit Replay(const amap &mm) : m(mm), got((size_t)volume_of(mm.shape), kUnwritten) {
+        for (const auto &s : m.src_shapes) src_vol.push_back(s.empty() ? 0 : volume_of(s));
+    }
+
+    void write(int64_t d, int64_t code) {
+        if (d < 0 || d >= (int64_t)got.size()) {
+            ++errors;
+            return;
+        }
+        if (got[(size_t)d] != kUnwritten) ++errors;  // second writer
+        got[(size_t)d] = code;
+    }
+    int64_t code_of(int sid, int64_t soff) {
+        if (sid < 0) return kFill;
+        if (soff < 0 || soff >= src_vol[(size_t)sid]) {
+            ++errors;
+            return kFill;
+        }
+        return ((int64_t)sid << 40) + soff;
+    }
+
+    void rows(const DevPiece &P, int sid, uint32_t blk) {
+        const uint32_t V = 1u << P.vlog;
+        for (uint32_t tid = 0; tid < (uint32_t)kThreads; ++tid)
+            for (int u = 0; u < kRowsUnroll; ++u) {
+                const uint32_t r = blk * (kThreads * kRowsUnroll) + tid + u * kThreads;
+                if (r >= P.n_units) continue;
+                uint32_t d, s;
+                rows_offsets(P, r, d, s);
+                for (uint32_t e = 0; e < V; ++e) write((int64_t)d + e, code_of(sid, (int64_t)s + e));
+            }
+    }
+
+    void tile(const DevPiece &P, int sid, uint32_t t, uint32_t lds_bytes) {
+        const uint32_t vlog = P.vlog, V = 1u << vlog;
+        const TileGeom G = tile_geometry(P, vlog, t);
+        const bool use_lds = P.kind == PK_TILE;
+        std::vector<int64_t> lds;
+        if (use_lds) {
+            if ((uint64_t)G.TP * G.TQ * m.elem > lds_bytes) {
+                ++errors;
+                return;
+            }
+            lds.assign((size_t)G.TP * G.TQ, kUnwritten);
+        }
+        for (uint32_t tid = 0; tid < (uint32_t)kThreads; ++tid) {
+            const TileLane L = tile_lane(P, G, vlog, tid);
+            if (!L.valid) continue;
+            for (uint32_t j = 0; j < V; ++j) {
+                // out[j] = elements along P (i = 0..V-1) at Q position w0 + j: in[i].elem[j]
+                for (uint32_t i = 0; i < V; ++i) {
+                    const int64_t code = code_of(sid, (int64_t)L.soff + (int64_t)i * P.ssP + j);
+                    if (use_lds) {
+                        const uint64_t slot = tile_lds_slot(G, vlog, L.r0 + j, L.pvl);
+                        const uint64_t at = slot * V + i;
+                        if (at >= lds.size() || lds[at] != kUnwritten)
+                            ++errors;
+                        else
+                            lds[at] = code;
+                    } else {
+                        write((int64_t)G.db + q_chain_offset(P, L.w0 + j) + L.p + i, code);
+                    }
+                }
+            }
+        }
+        if (!use_lds) return;
+        const uint32_t nvec = G.TQ << G.ncvlog;
+        for (uint32_t vi = 0; vi < nvec; ++vi) {
+            const TileStore S = tile_store(P, G, vlog, vi);
+            if (!S.ok) continue;
+            for (uint32_t i = 0; i < V; ++i) {
+                const uint64_t at = (uint64_t)S.slot * V + i;
+                if (at >= lds.size() || lds[at] == kUnwritten) {
+                    ++errors;
+                    continue;
+                }
+                write((int64_t)S.doff + i, lds[at]);
+            }
+        }
+    }
+};
+
+}  // namespace
+
+// Replays the plan of `m` for the given kernel family (-1 = planned) on the
+// host.  *n_errors = out-of-bounds accesses + dst elements with no or several
+// writers + dst elements routed from the wrong source element.
+extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64_t *n_errors) {
+    if (!m || !n_errors) return AMAP_E_INVALID;
+    try {
+        Plan forced;
+        const Plan *plan = nullptr;
+        if (kernel_id < 0) {
+            plan = plan_of(*m);
+        } else {
+            if (!plan_strided(*m, kernel_id, forced)) return AMAP_E_UNSUPPORTED;
+            plan = &forced;
+        }
+        if (!plan || !plan->strided_ok) return AMAP_E_UNSUPPORTED;
+        Replay R(*m);
+        for (size_t li = 0; li < plan->launches.size(); ++li) {
+            const LaunchArgs &A = plan->launches[li];
+            for (uint32_t b = 0; b < plan->grid[li]; ++b) {
+                uint32_t pi = 0;
+                for (uint32_t k = 1; k < A.n_pieces; ++k)
+                    if (b >= A.p[k].first_block) pi = k;
+                const DevPiece &P = A.p[pi];
+                const int sid = (int)(uintptr_t)P.src - 1;
+                const uint32_t local = b - P.first_block;
+                if (local >= P.n_blocks) {
+                    ++R.errors;
+                    continue;
+                }
+                if (P.kind == PK_ROWS)
+                    R.rows(P, sid, local);
+                else
+                    R.tile(P, sid, local, plan->lds_bytes[li]);
+            }
+        }
+        // expected routing straight from the pieces
+        std::vector<int64_t> want(R.got.size(), kUnwritten);
+        for (const KPiece &p : m->kpieces) {
+            const int nd = (int)p.dims.size();
+            std::vector<int64_t> i(nd, 0);
+            int64_t d = p.dbase, s = p.sbase;
+            for (;;) {
+                if (d >= 0 && d < (int64_t)want.size()) want[(size_t)d] = p.fill ? kFill : (((int64_t)p.src << 40) + s);
+                int k = nd - 1;
+                for (; k >= 0; --k) {
+                    d += p.dims[k].ds;
+                    s += p.dims[k].ss;
+                    if (++i[k] < p.dims[k].extent) break;
+                    d -= p.dims[k].ds * p.dims[k].extent;
+                    s -= p.dims[k].ss * p.dims[k].extent;
+                    i[k] = 0;
+                }
+                if (k < 0) break;
+            }
+        }
+        for (size_t d = 0; d < want.size(); ++d)
+            if (want[d] != R.got[d]) ++R.errors;
+        *n_errors = R.errors;
+        return AMAP_OK;
+    } catch (...) {
+        return AMAP_E_NOMEM;
+    }
+}

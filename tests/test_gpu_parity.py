@@ -1,0 +1,162 @@
+"""GPU parity: every kernel family against the CPU oracle, bit for bit, called
+through the C ABI.  Needs an MI355X (-m gpu)."""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2002_12798_amd import binding as B
+from paper_2002_12798_amd import synth
+from tests import chains
+from tests.test_plan_replay import ALIGNED
+
+pytestmark = pytest.mark.gpu
+
+FAMILIES = [None, B.AMAP_K_PROGRAM, B.AMAP_K_ELEMENT, B.AMAP_K_ROWS, B.AMAP_K_TILE, B.AMAP_K_WAVE]
+
+
+@pytest.fixture(scope="module")
+def dev():
+    from paper_2002_12798_amd import device
+    device.require_gpu()
+    return device
+
+
+def _run_families(dev, m, srcs, want, families=FAMILIES, min_ran=2):
+    import torch
+    d_srcs = [dev.to_device(s) for s in srcs]
+    sentinel = 0x5A5A if want.dtype.itemsize == 2 else 0x5A5A5A5A
+    ran = []
+    for fam in families:
+        dst = dev.empty_dst(m, fill=sentinel)
+        try:
+            dev.execute(m, d_srcs, dst, kernel_id=fam)
+        except B.AmapError as e:
+            assert e.status == B.AMAP_E_UNSUPPORTED and fam is not None, (fam, e)
+            continue
+        torch.cuda.synchronize()
+        got = dev.to_host(dst)
+        assert got.shape == want.shape
+        if not np.array_equal(got, want):
+            bad = np.argwhere(got != want)
+            raise AssertionError(f"family {fam}: {len(bad)} mismatches, first at {bad[0]}: "
+                                 f"got {got[tuple(bad[0])]:#x} want {want[tuple(bad[0])]:#x}")
+        ran.append(fam)
+    assert len(ran) >= min_ran, ran
+    return ran
+
+
+@pytest.mark.parametrize("name", synth.WORKLOAD_NAMES)
+def test_workloads_all_families(dev, name):
+    print(f"[gpu] workload {name}", flush=True)
+    w = synth.workload(name)
+    srcs = w.sources()
+    oracle.set_threads(8)
+    try:
+        want = oracle.run_chain(srcs, w.ops)
+    finally:
+        oracle.set_threads(1)
+    m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
+    ran = _run_families(dev, m, srcs, want, min_ran=4)
+    assert None in ran and B.AMAP_K_PROGRAM in ran and B.AMAP_K_ELEMENT in ran
+
+
+def test_secondary_readings(dev):
+    """cfg0 with exclusive slice end / symmetric pad, and one chain per Q/K/V output."""
+    w = synth.workload("cfg0")
+    srcs = w.sources()
+    for ops in (
+        [w.ops[0], w.ops[1], ("slice", 1, 128, 895, 1), w.ops[3]],
+        [w.ops[0], w.ops[1], w.ops[2], ("pad", (0, 0, 2), (0, 0, 2), 0)],
+    ):
+        m = B.amap_compose(w.src_shapes, 4, ops)
+        _run_families(dev, m, srcs, oracle.run_chain(srcs, ops))
+    w2 = synth.workload("cfg2_fwd", b=2)
+    s2 = w2.sources()
+    for t in range(3):
+        ops = synth.split_qkv_ops(t, b=2)
+        m = B.amap_compose(w2.src_shapes, 2, ops)
+        _run_families(dev, m, s2, oracle.run_chain(s2, ops))
+
+
+def test_random_bit_payloads_survive(dev):
+    """NaN payloads, -0, subnormals: data are moved as integers."""
+    for name in ("cfg0", "cfg3"):
+        w = synth.workload(name) if name == "cfg0" else synth.workload(name, n=2)
+        srcs = [synth.random_bits(s, w.elem_size, 77 + i) for i, s in enumerate(w.src_shapes)]
+        m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
+        _run_families(dev, m, srcs, oracle.run_chain(srcs, w.ops))
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_chains(dev, block):
+    for seed in range(block * 40, block * 40 + 40):
+        print(f"[gpu] random chain seed {seed}", flush=True)
+        src_shapes, ops = chains.random_chain(seed)
+        es = 2 if seed % 2 else 4
+        srcs = [synth.random_bits(s, es, 1000 + seed + i) for i, s in enumerate(src_shapes)]
+        m = B.amap_compose(src_shapes, es, ops)
+        _run_families(dev, m, srcs, oracle.run_chain(srcs, ops), min_ran=2)
+
+
+@pytest.mark.parametrize("case", range(len(ALIGNED)))
+def test_aligned_shapes(dev, case):
+    shape, es, ops = ALIGNED[case]
+    print(f"[gpu] aligned case {case} {shape} {ops}", flush=True)
+    srcs = [synth.random_bits(shape, es, 5 + case)]
+    m = B.amap_compose([shape], es, ops)
+    ran = _run_families(dev, m, srcs, oracle.run_chain(srcs, ops), min_ran=3)
+    assert None in ran
+
+
+def test_ragged_tiles_and_tails(dev):
+    """Extents that are not multiples of the tile: masked lanes on both axes."""
+    for shape, es in [((3, 200, 72), 2), ((2, 100, 36), 4), ((1, 24, 1032), 2), ((5, 8, 8), 2)]:
+        ops = [("transpose", (0, 2, 1))]
+        srcs = [synth.random_bits(shape, es, 9)]
+        m = B.amap_compose([shape], es, ops)
+        _run_families(dev, m, srcs, oracle.run_chain(srcs, ops), min_ran=3)
+
+
+def test_empty_and_single_element(dev):
+    import torch
+    m = B.amap_compose([(3, 0, 4)], 4, [("transpose", (2, 0, 1))])
+    dst = dev.execute(m, [torch.empty((3, 0, 4), dtype=torch.int32, device="cuda")])
+    assert dst.numel() == 0
+    x = np.array([[0xBEEF]], dtype=np.uint16)
+    m = B.amap_compose([(1, 1)], 2, [("transpose", (1, 0)), ("pad", (1, 0), (0, 1), 7)])
+    _run_families(dev, m, [x], oracle.run_chain([x], [("transpose", (1, 0)), ("pad", (1, 0), (0, 1), 7)]))
+
+
+def test_error_paths_on_device(dev):
+    import torch
+    m = B.amap_compose([(8, 16)], 4, [("transpose", (1, 0))])
+    x = torch.zeros((8, 16), dtype=torch.int32, device="cuda")
+    with pytest.raises(B.AmapError) as e:
+        B.amap_execute([x.data_ptr()], x.data_ptr(), m, 0)
+    assert e.value.status == B.AMAP_E_ALIAS
+    with pytest.raises(B.AmapError) as e:
+        B.amap_execute([x.data_ptr()], x.data_ptr() + 64, m, 0)   # partial overlap
+    assert e.value.status == B.AMAP_E_ALIAS
+    y = torch.zeros((16, 8), dtype=torch.int32, device="cuda")
+    with pytest.raises(B.AmapError) as e:
+        B.amap_execute([0], y.data_ptr(), m, 0)
+    assert e.value.status == B.AMAP_E_INVALID
+    with pytest.raises(B.AmapError) as e:
+        B.amap_execute([x.data_ptr() + 4], y.data_ptr(), m, 0)    # misaligned source
+    assert e.value.status == B.AMAP_E_INVALID
+    torch.cuda.synchronize()
+
+
+def test_non_default_stream(dev):
+    import torch
+    w = synth.workload("cfg2_rev", b=2)
+    srcs = w.sources()
+    m = B.amap_compose(w.src_shapes, 2, w.ops)
+    want = oracle.run_chain(srcs, w.ops)
+    s = torch.cuda.Stream()
+    d = [dev.to_device(x) for x in srcs]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        dst = dev.execute(m, d)
+    s.synchronize()
+    assert np.array_equal(dev.to_host(dst), want)

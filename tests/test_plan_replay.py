@@ -1,0 +1,67 @@
+"""Host replay of the device launch plans (CPU only): every lane of every
+launch is walked with the index functions the kernels use; all addresses must
+be in bounds and the routing dst <- src must equal the map's pieces."""
+import numpy as np
+import pytest
+
+from paper_2002_12798_amd import binding as B
+from paper_2002_12798_amd import synth
+from tests import chains
+
+FAMILIES = [-1, B.AMAP_K_ELEMENT, B.AMAP_K_ROWS, B.AMAP_K_TILE, B.AMAP_K_WAVE]
+
+
+def _replay_all(m):
+    ran = 0
+    for k in FAMILIES:
+        try:
+            assert B.amap_plan_selfcheck(m, k) == 0, k
+            ran += 1
+        except B.AmapError as e:
+            assert e.status == B.AMAP_E_UNSUPPORTED and k != -1
+    return ran
+
+
+@pytest.mark.parametrize("name", synth.WORKLOAD_NAMES)
+def test_workload_plans(name):
+    w = synth.workload(name)
+    m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
+    assert _replay_all(m) >= 3
+
+
+def test_planned_families():
+    fam = {n: B.amap_describe(B.amap_compose(w.src_shapes, w.elem_size, w.ops)).kernel_id
+           for n, w in ((n, synth.workload(n)) for n in synth.WORKLOAD_NAMES)}
+    assert fam["cfg0"] == B.AMAP_K_WAVE
+    assert fam["cfg1"] == B.AMAP_K_TILE and fam["cfg3"] == B.AMAP_K_TILE
+    assert fam["cfg2_fwd"] == fam["cfg2_rev"] == fam["cfg4"] == B.AMAP_K_ROWS
+
+
+@pytest.mark.parametrize("seed", range(200))
+def test_random_chain_plans(seed):
+    src_shapes, ops = chains.random_chain(seed)
+    m = B.amap_compose(src_shapes, 2 if seed % 2 else 4, ops)
+    if B.amap_describe(m).strided:
+        _replay_all(m)
+
+
+# shapes with aligned inner extents so that the vector / tile paths are planned
+ALIGNED = [
+    ((3, 40, 24), 2, [("transpose", (0, 2, 1))]),
+    ((3, 40, 24), 4, [("transpose", (2, 1, 0))]),
+    ((2, 5, 16, 72), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 2, 1, 3), 9)]),
+    ((4, 36, 8, 8), 4, [("reshape", (4, 36, 64)), ("transpose", (0, 2, 1)), ("slice", 1, 8, 56, 1)]),
+    ((6, 200), 2, [("transpose", (1, 0))]),
+    ((130, 66), 2, [("transpose", (1, 0))]),
+    ((2, 3, 64, 8), 2, [("transpose", (0, 2, 1, 3)), ("reshape", (2, 64, 24))]),
+    ((7, 33, 65), 4, [("transpose", (2, 0, 1))]),
+    ((5, 264, 40), 2, [("slice", 1, 8, 264, 2), ("transpose", (0, 2, 1))]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(ALIGNED)))
+def test_aligned_plans(case):
+    shape, es, ops = ALIGNED[case]
+    m = B.amap_compose([shape], es, ops)
+    assert B.amap_describe(m).strided
+    assert _replay_all(m) >= 2
