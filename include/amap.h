@@ -190,6 +190,10 @@ amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *
 
 const char *amap_status_str(amap_status s);
 
+/* Text of the HIP error behind the last AMAP_E_HIP returned on this thread
+ * (empty string if none). */
+const char *amap_last_error(void);
+
 #ifdef __cplusplus
 }
 #endif

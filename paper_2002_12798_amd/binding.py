@@ -9,6 +9,12 @@ from __future__ import annotations
 import ctypes as C
 import os
 
+# PyTorch allocates the device memory and owns the streams this library is
+# handed, so both must sit on ONE HIP runtime: torch ships its own
+# libamdhip64 (same soname as the system one) and has to be loaded first, so
+# that libamap.so binds to that copy instead of bringing in a second runtime.
+import torch  # noqa: F401  (import order matters)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libamap.so")
 
@@ -22,14 +28,15 @@ EXPORTS = [
     "amap_source", "amap_transpose", "amap_reshape", "amap_slice", "amap_pad", "amap_concat",
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
     "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_kernel",
-    "amap_gemm_fused", "amap_status_str",
+    "amap_gemm_fused", "amap_status_str", "amap_last_error",
 ]
 
 
 class AmapError(RuntimeError):
     def __init__(self, status, what):
         self.status = status
-        super().__init__(f"{what}: {_status_str(status)} (status {status})")
+        detail = f" [{_L.amap_last_error().decode()}]" if status == AMAP_E_HIP else ""
+        super().__init__(f"{what}: {_status_str(status)} (status {status}){detail}")
 
 
 class amap_src_desc(C.Structure):
@@ -77,6 +84,8 @@ _L.amap_execute_kernel.argtypes = [_pp, _vp, _vp, _vp, C.c_int]
 _L.amap_gemm_fused.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp]
 _L.amap_status_str.argtypes = [C.c_int]
 _L.amap_status_str.restype = C.c_char_p
+
+_L.amap_last_error.restype = C.c_char_p
 
 raw = _L  # the raw CDLL, for callers that pre-marshal their arguments
 

@@ -7,6 +7,7 @@
 // intermediate tensor.  Data are moved as opaque integers of 2..16 bytes.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstring>
 
 #include "amap_index.hpp"
@@ -273,6 +274,16 @@ __global__ __launch_bounds__(kThreads) void amap_program_kernel(const Program pr
 
 // ------------------------------------------------------------------ host side
 
+thread_local char g_last_error[256] = "";
+
+// true if the launch just made (or an earlier call on this thread) left an error
+bool launch_failed(const char *what) {
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return false;
+    std::snprintf(g_last_error, sizeof(g_last_error), "%s: %s (%s)", what, hipGetErrorString(e), hipGetErrorName(e));
+    return true;
+}
+
 bool overlaps(const void *a, int64_t an, const void *b, int64_t bn) {
     const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
     return a0 < b0 + (uintptr_t)bn && b0 < a0 + (uintptr_t)an;
@@ -303,7 +314,7 @@ amap_status launch_strided(const amap *m, const Plan &plan, const void *const *s
         else
             hipLaunchKernelGGL(amap_pieces_kernel<4>, dim3(plan.grid[i]), dim3(kThreads), plan.lds_bytes[i], stream, args,
                                (char *)dst);
-        if (hipGetLastError() != hipSuccess) return AMAP_E_HIP;
+        if (launch_failed("amap_pieces_kernel")) return AMAP_E_HIP;
     }
     return AMAP_OK;
 }
@@ -319,7 +330,7 @@ amap_status launch_program(const amap *m, const Plan &plan, const void *const *s
         hipLaunchKernelGGL(amap_program_kernel<2>, dim3(grid), dim3(kThreads), 0, stream, plan.prog, t, (char *)dst, total);
     else
         hipLaunchKernelGGL(amap_program_kernel<4>, dim3(grid), dim3(kThreads), 0, stream, plan.prog, t, (char *)dst, total);
-    return hipGetLastError() == hipSuccess ? AMAP_OK : AMAP_E_HIP;
+    return launch_failed("amap_program_kernel") ? AMAP_E_HIP : AMAP_OK;
 }
 
 }  // namespace
@@ -351,6 +362,8 @@ extern "C" amap_status amap_execute_kernel(const void *const *src, void *dst, co
         return AMAP_E_NOMEM;
     }
 }
+
+extern "C" const char *amap_last_error(void) { return g_last_error; }
 
 extern "C" amap_status amap_execute(const void *const *src, void *dst, const amap_t *map, void *stream) {
     return amap_execute_kernel(src, dst, map, stream, -1);
