@@ -16,7 +16,7 @@ import os
 import torch  # noqa: F401  (import order matters)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libamap.so")
+LIB_PATH = os.environ.get("AMAP_LIB_PATH") or os.path.join(_HERE, "libamap.so")
 
 AMAP_OK, AMAP_E_INVALID, AMAP_E_SHAPE, AMAP_E_UNSUPPORTED, AMAP_E_NOMEM, AMAP_E_ALIAS, AMAP_E_HIP = range(7)
 AMAP_TRANSPOSE, AMAP_RESHAPE, AMAP_SLICE, AMAP_PAD, AMAP_CONCAT = range(5)

@@ -9,7 +9,8 @@ namespace amap_dev {
 
 constexpr int kMaxLoops = 8;             // loops per piece after merging
 constexpr int kMaxPiecesPerLaunch = 12;  // keeps the argument block under 4 KiB
-constexpr int kThreads = 256;            // 4 wavefronts per workgroup
+constexpr int kMaxThreads = 256;         // up to 4 wavefronts per workgroup
+constexpr int kProgramThreads = 256;
 constexpr int kRowsUnroll = 4;           // vectors per lane in the row kernel
 
 // n / d for n < 2^31:  q = (umulhi(n, mul) + n) >> shift
@@ -40,8 +41,14 @@ enum PieceKind : uint32_t {
     PK_WAVE = 2   // P x Q tile per wavefront, register micro-transpose, no LDS
 };
 
+enum PieceFlags : uint32_t {
+    PF_NT_LOAD = 1,   // source accesses of a wavefront cover whole 128-byte lines
+    PF_NT_STORE = 2   // dst accesses of a wavefront cover whole 128-byte lines
+};
+
 struct DevPiece {
     uint32_t kind;
+    uint32_t flags;
     uint32_t first_block;  // first workgroup of this piece within the launch
     uint32_t n_blocks;
     uint32_t n_units;      // ROWS: vectors in the piece
@@ -60,12 +67,15 @@ struct DevPiece {
     uint32_t tilesP, tilesQ;
     FastDiv fdTP, fdTQ;
     uint32_t lqlog;        // log2(lanes along Q); lanes along P = 64 >> lqlog
-    uint32_t nwplog;       // log2(wavefronts along P); wavefronts along Q = 4 >> nwplog
+    uint32_t nwplog;       // log2(wavefronts along P); wavefronts along Q = (1 << nwlog) >> nwplog
+    uint32_t nwlog;        // log2(wavefronts per workgroup), the same for every piece of a launch
 };
 
 struct LaunchArgs {
     uint32_t n_pieces;
-    uint32_t pad_;
+    uint32_t nwlog;      // workgroup size = 64 << nwlog
+    uint32_t nt;         // PieceFlags every piece of the launch agrees on
+    uint32_t xcd_remap;  // 1: remap workgroup indices so each XCD gets a contiguous range
     DevPiece p[kMaxPiecesPerLaunch];
 };
 

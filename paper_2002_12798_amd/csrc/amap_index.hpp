@@ -22,6 +22,17 @@ AMAP_HD uint32_t fdiv(uint32_t n, FastDiv f) {
 #endif
 }
 
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD
+// b % 8), and each XCD has its own L2.  Remap the hardware workgroup index so
+// that every XCD works on one contiguous eighth of the logical tile sequence:
+// tiles that are neighbours in memory (and may share a cache line at their
+// edges) then meet in the same L2.  A bijection on [0, grid).
+AMAP_HD uint32_t xcd_remap(uint32_t b, uint32_t grid) {
+    const uint32_t x = b & 7, idx = b >> 3;
+    const uint32_t q = grid >> 3, r = grid & 7;
+    return x * q + (x < r ? x : r) + idx;
+}
+
 // ---- row kernel: vector r of the piece (dst order) -> element offsets
 AMAP_HD void rows_offsets(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_t &soff) {
     uint32_t d = P.dbase, s = P.sbase;
@@ -66,7 +77,7 @@ AMAP_HD TileGeom tile_geometry(const DevPiece &P, uint32_t vlog, uint32_t t) {
     G.lplog = 6 - P.lqlog;
     G.nwplog = P.nwplog;
     G.TP = ((1u << G.nwplog) << G.lplog) << vlog;
-    G.TQ = ((4u >> G.nwplog) << G.lqlog) << vlog;
+    G.TQ = (((1u << P.nwlog) >> G.nwplog) << G.lqlog) << vlog;
     G.ncvlog = G.nwplog + G.lplog;
     return G;
 }

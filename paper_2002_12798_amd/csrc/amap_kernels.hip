@@ -18,14 +18,17 @@ using namespace amap_detail;
 
 namespace {
 
-// VB-byte global / LDS accesses (VB = 4, 8, 16 go through dword vectors)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// VB-byte LDS accesses (VB = 4, 8, 16 go through dword vectors)
 template <int VB>
 __device__ __forceinline__ void ld(uint32_t (&r)[VB / 4], const void *p) {
     if constexpr (VB == 16) {
-        uint4 v = *reinterpret_cast<const uint4 *>(p);
+        u32x4 v = *reinterpret_cast<const u32x4 *>(p);
         r[0] = v.x, r[1] = v.y, r[2] = v.z, r[3] = v.w;
     } else if constexpr (VB == 8) {
-        uint2 v = *reinterpret_cast<const uint2 *>(p);
+        u32x2 v = *reinterpret_cast<const u32x2 *>(p);
         r[0] = v.x, r[1] = v.y;
     } else {
         r[0] = *reinterpret_cast<const uint32_t *>(p);
@@ -34,18 +37,58 @@ __device__ __forceinline__ void ld(uint32_t (&r)[VB / 4], const void *p) {
 template <int VB>
 __device__ __forceinline__ void st(void *p, const uint32_t (&r)[VB / 4]) {
     if constexpr (VB == 16) {
-        *reinterpret_cast<uint4 *>(p) = make_uint4(r[0], r[1], r[2], r[3]);
+        u32x4 v = {r[0], r[1], r[2], r[3]};
+        *reinterpret_cast<u32x4 *>(p) = v;
     } else if constexpr (VB == 8) {
-        *reinterpret_cast<uint2 *>(p) = make_uint2(r[0], r[1]);
+        u32x2 v = {r[0], r[1]};
+        *reinterpret_cast<u32x2 *>(p) = v;
     } else {
         *reinterpret_cast<uint32_t *>(p) = r[0];
+    }
+}
+
+// VB-byte global accesses.  Every source element is read once and every dst
+// element written once, so where a wavefront covers whole 128-byte lines the
+// accesses are issued non-temporal (streaming; a compile-time choice, since
+// a run-time choice between the two forms is merged back into a plain access): the lines do not linger in the
+// per-XCD L2s, which shortens the write-back at the end of the kernel.
+template <int VB, bool NT>
+__device__ __forceinline__ void gld(uint32_t (&r)[VB / 4], const void *p) {
+    if constexpr (NT) {
+        if constexpr (VB == 16) {
+            u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+            r[0] = v.x, r[1] = v.y, r[2] = v.z, r[3] = v.w;
+        } else if constexpr (VB == 8) {
+            u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
+            r[0] = v.x, r[1] = v.y;
+        } else {
+            r[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+        }
+    } else {
+        ld<VB>(r, p);
+    }
+}
+template <int VB, bool NT>
+__device__ __forceinline__ void gst(void *p, const uint32_t (&r)[VB / 4]) {
+    if constexpr (NT) {
+        if constexpr (VB == 16) {
+            u32x4 v = {r[0], r[1], r[2], r[3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+        } else if constexpr (VB == 8) {
+            u32x2 v = {r[0], r[1]};
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(p));
+        } else {
+            __builtin_nontemporal_store(r[0], reinterpret_cast<uint32_t *>(p));
+        }
+    } else {
+        st<VB>(p, r);
     }
 }
 
 // ------------------------------------------------------------------ rows
 // One lane per vector of VB bytes, vectors enumerated in dst order, so the
 // stores of a wavefront are contiguous; loads are contiguous per source run.
-template <int VB>
+template <int VB, int NT>
 __device__ __forceinline__ void rows_move(const DevPiece &P, char *dst, int es, const uint32_t (&doff)[kRowsUnroll],
                                           const uint32_t (&soff)[kRowsUnroll], const bool (&ok)[kRowsUnroll]) {
     if constexpr (VB == 2) {
@@ -62,7 +105,7 @@ __device__ __forceinline__ void rows_move(const DevPiece &P, char *dst, int es, 
 #pragma unroll
         for (int u = 0; u < kRowsUnroll; ++u) {
             if (P.src && ok[u]) {
-                ld<VB>(v[u], (const char *)P.src + (size_t)soff[u] * es);
+                gld<VB, (NT & PF_NT_LOAD) != 0>(v[u], (const char *)P.src + (size_t)soff[u] * es);
             } else {
 #pragma unroll
                 for (int k = 0; k < VB / 4; ++k) v[u][k] = P.fill;
@@ -70,27 +113,28 @@ __device__ __forceinline__ void rows_move(const DevPiece &P, char *dst, int es, 
         }
 #pragma unroll
         for (int u = 0; u < kRowsUnroll; ++u)
-            if (ok[u]) st<VB>(dst + (size_t)doff[u] * es, v[u]);
+            if (ok[u]) gst<VB, (NT & PF_NT_STORE) != 0>(dst + (size_t)doff[u] * es, v[u]);
     }
 }
 
-template <int ES>
+template <int ES, int NT>
 __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t blk, uint32_t tid) {
     uint32_t doff[kRowsUnroll], soff[kRowsUnroll];
     bool ok[kRowsUnroll];
-    const uint32_t base = blk * (kThreads * kRowsUnroll) + tid;
+    const uint32_t threads = 64u << P.nwlog;
+    const uint32_t base = blk * (threads * kRowsUnroll) + tid;
 #pragma unroll
     for (int u = 0; u < kRowsUnroll; ++u) {
-        const uint32_t r = base + u * kThreads;
+        const uint32_t r = base + u * threads;
         ok[u] = r < P.n_units;
         rows_offsets(P, r, doff[u], soff[u]);
     }
     switch (ES << P.vlog) {
-    case 16: rows_move<16>(P, dst, ES, doff, soff, ok); break;
-    case 8: rows_move<8>(P, dst, ES, doff, soff, ok); break;
-    case 4: rows_move<4>(P, dst, ES, doff, soff, ok); break;
+    case 16: rows_move<16, NT>(P, dst, ES, doff, soff, ok); break;
+    case 8: rows_move<8, NT>(P, dst, ES, doff, soff, ok); break;
+    case 4: rows_move<4, NT>(P, dst, ES, doff, soff, ok); break;
     default:
-        if constexpr (ES == 2) rows_move<2>(P, dst, ES, doff, soff, ok);
+        if constexpr (ES == 2) rows_move<2, 0>(P, dst, ES, doff, soff, ok);
         break;
     }
 }
@@ -116,7 +160,7 @@ __device__ __forceinline__ void micro_transpose(const uint32_t (&in)[V][ES * V /
     }
 }
 
-template <int ES, int V, bool USE_LDS>
+template <int ES, int V, bool USE_LDS, int NT>
 __device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
     constexpr int VB = ES * V;
     constexpr int NW = VB / 4;
@@ -129,7 +173,7 @@ __device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t
         const char *s = (const char *)P.src + (size_t)L.soff * ES;
         const size_t pitch = (size_t)P.ssP * ES;
 #pragma unroll
-        for (int i = 0; i < V; ++i) ld<VB>(in[i], s + i * pitch);
+        for (int i = 0; i < V; ++i) gld<VB, (NT & PF_NT_LOAD) != 0>(in[i], s + i * pitch);
     } else {
 #pragma unroll
         for (int i = 0; i < V; ++i)
@@ -143,7 +187,7 @@ __device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t
 #pragma unroll
             for (int j = 0; j < V; ++j) {
                 const uint32_t doff = G.db + q_chain_offset(P, L.w0 + j) + L.p;
-                st<VB>(dst + (size_t)doff * ES, out[j]);
+                gst<VB, (NT & PF_NT_STORE) != 0>(dst + (size_t)doff * ES, out[j]);
             }
         }
     } else {
@@ -154,51 +198,51 @@ __device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t
         }
         __syncthreads();
         const uint32_t nvec = G.TQ << G.ncvlog;
-        for (uint32_t vi = tid; vi < nvec; vi += kThreads) {
+        for (uint32_t vi = tid; vi < nvec; vi += (64u << P.nwlog)) {
             const TileStore S = tile_store(P, G, VLOG, vi);
             if (S.ok) {
                 uint32_t v[NW];
                 ld<VB>(v, smem + (size_t)S.slot * VB);
-                st<VB>(dst + (size_t)S.doff * ES, v);
+                gst<VB, (NT & PF_NT_STORE) != 0>(dst + (size_t)S.doff * ES, v);
             }
         }
     }
 }
 
-template <int ES, bool USE_LDS>
+template <int ES, bool USE_LDS, int NT>
 __device__ __forceinline__ void tile_dispatch(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
     if constexpr (ES == 2) {
         switch (P.vlog) {
-        case 3: tile_body<2, 8, USE_LDS>(P, dst, t, tid, smem); break;
-        case 2: tile_body<2, 4, USE_LDS>(P, dst, t, tid, smem); break;
-        default: tile_body<2, 2, USE_LDS>(P, dst, t, tid, smem); break;
+        case 3: tile_body<2, 8, USE_LDS, NT>(P, dst, t, tid, smem); break;
+        case 2: tile_body<2, 4, USE_LDS, NT>(P, dst, t, tid, smem); break;
+        default: tile_body<2, 2, USE_LDS, NT>(P, dst, t, tid, smem); break;
         }
     } else {
         switch (P.vlog) {
-        case 2: tile_body<4, 4, USE_LDS>(P, dst, t, tid, smem); break;
-        case 1: tile_body<4, 2, USE_LDS>(P, dst, t, tid, smem); break;
-        default: tile_body<4, 1, USE_LDS>(P, dst, t, tid, smem); break;
+        case 2: tile_body<4, 4, USE_LDS, NT>(P, dst, t, tid, smem); break;
+        case 1: tile_body<4, 2, USE_LDS, NT>(P, dst, t, tid, smem); break;
+        default: tile_body<4, 1, USE_LDS, NT>(P, dst, t, tid, smem); break;
         }
     }
 }
 
 // One launch executes up to kMaxPiecesPerLaunch pieces: each workgroup finds
 // its piece from the block ranges and runs that piece's body.
-template <int ES>
-__global__ __launch_bounds__(kThreads) void amap_pieces_kernel(const LaunchArgs args, char *dst) {
+template <int ES, int NT>
+__global__ __launch_bounds__(kMaxThreads) void amap_pieces_kernel(const LaunchArgs args, char *dst) {
     extern __shared__ uint4 smem_v[];
-    const uint32_t b = blockIdx.x;
+    const uint32_t b = args.xcd_remap ? xcd_remap(blockIdx.x, gridDim.x) : blockIdx.x;
     uint32_t pi = 0;
     for (uint32_t k = 1; k < args.n_pieces; ++k)
         if (b >= args.p[k].first_block) pi = k;
     const DevPiece &P = args.p[pi];
     const uint32_t local = b - P.first_block;
     if (P.kind == PK_ROWS)
-        rows_body<ES>(P, dst, local, threadIdx.x);
+        rows_body<ES, NT>(P, dst, local, threadIdx.x);
     else if (P.kind == PK_TILE)
-        tile_dispatch<ES, true>(P, dst, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
+        tile_dispatch<ES, true, NT>(P, dst, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
     else
-        tile_dispatch<ES, false>(P, dst, local, threadIdx.x, nullptr);
+        tile_dispatch<ES, false, NT>(P, dst, local, threadIdx.x, nullptr);
 }
 
 // ------------------------------------------------------------------ program
@@ -206,9 +250,9 @@ __global__ __launch_bounds__(kThreads) void amap_pieces_kernel(const LaunchArgs 
 // function of every operator of the chain in turn (eq. 4 evaluated lazily).
 // Handles any map, at one dst element per lane.
 template <int ES>
-__global__ __launch_bounds__(kThreads) void amap_program_kernel(const Program prog, const SrcTable srcs, char *dst,
+__global__ __launch_bounds__(kProgramThreads) void amap_program_kernel(const Program prog, const SrcTable srcs, char *dst,
                                                                uint32_t total) {
-    const uint32_t L = blockIdx.x * kThreads + threadIdx.x;
+    const uint32_t L = blockIdx.x * kProgramThreads + threadIdx.x;
     if (L >= total) return;
     int32_t idx[8], tmp[8];
     {
@@ -308,12 +352,21 @@ amap_status launch_strided(const amap *m, const Plan &plan, const void *const *s
             const uintptr_t id = (uintptr_t)args.p[k].src;
             args.p[k].src = id ? src[id - 1] : nullptr;
         }
-        if (m->elem == 2)
-            hipLaunchKernelGGL(amap_pieces_kernel<2>, dim3(plan.grid[i]), dim3(kThreads), plan.lds_bytes[i], stream, args,
-                               (char *)dst);
-        else
-            hipLaunchKernelGGL(amap_pieces_kernel<4>, dim3(plan.grid[i]), dim3(kThreads), plan.lds_bytes[i], stream, args,
-                               (char *)dst);
+        const dim3 grid(plan.grid[i]), block(64u << args.nwlog);
+        const size_t lds = plan.lds_bytes[i];
+        char *d = (char *)dst;
+#define AMAP_LAUNCH(ES, NT) hipLaunchKernelGGL((amap_pieces_kernel<ES, NT>), grid, block, lds, stream, args, d)
+        switch ((m->elem == 2 ? 0 : 4) + (int)(args.nt & 3)) {
+        case 0: AMAP_LAUNCH(2, 0); break;
+        case 1: AMAP_LAUNCH(2, 1); break;
+        case 2: AMAP_LAUNCH(2, 2); break;
+        case 3: AMAP_LAUNCH(2, 3); break;
+        case 4: AMAP_LAUNCH(4, 0); break;
+        case 5: AMAP_LAUNCH(4, 1); break;
+        case 6: AMAP_LAUNCH(4, 2); break;
+        default: AMAP_LAUNCH(4, 3); break;
+        }
+#undef AMAP_LAUNCH
         if (launch_failed("amap_pieces_kernel")) return AMAP_E_HIP;
     }
     return AMAP_OK;
@@ -325,11 +378,11 @@ amap_status launch_program(const amap *m, const Plan &plan, const void *const *s
     std::memset(&t, 0, sizeof(t));
     for (int i = 0; i < plan.n_prog_src; ++i) t.p[i] = src[i];
     const uint32_t total = (uint32_t)volume_of(m->shape);
-    const uint32_t grid = (total + kThreads - 1) / kThreads;
+    const uint32_t grid = (total + kProgramThreads - 1) / kProgramThreads;
     if (m->elem == 2)
-        hipLaunchKernelGGL(amap_program_kernel<2>, dim3(grid), dim3(kThreads), 0, stream, plan.prog, t, (char *)dst, total);
+        hipLaunchKernelGGL(amap_program_kernel<2>, dim3(grid), dim3(kProgramThreads), 0, stream, plan.prog, t, (char *)dst, total);
     else
-        hipLaunchKernelGGL(amap_program_kernel<4>, dim3(grid), dim3(kThreads), 0, stream, plan.prog, t, (char *)dst, total);
+        hipLaunchKernelGGL(amap_program_kernel<4>, dim3(grid), dim3(kProgramThreads), 0, stream, plan.prog, t, (char *)dst, total);
     return launch_failed("amap_program_kernel") ? AMAP_E_HIP : AMAP_OK;
 }
 

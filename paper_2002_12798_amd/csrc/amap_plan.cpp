@@ -49,12 +49,23 @@ static uint32_t common_pow2(uint32_t vmax, std::initializer_list<int64_t> xs, co
     return v;
 }
 
+// true if every number, taken in elements of es bytes, is a multiple of a 128-byte line
+static bool line_aligned(int es, std::initializer_list<int64_t> xs, const std::vector<int64_t> &more) {
+    for (int64_t x : xs)
+        if ((x * es) % 128 != 0) return false;
+    for (int64_t x : more)
+        if ((x * es) % 128 != 0) return false;
+    return true;
+}
+
 static uint32_t replicate_fill(uint32_t bits, int es) {
     if (es == 2) return (bits & 0xFFFFu) | (bits << 16);
     return bits;
 }
 
-static void fill_rows(DevPiece &dp, const KPiece &kp, uint32_t V) {
+static void fill_rows(DevPiece &dp, const KPiece &kp, uint32_t V, uint32_t nwlog) {
+    const int64_t chunk = (int64_t)(64u << nwlog) * kRowsUnroll;
+    dp.nwlog = nwlog;
     dp.kind = PK_ROWS;
     dp.vlog = ilog2(V);
     dp.nloops = (uint32_t)kp.dims.size();
@@ -74,11 +85,12 @@ static void fill_rows(DevPiece &dp, const KPiece &kp, uint32_t V) {
         vol *= l.extent;
     }
     dp.n_units = (uint32_t)vol;
-    dp.n_blocks = (uint32_t)((vol + kThreads * kRowsUnroll - 1) / (kThreads * kRowsUnroll));
+    dp.n_blocks = (uint32_t)((vol + chunk - 1) / chunk);
 }
 
 // returns the family used (amap_kernel_id) or -1 if the forced family cannot run the piece
-static int plan_piece(const amap &m, const KPiece &kp, int family, DevPiece &dp, uint32_t &lds, int &vec_bytes) {
+static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlog, DevPiece &dp, uint32_t &lds,
+                      int &vec_bytes) {
     const int es = m.elem;
     const uint32_t vmax = 16 / es;
     std::memset(&dp, 0, sizeof(dp));
@@ -119,7 +131,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, DevPiece &dp,
     if (kp.fill && (fam == AMAP_K_TILE || fam == AMAP_K_WAVE)) fam = AMAP_K_ROWS;  // constants need no transpose
 
     if (fam == AMAP_K_ELEMENT) {
-        fill_rows(dp, kp, 1);
+        fill_rows(dp, kp, 1, nwlog);
         vec_bytes = es;
         return fam;
     }
@@ -128,8 +140,13 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, DevPiece &dp,
         std::vector<int64_t> all = ds_others;
         all.insert(all.end(), ss_others.begin(), ss_others.end());
         uint32_t V = common_pow2(vmax, {kp.dims[iP].extent, kp.dbase, kp.fill ? 0 : kp.sbase}, all);
-        fill_rows(dp, kp, V);
+        fill_rows(dp, kp, V, nwlog);
         vec_bytes = (int)V * es;
+        // streaming accesses where the piece touches only whole lines
+        if (line_aligned(es, {kp.dims[iP].extent, kp.dbase}, ds_others)) dp.flags |= PF_NT_STORE;
+        // a fill piece loads nothing, so it never vetoes streaming loads for its launch
+        if (kp.fill || line_aligned(es, {kp.dims[iP].extent, kp.sbase}, ss_others)) dp.flags |= PF_NT_LOAD;
+        dp.flags &= (uint32_t)env_int("AMAP_NT", 3);
         return fam;
     }
     if (fam != AMAP_K_TILE && fam != AMAP_K_WAVE) return -1;
@@ -191,18 +208,20 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, DevPiece &dp,
         LP = 64 / LQ;
     }
     const uint64_t remP = (pv + LP - 1) / LP, remQ = (qv + LQ - 1) / LQ;
+    const uint32_t NW = 1u << nwlog;
     uint32_t NWP;
-    if (remP >= 2 && remQ >= 2)
+    if (NW >= 4 && remP >= 2 && remQ >= 2)
         NWP = 2;
     else if (remQ < 2)
-        NWP = std::min<uint32_t>(4, pow2ceil(remP));
+        NWP = std::min<uint32_t>(NW, pow2ceil(remP));
     else
         NWP = 1;
     int nwp_env = env_int("AMAP_TILE_NWPLOG", -1);
-    if (nwp_env >= 0 && nwp_env <= 2) NWP = 1u << nwp_env;
+    if (nwp_env >= 0 && (uint32_t)nwp_env <= nwlog) NWP = 1u << nwp_env;
     dp.lqlog = ilog2(LQ);
     dp.nwplog = ilog2(NWP);
-    const uint32_t TP = NWP * LP * V, TQ = (4 / NWP) * LQ * V;
+    dp.nwlog = nwlog;
+    const uint32_t TP = NWP * LP * V, TQ = (NW / NWP) * LQ * V;
     dp.tilesP = (dp.eP + TP - 1) / TP;
     dp.tilesQ = (uint32_t)((EQ + TQ - 1) / TQ);
     dp.fdTP = make_fastdiv(dp.tilesP);
@@ -211,6 +230,17 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, DevPiece &dp,
     if (nb >= (1ll << 31)) return -1;
     dp.n_blocks = (uint32_t)nb;
     if (dp.kind == PK_TILE) lds = TP * TQ * es;
+    {
+        std::vector<int64_t> batch_ds, batch_ss;
+        for (uint32_t k = dp.nq; k < dp.nloops; ++k) {
+            batch_ds.push_back(dp.loops[k].ds);
+            batch_ss.push_back(dp.loops[k].ss);
+        }
+        for (uint32_t k = 0; k < dp.nq; ++k) batch_ds.push_back(dp.loops[k].ds);
+        if (line_aligned(es, {dp.eP, (int64_t)LP * V, kp.dbase}, batch_ds)) dp.flags |= PF_NT_STORE;
+        if (line_aligned(es, {EQ, (int64_t)LQ * V, kp.sbase, dp.ssP}, batch_ss)) dp.flags |= PF_NT_LOAD;
+        dp.flags &= (uint32_t)env_int("AMAP_NT", 3);
+    }
     vec_bytes = (int)V * es;
     return fam;
 }
@@ -224,10 +254,18 @@ bool plan_strided(const amap &m, int family, Plan &out) {
     for (const auto &s : m.src_shapes)
         if (!s.empty() && volume_of(s) >= (1ll << 31)) out.fits32 = false;
     if (!m.strided || !out.fits32) return false;
+    // workgroup size: single wavefronts balance small problems over the
+    // 256 compute units and keep the tail short; large problems amortise
+    // dispatch with 4 wavefronts per workgroup
+    uint32_t nwlog = volume_of(m.shape) * m.elem < env_int("AMAP_SMALL_BYTES_MB", 256) * (1ll << 20) ? 0 : 2;
+    int nw_env = env_int("AMAP_WAVES_LOG", -1);
+    if (nw_env >= 0 && nw_env <= 2) nwlog = (uint32_t)nw_env;
     int64_t best_vol = -1;
     out.min_vec_bytes = 16;
     LaunchArgs cur;
     std::memset(&cur, 0, sizeof(cur));
+    cur.nwlog = nwlog;
+    cur.xcd_remap = (uint32_t)env_int("AMAP_XCD_REMAP", 0);
     uint32_t blocks = 0, lds_max = 0;
     auto flush = [&]() {
         if (cur.n_pieces == 0) return;
@@ -235,20 +273,32 @@ bool plan_strided(const amap &m, int family, Plan &out) {
         out.grid.push_back(blocks);
         out.lds_bytes.push_back(lds_max);
         std::memset(&cur, 0, sizeof(cur));
+        cur.nwlog = nwlog;
+        cur.xcd_remap = (uint32_t)env_int("AMAP_XCD_REMAP", 0);
         blocks = 0;
         lds_max = 0;
     };
-    for (const KPiece &kp : m.kpieces) {
+    // copy pieces first, fill pieces last (measured: constant stores at the
+    // head of the launch delay the first loads more than they gain)
+    std::vector<const KPiece *> order;
+    const bool fill_first = env_int("AMAP_FILL_FIRST", 0) != 0;
+    for (const KPiece &kp : m.kpieces)
+        if (kp.fill == fill_first) order.push_back(&kp);
+    for (const KPiece &kp : m.kpieces)
+        if (kp.fill != fill_first) order.push_back(&kp);
+    for (const KPiece *kpp : order) {
+        const KPiece &kp = *kpp;
         if ((int)kp.dims.size() > kMaxLoops) return false;
         DevPiece dp;
         uint32_t lds = 0;
         int vb = 0;
-        int fam = plan_piece(m, kp, family, dp, lds, vb);
+        int fam = plan_piece(m, kp, family, nwlog, dp, lds, vb);
         if (fam < 0) return false;
         if (cur.n_pieces == (uint32_t)kMaxPiecesPerLaunch || (uint64_t)blocks + dp.n_blocks >= (1u << 31)) flush();
         dp.first_block = blocks;
         blocks += dp.n_blocks;
         lds_max = std::max(lds_max, lds);
+        cur.nt = cur.n_pieces == 0 ? dp.flags : (cur.nt & dp.flags);
         cur.p[cur.n_pieces++] = dp;
         out.min_vec_bytes = std::min(out.min_vec_bytes, vb);
         if (kp.volume() > best_vol) {

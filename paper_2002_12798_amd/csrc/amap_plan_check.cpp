@@ -47,9 +47,10 @@ struct Replay {
 
     void rows(const DevPiece &P, int sid, uint32_t blk) {
         const uint32_t V = 1u << P.vlog;
-        for (uint32_t tid = 0; tid < (uint32_t)kThreads; ++tid)
+        const uint32_t threads = 64u << P.nwlog;
+        for (uint32_t tid = 0; tid < threads; ++tid)
             for (int u = 0; u < kRowsUnroll; ++u) {
-                const uint32_t r = blk * (kThreads * kRowsUnroll) + tid + u * kThreads;
+                const uint32_t r = blk * (threads * kRowsUnroll) + tid + u * threads;
                 if (r >= P.n_units) continue;
                 uint32_t d, s;
                 rows_offsets(P, r, d, s);
@@ -69,7 +70,7 @@ struct Replay {
             }
             lds.assign((size_t)G.TP * G.TQ, kUnwritten);
         }
-        for (uint32_t tid = 0; tid < (uint32_t)kThreads; ++tid) {
+        for (uint32_t tid = 0; tid < (64u << P.nwlog); ++tid) {
             const TileLane L = tile_lane(P, G, vlog, tid);
             if (!L.valid) continue;
             for (uint32_t j = 0; j < V; ++j) {
@@ -126,11 +127,18 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
         Replay R(*m);
         for (size_t li = 0; li < plan->launches.size(); ++li) {
             const LaunchArgs &A = plan->launches[li];
-            for (uint32_t b = 0; b < plan->grid[li]; ++b) {
+            std::vector<uint8_t> seen(plan->grid[li], 0);
+            for (uint32_t hw = 0; hw < plan->grid[li]; ++hw) {
+                const uint32_t b = A.xcd_remap ? xcd_remap(hw, plan->grid[li]) : hw;
+                if (b >= plan->grid[li] || seen[b]++) {
+                    ++R.errors;
+                    continue;
+                }
                 uint32_t pi = 0;
                 for (uint32_t k = 1; k < A.n_pieces; ++k)
                     if (b >= A.p[k].first_block) pi = k;
                 const DevPiece &P = A.p[pi];
+                if (P.nwlog != A.nwlog || P.nwplog > P.nwlog) ++R.errors;
                 const int sid = (int)(uintptr_t)P.src - 1;
                 const uint32_t local = b - P.first_block;
                 if (local >= P.n_blocks) {
