@@ -63,7 +63,7 @@ def _unfused_maps(B, w):
     return maps
 
 
-def bench_workload(torch, device, B, synth, name, steps, warmup, with_unfused=True, **kw):
+def bench_workload(torch, device, B, synth, name, steps, warmup, with_unfused=True, with_hot=True, **kw):
     w = synth.workload(name, **kw)
     m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
     info = B.amap_describe(m)
@@ -77,7 +77,7 @@ def bench_workload(torch, device, B, synth, name, steps, warmup, with_unfused=Tr
             raise RuntimeError(B.amap_status_str(st))
 
     wall_ms, gpu_ms = _time_launches(torch, fused, sets, steps, warmup)
-    hot_wall, hot_gpu = _time_launches(torch, fused, sets[:1], steps, warmup)
+    hot_gpu = _time_launches(torch, fused, sets[:1], steps, warmup)[1] if with_hot else float("nan")
     res = {
         "workload": w.name, "min_bytes": int(min_bytes), "kernel": B.KERNEL_NAMES[info.kernel_id],
         "pieces": info.n_pieces, "cold_sets": len(sets),
@@ -131,6 +131,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads and the CPU baseline")
+    ap.add_argument("--fused-only", action="store_true",
+                    help="launch nothing but the fused kernel on cold buffers (for a clean rocprofv3 kernel summary)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
@@ -141,7 +143,10 @@ def main():
     from paper_2002_12798_amd import device, synth
     device.require_gpu()
 
-    main_res = bench_workload(torch, device, B, synth, a.workload, a.steps, a.warmup)
+    if a.fused_only:
+        a.no_extras = True
+    main_res = bench_workload(torch, device, B, synth, a.workload, a.steps, a.warmup,
+                              with_unfused=not a.fused_only, with_hot=not a.fused_only)
     extras = {}
     if not a.no_extras:
         for name, kw in [("cfg0", {}), ("cfg2_fwd", {}), ("cfg2_rev", {}), ("cfg3", {}),
@@ -164,7 +169,7 @@ def main():
         "pct_of_peak": round(100.0 * main_res["fused_gbs"] / HBM_PEAK_GBS, 2),
         "unfused_gbs": round(main_res.get("unfused_gbs", 0.0), 2),
         "speedup_vs_unfused": round(main_res.get("speedup_vs_unfused", 0.0), 3),
-        "hot_cache_kernel_gbs": round(main_res["hot_kernel_gbs"], 2),
+        "hot_cache_kernel_gbs": None if a.fused_only else round(main_res["hot_kernel_gbs"], 2),
         "roofline": {"bound": "hbm", "achieved": round(main_res["fused_kernel_gbs"], 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(main_res["fused_kernel_gbs"] / HBM_PEAK_GBS, 4), "traffic": None},
     }
