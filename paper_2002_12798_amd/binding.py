@@ -119,7 +119,7 @@ class Map:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and _L is not None:  # _L is gone when the interpreter shuts down
             _L.amap_free(h)
 
 

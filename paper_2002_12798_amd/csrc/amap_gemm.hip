@@ -1,5 +1,293 @@
-// placeholder until the fused GEMM lands
-#include "amap_map.hpp"
-extern "C" amap_status amap_gemm_fused(const void *, const amap_t *, const void *, int64_t, void *, void *) {
-    return AMAP_E_UNSUPPORTED;
+// bf16 GEMM whose A operand is fetched through a composed access map:
+//     out[m,n] = bf16( sum_k A[m,k] * W[k,n] ),   A[m,k] = A_src[g(m,k)].
+// This is the consumer side of the paper's eq. 4: the load of the GEMM that
+// used to read the materialised chain output t_s reads the chain's source t_l
+// through g' instead, in its operand-load prologue, and t_s never exists.
+//
+// Kernel shape (gfx950): 256 x 256 output tile per workgroup of 4 wavefronts,
+// each wavefront 128 x 128 = 4 x 4 MFMA tiles of v_mfma_f32_32x32x16_bf16
+// (fp32 accumulate), K stepped by 64 through double-buffered LDS, global loads
+// of step s+1 in flight while step s is multiplied.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+
+#include "amap_index.hpp"
+#include "amap_plan.hpp"
+
+using namespace amap_dev;
+using namespace amap_detail;
+
+namespace {
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kGemmThreads = 256;
+constexpr int kTileBytes = BM * BK * 2;  // one operand tile in LDS (A and W tiles have equal size)
+constexpr int kMaxDigits = 4;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// One dst dimension of the A map written as mixed-radix digits of its index:
+// digit j = (x / mult[j]) % ext[j] contributes digit * ss[j] source elements.
+struct Digits {
+    uint32_t n;
+    uint32_t mult[kMaxDigits], ext[kMaxDigits];
+    int32_t ss[kMaxDigits];
+    FastDiv fmult[kMaxDigits], fext[kMaxDigits];
+};
+
+struct GemmArgs {
+    const uint16_t *A_src;
+    const uint16_t *W;
+    uint16_t *C;
+    uint32_t M, N, K;
+    uint32_t sbase;
+    uint32_t tiles_m, tiles_n;
+    Digits dm, dk;
+};
+
+__device__ __forceinline__ uint32_t digits_offset(const Digits &d, uint32_t x) {
+    uint32_t off = 0;
+    for (uint32_t j = 0; j < d.n; ++j) {
+        const uint32_t q = fdiv(x, d.fmult[j]);
+        const uint32_t dig = q - fdiv(q, d.fext[j]) * d.ext[j];
+        off += dig * (uint32_t)d.ss[j];
+    }
+    return off;
+}
+
+// Byte offset inside an operand tile kept as [row][64 k] bf16 (128 B per row,
+// eight 16-byte chunks).  The chunk index is XOR-swizzled with the row so
+// that (a) the 32 rows a wavefront reads for one MFMA operand and (b) the
+// rows 8 apart that the W transposition writes both spread over the banks.
+__device__ __forceinline__ uint32_t tile_offset(uint32_t row, uint32_t chunk) {
+    return row * 128u + ((chunk ^ (row & 7u) ^ ((row >> 3) & 7u)) << 4);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;  // NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Workgroup index -> output tile.  Workgroups go to the 8 XCDs round-robin;
+// each XCD gets a compact 2-D block of tiles so that the A rows and W columns
+// its workgroups share are fetched into that XCD's L2 once.
+__device__ __forceinline__ void tile_of_block(uint32_t b, uint32_t tiles_m, uint32_t tiles_n, uint32_t &tm, uint32_t &tn) {
+    if ((tiles_m & 3u) == 0 && (tiles_n & 1u) == 0) {
+        const uint32_t xcd = b & 7u, j = b >> 3;        // j-th tile of this XCD
+        const uint32_t rm = tiles_m >> 2, rn = tiles_n >> 1;  // region extents: 4 x 2 regions
+        const uint32_t xm = xcd >> 1, xn = xcd & 1u;
+        tm = xm * rm + j % rm;
+        tn = xn * rn + j / rm;
+    } else {
+        tm = b % tiles_m;
+        tn = b / tiles_m;
+    }
+}
+
+__global__ __launch_bounds__(kGemmThreads) void amap_gemm_kernel(const GemmArgs g) {
+    extern __shared__ uint4 smem_v[];
+    char *smem = reinterpret_cast<char *>(smem_v);
+    // LDS: [A buf0 | W buf0 | A buf1 | W buf1], 32 KiB each
+    const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    uint32_t tm, tn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
+    const uint32_t m0 = tm * BM, n0 = tn * BN;
+
+    // ---- A prologue assignment: 8 vectors of 8 k per lane and step:
+    // vector v = tid + 256 i -> row v / 8 of the tile, k chunk v % 8
+    const uint32_t a_chunk = tid & 7u;
+    uint32_t a_soff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a_soff[i] = g.sbase + digits_offset(g.dm, m0 + (tid >> 3) + 32u * i);
+    // ---- W assignment: one 8 k x 8 n block per lane and step
+    const uint32_t w_nb = tid & 31u, w_kb = tid >> 5;
+    const uint16_t *w_ptr = g.W + (size_t)(w_kb * 8u) * g.N + n0 + w_nb * 8u;
+
+    u32x4 ra[8], rw[8];
+    auto load_step = [&](uint32_t k0) {
+        const uint32_t koff = digits_offset(g.dk, k0 + a_chunk * 8u);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            ra[i] = *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[i] + koff));
+        const uint16_t *w = w_ptr + (size_t)k0 * g.N;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) rw[i] = *reinterpret_cast<const u32x4 *>(w + (size_t)i * g.N);
+    };
+    auto store_step = [&](uint32_t buf) {
+        char *sa = smem + buf * (2 * kTileBytes);
+        char *sw = sa + kTileBytes;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<u32x4 *>(sa + tile_offset((tid >> 3) + 32u * i, a_chunk)) = ra[i];
+        // rw[i] = W[k = 8 kb + i][n = 8 nb .. 8 nb + 7]; the MFMA wants, per n, 8
+        // consecutive k: transpose the 8 x 8 block of 16-bit values in registers
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            u32x4 o;
+#pragma unroll
+            for (int i2 = 0; i2 < 4; ++i2) {
+                const uint32_t a = rw[2 * i2][j >> 1], b = rw[2 * i2 + 1][j >> 1];
+                o[i2] = (j & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+            }
+            *reinterpret_cast<u32x4 *>(sw + tile_offset(w_nb * 8u + j, w_kb)) = o;
+        }
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const uint32_t wm = wave >> 1, wn = wave & 1u;
+    const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
+    const uint32_t steps = g.K / BK;
+
+    load_step(0);
+    store_step(0);
+    __syncthreads();
+    for (uint32_t s = 0; s < steps; ++s) {
+        if (s + 1 < steps) load_step((s + 1) * BK);
+        const char *sa = smem + (s & 1u) * (2 * kTileBytes);
+        const char *sw = sa + kTileBytes;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 fa[4], fb[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const u32x4 va = *reinterpret_cast<const u32x4 *>(
+                    sa + tile_offset(wm * 128u + i * 32u + frag_row, 2u * kk + frag_half));
+                const u32x4 vb = *reinterpret_cast<const u32x4 *>(
+                    sw + tile_offset(wn * 128u + i * 32u + frag_row, 2u * kk + frag_half));
+                fa[i] = __builtin_bit_cast(bf16x8, va);
+                fb[i] = __builtin_bit_cast(bf16x8, vb);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (s + 1 < steps) store_step((s + 1) & 1u);
+        __syncthreads();
+    }
+
+    // ---- epilogue: round to bf16, stage the 256 x 256 tile in LDS (512 B per
+    // row), then write whole rows with 16-byte stores.
+    // Accumulator v of a 32 x 32 MFMA tile in lane l: column l % 32,
+    // row 8 (v / 4) + 4 (l / 32) + v % 4.
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t row = wm * 128u + i * 32u + 8u * (v >> 2) + 4u * frag_half + (v & 3);
+                const uint32_t col = wn * 128u + j * 32u + frag_row;
+                *reinterpret_cast<uint16_t *>(smem + row * (BN * 2) + col * 2) = f32_to_bf16_rne(acc[i][j][v]);
+            }
+    __syncthreads();
+#pragma unroll 4
+    for (int i = 0; i < 32; ++i) {
+        const uint32_t v = tid + 256u * i, row = v >> 5, cv = v & 31u;
+        const u32x4 x = *reinterpret_cast<const u32x4 *>(smem + row * (BN * 2) + cv * 16);
+        __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + (size_t)(m0 + row) * g.N + n0 + cv * 8u));
+    }
+}
+
+// Split the loops of one dst dimension of the A map into digits.
+bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d) {
+    std::memset(&d, 0, sizeof(d));
+    std::vector<IterDim> its;
+    for (const IterDim &it : p.it)
+        if (it.dim == dim) its.push_back(it);
+    if (its.size() > (size_t)kMaxDigits) return false;
+    int64_t covered = 1;
+    for (const IterDim &it : its) covered *= it.extent;
+    if (covered != extent || p.lo[dim] != 0) return false;  // the piece must span the whole dimension
+    for (const IterDim &it : its) {
+        const uint32_t j = d.n++;
+        d.mult[j] = (uint32_t)it.mult;
+        d.ext[j] = (uint32_t)it.extent;
+        d.ss[j] = (int32_t)it.sstride;
+        d.fmult[j] = make_fastdiv(d.mult[j]);
+        d.fext[j] = make_fastdiv(d.ext[j]);
+    }
+    return true;
+}
+
+}  // namespace
+
+extern "C" amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N, void *out,
+                                       void *stream) {
+    if (!A_src || !A_map || !W || !out || N <= 0) return AMAP_E_INVALID;
+    if (((uintptr_t)A_src | (uintptr_t)W | (uintptr_t)out) & 15) return AMAP_E_INVALID;
+    if (A_map->shape.size() != 2 || A_map->elem != 2) return AMAP_E_INVALID;
+    const int64_t M = A_map->shape[0], K = A_map->shape[1];
+    if (M % BM || N % BN || K % BK || M == 0 || K == 0) return AMAP_E_UNSUPPORTED;
+    if (!A_map->strided || A_map->pieces.size() != 1 || A_map->pieces[0].fill) return AMAP_E_UNSUPPORTED;
+    const Piece &p = A_map->pieces[0];
+    const int64_t svol = volume_of(A_map->src_shapes[p.src]);
+    if (svol >= (1ll << 31) || M * K >= (1ll << 31) || M * N >= (1ll << 40) || K * N >= (1ll << 31))
+        return AMAP_E_UNSUPPORTED;
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    if (!make_digits(p, 0, M, g.dm) || !make_digits(p, 1, K, g.dk)) return AMAP_E_UNSUPPORTED;
+    // 16-byte vectors along k: the innermost k digit must be contiguous in the
+    // source in runs of a multiple of 8 elements, everything else 8-aligned
+    bool inner_ok = false;
+    for (uint32_t j = 0; j < g.dk.n; ++j) {
+        if (g.dk.mult[j] == 1) {
+            inner_ok = g.dk.ss[j] == 1 && g.dk.ext[j] % 8 == 0;
+        } else if (g.dk.ss[j] % 8 != 0 || g.dk.mult[j] % 8 != 0) {
+            return AMAP_E_UNSUPPORTED;
+        }
+    }
+    for (uint32_t j = 0; j < g.dm.n; ++j)
+        if (g.dm.ss[j] % 8 != 0) return AMAP_E_UNSUPPORTED;
+    if (!inner_ok || p.sbase % 8 != 0) return AMAP_E_UNSUPPORTED;
+    const int64_t cbytes = M * N * 2;
+    auto overlaps = [](const void *a, int64_t an, const void *b, int64_t bn) {
+        const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+        return a0 < b0 + (uintptr_t)bn && b0 < a0 + (uintptr_t)an;
+    };
+    if (overlaps(out, cbytes, A_src, svol * 2) || overlaps(out, cbytes, W, K * N * 2)) return AMAP_E_ALIAS;
+
+    g.A_src = static_cast<const uint16_t *>(A_src);
+    g.W = static_cast<const uint16_t *>(W);
+    g.C = static_cast<uint16_t *>(out);
+    g.M = (uint32_t)M;
+    g.N = (uint32_t)N;
+    g.K = (uint32_t)K;
+    g.sbase = (uint32_t)p.sbase;
+    g.tiles_m = (uint32_t)(M / BM);
+    g.tiles_n = (uint32_t)(N / BN);
+    const size_t lds = 4 * (size_t)kTileBytes;  // 128 KiB: two double-buffered operand tiles, reused by the epilogue
+    static thread_local bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(amap_gemm_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            set_last_error("amap_gemm_kernel: cannot reserve 128 KiB of LDS");
+            return AMAP_E_HIP;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(amap_gemm_kernel, dim3(g.tiles_m * g.tiles_n), dim3(kGemmThreads), lds,
+                       reinterpret_cast<hipStream_t>(stream), g);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_last_error("amap_gemm_kernel", hipGetErrorString(e));
+        return AMAP_E_HIP;
+    }
+    return AMAP_OK;
 }

@@ -319,6 +319,16 @@ __global__ __launch_bounds__(kProgramThreads) void amap_program_kernel(const Pro
 // ------------------------------------------------------------------ host side
 
 thread_local char g_last_error[256] = "";
+}  // namespace
+
+void amap_detail::set_last_error(const char *what, const char *detail) {
+    if (detail)
+        std::snprintf(g_last_error, sizeof(g_last_error), "%s: %s", what, detail);
+    else
+        std::snprintf(g_last_error, sizeof(g_last_error), "%s", what);
+}
+
+namespace {
 
 // true if the launch just made (or an earlier call on this thread) left an error
 bool launch_failed(const char *what) {

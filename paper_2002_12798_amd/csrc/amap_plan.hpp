@@ -32,6 +32,9 @@ bool plan_program(const amap &m, Plan &out);
 // Build and attach the default plan (called when a map is finalised).
 void attach_plan(amap &m);
 
+// Remember the text behind an AMAP_E_HIP for amap_last_error() (per thread).
+void set_last_error(const char *what, const char *detail = nullptr);
+
 inline const Plan *plan_of(const amap &m) { return static_cast<const Plan *>(m.plan.get()); }
 
 }  // namespace amap_detail

@@ -1,0 +1,149 @@
+"""GPU parity of the fused-prologue GEMM against the CPU oracle (which
+materialises A with the operator chain, then multiplies in float64)."""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2002_12798_amd import binding as B
+from paper_2002_12798_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2  # max|err| <= TOL * max|ref|  (bf16 inputs, fp32 accumulation, bf16 output)
+
+
+@pytest.fixture(scope="module")
+def dev():
+    from paper_2002_12798_amd import device
+    device.require_gpu()
+    return device
+
+
+def _gemm(dev, src_bits, shape, ops, w_bits):
+    import torch
+    m = B.amap_compose([shape], 2, ops)
+    out = dev.gemm_fused(dev.to_device(src_bits), m, dev.to_device(w_bits))
+    torch.cuda.synchronize()
+    return dev.to_host(out)
+
+
+def _check(got_bits, a_bits, w_bits, exact=False):
+    oracle.set_threads(8)
+    try:
+        want_bits = oracle.gemm_bf16(a_bits, w_bits)
+    finally:
+        oracle.set_threads(1)
+    if exact:
+        assert np.array_equal(got_bits, want_bits)
+        return
+    got, want = synth.bf16_bits_to_f32(got_bits).astype(np.float64), synth.bf16_bits_to_f32(want_bits).astype(np.float64)
+    err = np.abs(got - want).max()
+    ref = np.abs(want).max()
+    assert err <= TOL * ref, (err, ref)
+    # much tighter in practice: both sides round an almost identical sum to bf16
+    ulp = np.maximum(np.abs(want), 2.0 ** -126) * 2.0 ** -7
+    assert np.mean(np.abs(got - want) <= ulp) > 0.999
+
+
+def test_cfg4_full_size(dev):
+    print("[gpu] gemm cfg4", flush=True)
+    w = synth.workload("cfg4")
+    src = w.sources()[0]
+    wt = w.weight()
+    got = _gemm(dev, src, w.src_shapes[0], w.ops, wt)
+    a = oracle.run_chain([src], w.ops)
+    assert got.shape == (8192, 4096)
+    _check(got, a, wt)
+    # sampled outputs recomputed one by one
+    rng = np.random.default_rng(1)
+    gf = synth.bf16_bits_to_f32(got)
+    for m, n in zip(rng.integers(0, 8192, 64), rng.integers(0, 4096, 64)):
+        ref = oracle.gemm_bf16_point(a, wt, m, n)
+        assert abs(gf[m, n] - ref) <= 2.0 ** -7 * abs(ref) + 1e-6
+
+
+def test_identity_weight_isolates_the_prologue(dev):
+    """W = shifted identity: every output is one A element times 1.0, exact in
+    any summation order, so C must reproduce A bit for bit."""
+    shape, ops = (2, 4, 128, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (256, 256))]
+    src = synth.f32_to_bf16_bits(np.random.default_rng(3).standard_normal(shape).astype(np.float32))
+    wf = np.zeros((256, 512), dtype=np.float32)
+    wf[np.arange(256), (np.arange(256) * 7 + 5) % 512] = 1.0
+    got = _gemm(dev, src, shape, ops, synth.f32_to_bf16_bits(wf))
+    a = oracle.run_chain([src], ops)
+    want = np.zeros((256, 512), dtype=np.uint16)
+    want[:, (np.arange(256) * 7 + 5) % 512] = a
+    # -0.0 * 1 + 0 sums to +0.0 in both; compare values of zeros, bits elsewhere
+    nz = (a & 0x7FFF) != 0
+    assert np.array_equal(got[:, (np.arange(256) * 7 + 5) % 512][nz], a[nz])
+    assert not (got & 0x7FFF)[want == 0].any()
+
+
+def test_small_integers_are_exact(dev):
+    rng = np.random.default_rng(4)
+    shape = (256, 192)
+    a = rng.integers(-3, 4, shape).astype(np.float32)
+    wf = rng.integers(-3, 4, (192, 256)).astype(np.float32)   # |sum| <= 192*9 = 1728 < 2^11: exact in fp32
+    got = _gemm(dev, synth.f32_to_bf16_bits(a), shape, [], synth.f32_to_bf16_bits(wf))
+    _check(got, synth.f32_to_bf16_bits(a), synth.f32_to_bf16_bits(wf), exact=True)
+
+
+CASES = [
+    # source shape, chain producing A[M,K]
+    ((256, 64), []),                                                            # smallest, identity map
+    ((512, 192), []),
+    ((8, 64, 64), [("transpose", (1, 0, 2)), ("reshape", (64, 512)), ("transpose", (1, 0)), ("reshape", (8, 64, 64)),
+                   ("transpose", (0, 2, 1)), ("reshape", (512, 64))]),          # several ops, k = former row index
+    ((4, 2, 128, 32), [("transpose", (0, 2, 1, 3)), ("reshape", (512, 64))]),    # head merge, 32-element runs
+    ((3, 256, 8, 8), [("transpose", (1, 0, 2, 3)), ("reshape", (256, 192))]),    # 64-element runs, 3 k digits
+    ((2, 8, 128, 8), [("transpose", (0, 2, 1, 3)), ("reshape", (256, 64))]),     # 8-element runs (one vector)
+    ((300, 128), [("slice", 0, 22, 278, 1)]),                                    # base offset in the source
+    ((2, 256, 2, 64), [("transpose", (0, 1, 3, 2)), ("transpose", (0, 1, 3, 2)), ("reshape", (512, 128))]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_maps_vs_oracle(dev, case):
+    shape, ops = CASES[case]
+    print(f"[gpu] gemm case {case} {shape} {ops}", flush=True)
+    rng = np.random.default_rng(10 + case)
+    src = synth.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    a = oracle.run_chain([src], ops) if ops else src
+    K = a.shape[1]
+    N = 256 * (1 + case % 3)
+    wt = synth.f32_to_bf16_bits((rng.standard_normal((K, N)) * 0.05).astype(np.float32))
+    got = _gemm(dev, src, shape, ops, wt)
+    _check(got, a, wt)
+
+
+def test_unsupported_and_error_paths(dev):
+    import torch
+    x = torch.zeros(1 << 20, dtype=torch.int16, device="cuda")
+    y = torch.zeros(1 << 20, dtype=torch.int16, device="cuda")
+    w = torch.zeros(1 << 20, dtype=torch.int16, device="cuda")
+
+    def call(m, n=256, a=None, wp=None, o=None):
+        B.amap_gemm_fused((x if a is None else a).data_ptr(), m, (w if wp is None else wp).data_ptr(), n,
+                          (y if o is None else o).data_ptr(), 0)
+
+    for m, n, status in [
+        (B.amap_compose([(200, 64)], 2, []), 256, B.AMAP_E_UNSUPPORTED),                    # M % 256
+        (B.amap_compose([(256, 72)], 2, []), 256, B.AMAP_E_UNSUPPORTED),                    # K % 64
+        (B.amap_compose([(256, 64)], 2, []), 200, B.AMAP_E_UNSUPPORTED),                    # N % 256
+        (B.amap_compose([(256, 64)], 4, []), 256, B.AMAP_E_INVALID),                        # not 2-byte
+        (B.amap_compose([(4, 256, 64)], 2, []), 256, B.AMAP_E_INVALID),                     # not a matrix
+        (B.amap_compose([(256, 60)], 2, [("pad", (0, 0), (0, 4), 0)]), 256, B.AMAP_E_UNSUPPORTED),  # fill piece
+        (B.amap_compose([(64, 256)], 2, [("transpose", (1, 0))]), 256, B.AMAP_E_UNSUPPORTED),       # k not contiguous
+        (B.amap_compose([(256, 128)], 2, [("slice", 1, 0, 128, 2)]), 256, B.AMAP_E_UNSUPPORTED),    # strided k
+    ]:
+        with pytest.raises(B.AmapError) as e:
+            call(m, n)
+        assert e.value.status == status, (e.value.status, status)
+    m = B.amap_compose([(256, 64)], 2, [])
+    with pytest.raises(B.AmapError) as e:
+        call(m, o=x)
+    assert e.value.status == B.AMAP_E_ALIAS
+    with pytest.raises(B.AmapError) as e:
+        B.amap_gemm_fused(x.data_ptr() + 2, m, w.data_ptr(), 256, y.data_ptr(), 0)
+    assert e.value.status == B.AMAP_E_INVALID
+    torch.cuda.synchronize()
