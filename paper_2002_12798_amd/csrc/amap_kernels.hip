@@ -231,7 +231,7 @@ __device__ __forceinline__ void tile_dispatch(const DevPiece &P, char *dst, uint
 template <int ES, int NT>
 __global__ __launch_bounds__(kMaxThreads) void amap_pieces_kernel(const LaunchArgs args, char *dst) {
     extern __shared__ uint4 smem_v[];
-    const uint32_t b = args.xcd_remap ? xcd_remap(blockIdx.x, gridDim.x) : blockIdx.x;
+    const uint32_t b = logical_block(args, blockIdx.x, gridDim.x);
     uint32_t pi = 0;
     for (uint32_t k = 1; k < args.n_pieces; ++k)
         if (b >= args.p[k].first_block) pi = k;

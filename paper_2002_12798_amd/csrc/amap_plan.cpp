@@ -269,6 +269,11 @@ bool plan_strided(const amap &m, int family, Plan &out) {
     uint32_t blocks = 0, lds_max = 0;
     auto flush = [&]() {
         if (cur.n_pieces == 0) return;
+        // fill pieces come last in a launch: count their workgroups and spread them
+        uint32_t nf = 0;
+        for (uint32_t k = cur.n_pieces; k-- > 0 && cur.p[k].src == nullptr;) nf += cur.p[k].n_blocks;
+        cur.n_fill_blocks = nf;
+        cur.fill_stride = (nf > 0 && nf < blocks && env_int("AMAP_FILL_INTERLEAVE", 0)) ? blocks / nf : 0;
         out.launches.push_back(cur);
         out.grid.push_back(blocks);
         out.lds_bytes.push_back(lds_max);

@@ -129,7 +129,7 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
             const LaunchArgs &A = plan->launches[li];
             std::vector<uint8_t> seen(plan->grid[li], 0);
             for (uint32_t hw = 0; hw < plan->grid[li]; ++hw) {
-                const uint32_t b = A.xcd_remap ? xcd_remap(hw, plan->grid[li]) : hw;
+                const uint32_t b = logical_block(A, hw, plan->grid[li]);
                 if (b >= plan->grid[li] || seen[b]++) {
                     ++R.errors;
                     continue;
