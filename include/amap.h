@@ -183,7 +183,7 @@ amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t 
  * materialised.  A_map: dst shape [M,K], 2-byte elements (bf16), one source,
  * no fill pieces.  W: [K,N] row-major bf16.  out: [M,N] row-major bf16,
  * fp32 accumulation, round-to-nearest-even on output.
- * Needs M % 256 == 0, N % 256 == 0, K % 64 == 0 and 8-element aligned
+ * Needs M % 256 == 0, N % 128 == 0, K % 64 == 0 and 8-element aligned
  * contiguous runs along k in the map, else AMAP_E_UNSUPPORTED. */
 amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
                             void *out, void *stream);

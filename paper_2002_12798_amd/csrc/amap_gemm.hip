@@ -4,10 +4,14 @@
 // used to read the materialised chain output t_s reads the chain's source t_l
 // through g' instead, in its operand-load prologue, and t_s never exists.
 //
-// Kernel shape (gfx950): 256 x 256 output tile per workgroup of 4 wavefronts,
-// each wavefront 128 x 128 = 4 x 4 MFMA tiles of v_mfma_f32_32x32x16_bf16
-// (fp32 accumulate), K stepped by 64 through double-buffered LDS, global loads
-// of step s+1 in flight while step s is multiplied.
+// Kernel shape (gfx950): 256 x 128 output tile per workgroup of 4 wavefronts,
+// each wavefront 128 x 64 = 4 x 2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (fp32
+// accumulate in 128 AGPRs), K stepped by 64 through one LDS stage with the
+// next step prefetched into registers.  Registers (<= 256 per lane) and LDS
+// (68 KiB) are sized so that TWO workgroups share a compute unit: while one
+// waits at a barrier, refills LDS or runs its epilogue, the other one keeps the
+// MFMA pipes busy.  K = 1024 means only 16 steps per tile, so hiding the
+// per-tile prologue and epilogue matters as much as the steady-state loop.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -22,14 +26,19 @@ using namespace amap_detail;
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BM = 256, BN = 128, BK = 64;
 constexpr int kGemmThreads = 256;
-constexpr int kTileBytes = BM * BK * 2;  // one operand tile in LDS (A and W tiles have equal size)
+constexpr int kATileBytes = BM * BK * 2;  // 32 KiB
+constexpr int kCPitch = BN * 2 + 16;      // bytes per row of the staged output tile (padded against bank conflicts)
+constexpr int kLdsBytes = BM * kCPitch;   // 69,632 B: covers the operand stage (48 KiB) and the output stage
 constexpr int kMaxDigits = 4;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // One dst dimension of the A map written as mixed-radix digits of its index:
 // digit j = (x / mult[j]) % ext[j] contributes digit * ss[j] source elements.
@@ -68,11 +77,10 @@ __device__ __forceinline__ uint32_t tile_offset(uint32_t row, uint32_t chunk) {
     return row * 128u + ((chunk ^ (row & 7u) ^ ((row >> 3) & 7u)) << 4);
 }
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
-    uint32_t u = __float_as_uint(x);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;  // NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+// two fp32 -> two bf16 (round to nearest even; the hardware conversion of gfx950)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // Workgroup index -> output tile.  Workgroups go to the 8 XCDs round-robin;
@@ -91,10 +99,11 @@ __device__ __forceinline__ void tile_of_block(uint32_t b, uint32_t tiles_m, uint
     }
 }
 
-__global__ __launch_bounds__(kGemmThreads) void amap_gemm_kernel(const GemmArgs g) {
+__global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmArgs g) {
     extern __shared__ uint4 smem_v[];
     char *smem = reinterpret_cast<char *>(smem_v);
-    // LDS: [A buf0 | W buf0 | A buf1 | W buf1], 32 KiB each
+    char *const sa = smem;                // A stage: [256 rows][64 k]
+    char *const sw = smem + kATileBytes;  // W stage: [128 n][64 k], 16 KiB
     const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     uint32_t tm, tn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
@@ -106,11 +115,11 @@ __global__ __launch_bounds__(kGemmThreads) void amap_gemm_kernel(const GemmArgs 
     uint32_t a_soff[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) a_soff[i] = g.sbase + digits_offset(g.dm, m0 + (tid >> 3) + 32u * i);
-    // ---- W assignment: one 8 k x 8 n block per lane and step
-    const uint32_t w_nb = tid & 31u, w_kb = tid >> 5;
-    const uint16_t *w_ptr = g.W + (size_t)(w_kb * 8u) * g.N + n0 + w_nb * 8u;
+    // ---- W assignment: one 4 k x 8 n block per lane and step
+    const uint32_t w_nb = tid & 15u, w_kq = tid >> 4;
+    const uint16_t *w_ptr = g.W + (size_t)(w_kq * 4u) * g.N + n0 + w_nb * 8u;
 
-    u32x4 ra[8], rw[8];
+    u32x4 ra[8], rw[4];
     auto load_step = [&](uint32_t k0) {
         const uint32_t koff = digits_offset(g.dk, k0 + a_chunk * 8u);
 #pragma unroll
@@ -118,33 +127,30 @@ __global__ __launch_bounds__(kGemmThreads) void amap_gemm_kernel(const GemmArgs 
             ra[i] = *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[i] + koff));
         const uint16_t *w = w_ptr + (size_t)k0 * g.N;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) rw[i] = *reinterpret_cast<const u32x4 *>(w + (size_t)i * g.N);
+        for (int i = 0; i < 4; ++i) rw[i] = *reinterpret_cast<const u32x4 *>(w + (size_t)i * g.N);
     };
-    auto store_step = [&](uint32_t buf) {
-        char *sa = smem + buf * (2 * kTileBytes);
-        char *sw = sa + kTileBytes;
+    auto store_step = [&]() {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             *reinterpret_cast<u32x4 *>(sa + tile_offset((tid >> 3) + 32u * i, a_chunk)) = ra[i];
-        // rw[i] = W[k = 8 kb + i][n = 8 nb .. 8 nb + 7]; the MFMA wants, per n, 8
-        // consecutive k: transpose the 8 x 8 block of 16-bit values in registers
+        // rw[i] = W[k = 4 kq + i][n = 8 nb .. 8 nb + 7]; the MFMA wants, per n,
+        // consecutive k: transpose the 4 x 8 block of 16-bit values in registers
+        // and write 8 bytes (4 k) per n
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            u32x4 o;
-#pragma unroll
-            for (int i2 = 0; i2 < 4; ++i2) {
-                const uint32_t a = rw[2 * i2][j >> 1], b = rw[2 * i2 + 1][j >> 1];
-                o[i2] = (j & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
-            }
-            *reinterpret_cast<u32x4 *>(sw + tile_offset(w_nb * 8u + j, w_kb)) = o;
+            const uint32_t a0 = rw[0][j >> 1], a1 = rw[1][j >> 1], a2 = rw[2][j >> 1], a3 = rw[3][j >> 1];
+            u32x2 o;
+            o.x = (j & 1) ? ((a0 >> 16) | (a1 & 0xFFFF0000u)) : ((a0 & 0xFFFFu) | (a1 << 16));
+            o.y = (j & 1) ? ((a2 >> 16) | (a3 & 0xFFFF0000u)) : ((a2 & 0xFFFFu) | (a3 << 16));
+            *reinterpret_cast<u32x2 *>(sw + tile_offset(w_nb * 8u + j, w_kq >> 1) + (w_kq & 1u) * 8u) = o;
         }
     };
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
@@ -153,53 +159,60 @@ __global__ __launch_bounds__(kGemmThreads) void amap_gemm_kernel(const GemmArgs 
     const uint32_t steps = g.K / BK;
 
     load_step(0);
-    store_step(0);
+    store_step();
     __syncthreads();
+    if (steps > 1) load_step(BK);
     for (uint32_t s = 0; s < steps; ++s) {
-        if (s + 1 < steps) load_step((s + 1) * BK);
-        const char *sa = smem + (s & 1u) * (2 * kTileBytes);
-        const char *sw = sa + kTileBytes;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 fa[4], fb[4];
+            bf16x8 fa[4], fb[2];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const u32x4 va = *reinterpret_cast<const u32x4 *>(
-                    sa + tile_offset(wm * 128u + i * 32u + frag_row, 2u * kk + frag_half));
-                const u32x4 vb = *reinterpret_cast<const u32x4 *>(
-                    sw + tile_offset(wn * 128u + i * 32u + frag_row, 2u * kk + frag_half));
-                fa[i] = __builtin_bit_cast(bf16x8, va);
-                fb[i] = __builtin_bit_cast(bf16x8, vb);
-            }
+            for (int i = 0; i < 4; ++i)
+                fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
+                                                       sa + tile_offset(wm * 128u + i * 32u + frag_row, 2u * kk + frag_half)));
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                fb[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
+                                                       sw + tile_offset(wn * 64u + j * 32u + frag_row, 2u * kk + frag_half)));
+            // W fragment as the row operand, A fragment as the column operand:
+            // the 32 x 32 result tile is C^T, so that a lane ends up with four
+            // consecutive n of one output row m (8 contiguous bytes of C)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
-        if (s + 1 < steps) store_step((s + 1) & 1u);
-        __syncthreads();
+        __syncthreads();  // every wavefront is done reading this step's stage
+        if (s + 1 < steps) {
+            store_step();
+            if (s + 2 < steps) load_step((s + 2) * BK);
+            __syncthreads();
+        }
     }
 
-    // ---- epilogue: round to bf16, stage the 256 x 256 tile in LDS (512 B per
-    // row), then write whole rows with 16-byte stores.
-    // Accumulator v of a 32 x 32 MFMA tile in lane l: column l % 32,
-    // row 8 (v / 4) + 4 (l / 32) + v % 4.
+    // ---- epilogue: round to bf16 and stage the 256 x 128 tile in LDS, then
+    // write whole 256-byte rows with 16-byte stores.
+    // Accumulator v of a transposed 32 x 32 tile in lane l: m = l % 32,
+    // n = 8 (v / 4) + 4 (l / 32) + v % 4.
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const uint32_t row = wm * 128u + i * 32u + 8u * (v >> 2) + 4u * frag_half + (v & 3);
-                const uint32_t col = wn * 128u + j * 32u + frag_row;
-                *reinterpret_cast<uint16_t *>(smem + row * (BN * 2) + col * 2) = f32_to_bf16_rne(acc[i][j][v]);
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t row = wm * 128u + i * 32u + frag_row;
+                const uint32_t col = wn * 64u + j * 32u + 8u * q + 4u * frag_half;
+                u32x2 o;
+                o.x = pack_bf16(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+                o.y = pack_bf16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                *reinterpret_cast<u32x2 *>(smem + row * kCPitch + col * 2) = o;
             }
     __syncthreads();
 #pragma unroll 4
-    for (int i = 0; i < 32; ++i) {
-        const uint32_t v = tid + 256u * i, row = v >> 5, cv = v & 31u;
-        const u32x4 x = *reinterpret_cast<const u32x4 *>(smem + row * (BN * 2) + cv * 16);
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t v = tid + 256u * i, row = v >> 4, cv = v & 15u;
+        const u32x4 x = *reinterpret_cast<const u32x4 *>(smem + row * kCPitch + cv * 16);
         __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + (size_t)(m0 + row) * g.N + n0 + cv * 8u));
     }
 }
@@ -271,13 +284,13 @@ extern "C" amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, c
     g.sbase = (uint32_t)p.sbase;
     g.tiles_m = (uint32_t)(M / BM);
     g.tiles_n = (uint32_t)(N / BN);
-    const size_t lds = 4 * (size_t)kTileBytes;  // 128 KiB: two double-buffered operand tiles, reused by the epilogue
+    const size_t lds = kLdsBytes;
     static thread_local bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(amap_gemm_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
             (void)hipGetLastError();
-            set_last_error("amap_gemm_kernel: cannot reserve 128 KiB of LDS");
+            set_last_error("amap_gemm_kernel: cannot reserve its LDS stage");
             return AMAP_E_HIP;
         }
         attr_done = true;

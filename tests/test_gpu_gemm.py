@@ -110,7 +110,7 @@ def test_maps_vs_oracle(dev, case):
     src = synth.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
     a = oracle.run_chain([src], ops) if ops else src
     K = a.shape[1]
-    N = 256 * (1 + case % 3)
+    N = 128 * (1 + case % 4)
     wt = synth.f32_to_bf16_bits((rng.standard_normal((K, N)) * 0.05).astype(np.float32))
     got = _gemm(dev, src, shape, ops, wt)
     _check(got, a, wt)
