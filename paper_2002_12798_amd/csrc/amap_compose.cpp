@@ -110,6 +110,21 @@ bool eval_program(const PNode *n, const int64_t *idx_in, int *src, int64_t *off,
 
 // ---------------------------------------------------------------- finalise
 
+std::vector<KDim> merge_loops(std::vector<KDim> dims) {
+    std::stable_sort(dims.begin(), dims.end(), [](const KDim &a, const KDim &b) { return a.ds > b.ds; });
+    std::vector<KDim> out;
+    for (const KDim &d : dims) {
+        if (!out.empty() && out.back().ds == d.ds * d.extent && out.back().ss == d.ss * d.extent) {
+            out.back().extent *= d.extent;
+            out.back().ds = d.ds;
+            out.back().ss = d.ss;
+        } else {
+            out.push_back(d);
+        }
+    }
+    return out;
+}
+
 void finalise(amap &m) {
     m.kpieces.clear();
     m.plan.reset();
@@ -125,19 +140,7 @@ void finalise(amap &m) {
         k.dbase = 0;
         for (int d = 0; d < rank; ++d) k.dbase += p.lo[d] * R[d];
         for (const IterDim &it : p.it) k.dims.push_back({it.extent, it.mult * R[it.dim], p.fill ? 0 : it.sstride});
-        std::stable_sort(k.dims.begin(), k.dims.end(), [](const KDim &a, const KDim &b) { return a.ds > b.ds; });
-        // merge loops that are contiguous on both sides
-        std::vector<KDim> out;
-        for (const KDim &d : k.dims) {
-            if (!out.empty() && out.back().ds == d.ds * d.extent && out.back().ss == d.ss * d.extent) {
-                out.back().extent *= d.extent;
-                out.back().ds = d.ds;
-                out.back().ss = d.ss;
-            } else {
-                out.push_back(d);
-            }
-        }
-        k.dims = out;
+        k.dims = merge_loops(std::move(k.dims));
         m.kpieces.push_back(std::move(k));
     }
 }

@@ -8,7 +8,7 @@
 namespace amap_dev {
 
 constexpr int kMaxLoops = 8;             // loops per piece after merging
-constexpr int kMaxPiecesPerLaunch = 12;  // keeps the argument block under 4 KiB
+constexpr int kMaxPiecesPerLaunch = 11;  // keeps the argument block under 4 KiB
 constexpr int kMaxThreads = 256;         // up to 4 wavefronts per workgroup
 constexpr int kProgramThreads = 256;
 constexpr int kRowsUnroll = 4;           // vectors per lane in the row kernel
@@ -69,6 +69,13 @@ struct DevPiece {
     uint32_t lqlog;        // log2(lanes along Q); lanes along P = 64 >> lqlog
     uint32_t nwplog;       // log2(wavefronts along P); wavefronts along Q = (1 << nwlog) >> nwplog
     uint32_t nwlog;        // log2(wavefronts per workgroup), the same for every piece of a launch
+    // Pieces that are neighbours along P (concat on the dst-contiguous dimension,
+    // padding of it) are executed as one tile piece so that tiles follow the dst
+    // lines, not the piece boundaries: the head entry carries the geometry and
+    // the total P extent, it and the group_n - 1 entries after it carry their own
+    // source, source strides and first P index.  group_n = 1: a plain piece.
+    uint32_t group_n;
+    uint32_t p_begin;
 };
 
 struct LaunchArgs {

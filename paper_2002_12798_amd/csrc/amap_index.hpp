@@ -68,7 +68,9 @@ AMAP_HD void rows_offsets(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_
 // ---- tile kernels
 struct TileGeom {
     uint32_t tp, tq;      // tile coordinates along P and Q
-    uint32_t db, sb;      // element offsets of the tile's batch point (dst / source)
+    uint32_t db;          // dst element offset of the tile's batch point
+    uint32_t sb;          // source element offset of the batch point in the head entry
+    uint32_t dig[kMaxLoops];  // batch loop indices of the tile; dig[i] belongs to loop nq + i
     uint32_t TP, TQ;      // tile extents in elements
     uint32_t ncvlog;      // log2(vectors along P per tile row)
     uint32_t lqlog, lplog, nwplog;
@@ -84,12 +86,18 @@ AMAP_HD TileGeom tile_geometry(const DevPiece &P, uint32_t vlog, uint32_t t) {
     t = q;
     G.db = P.dbase;
     G.sb = P.sbase;
-    for (uint32_t k = P.nq; k < P.nloops; ++k) {
-        q = fdiv(t, P.loops[k].fd);
-        const uint32_t dig = t - q * P.loops[k].extent;
-        G.db += dig * (uint32_t)P.loops[k].ds;
-        G.sb += dig * (uint32_t)P.loops[k].ss;
-        t = q;
+    // fixed trip count and constant subscripts: dig[] stays in registers
+#pragma unroll
+    for (uint32_t i = 0; i < (uint32_t)kMaxLoops; ++i) {
+        G.dig[i] = 0;
+        const uint32_t k = P.nq + i;
+        if (k < P.nloops) {
+            q = fdiv(t, P.loops[k].fd);
+            G.dig[i] = t - q * P.loops[k].extent;
+            G.db += G.dig[i] * (uint32_t)P.loops[k].ds;
+            G.sb += G.dig[i] * (uint32_t)P.loops[k].ss;
+            t = q;
+        }
     }
     G.lqlog = P.lqlog;
     G.lplog = 6 - P.lqlog;
@@ -103,13 +111,22 @@ AMAP_HD TileGeom tile_geometry(const DevPiece &P, uint32_t vlog, uint32_t t) {
 // what one lane loads: V vectors along Q at P indices p .. p+V-1, Q position w0
 struct TileLane {
     bool valid;
-    uint32_t pvl;   // vector index along P inside the tile
-    uint32_t r0;    // first row (Q position) inside the tile
-    uint32_t p, w0; // the same in piece coordinates (elements)
-    uint32_t soff;  // source element offset of the first vector
+    uint32_t pvl;     // vector index along P inside the tile
+    uint32_t r0;      // first row (Q position) inside the tile
+    uint32_t p, w0;   // the same in piece coordinates (elements)
+    uint32_t sub;     // which entry of the piece group the lane reads from
+    const void *src;  // that entry's source (null: constant), P stride and fill pattern
+    int32_t ssP;
+    uint32_t fill;
+    uint32_t soff;    // source element offset of the first vector
 };
 
-AMAP_HD TileLane tile_lane(const DevPiece &P, const TileGeom &G, uint32_t vlog, uint32_t tid) {
+// P is the head of a piece group ((&P)[0 .. group_n) are its entries).  The
+// entries are walked with a wave-uniform index and each lane keeps the fields
+// of the entry its P index falls into: indexing the kernel arguments with a
+// per-lane index would force the whole argument block into scratch memory.
+// `grouped` = false promises group_n == 1 (everything stays in scalar registers).
+AMAP_HD TileLane tile_lane(const DevPiece &P, const TileGeom &G, uint32_t vlog, uint32_t tid, bool grouped = true) {
     TileLane L;
     const uint32_t wave = tid >> 6, lane = tid & 63;
     const uint32_t wp = wave & ((1u << G.nwplog) - 1), wq = wave >> G.nwplog;
@@ -119,7 +136,27 @@ AMAP_HD TileLane tile_lane(const DevPiece &P, const TileGeom &G, uint32_t vlog, 
     L.p = G.tp * G.TP + (L.pvl << vlog);
     L.w0 = G.tq * G.TQ + L.r0;
     L.valid = L.p < P.eP && L.w0 < P.EQ;
+    L.sub = 0;
+    L.src = P.src;
+    L.ssP = P.ssP;
+    L.fill = P.fill;
     L.soff = G.sb + L.p * (uint32_t)P.ssP + L.w0;
+    if (!grouped) return L;
+    const uint32_t n = P.group_n;
+    for (uint32_t k = 1; k < n; ++k) {
+        const DevPiece &S = (&P)[k];
+        uint32_t sb = S.sbase;
+#pragma unroll
+        for (uint32_t i = 0; i < (uint32_t)kMaxLoops; ++i)
+            if (P.nq + i < P.nloops) sb += G.dig[i] * (uint32_t)S.loops[P.nq + i].ss;
+        if (L.p >= S.p_begin) {  // entries are in increasing p_begin order: the last match wins
+            L.sub = k;
+            L.src = S.src;
+            L.ssP = S.ssP;
+            L.fill = S.fill;
+            L.soff = sb + (L.p - S.p_begin) * (uint32_t)S.ssP + L.w0;
+        }
+    }
     return L;
 }
 

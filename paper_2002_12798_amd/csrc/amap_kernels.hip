@@ -160,25 +160,26 @@ __device__ __forceinline__ void micro_transpose(const uint32_t (&in)[V][ES * V /
     }
 }
 
-template <int ES, int V, bool USE_LDS, int NT>
+template <int ES, int V, bool USE_LDS, int NT, bool GROUPED>
 __device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
     constexpr int VB = ES * V;
     constexpr int NW = VB / 4;
     constexpr uint32_t VLOG = V == 8 ? 3 : V == 4 ? 2 : V == 2 ? 1 : 0;
     const TileGeom G = tile_geometry(P, VLOG, t);
-    const TileLane L = tile_lane(P, G, VLOG, tid);
+    const TileLane L = tile_lane(P, G, VLOG, tid, GROUPED);
 
     uint32_t in[V][NW], out[V][NW];
-    if (L.valid) {
-        const char *s = (const char *)P.src + (size_t)L.soff * ES;
-        const size_t pitch = (size_t)P.ssP * ES;
+    if (L.valid && L.src) {
+        const char *s = (const char *)L.src + (size_t)L.soff * ES;
+        const size_t pitch = (size_t)L.ssP * ES;
 #pragma unroll
         for (int i = 0; i < V; ++i) gld<VB, (NT & PF_NT_LOAD) != 0>(in[i], s + i * pitch);
     } else {
+        // lanes outside the piece, and lanes of a constant (fill) entry
 #pragma unroll
         for (int i = 0; i < V; ++i)
 #pragma unroll
-            for (int k = 0; k < NW; ++k) in[i][k] = 0;
+            for (int k = 0; k < NW; ++k) in[i][k] = L.fill;
     }
     micro_transpose<ES, V>(in, out);
 
@@ -209,40 +210,44 @@ __device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t
     }
 }
 
-template <int ES, bool USE_LDS, int NT>
+template <int ES, bool USE_LDS, int NT, bool GROUPED>
 __device__ __forceinline__ void tile_dispatch(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
     if constexpr (ES == 2) {
         switch (P.vlog) {
-        case 3: tile_body<2, 8, USE_LDS, NT>(P, dst, t, tid, smem); break;
-        case 2: tile_body<2, 4, USE_LDS, NT>(P, dst, t, tid, smem); break;
-        default: tile_body<2, 2, USE_LDS, NT>(P, dst, t, tid, smem); break;
+        case 3: tile_body<2, 8, USE_LDS, NT, GROUPED>(P, dst, t, tid, smem); break;
+        case 2: tile_body<2, 4, USE_LDS, NT, GROUPED>(P, dst, t, tid, smem); break;
+        default: tile_body<2, 2, USE_LDS, NT, GROUPED>(P, dst, t, tid, smem); break;
         }
     } else {
         switch (P.vlog) {
-        case 2: tile_body<4, 4, USE_LDS, NT>(P, dst, t, tid, smem); break;
-        case 1: tile_body<4, 2, USE_LDS, NT>(P, dst, t, tid, smem); break;
-        default: tile_body<4, 1, USE_LDS, NT>(P, dst, t, tid, smem); break;
+        case 2: tile_body<4, 4, USE_LDS, NT, GROUPED>(P, dst, t, tid, smem); break;
+        case 1: tile_body<4, 2, USE_LDS, NT, GROUPED>(P, dst, t, tid, smem); break;
+        default: tile_body<4, 1, USE_LDS, NT, GROUPED>(P, dst, t, tid, smem); break;
         }
     }
 }
 
 // One launch executes up to kMaxPiecesPerLaunch pieces: each workgroup finds
-// its piece from the block ranges and runs that piece's body.
-template <int ES, int NT>
+// its piece from the block ranges and runs that piece's body.  GROUPED is set
+// by the host when some tile piece of the launch is a group of more than one
+// entry; the two forms are separate kernels so that each stays small enough
+// for the compiler to read the argument block in place (scalar loads) instead
+// of copying it to private memory.
+template <int ES, int NT, bool GROUPED>
 __global__ __launch_bounds__(kMaxThreads) void amap_pieces_kernel(const LaunchArgs args, char *dst) {
     extern __shared__ uint4 smem_v[];
     const uint32_t b = logical_block(args, blockIdx.x, gridDim.x);
     uint32_t pi = 0;
     for (uint32_t k = 1; k < args.n_pieces; ++k)
-        if (b >= args.p[k].first_block) pi = k;
+        if (args.p[k].n_blocks && b >= args.p[k].first_block) pi = k;
     const DevPiece &P = args.p[pi];
     const uint32_t local = b - P.first_block;
     if (P.kind == PK_ROWS)
         rows_body<ES, NT>(P, dst, local, threadIdx.x);
     else if (P.kind == PK_TILE)
-        tile_dispatch<ES, true, NT>(P, dst, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
+        tile_dispatch<ES, true, NT, GROUPED>(P, dst, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
     else
-        tile_dispatch<ES, false, NT>(P, dst, local, threadIdx.x, nullptr);
+        tile_dispatch<ES, false, NT, GROUPED>(P, dst, local, threadIdx.x, nullptr);
 }
 
 // ------------------------------------------------------------------ program
@@ -358,14 +363,22 @@ amap_status check_pointers(const amap *m, const void *const *src, const void *ds
 amap_status launch_strided(const amap *m, const Plan &plan, const void *const *src, void *dst, hipStream_t stream) {
     for (size_t i = 0; i < plan.launches.size(); ++i) {
         LaunchArgs args = plan.launches[i];
+        bool grouped = false;
         for (uint32_t k = 0; k < args.n_pieces; ++k) {
             const uintptr_t id = (uintptr_t)args.p[k].src;
             args.p[k].src = id ? src[id - 1] : nullptr;
+            grouped = grouped || (args.p[k].kind != PK_ROWS && args.p[k].group_n > 1);
         }
         const dim3 grid(plan.grid[i]), block(64u << args.nwlog);
         const size_t lds = plan.lds_bytes[i];
         char *d = (char *)dst;
-#define AMAP_LAUNCH(ES, NT) hipLaunchKernelGGL((amap_pieces_kernel<ES, NT>), grid, block, lds, stream, args, d)
+#define AMAP_LAUNCH(ES, NT)                                                                                  \
+    do {                                                                                                     \
+        if (grouped)                                                                                         \
+            hipLaunchKernelGGL((amap_pieces_kernel<ES, NT, true>), grid, block, lds, stream, args, d);       \
+        else                                                                                                 \
+            hipLaunchKernelGGL((amap_pieces_kernel<ES, NT, false>), grid, block, lds, stream, args, d);      \
+    } while (0)
         switch ((m->elem == 2 ? 0 : 4) + (int)(args.nt & 3)) {
         case 0: AMAP_LAUNCH(2, 0); break;
         case 1: AMAP_LAUNCH(2, 1); break;

@@ -106,6 +106,10 @@ inline int64_t volume_of(const std::vector<int64_t> &s) {
 
 std::vector<int64_t> row_major_strides(const std::vector<int64_t> &shape);
 
+// Sort loops by dst stride (descending) and merge neighbours that are
+// contiguous on both sides.
+std::vector<KDim> merge_loops(std::vector<KDim> dims);
+
 // Recompute m.kpieces from m.pieces (no-op if not strided).
 void finalise(amap &m);
 

@@ -12,6 +12,8 @@
 //   read along Q, transposed in registers in V x V blocks, and written along P
 //   (through LDS for long dst runs, straight from registers for small P).
 #include <algorithm>
+#include <climits>
+#include <cstdint>
 #include <cstdlib>
 #include <cstring>
 
@@ -90,7 +92,7 @@ static void fill_rows(DevPiece &dp, const KPiece &kp, uint32_t V, uint32_t nwlog
 
 // returns the family used (amap_kernel_id) or -1 if the forced family cannot run the piece
 static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlog, DevPiece &dp, uint32_t &lds,
-                      int &vec_bytes) {
+                      int &vec_bytes, std::vector<int> *slot_dim = nullptr) {
     const int es = m.elem;
     const uint32_t vmax = 16 / es;
     std::memset(&dp, 0, sizeof(dp));
@@ -98,6 +100,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     dp.fill = replicate_fill(kp.fill_bits, es);
     dp.dbase = (uint32_t)kp.dbase;
     dp.sbase = (uint32_t)kp.sbase;
+    dp.group_n = 1;
     lds = 0;
     const int n = (int)kp.dims.size();
     int iP = -1, iQ = -1;
@@ -175,7 +178,9 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     dp.EQ = (uint32_t)EQ;
     dp.nq = (uint32_t)chain.size();
     uint32_t nl = 0;
+    if (slot_dim) slot_dim->clear();
     for (int k : chain) {
+        if (slot_dim) slot_dim->push_back(k);
         Loop &l = dp.loops[nl++];
         l.extent = (uint32_t)kp.dims[k].extent;
         l.ds = (int32_t)kp.dims[k].ds;
@@ -185,6 +190,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     int64_t batch = 1;
     for (int k = n - 1; k >= 0; --k) {
         if (k == iP || std::find(chain.begin(), chain.end(), k) != chain.end()) continue;
+        if (slot_dim) slot_dim->push_back(k);
         Loop &l = dp.loops[nl++];
         l.extent = (uint32_t)kp.dims[k].extent;
         l.ds = (int32_t)kp.dims[k].ds;
@@ -216,6 +222,10 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         NWP = std::min<uint32_t>(NW, pow2ceil(remP));
     else
         NWP = 1;
+    // dst rows that are not a whole number of 128-byte lines: a tile boundary
+    // inside the row would leave partial lines to two workgroups, so let one
+    // tile span the whole row if the workgroup is large enough
+    if ((dp.eP * (uint64_t)es) % 128 != 0) NWP = std::min<uint32_t>(NW, pow2ceil(remP));
     int nwp_env = env_int("AMAP_TILE_NWPLOG", -1);
     if (nwp_env >= 0 && (uint32_t)nwp_env <= nwlog) NWP = 1u << nwp_env;
     dp.lqlog = ilog2(LQ);
@@ -245,7 +255,184 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     return fam;
 }
 
-bool plan_strided(const amap &m, int family, Plan &out) {
+// ---------------------------------------------------------------- piece groups
+//
+// Pieces that tile the dst-contiguous dimension P between them (concat on the
+// innermost dst dimension, padding of it) are planned as ONE tile piece whose
+// P extent is the sum: tiles then follow the 128-byte lines of dst instead of
+// the piece boundaries, and no workgroup writes a fraction of a line that some
+// other workgroup completes much later (measured: 3.3 vs 5.4 TB/s).
+
+namespace {
+
+struct Member {
+    const KPiece *kp;
+    std::vector<KDim> dims;  // loops in the order of the group's first copy piece
+    int64_t p_extent;
+};
+
+int p_loop(const std::vector<KDim> &dims) {
+    for (size_t k = 0; k < dims.size(); ++k)
+        if (dims[k].ds == 1) return (int)k;
+    return -1;
+}
+
+// Can piece x continue anchor a along P, starting at dst offset `at`?  On
+// success returns x's loops in a's loop order.
+bool continues(const KPiece &a, int iP, const KPiece &x, int64_t at, Member &out) {
+    if (x.dbase != at) return false;
+    out.kp = &x;
+    if (!x.fill) {
+        if (x.dims.size() != a.dims.size() || p_loop(x.dims) != iP) return false;
+        for (size_t k = 0; k < a.dims.size(); ++k) {
+            if ((int)k == iP) continue;
+            if (x.dims[k].extent != a.dims[k].extent || x.dims[k].ds != a.dims[k].ds) return false;
+        }
+        out.dims = x.dims;
+        out.p_extent = x.dims[iP].extent;
+        return true;
+    }
+    // a fill piece merges more loops than a copy piece: rebuild it in a's loop
+    // structure and check that this is the same box
+    int64_t vol_rest = 1;
+    for (size_t k = 0; k < a.dims.size(); ++k)
+        if ((int)k != iP) vol_rest *= a.dims[k].extent;
+    if (x.volume() % vol_rest != 0) return false;
+    const int64_t pe = x.volume() / vol_rest;
+    if (pe < 1) return false;
+    std::vector<KDim> cand = a.dims;
+    for (auto &d : cand) d.ss = 0;
+    cand[iP].extent = pe;
+    std::vector<KDim> nontrivial;
+    for (const auto &d : cand)
+        if (d.extent > 1) nontrivial.push_back(d);
+    const std::vector<KDim> merged = merge_loops(nontrivial);
+    if (merged.size() != x.dims.size()) return false;
+    for (size_t k = 0; k < merged.size(); ++k)
+        if (merged[k].extent != x.dims[k].extent || merged[k].ds != x.dims[k].ds) return false;
+    out.dims = cand;
+    out.p_extent = pe;
+    return true;
+}
+
+// Greedy grouping: every copy piece with a P loop anchors a group and absorbs
+// the pieces that follow / precede it along P.
+std::vector<std::vector<Member>> find_groups(const amap &m, std::vector<char> &grouped) {
+    std::vector<std::vector<Member>> groups;
+    const auto &ks = m.kpieces;
+    grouped.assign(ks.size(), 0);
+    for (size_t a = 0; a < ks.size(); ++a) {
+        if (grouped[a] || ks[a].fill) continue;
+        const int iP = p_loop(ks[a].dims);
+        if (iP < 0) continue;
+        std::vector<Member> g;
+        g.push_back(Member{&ks[a], ks[a].dims, ks[a].dims[iP].extent});
+        std::vector<size_t> idx{a};
+        int64_t lo = ks[a].dbase, hi = ks[a].dbase + ks[a].dims[iP].extent;
+        // the run of P must stay inside one dst row of the anchor's loop structure:
+        // the next larger dst stride bounds it
+        int64_t row = INT64_MAX;
+        for (size_t k = 0; k < ks[a].dims.size(); ++k)
+            if ((int)k != iP) row = std::min(row, ks[a].dims[k].ds);
+        for (bool grown = true; grown;) {
+            grown = false;
+            for (size_t x = 0; x < ks.size(); ++x) {
+                if (grouped[x] || std::find(idx.begin(), idx.end(), x) != idx.end()) continue;
+                Member mem;
+                if (continues(ks[a], iP, ks[x], hi, mem) && hi - lo + mem.p_extent <= row) {
+                    g.push_back(mem);
+                    idx.push_back(x);
+                    hi += mem.p_extent;
+                    grown = true;
+                } else if (ks[x].fill && continues(ks[a], iP, ks[x], ks[x].dbase, mem) &&
+                           ks[x].dbase + mem.p_extent == lo && hi - lo + mem.p_extent <= row) {
+                    g.insert(g.begin(), mem);
+                    idx.push_back(x);
+                    lo -= mem.p_extent;
+                    grown = true;
+                }
+            }
+        }
+        if (g.size() >= 2 && g.size() <= (size_t)kMaxPiecesPerLaunch) {
+            for (size_t x : idx) grouped[x] = 1;
+            groups.push_back(std::move(g));
+        }
+    }
+    return groups;
+}
+
+}  // namespace
+
+// Plan a group as one tile piece: out[0] is the head (geometry, total P
+// extent), out[i] the entry of member i.  False if the members do not share
+// one vector width / source chain, in which case they are planned one by one.
+static bool plan_group(const amap &m, const std::vector<Member> &g, int family, uint32_t nwlog,
+                       std::vector<DevPiece> &out, uint32_t &lds, int &vec_bytes) {
+    const int es = m.elem;
+    const Member *first_copy = nullptr;
+    for (const Member &mem : g)
+        if (!mem.kp->fill && !first_copy) first_copy = &mem;
+    if (!first_copy) return false;
+    const int iP = p_loop(first_copy->dims);
+    int64_t total = 0;
+    for (const Member &mem : g) total += mem.p_extent;
+    // synthetic piece: the first copy member's loops with the whole P run
+    KPiece H = *first_copy->kp;
+    H.dims = first_copy->dims;
+    H.dims[iP].extent = total;
+    H.dbase = g[0].kp->dbase;
+    DevPiece head;
+    std::vector<int> slot_dim;
+    int fam = family < 0 ? AMAP_K_TILE : family;
+    if (fam != AMAP_K_TILE && fam != AMAP_K_WAVE) return false;
+    if (plan_piece(m, H, fam, nwlog, head, lds, vec_bytes, &slot_dim) != fam) return false;
+    const int64_t V = 1ll << head.vlog;
+    bool nt_load = true;
+    int64_t at = 0;
+    out.clear();
+    for (const Member &mem : g) {
+        DevPiece s = head;
+        const KPiece &kp = *mem.kp;
+        if (at % V != 0 || mem.p_extent % V != 0) return false;
+        s.p_begin = (uint32_t)at;
+        s.n_blocks = 0;
+        s.group_n = 1;
+        s.fill = replicate_fill(kp.fill_bits, es);
+        if (kp.fill) {
+            s.src = nullptr;
+            s.sbase = 0;
+            s.ssP = 0;
+            for (uint32_t k = 0; k < s.nloops; ++k) s.loops[k].ss = 0;
+        } else {
+            s.src = reinterpret_cast<const void *>((uintptr_t)(kp.src + 1));
+            s.sbase = (uint32_t)kp.sbase;
+            s.ssP = (int32_t)mem.dims[iP].ss;
+            if (kp.sbase % V != 0 || mem.dims[iP].ss % V != 0) return false;
+            std::vector<int64_t> bss;
+            for (uint32_t k = 0; k < s.nloops; ++k) {
+                const int64_t ss = mem.dims[slot_dim[k]].ss;
+                // the Q chain must be the same contiguous chain in every source
+                if (k < s.nq && ss != head.loops[k].ss) return false;
+                if (k >= s.nq && ss % V != 0) return false;
+                s.loops[k].ss = (int32_t)ss;
+                if (k >= s.nq) bss.push_back(ss);
+            }
+            nt_load = nt_load && line_aligned(es, {kp.sbase, mem.dims[iP].ss}, bss);
+        }
+        out.push_back(s);
+        at += mem.p_extent;
+    }
+    // the head entry is member 0 with the group's geometry
+    out[0].n_blocks = head.n_blocks;
+    out[0].group_n = (uint32_t)g.size();
+    uint32_t flags = head.flags & PF_NT_STORE;
+    if ((head.flags & PF_NT_LOAD) && nt_load) flags |= PF_NT_LOAD;
+    for (DevPiece &s : out) s.flags = flags & (uint32_t)env_int("AMAP_NT", 3);
+    return true;
+}
+
+static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out, bool &split_rows) {
+    split_rows = false;
     out.launches.clear();
     out.grid.clear();
     out.lds_bytes.clear();
@@ -258,14 +445,12 @@ bool plan_strided(const amap &m, int family, Plan &out) {
     // 256 compute units and keep the tail short; large problems amortise
     // dispatch with 4 wavefronts per workgroup
     uint32_t nwlog = volume_of(m.shape) * m.elem < env_int("AMAP_SMALL_BYTES_MB", 256) * (1ll << 20) ? 0 : 2;
-    int nw_env = env_int("AMAP_WAVES_LOG", -1);
-    if (nw_env >= 0 && nw_env <= 2) nwlog = (uint32_t)nw_env;
+    if (nw_forced >= 0) nwlog = (uint32_t)nw_forced;
     int64_t best_vol = -1;
     out.min_vec_bytes = 16;
     LaunchArgs cur;
     std::memset(&cur, 0, sizeof(cur));
     cur.nwlog = nwlog;
-    cur.xcd_remap = (uint32_t)env_int("AMAP_XCD_REMAP", 0);
     uint32_t blocks = 0, lds_max = 0;
     auto flush = [&]() {
         if (cur.n_pieces == 0) return;
@@ -273,24 +458,69 @@ bool plan_strided(const amap &m, int family, Plan &out) {
         uint32_t nf = 0;
         for (uint32_t k = cur.n_pieces; k-- > 0 && cur.p[k].src == nullptr;) nf += cur.p[k].n_blocks;
         cur.n_fill_blocks = nf;
+        // XCD-aware order only where it pays: tile pieces whose source segments
+        // are not line-aligned share lines between neighbouring tiles, and those
+        // neighbours should meet in one L2 (measured +6..11 %); for aligned
+        // streaming pieces the plain round-robin order is faster
+        int xr = env_int("AMAP_XCD_REMAP", -1);
+        if (xr < 0) {
+            xr = 0;
+            for (uint32_t k = 0; k < cur.n_pieces; ++k)
+                if (cur.p[k].kind != PK_ROWS && cur.p[k].src && !(cur.p[k].flags & PF_NT_LOAD)) xr = 1;
+        }
+        cur.xcd_remap = (uint32_t)xr;
         cur.fill_stride = (nf > 0 && nf < blocks && env_int("AMAP_FILL_INTERLEAVE", 0)) ? blocks / nf : 0;
         out.launches.push_back(cur);
         out.grid.push_back(blocks);
         out.lds_bytes.push_back(lds_max);
         std::memset(&cur, 0, sizeof(cur));
         cur.nwlog = nwlog;
-        cur.xcd_remap = (uint32_t)env_int("AMAP_XCD_REMAP", 0);
-        blocks = 0;
+            blocks = 0;
         lds_max = 0;
     };
-    // copy pieces first, fill pieces last (measured: constant stores at the
-    // head of the launch delay the first loads more than they gain)
+    auto emit = [&](const std::vector<DevPiece> &dps, uint32_t lds, int vb, int fam, int64_t vol) {
+        uint32_t nb = 0;
+        for (const DevPiece &d : dps) nb += d.n_blocks;
+        if (cur.n_pieces + dps.size() > (size_t)kMaxPiecesPerLaunch || (uint64_t)blocks + nb >= (1u << 31)) flush();
+        for (DevPiece d : dps) {
+            if (d.kind != PK_ROWS && d.n_blocks && d.tilesP > 1 && (d.eP * (uint64_t)m.elem) % 128 != 0) split_rows = true;
+            d.first_block = blocks;
+            cur.nt = cur.n_pieces == 0 ? d.flags : (cur.nt & d.flags);
+            cur.p[cur.n_pieces++] = d;
+        }
+        blocks += nb;
+        lds_max = std::max(lds_max, lds);
+        out.min_vec_bytes = std::min(out.min_vec_bytes, vb);
+        if (vol > best_vol) {
+            best_vol = vol;
+            out.main_kernel = fam;
+        }
+    };
+    // groups of pieces that are neighbours along the dst-contiguous dimension
+    std::vector<char> grouped(m.kpieces.size(), 0);
+    if ((family < 0 || family == AMAP_K_TILE || family == AMAP_K_WAVE) && env_int("AMAP_GROUPS", 1)) {
+        std::vector<char> in_group;
+        for (const auto &g : find_groups(m, in_group)) {
+            std::vector<DevPiece> dps;
+            uint32_t lds = 0;
+            int vb = 0;
+            bool fits = true;
+            for (const Member &mem : g) fits = fits && (int)mem.dims.size() <= kMaxLoops;
+            if (!fits || !plan_group(m, g, family, nwlog, dps, lds, vb)) continue;
+            int64_t vol = 0;
+            for (const Member &mem : g) vol += mem.kp->volume();
+            emit(dps, lds, vb, dps[0].kind == PK_TILE ? AMAP_K_TILE : AMAP_K_WAVE, vol);
+            for (const Member &mem : g) grouped[mem.kp - m.kpieces.data()] = 1;
+        }
+    }
+    // then the remaining copy pieces, fill pieces last (measured: constant
+    // stores at the head of the launch delay the first loads more than they gain)
     std::vector<const KPiece *> order;
     const bool fill_first = env_int("AMAP_FILL_FIRST", 0) != 0;
-    for (const KPiece &kp : m.kpieces)
-        if (kp.fill == fill_first) order.push_back(&kp);
-    for (const KPiece &kp : m.kpieces)
-        if (kp.fill != fill_first) order.push_back(&kp);
+    for (size_t i = 0; i < m.kpieces.size(); ++i)
+        if (!grouped[i] && m.kpieces[i].fill == fill_first) order.push_back(&m.kpieces[i]);
+    for (size_t i = 0; i < m.kpieces.size(); ++i)
+        if (!grouped[i] && m.kpieces[i].fill != fill_first) order.push_back(&m.kpieces[i]);
     for (const KPiece *kpp : order) {
         const KPiece &kp = *kpp;
         if ((int)kp.dims.size() > kMaxLoops) return false;
@@ -299,20 +529,25 @@ bool plan_strided(const amap &m, int family, Plan &out) {
         int vb = 0;
         int fam = plan_piece(m, kp, family, nwlog, dp, lds, vb);
         if (fam < 0) return false;
-        if (cur.n_pieces == (uint32_t)kMaxPiecesPerLaunch || (uint64_t)blocks + dp.n_blocks >= (1u << 31)) flush();
-        dp.first_block = blocks;
-        blocks += dp.n_blocks;
-        lds_max = std::max(lds_max, lds);
-        cur.nt = cur.n_pieces == 0 ? dp.flags : (cur.nt & dp.flags);
-        cur.p[cur.n_pieces++] = dp;
-        out.min_vec_bytes = std::min(out.min_vec_bytes, vb);
-        if (kp.volume() > best_vol) {
-            best_vol = kp.volume();
-            out.main_kernel = fam;
-        }
+        emit({dp}, lds, vb, fam, kp.volume());
     }
     flush();
     out.strided_ok = true;
+    return true;
+}
+
+bool plan_strided(const amap &m, int family, Plan &out) {
+    const int nw_env = env_int("AMAP_WAVES_LOG", -1);
+    bool split_rows = false;
+    if (nw_env >= 0 && nw_env <= 2) return plan_strided_nw(m, family, nw_env, out, split_rows);
+    if (!plan_strided_nw(m, family, -1, out, split_rows)) return false;
+    // rows that are not whole lines were split between workgroups: larger
+    // workgroups can span them
+    if (split_rows && !out.launches.empty() && out.launches[0].nwlog < 2) {
+        Plan wide = out;
+        bool still = false;
+        if (plan_strided_nw(m, family, 2, wide, still)) out = wide;
+    }
     return true;
 }
 

@@ -58,7 +58,7 @@ struct Replay {
             }
     }
 
-    void tile(const DevPiece &P, int sid, uint32_t t, uint32_t lds_bytes) {
+    void tile(const DevPiece &P, uint32_t t, uint32_t lds_bytes) {
         const uint32_t vlog = P.vlog, V = 1u << vlog;
         const TileGeom G = tile_geometry(P, vlog, t);
         const bool use_lds = P.kind == PK_TILE;
@@ -73,10 +73,11 @@ struct Replay {
         for (uint32_t tid = 0; tid < (64u << P.nwlog); ++tid) {
             const TileLane L = tile_lane(P, G, vlog, tid);
             if (!L.valid) continue;
+            const int sid = (int)(uintptr_t)L.src - 1;
             for (uint32_t j = 0; j < V; ++j) {
                 // out[j] = elements along P (i = 0..V-1) at Q position w0 + j: in[i].elem[j]
                 for (uint32_t i = 0; i < V; ++i) {
-                    const int64_t code = code_of(sid, (int64_t)L.soff + (int64_t)i * P.ssP + j);
+                    const int64_t code = code_of(sid, (int64_t)L.soff + (int64_t)i * L.ssP + j);
                     if (use_lds) {
                         const uint64_t slot = tile_lds_slot(G, vlog, L.r0 + j, L.pvl);
                         const uint64_t at = slot * V + i;
@@ -136,9 +137,9 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
                 }
                 uint32_t pi = 0;
                 for (uint32_t k = 1; k < A.n_pieces; ++k)
-                    if (b >= A.p[k].first_block) pi = k;
+                    if (A.p[k].n_blocks && b >= A.p[k].first_block) pi = k;
                 const DevPiece &P = A.p[pi];
-                if (P.nwlog != A.nwlog || P.nwplog > P.nwlog) ++R.errors;
+                if (P.nwlog != A.nwlog || P.nwplog > P.nwlog || P.group_n < 1 || pi + P.group_n > A.n_pieces) ++R.errors;
                 const int sid = (int)(uintptr_t)P.src - 1;
                 const uint32_t local = b - P.first_block;
                 if (local >= P.n_blocks) {
@@ -148,7 +149,7 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
                 if (P.kind == PK_ROWS)
                     R.rows(P, sid, local);
                 else
-                    R.tile(P, sid, local, plan->lds_bytes[li]);
+                    R.tile(P, local, plan->lds_bytes[li]);
             }
         }
         // expected routing straight from the pieces

@@ -32,7 +32,7 @@ def test_workload_plans(name):
 def test_planned_families():
     fam = {n: B.amap_describe(B.amap_compose(w.src_shapes, w.elem_size, w.ops)).kernel_id
            for n, w in ((n, synth.workload(n)) for n in synth.WORKLOAD_NAMES)}
-    assert fam["cfg0"] == B.AMAP_K_WAVE
+    assert fam["cfg0"] == B.AMAP_K_TILE  # copy piece + channel padding planned as one group
     assert fam["cfg1"] == B.AMAP_K_TILE and fam["cfg3"] == B.AMAP_K_TILE
     assert fam["cfg2_fwd"] == fam["cfg2_rev"] == fam["cfg4"] == B.AMAP_K_ROWS
 
