@@ -162,9 +162,26 @@ def cpu_baseline(synth, name, min_bytes, budget_s=12.0):
         dt = time.perf_counter() - t0
         if dt > budget_s or n >= 20:
             break
-    return {"value": min_bytes * n / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{n} full passes of the {name} chain, operator by operator with materialised intermediates",
-            "ms_per_pass": dt / n * 1e3}
+    res = {"value": min_bytes * n / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+           "sample": f"{n} full passes of the {name} chain, operator by operator with materialised intermediates",
+           "ms_per_pass": dt / n * 1e3}
+    # the same oracle with its outermost loop spread over the host cores this process may use
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
+    if cores > 1:
+        oracle.set_threads(cores)
+        oracle.run_chain(srcs, w.ops)
+        n2, t0 = 0, time.perf_counter()
+        while True:
+            oracle.run_chain(srcs, w.ops)
+            n2 += 1
+            dt2 = time.perf_counter() - t0
+            if dt2 > budget_s / 3 or n2 >= 20:
+                break
+        oracle.set_threads(1)
+        res["all_cores"] = {"value": min_bytes * n2 / dt2 / 1e9, "unit": "GB/s", "cores": cores,
+                            "ms_per_pass": dt2 / n2 * 1e3}
+    return res
 
 
 def measured_traffic(workload):
@@ -187,6 +204,8 @@ def main():
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="cfg1")
+    ap.add_argument("--scale", type=int, default=0,
+                    help="batch extent of the workload instead of the named one (cfg1/cfg3: n, cfg2_*: b)")
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads and the CPU baseline")
     ap.add_argument("--copy-only", action="store_true",
                     help="launch only a plain copy (identity map) of 53,248,000 2-byte elements on cold buffers: "
@@ -225,8 +244,11 @@ def main():
         return
     if a.fused_only:
         a.no_extras = True
+    scale_kw = {}
+    if a.scale:
+        scale_kw = {"b" if a.workload.startswith("cfg2") else "n": a.scale}
     main_res = bench_workload(torch, device, B, synth, a.workload, a.steps, a.warmup,
-                              with_unfused=not a.fused_only, with_hot=not a.fused_only)
+                              with_unfused=not a.fused_only, with_hot=not a.fused_only, **scale_kw)
     extras = {}
     if not a.no_extras:
         for name, kw in [("cfg0", {}), ("cfg2_fwd", {}), ("cfg2_rev", {}), ("cfg3", {}),

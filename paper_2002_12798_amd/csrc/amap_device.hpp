@@ -69,6 +69,8 @@ struct DevPiece {
     uint32_t lqlog;        // log2(lanes along Q); lanes along P = 64 >> lqlog
     uint32_t nwplog;       // log2(wavefronts along P); wavefronts along Q = (1 << nwlog) >> nwplog
     uint32_t nwlog;        // log2(wavefronts per workgroup), the same for every piece of a launch
+    // LDS column swizzle of the staged tile: column ^= (lq & ((1 << swz_bits) - 1)) << swz_shift
+    uint32_t swz_bits, swz_shift;
     // Pieces that are neighbours along P (concat on the dst-contiguous dimension,
     // padding of it) are executed as one tile piece so that tiles follow the dst
     // lines, not the piece boundaries: the head entry carries the geometry and

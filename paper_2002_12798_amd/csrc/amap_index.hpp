@@ -74,6 +74,7 @@ struct TileGeom {
     uint32_t TP, TQ;      // tile extents in elements
     uint32_t ncvlog;      // log2(vectors along P per tile row)
     uint32_t lqlog, lplog, nwplog;
+    uint32_t swz_bits, swz_shift;
 };
 
 AMAP_HD TileGeom tile_geometry(const DevPiece &P, uint32_t vlog, uint32_t t) {
@@ -102,6 +103,8 @@ AMAP_HD TileGeom tile_geometry(const DevPiece &P, uint32_t vlog, uint32_t t) {
     G.lqlog = P.lqlog;
     G.lplog = 6 - P.lqlog;
     G.nwplog = P.nwplog;
+    G.swz_bits = P.swz_bits;
+    G.swz_shift = P.swz_shift;
     G.TP = ((1u << G.nwplog) << G.lplog) << vlog;
     G.TQ = (((1u << P.nwlog) >> G.nwplog) << G.lqlog) << vlog;
     G.ncvlog = G.nwplog + G.lplog;
@@ -172,13 +175,17 @@ AMAP_HD uint32_t q_chain_offset(const DevPiece &P, uint32_t w) {
 }
 
 // LDS slot (in vectors) of the vector at (row, column cv) of the tile.  The tile
-// is kept in dst order; the column is XOR-swizzled with the lane coordinate
-// that produced the row, so the column-wise writes of the load phase spread
-// over the banks while the row-wise reads of the store phase stay contiguous.
+// is kept in dst order (one row per Q position, pitch = the tile's P extent),
+// so the store phase reads whole rows.  In the load phase the lanes of a
+// wavefront that are served together (16 lanes for 16-byte accesses) sit at
+// different rows of ONE column, or of a few neighbouring columns: the column
+// is XOR-ed with the low bits of the lane's Q coordinate, shifted above the
+// column bits that already differ inside such a lane group, so that the group
+// covers all 64 banks.
 AMAP_HD uint32_t tile_lds_slot(const TileGeom &G, uint32_t vlog, uint32_t row, uint32_t cv) {
     const uint32_t lqv = (row >> vlog) & ((1u << G.lqlog) - 1);
     const uint32_t ncv = 1u << G.ncvlog;
-    const uint32_t swz = (G.nwplog ? (lqv << G.lplog) : lqv) & (ncv - 1);
+    const uint32_t swz = ((lqv & ((1u << G.swz_bits) - 1)) << G.swz_shift) & (ncv - 1);
     return (row << G.ncvlog) + (cv ^ swz);
 }
 

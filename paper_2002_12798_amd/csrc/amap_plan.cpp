@@ -231,6 +231,14 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     dp.lqlog = ilog2(LQ);
     dp.nwplog = ilog2(NWP);
     dp.nwlog = nwlog;
+    {
+        // lanes served together by one LDS access of V * es bytes: 256 bytes' worth
+        const uint32_t group_log = 8 - ilog2((uint32_t)(V * es));
+        const uint32_t ncvlog = ilog2(NWP * LP);
+        dp.swz_bits = std::min(group_log, dp.lqlog);
+        const uint32_t span = std::min(group_log, ncvlog);
+        dp.swz_shift = span > dp.swz_bits ? span - dp.swz_bits : 0;
+    }
     const uint32_t TP = NWP * LP * V, TQ = (NW / NWP) * LQ * V;
     dp.tilesP = (dp.eP + TP - 1) / TP;
     dp.tilesQ = (uint32_t)((EQ + TQ - 1) / TQ);
