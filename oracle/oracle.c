@@ -146,8 +146,12 @@ int oracle_reshape(const void *in, void *out, int in_rank, const int64_t *d,
 }
 
 /*
- * slice on one axis: 0 <= begin < end <= d[axis], step >= 1,
- * e[axis] = ceil((end - begin) / step);  out[.., i, ..] = in[.., begin + i*step, ..].
+ * slice on one axis (strided_slice in the paper's operator list, Section 2.1).
+ * step >= 1:  0 <= begin < end <= d[axis],  e[axis] = ceil((end - begin) / step);
+ * step <= -1: -1 <= end < begin <= d[axis] - 1, e[axis] = ceil((begin - end) / -step)
+ * (the axis is walked downwards from begin and stops before end; end = -1
+ * means "down to and including index 0").
+ * out[.., i, ..] = in[.., begin + i*step, ..].
  * Affine: C = diag(1, .., step, .., 1), b = begin on that axis.
  */
 int oracle_slice(const void *in, void *out, int rank, const int64_t *d, int axis,
@@ -155,10 +159,17 @@ int oracle_slice(const void *in, void *out, int rank, const int64_t *d, int axis
 {
     if (check_common(rank, d, es)) return -1;
     if (axis < 0 || axis >= rank) return -2;
-    if (step < 1 || begin < 0 || begin >= end || end > d[axis]) return -3;
     int64_t e[ORACLE_MAX_RANK];
     for (int k = 0; k < rank; ++k) e[k] = d[k];
-    e[axis] = (end - begin + step - 1) / step;
+    if (step >= 1) {
+        if (begin < 0 || begin >= end || end > d[axis]) return -3;
+        e[axis] = (end - begin + step - 1) / step;
+    } else if (step <= -1) {
+        if (end < -1 || end >= begin || begin > d[axis] - 1) return -3;
+        e[axis] = (begin - end + (-step) - 1) / (-step);
+    } else {
+        return -3;
+    }
     if (volume(rank, e) == 0) return 0;
 #pragma omp parallel for num_threads(g_threads) schedule(static)
     for (int64_t i0 = 0; i0 < e[0]; ++i0) {
@@ -167,6 +178,63 @@ int oracle_slice(const void *in, void *out, int rank, const int64_t *d, int axis
         do {
             for (int k = 0; k < rank; ++k) j[k] = i[k];
             j[axis] = begin + i[axis] * step;
+            move_elem(in, linearise(rank, d, j), out, linearise(rank, e, i), es);
+        } while (next_inner(rank, e, i));
+    }
+    return 0;
+}
+
+/*
+ * repeat (Section 2.1 operator list): every index of one axis appears r times
+ * in a row.  e[axis] = d[axis] * r;  out[.., i, ..] = in[.., i div r, ..].
+ * A non-injective load: the map has a floor-division by the constant r.
+ */
+int oracle_repeat(const void *in, void *out, int rank, const int64_t *d, int axis,
+                  int64_t r, int es)
+{
+    if (check_common(rank, d, es)) return -1;
+    if (axis < 0 || axis >= rank) return -2;
+    if (r < 1) return -3;
+    int64_t e[ORACLE_MAX_RANK];
+    for (int k = 0; k < rank; ++k) e[k] = d[k];
+    e[axis] = d[axis] * r;
+    if (volume(rank, e) == 0) return 0;
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t i0 = 0; i0 < e[0]; ++i0) {
+        int64_t i[ORACLE_MAX_RANK] = {0}, j[ORACLE_MAX_RANK];
+        i[0] = i0;
+        do {
+            for (int k = 0; k < rank; ++k) j[k] = i[k];
+            j[axis] = i[axis] / r;
+            move_elem(in, linearise(rank, d, j), out, linearise(rank, e, i), es);
+        } while (next_inner(rank, e, i));
+    }
+    return 0;
+}
+
+/*
+ * tile (Section 2.1 operator list): the whole axis is laid out t times one
+ * after the other.  e[axis] = d[axis] * t;  out[.., i, ..] = in[.., i mod d[axis], ..].
+ * A non-injective load: the map has a remainder by the constant d[axis].
+ * Broadcasting an extent-1 axis to t is the case d[axis] = 1.
+ */
+int oracle_tile(const void *in, void *out, int rank, const int64_t *d, int axis,
+                int64_t t, int es)
+{
+    if (check_common(rank, d, es)) return -1;
+    if (axis < 0 || axis >= rank) return -2;
+    if (t < 1) return -3;
+    int64_t e[ORACLE_MAX_RANK];
+    for (int k = 0; k < rank; ++k) e[k] = d[k];
+    e[axis] = d[axis] * t;
+    if (volume(rank, e) == 0) return 0;
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t i0 = 0; i0 < e[0]; ++i0) {
+        int64_t i[ORACLE_MAX_RANK] = {0}, j[ORACLE_MAX_RANK];
+        i[0] = i0;
+        do {
+            for (int k = 0; k < rank; ++k) j[k] = i[k];
+            j[axis] = i[axis] % d[axis];
             move_elem(in, linearise(rank, d, j), out, linearise(rank, e, i), es);
         } while (next_inner(rank, e, i));
     }

@@ -46,6 +46,8 @@ def lib():
         L.oracle_reshape.argtypes = [C.c_void_p, C.c_void_p, C.c_int, i64p, C.c_int, i64p, C.c_int]
         L.oracle_slice.argtypes = [C.c_void_p, C.c_void_p, C.c_int, i64p, C.c_int, C.c_int64,
                                    C.c_int64, C.c_int64, C.c_int]
+        L.oracle_repeat.argtypes = [C.c_void_p, C.c_void_p, C.c_int, i64p, C.c_int, C.c_int64, C.c_int]
+        L.oracle_tile.argtypes = [C.c_void_p, C.c_void_p, C.c_int, i64p, C.c_int, C.c_int64, C.c_int]
         L.oracle_pad.argtypes = [C.c_void_p, C.c_void_p, C.c_int, i64p, i64p, i64p, C.c_uint32,
                                  C.c_int]
         L.oracle_concat.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_void_p, C.c_int, i64p,
@@ -118,14 +120,47 @@ def reshape(x, shape):
 
 
 def slice_(x, axis, begin, end, step=1):
+    """step >= 1: indices begin, begin+step, .. < end.  step <= -1: begin, begin+step, .. > end
+    (end = -1 reaches index 0)."""
     x = _prep(x)
-    if not (0 <= axis < x.ndim and step >= 1 and 0 <= begin < end <= x.shape[axis]):
+    if not 0 <= axis < x.ndim:
+        raise OracleError("slice: bad axis")
+    n = x.shape[axis]
+    if step >= 1 and 0 <= begin < end <= n:
+        count = -((begin - end) // step)
+    elif step <= -1 and -1 <= end < begin <= n - 1:
+        count = -((end - begin) // -step)
+    else:
         raise OracleError("slice: out of range")
     shp = list(x.shape)
-    shp[axis] = -((begin - end) // step)
+    shp[axis] = count
     out = np.empty(shp, dtype=x.dtype)
     _check(lib().oracle_slice(x.ctypes.data, out.ctypes.data, x.ndim, _i64(x.shape), axis,
                               begin, end, step, x.dtype.itemsize), "slice")
+    return out
+
+
+def repeat(x, axis, r):
+    x = _prep(x)
+    if not (0 <= axis < x.ndim and r >= 1):
+        raise OracleError("repeat: bad axis or count")
+    shp = list(x.shape)
+    shp[axis] *= int(r)
+    out = np.empty(shp, dtype=x.dtype)
+    _check(lib().oracle_repeat(x.ctypes.data, out.ctypes.data, x.ndim, _i64(x.shape), axis,
+                               int(r), x.dtype.itemsize), "repeat")
+    return out
+
+
+def tile(x, axis, t):
+    x = _prep(x)
+    if not (0 <= axis < x.ndim and t >= 1):
+        raise OracleError("tile: bad axis or count")
+    shp = list(x.shape)
+    shp[axis] *= int(t)
+    out = np.empty(shp, dtype=x.dtype)
+    _check(lib().oracle_tile(x.ctypes.data, out.ctypes.data, x.ndim, _i64(x.shape), axis,
+                             int(t), x.dtype.itemsize), "tile")
     return out
 
 
@@ -176,6 +211,10 @@ def apply_op(xs, op):
         return [slice_(x, op[1], op[2], op[3], op[4] if len(op) > 4 else 1)]
     if kind == "pad":
         return [pad(x, op[1], op[2], op[3] if len(op) > 3 else 0)]
+    if kind == "repeat":
+        return [repeat(x, op[1], op[2])]
+    if kind == "tile":
+        return [tile(x, op[1], op[2])]
     raise OracleError(f"unknown operator {kind}")
 
 

@@ -50,12 +50,18 @@ def test_handworked_fixture(golden_dir, dtype):
                              [int(v) for v in kv["hi"].split(",")], int(kv["fill"]))
         elif op == "concat":
             got = oracle.concat(xs, int(args.split("=")[1]))
+        elif op == "repeat":
+            kv = dict(a.split("=") for a in args.split(","))
+            got = oracle.repeat(xs[0], int(kv["axis"]), int(kv["r"]))
+        elif op == "tile":
+            kv = dict(a.split("=") for a in args.split(","))
+            got = oracle.tile(xs[0], int(kv["axis"]), int(kv["t"]))
         else:
             raise AssertionError(op)
         assert got.shape == want.shape, (op, args)
         assert np.array_equal(got, want), (op, args)
         n += 1
-    assert n == 7
+    assert n == 13
 
 
 SHAPES = [(1,), (5,), (3, 4), (1, 7), (2, 3, 4), (4, 1, 3), (2, 3, 2, 5), (3, 2, 1, 2, 4),
@@ -119,6 +125,54 @@ def test_slice_vs_numpy(es):
             sl = [slice(None)] * len(shape)
             sl[ax] = slice(b, e, st)
             assert np.array_equal(oracle.slice_(x, ax, b, e, st), x[tuple(sl)]), (shape, ax, b, e, st)
+
+
+@pytest.mark.parametrize("es", [2, 4])
+def test_negative_step_slice_vs_numpy(es):
+    rng = np.random.default_rng(31)
+    for shape in SHAPES:
+        x = synth.iota(shape, es)
+        for _ in range(8):
+            ax = int(rng.integers(len(shape)))
+            n = shape[ax]
+            b = int(rng.integers(0, n))
+            e = int(rng.integers(-1, b))
+            st = -int(rng.integers(1, 4))
+            sl = [slice(None)] * len(shape)
+            sl[ax] = slice(b, e if e >= 0 else None, st)   # numpy spells "past index 0" as None
+            assert np.array_equal(oracle.slice_(x, ax, b, e, st), x[tuple(sl)]), (shape, ax, b, e, st)
+        # reversing an axis twice is the identity
+        n = shape[0]
+        assert np.array_equal(oracle.slice_(oracle.slice_(x, 0, n - 1, -1, -1), 0, n - 1, -1, -1), x)
+
+
+@pytest.mark.parametrize("es", [2, 4])
+def test_repeat_and_tile_vs_numpy_and_inverses(es):
+    rng = np.random.default_rng(32)
+    for shape in SHAPES:
+        x = synth.iota(shape, es)
+        for _ in range(4):
+            ax = int(rng.integers(len(shape)))
+            k = int(rng.integers(1, 5))
+            r = oracle.repeat(x, ax, k)
+            assert np.array_equal(r, np.repeat(x, k, axis=ax)), (shape, ax, k)
+            reps = [1] * len(shape)
+            reps[ax] = k
+            t = oracle.tile(x, ax, k)
+            assert np.array_equal(t, np.tile(x, reps)), (shape, ax, k)
+            n = shape[ax]
+            # every k-th element of a repeat, from any phase, is the input again
+            for ph in range(k):
+                assert np.array_equal(oracle.slice_(r, ax, ph, n * k, k), x)
+            # every block of a tile is the input again
+            for blk in range(k):
+                assert np.array_equal(oracle.slice_(t, ax, blk * n, (blk + 1) * n, 1), x)
+        # repeat = reshape(.., n, 1) -> tile the new axis -> reshape(.., n*k), a second definition
+        ax, k = len(shape) - 1, 3
+        y = oracle.reshape(x, list(shape) + [1])
+        y = oracle.tile(y, len(shape), k)
+        y = oracle.reshape(y, list(shape[:-1]) + [shape[-1] * k])
+        assert np.array_equal(y, oracle.repeat(x, ax, k))
 
 
 @pytest.mark.parametrize("es", [2, 4])
@@ -202,6 +256,15 @@ def test_brute_force_index_enumeration_tiny():
     s = oracle.slice_(x, 2, 1, 4, 2)
     for a, b, c in itertools.product(range(2), range(3), range(2)):
         assert s[a, b, c] == x[a, b, 1 + 2 * c]
+    s = oracle.slice_(x, 2, 3, 0, -2)
+    for a, b, c in itertools.product(range(2), range(3), range(2)):
+        assert s[a, b, c] == x[a, b, 3 - 2 * c]
+    rp = oracle.repeat(x, 1, 2)
+    for a, b, c in itertools.product(range(2), range(6), range(4)):
+        assert rp[a, b, c] == x[a, b // 2, c]
+    tl = oracle.tile(x, 2, 3)
+    for a, b, c in itertools.product(range(2), range(3), range(12)):
+        assert tl[a, b, c] == x[a, b, c % 4]
     p = oracle.pad(x, (1, 0, 2), (0, 1, 0), 77)
     for a, b, c in itertools.product(range(3), range(4), range(6)):
         inside = 1 <= a < 3 and b < 3 and 2 <= c < 6
@@ -218,6 +281,18 @@ def test_error_paths():
         oracle.slice_(x, 1, 2, 4, 1)
     with pytest.raises(oracle.OracleError):
         oracle.slice_(x, 1, 2, 2, 1)
+    with pytest.raises(oracle.OracleError):
+        oracle.slice_(x, 1, 1, 1, -1)
+    with pytest.raises(oracle.OracleError):
+        oracle.slice_(x, 1, 3, 0, -1)
+    with pytest.raises(oracle.OracleError):
+        oracle.slice_(x, 1, 2, -2, -1)
+    with pytest.raises(oracle.OracleError):
+        oracle.slice_(x, 1, 0, 2, 0)
+    with pytest.raises(oracle.OracleError):
+        oracle.repeat(x, 2, 2)
+    with pytest.raises(oracle.OracleError):
+        oracle.tile(x, 0, 0)
     with pytest.raises(oracle.OracleError):
         oracle.pad(x, (0, -1), (0, 0))
     with pytest.raises(oracle.OracleError):
