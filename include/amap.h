@@ -69,10 +69,21 @@ amap_status amap_transpose(const amap_t *m, const int32_t *perm, amap_t **out);
 /* Row-major reshape; the volume must be preserved. */
 amap_status amap_reshape(const amap_t *m, int rank, const int64_t *shape, amap_t **out);
 
-/* Keep indices begin, begin+step, ... < end of one axis.
- * Needs 0 <= begin < end <= extent and step >= 1. */
+/* One axis strided (strided_slice in the paper's Section 2.1 operator list).
+ * step >= 1: keep indices begin, begin+step, ... < end; needs 0 <= begin < end <= extent.
+ * step <= -1: keep begin, begin+step, ... > end, walking the axis downwards;
+ * needs -1 <= end < begin <= extent - 1 (end = -1 reaches index 0). */
 amap_status amap_slice(const amap_t *m, int axis, int64_t begin, int64_t end, int64_t step,
                        amap_t **out);
+
+/* Section 2.1 operator list, "repeat": every index of one axis r >= 1 times in
+ * a row, out[.., i, ..] = in[.., i / r, ..].  A load that is not injective. */
+amap_status amap_repeat(const amap_t *m, int axis, int64_t r, amap_t **out);
+
+/* Section 2.1 operator list, "tile": the whole axis t >= 1 times one after the
+ * other, out[.., i, ..] = in[.., i % extent, ..].  Broadcasting an extent-1
+ * axis to t is the case extent = 1. */
+amap_status amap_tile(const amap_t *m, int axis, int64_t t, amap_t **out);
 
 /* lo[k] / hi[k] >= 0 fill elements before / after axis k; fill_bits is the
  * constant (its low 16 bits for 2-byte elements). */
@@ -96,13 +107,17 @@ typedef struct {
     amap_elem es;
 } amap_src_desc;
 
-typedef enum { AMAP_TRANSPOSE = 0, AMAP_RESHAPE = 1, AMAP_SLICE = 2, AMAP_PAD = 3, AMAP_CONCAT = 4 } amap_op_kind;
+typedef enum {
+    AMAP_TRANSPOSE = 0, AMAP_RESHAPE = 1, AMAP_SLICE = 2, AMAP_PAD = 3, AMAP_CONCAT = 4,
+    AMAP_REPEAT = 5, AMAP_TILE = 6
+} amap_op_kind;
 
 typedef struct {
     amap_op_kind kind;
-    int axis;           /* SLICE, CONCAT */
-    int n;              /* TRANSPOSE: rank; RESHAPE: new rank; PAD: rank; SLICE: 3 */
-    const int64_t *a;   /* TRANSPOSE: perm[n]; RESHAPE: shape[n]; SLICE: {begin,end,step}; PAD: lo[n] */
+    int axis;           /* SLICE, CONCAT, REPEAT, TILE */
+    int n;              /* TRANSPOSE: rank; RESHAPE: new rank; PAD: rank; SLICE: 3; REPEAT, TILE: 1 */
+    const int64_t *a;   /* TRANSPOSE: perm[n]; RESHAPE: shape[n]; SLICE: {begin,end,step}; PAD: lo[n];
+                           REPEAT, TILE: {count} */
     const int64_t *b;   /* PAD: hi[n] */
     uint32_t fill_bits; /* PAD */
 } amap_op;
@@ -132,7 +147,8 @@ typedef struct {
     int n_fill_pieces;
     int kernel_id;                   /* amap_kernel_id the planner chose for the largest piece */
     int vec_bytes;                   /* smallest access width planned over all pieces, both sides */
-    int64_t min_read_bytes;          /* distinct source elements needed x elem size */
+    int64_t min_read_bytes;          /* distinct source elements needed x elem size (an element that
+                                        repeat / tile / overlapping concat inputs read several times counts once) */
     int64_t write_bytes;             /* volume(dst) x elem size */
     int64_t fill_bytes;              /* part of write_bytes that is constant fill */
 } amap_info;

@@ -19,13 +19,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("AMAP_LIB_PATH") or os.path.join(_HERE, "libamap.so")
 
 AMAP_OK, AMAP_E_INVALID, AMAP_E_SHAPE, AMAP_E_UNSUPPORTED, AMAP_E_NOMEM, AMAP_E_ALIAS, AMAP_E_HIP = range(7)
-AMAP_TRANSPOSE, AMAP_RESHAPE, AMAP_SLICE, AMAP_PAD, AMAP_CONCAT = range(5)
+AMAP_TRANSPOSE, AMAP_RESHAPE, AMAP_SLICE, AMAP_PAD, AMAP_CONCAT, AMAP_REPEAT, AMAP_TILE = range(7)
 AMAP_K_PROGRAM, AMAP_K_ELEMENT, AMAP_K_ROWS, AMAP_K_TILE, AMAP_K_WAVE = range(5)
 KERNEL_NAMES = {0: "program", 1: "element", 2: "rows", 3: "tile", 4: "wave"}
 AMAP_MAX_RANK = 8
 
 EXPORTS = [
-    "amap_source", "amap_transpose", "amap_reshape", "amap_slice", "amap_pad", "amap_concat",
+    "amap_source", "amap_transpose", "amap_reshape", "amap_slice", "amap_repeat", "amap_tile", "amap_pad",
+    "amap_concat",
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
     "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_kernel",
     "amap_gemm_fused", "amap_status_str", "amap_last_error",
@@ -68,6 +69,8 @@ _L.amap_source.argtypes = [C.c_int, C.c_int, _i64p, C.c_int, _pp]
 _L.amap_transpose.argtypes = [_vp, _i32p, _pp]
 _L.amap_reshape.argtypes = [_vp, C.c_int, _i64p, _pp]
 _L.amap_slice.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int64, _pp]
+_L.amap_repeat.argtypes = [_vp, C.c_int, C.c_int64, _pp]
+_L.amap_tile.argtypes = [_vp, C.c_int, C.c_int64, _pp]
 _L.amap_pad.argtypes = [_vp, _i64p, _i64p, C.c_uint32, _pp]
 _L.amap_concat.argtypes = [_pp, C.c_int, C.c_int, _pp]
 _L.amap_inverse.argtypes = [_vp, _pp]
@@ -147,6 +150,14 @@ def amap_slice(m, axis, begin, end, step=1):
     return _new(_L.amap_slice, "amap_slice", m.handle, int(axis), int(begin), int(end), int(step))
 
 
+def amap_repeat(m, axis, count):
+    return _new(_L.amap_repeat, "amap_repeat", m.handle, int(axis), int(count))
+
+
+def amap_tile(m, axis, count):
+    return _new(_L.amap_tile, "amap_tile", m.handle, int(axis), int(count))
+
+
 def amap_pad(m, lo, hi, fill_bits=0):
     r = amap_describe(m).rank
     if len(lo) != r or len(hi) != r:
@@ -190,6 +201,9 @@ def marshal_chain(src_shapes, es, ops):
             keep.append(b)
             o.kind, o.n, o.a, o.b = AMAP_PAD, len(op[1]), a, b
             o.fill_bits = (int(op[3]) if len(op) > 3 else 0) & 0xFFFFFFFF
+        elif kind in ("repeat", "tile"):
+            a = _i64([op[2]])
+            o.kind, o.axis, o.n, o.a = (AMAP_REPEAT if kind == "repeat" else AMAP_TILE), int(op[1]), 1, a
         elif kind == "concat":
             a = None
             o.kind, o.axis = AMAP_CONCAT, int(op[1])

@@ -9,6 +9,7 @@
 // every operator only re-labels, clips, shifts or re-digits the dst side of a
 // piece, while the source strides ride along with the loops.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -79,6 +80,14 @@ bool eval_program(const PNode *n, const int64_t *idx_in, int *src, int64_t *off,
         }
         case PNode::SLICE:
             idx[n->axis] = n->begin + idx[n->axis] * n->step;
+            n = n->kids[0].get();
+            break;
+        case PNode::REPEAT:
+            idx[n->axis] /= n->count;
+            n = n->kids[0].get();
+            break;
+        case PNode::TILE:
+            idx[n->axis] %= n->count;
             n = n->kids[0].get();
             break;
         case PNode::PAD: {
@@ -164,6 +173,7 @@ static amap *clone_header(const amap *m) {
     if (!r) return nullptr;
     r->elem = m->elem;
     r->src_shapes = m->src_shapes;
+    r->injective = m->injective;
     return r;
 }
 
@@ -317,6 +327,39 @@ void slice_piece(SliceCtx &c, const Piece &p) {
         c.out->push_back(std::move(q));
         return;
     }
+    // several loops on the axis and a step: if every loop but the innermost
+    // moves by whole steps, the residue class is decided by the innermost loop
+    // alone.  Keep its admissible iterations, divide the axis by the step, and
+    // what is left is a unit-step slice (this is how slice(repeat(x, r), step r)
+    // and slice(reshape(x), step) lose their division).
+    if (c.s > 1) {
+        bool outer_whole = true;
+        for (size_t t = 0; t + 1 < on.size(); ++t) outer_whole = outer_whole && p.it[on[t]].mult % c.s == 0;
+        if (outer_whole) {
+            const IterDim &d = p.it[on.back()];
+            const int64_t g = std::gcd(d.mult, c.s), period = c.s / g;
+            int64_t i0 = -1;
+            for (int64_t i = 0; i < d.extent && i < period; ++i)
+                if ((lo + i * d.mult - c.b) % c.s == 0) {
+                    i0 = i;
+                    break;
+                }
+            if (i0 < 0) return;
+            Piece q = p;
+            q.sbase += i0 * d.sstride;
+            IterDim &qd = q.it[on.back()];
+            qd.extent = (d.extent - 1 - i0) / period + 1;
+            qd.mult = d.mult * period / c.s;
+            qd.sstride = d.sstride * period;
+            for (size_t t = 0; t + 1 < on.size(); ++t) q.it[on[t]].mult /= c.s;
+            q.lo[c.axis] = (lo + i0 * d.mult - c.b) / c.s;  // exact; may be negative until clipped below
+            sort_iter(q);
+            SliceCtx unit{c.axis, 0, cdiv(c.e - c.b, c.s), 1, c.out};
+            slice_piece(unit, q);
+            c.ok = c.ok && unit.ok;
+            return;
+        }
+    }
     // several loops on the axis: peel the outermost one
     const IterDim d = p.it[on[0]];
     int64_t inner_span = 0;
@@ -357,18 +400,44 @@ void slice_piece(SliceCtx &c, const Piece &p) {
 
 }  // namespace
 
+// The same piece with one dst axis of extent E reversed: position x becomes
+// E - 1 - x.  Every loop on the axis runs backwards (i -> n - 1 - i), which
+// moves the origin to the far end and negates the source stride.
+static Piece flip_piece(const Piece &p, int axis, int64_t E) {
+    Piece q = p;
+    int64_t span = 0;
+    for (IterDim &d : q.it) {
+        if (d.dim != axis) continue;
+        span += (d.extent - 1) * d.mult;
+        q.sbase += (d.extent - 1) * d.sstride;
+        d.sstride = -d.sstride;
+    }
+    q.lo[axis] = E - 1 - p.lo[axis] - span;
+    return q;
+}
+
 extern "C" amap_status amap_slice(const amap_t *m, int axis, int64_t begin, int64_t end, int64_t step,
                                   amap_t **out) {
     GUARD_BEGIN
     if (!m || !out) return AMAP_E_INVALID;
     int rank = (int)m->shape.size();
     if (axis < 0 || axis >= rank) return AMAP_E_INVALID;
-    if (step < 1 || begin < 0 || begin >= end || end > m->shape[axis]) return AMAP_E_SHAPE;
+    const int64_t E = m->shape[axis];
+    int64_t count;
+    if (step >= 1) {
+        if (begin < 0 || begin >= end || end > E) return AMAP_E_SHAPE;
+        count = (end - begin + step - 1) / step;
+    } else if (step <= -1) {
+        if (end < -1 || end >= begin || begin > E - 1) return AMAP_E_SHAPE;
+        count = (begin - end + (-step) - 1) / (-step);
+    } else {
+        return AMAP_E_SHAPE;
+    }
     amap *r = clone_header(m);
     if (!r) return AMAP_E_NOMEM;
     std::unique_ptr<amap> hold(r);
     r->shape = m->shape;
-    r->shape[axis] = (end - begin + step - 1) / step;
+    r->shape[axis] = count;
     auto n = unary_node(PNode::SLICE, m, r->shape);
     n->axis = axis;
     n->begin = begin;
@@ -376,9 +445,101 @@ extern "C" amap_status amap_slice(const amap_t *m, int axis, int64_t begin, int6
     r->prog = n;
     r->strided = m->strided;
     if (m->strided) {
+        // a negative step is the positive step on the reversed axis:
+        // in[begin + i step] = flipped[(E - 1 - begin) + i |step|]
         SliceCtx c{axis, begin, end, step, &r->pieces};
-        for (const Piece &p : m->pieces) slice_piece(c, p);
+        if (step < 0) c = SliceCtx{axis, E - 1 - begin, E - 1 - end, -step, &r->pieces};
+        for (const Piece &p : m->pieces) slice_piece(c, step < 0 ? flip_piece(p, axis, E) : p);
         if (!c.ok) {
+            r->strided = false;
+            r->pieces.clear();
+        }
+    }
+    finish(*r);
+    *out = hold.release();
+    return AMAP_OK;
+    GUARD_END
+}
+
+// ---------------------------------------------------------------- repeat, tile
+
+extern "C" amap_status amap_repeat(const amap_t *m, int axis, int64_t count, amap_t **out) {
+    GUARD_BEGIN
+    if (!m || !out) return AMAP_E_INVALID;
+    int rank = (int)m->shape.size();
+    if (axis < 0 || axis >= rank) return AMAP_E_INVALID;
+    if (count < 1) return AMAP_E_SHAPE;
+    amap *r = clone_header(m);
+    if (!r) return AMAP_E_NOMEM;
+    std::unique_ptr<amap> hold(r);
+    r->shape = m->shape;
+    r->shape[axis] *= count;
+    auto n = unary_node(PNode::REPEAT, m, r->shape);
+    n->axis = axis;
+    n->count = count;
+    r->prog = n;
+    r->strided = m->strided;
+    if (count > 1 && volume_of(m->shape) > 0) r->injective = false;
+    if (m->strided) {
+        // new index = old index * count + j: every loop on the axis steps count
+        // times as far in dst, and a new innermost loop j re-reads the element
+        for (const Piece &p : m->pieces) {
+            Piece q = p;
+            q.lo[axis] *= count;
+            for (IterDim &d : q.it)
+                if (d.dim == axis) d.mult *= count;
+            if (count > 1) q.it.push_back({count, axis, 1, 0});
+            sort_iter(q);
+            r->pieces.push_back(std::move(q));
+        }
+    }
+    finish(*r);
+    *out = hold.release();
+    return AMAP_OK;
+    GUARD_END
+}
+
+extern "C" amap_status amap_tile(const amap_t *m, int axis, int64_t count, amap_t **out) {
+    GUARD_BEGIN
+    if (!m || !out) return AMAP_E_INVALID;
+    int rank = (int)m->shape.size();
+    if (axis < 0 || axis >= rank) return AMAP_E_INVALID;
+    if (count < 1) return AMAP_E_SHAPE;
+    const int64_t E = m->shape[axis];
+    amap *r = clone_header(m);
+    if (!r) return AMAP_E_NOMEM;
+    std::unique_ptr<amap> hold(r);
+    r->shape = m->shape;
+    r->shape[axis] *= count;
+    auto n = unary_node(PNode::TILE, m, r->shape);
+    n->axis = axis;
+    n->count = E;
+    r->prog = n;
+    r->strided = m->strided;
+    if (count > 1 && volume_of(m->shape) > 0) r->injective = false;
+    if (m->strided) {
+        for (const Piece &p : m->pieces) {
+            int64_t span = 0;
+            for (const IterDim &d : p.it)
+                if (d.dim == axis) span += (d.extent - 1) * d.mult;
+            if (count == 1) {
+                r->pieces.push_back(p);
+            } else if (p.lo[axis] == 0 && span == E - 1) {
+                // the piece covers the whole axis: one more (outermost) loop over the copies
+                Piece q = p;
+                q.it.push_back({count, axis, E, 0});
+                sort_iter(q);
+                r->pieces.push_back(std::move(q));
+            } else {
+                for (int64_t k = 0; k < count; ++k) {
+                    Piece q = p;
+                    q.lo[axis] += k * E;
+                    r->pieces.push_back(std::move(q));
+                }
+            }
+            if ((int64_t)r->pieces.size() > kMaxPieces) break;
+        }
+        if ((int64_t)r->pieces.size() > kMaxPieces) {
             r->strided = false;
             r->pieces.clear();
         }
@@ -490,8 +651,11 @@ extern "C" amap_status amap_concat(const amap_t *const *ms, int n, int axis, ama
                 r->src_shapes[s] = m->src_shapes[s];
             else if (r->src_shapes[s] != m->src_shapes[s])
                 return AMAP_E_SHAPE;  // same id, different tensors
+            else
+                r->injective = false;  // two inputs read the same source
         }
         r->strided = r->strided && m->strided;
+        r->injective = r->injective && m->injective;
         if (r->strided) {
             for (const Piece &p : m->pieces) {
                 Piece q = p;
@@ -724,9 +888,17 @@ extern "C" amap_status amap_inverse(const amap_t *m, amap_t **out) {
     for (size_t d = 0; d < m->shape.size(); ++d) dbase += p.lo[d] * Rd[d];
     // the loops with the roles of the two sides exchanged
     std::vector<LinDim> dims;
+    int64_t sbase = p.sbase;
     for (const IterDim &it : p.it) {
-        if (it.sstride <= 0) return AMAP_E_UNSUPPORTED;
-        dims.push_back({it.extent, it.sstride, it.mult * Rd[it.dim]});
+        if (it.sstride == 0) return AMAP_E_UNSUPPORTED;  // an element read more than once
+        if (it.sstride > 0) {
+            dims.push_back({it.extent, it.sstride, it.mult * Rd[it.dim]});
+        } else {
+            // a loop that walks the source backwards: run it the other way round
+            sbase += (it.extent - 1) * it.sstride;
+            dbase += (it.extent - 1) * it.mult * Rd[it.dim];
+            dims.push_back({it.extent, -it.sstride, -it.mult * Rd[it.dim]});
+        }
     }
     std::stable_sort(dims.begin(), dims.end(), [](const LinDim &a, const LinDim &b) { return a.ds > b.ds; });
     if (!nested(dims)) return AMAP_E_UNSUPPORTED;  // not injective on the source side
@@ -745,7 +917,7 @@ extern "C" amap_status amap_inverse(const amap_t *m, amap_t **out) {
         if (sshape[d] > 1) rd.cand.push_back(d);
     rd.out = &r->pieces;
     rd.proto = &proto;
-    rd.rec(p.sbase, dbase, dims);
+    rd.rec(sbase, dbase, dims);
     if (!rd.ok) return AMAP_E_UNSUPPORTED;
     r->strided = true;
     // program: source(dst shape) -> reshape to the loop extents in dst order ->
@@ -759,7 +931,8 @@ extern "C" amap_status amap_inverse(const amap_t *m, amap_t **out) {
         int n = (int)by_dst.size();
         std::vector<int> order(n);
         std::iota(order.begin(), order.end(), 0);
-        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return by_dst[a].ss > by_dst[b].ss; });
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int a, int b) { return std::llabs(by_dst[a].ss) > std::llabs(by_dst[b].ss); });
         auto s0 = std::make_shared<PNode>();
         s0->kind = PNode::SOURCE;
         s0->shape = m->shape;
@@ -768,11 +941,24 @@ extern "C" amap_status amap_inverse(const amap_t *m, amap_t **out) {
         r1->kind = PNode::RESHAPE;
         for (auto &d : by_dst) r1->shape.push_back(d.extent);
         r1->kids.push_back(s0);
+        // loops that walk the source backwards: reverse that axis
+        std::shared_ptr<PNode> below = r1;
+        for (int k = 0; k < n; ++k) {
+            if (by_dst[k].ss >= 0) continue;
+            auto f = std::make_shared<PNode>();
+            f->kind = PNode::SLICE;
+            f->shape = r1->shape;
+            f->axis = k;
+            f->begin = by_dst[k].extent - 1;
+            f->step = -1;
+            f->kids.push_back(below);
+            below = f;
+        }
         auto t = std::make_shared<PNode>();
         t->kind = PNode::TRANSPOSE;
         t->perm = order;
         for (int k = 0; k < n; ++k) t->shape.push_back(by_dst[order[k]].extent);
-        t->kids.push_back(r1);
+        t->kids.push_back(below);
         auto r2 = std::make_shared<PNode>();
         r2->kind = PNode::RESHAPE;
         r2->shape = sshape;
@@ -832,6 +1018,14 @@ extern "C" amap_status amap_compose(const amap_src_desc *srcs, int n_src, const 
             case AMAP_PAD:
                 if (op.n != rank) break;
                 st = amap_pad(m, op.a, op.b, op.fill_bits, &next);
+                break;
+            case AMAP_REPEAT:
+                if (!op.a) break;
+                st = amap_repeat(m, op.axis, op.a[0], &next);
+                break;
+            case AMAP_TILE:
+                if (!op.a) break;
+                st = amap_tile(m, op.axis, op.a[0], &next);
                 break;
             default:
                 break;

@@ -94,13 +94,13 @@ static_assert(sizeof(LaunchArgs) <= 4000, "kernel argument block too large");
 
 // ---- operator program for the element-wise interpreter ----
 constexpr int kMaxInstr = 24;
-enum InstrKind : int32_t { I_SOURCE = 0, I_TRANSPOSE, I_RESHAPE, I_SLICE, I_PAD, I_CONCAT };
+enum InstrKind : int32_t { I_SOURCE = 0, I_TRANSPOSE, I_RESHAPE, I_SLICE, I_PAD, I_CONCAT, I_REPEAT, I_TILE };
 
 struct Instr {
     int32_t kind;
     int32_t rank;  // rank of the index the instruction receives
-    int32_t a;     // SOURCE: src id; SLICE/CONCAT: axis; RESHAPE: child rank
-    int32_t b;     // PAD: fill bits; CONCAT: number of children
+    int32_t a;     // SOURCE: src id; SLICE/CONCAT/REPEAT/TILE: axis; RESHAPE: child rank
+    int32_t b;     // PAD: fill bits; CONCAT: number of children; REPEAT: count; TILE: extent of the child's axis
     int32_t v[8];  // SOURCE: shape; TRANSPOSE: perm; RESHAPE: own shape; SLICE: {begin, step}; PAD: lo; CONCAT: child extents
     int32_t w[8];  // RESHAPE/PAD: child shape; CONCAT: jump targets
 };

@@ -1,6 +1,7 @@
 // Host-side inspection and the host evaluator of a map.  The evaluator exists
 // so that the composer can be tested on machines without a GPU; the device
 // entry points never call it.
+#include <algorithm>
 #include <cstring>
 #include <vector>
 
@@ -52,6 +53,36 @@ inline void put(void *dst, int64_t off, const void *src, int64_t soff, int es) {
 }
 
 }  // namespace
+
+int64_t amap_detail::distinct_source_elements(const amap &m) {
+    std::vector<std::vector<uint8_t>> seen(m.src_shapes.size());
+    for (size_t i = 0; i < m.src_shapes.size(); ++i)
+        if (!m.src_shapes[i].empty()) seen[i].assign((size_t)((volume_of(m.src_shapes[i]) + 7) / 8), 0);
+    int64_t n = 0;
+    auto mark = [&](int sid, int64_t off) {
+        uint8_t &b = seen[(size_t)sid][(size_t)(off >> 3)];
+        const uint8_t bit = (uint8_t)(1u << (off & 7));
+        n += !(b & bit);
+        b |= bit;
+    };
+    if (m.strided) {
+        for (const KPiece &p : m.kpieces) {
+            if (p.fill) continue;
+            KPiece q = p;  // loops that do not move in the source add nothing
+            q.dims.erase(std::remove_if(q.dims.begin(), q.dims.end(), [](const KDim &d) { return d.ss == 0; }),
+                         q.dims.end());
+            for_each_iteration(q, [&](int64_t, int64_t s) { mark(p.src, s); });
+        }
+    } else {
+        for_each_index(m.shape, [&](const int64_t *idx) {
+            int sid = -1;
+            int64_t off = 0;
+            uint32_t fill = 0;
+            if (eval_program(m.prog.get(), idx, &sid, &off, &fill)) mark(sid, off);
+        });
+    }
+    return n;
+}
 
 extern "C" amap_status amap_eval_host(const amap_t *m, const void *const *src, void *dst, int mode) {
     if (!m || !dst || mode < 0 || mode > 2) return AMAP_E_INVALID;

@@ -293,6 +293,12 @@ __global__ __launch_bounds__(kProgramThreads) void amap_program_kernel(const Pro
         } else if (I.kind == I_SLICE) {
             idx[I.a] = I.v[0] + idx[I.a] * I.v[1];
             ++pc;
+        } else if (I.kind == I_REPEAT) {
+            idx[I.a] = (int32_t)((uint32_t)idx[I.a] / (uint32_t)I.b);
+            ++pc;
+        } else if (I.kind == I_TILE) {
+            idx[I.a] = (int32_t)((uint32_t)idx[I.a] % (uint32_t)I.b);
+            ++pc;
         } else if (I.kind == I_PAD) {
             bool inside = true;
             for (int k = 0; k < I.rank; ++k) {
@@ -483,6 +489,7 @@ extern "C" amap_status amap_describe(const amap_t *m, amap_info *out) {
         o.min_read_bytes = data * m->elem;
         o.fill_bytes = (vol - data) * m->elem;
     }
+    if (!m->injective) o.min_read_bytes = distinct_source_elements(*m) * m->elem;
     const Plan *plan = plan_of(*m);
     o.kernel_id = plan ? plan->main_kernel : AMAP_K_PROGRAM;
     o.vec_bytes = plan ? plan->min_vec_bytes : m->elem;

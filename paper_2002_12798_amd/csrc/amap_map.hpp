@@ -28,11 +28,12 @@ constexpr int kMaxRank = AMAP_MAX_RANK;
 constexpr int kMaxPieces = 4096;  // beyond this the strided form is dropped
 
 struct PNode {
-    enum Kind { SOURCE, TRANSPOSE, RESHAPE, SLICE, PAD, CONCAT } kind = SOURCE;
+    enum Kind { SOURCE, TRANSPOSE, RESHAPE, SLICE, PAD, CONCAT, REPEAT, TILE } kind = SOURCE;
     std::vector<int64_t> shape;  // shape of this node's output tensor
     int src_id = -1;             // SOURCE
     std::vector<int> perm;       // TRANSPOSE
-    int axis = 0;                // SLICE, CONCAT
+    int axis = 0;                // SLICE, CONCAT, REPEAT, TILE
+    int64_t count = 1;           // REPEAT: r;  TILE: extent of the child's axis
     int64_t begin = 0, step = 1; // SLICE
     std::vector<int64_t> lo;     // PAD
     uint32_t fill = 0;           // PAD
@@ -91,6 +92,7 @@ struct amap {
     std::vector<std::vector<int64_t>> src_shapes;  // by source id; empty vector = id not used
     std::shared_ptr<const amap_detail::PNode> prog;
     bool strided = false;
+    bool injective = true;                         // false once repeat / tile / a repeated concat source may read an element twice
     std::vector<amap_detail::Piece> pieces;
     std::vector<amap_detail::KPiece> kpieces;      // derived from pieces when strided
     std::shared_ptr<void> plan;                    // device launch plan (owned by the executor)
@@ -112,6 +114,10 @@ std::vector<KDim> merge_loops(std::vector<KDim> dims);
 
 // Recompute m.kpieces from m.pieces (no-op if not strided).
 void finalise(amap &m);
+
+// Number of distinct source elements a map reads (exact; marks one bit per
+// source element, walks the pieces or, without a strided form, the program).
+int64_t distinct_source_elements(const amap &m);
 
 // Evaluate the operator program for one dst multi-index.
 // Returns true and sets (src, off) for a data element, false for fill (sets fill).

@@ -640,6 +640,12 @@ struct Flattener {
                 I.v[0] = (int32_t)n->begin;
                 I.v[1] = (int32_t)n->step;
                 break;
+            case PNode::REPEAT:
+            case PNode::TILE:
+                I.kind = n->kind == PNode::REPEAT ? I_REPEAT : I_TILE;
+                I.a = n->axis;
+                I.b = (int32_t)n->count;
+                break;
             case PNode::PAD: {
                 I.kind = I_PAD;
                 I.b = (int32_t)n->fill;

@@ -43,6 +43,23 @@ def random_op(rng, shape, allow_step=True):
     return ("pad", lo, hi, int(rng.integers(1, 60000)))
 
 
+def random_op_ext(rng, shape):
+    """Like random_op, plus the non-injective gathers and downward slices."""
+    u = rng.random()
+    r = len(shape)
+    if u < 0.18:
+        return ("repeat", int(rng.integers(r)), int(rng.integers(1, 5)))
+    if u < 0.36:
+        return ("tile", int(rng.integers(r)), int(rng.integers(1, 5)))
+    if u < 0.54:
+        ax = int(rng.integers(r))
+        n = shape[ax]
+        b = int(rng.integers(0, n))
+        e = int(rng.integers(-1, b)) if b > 0 else -1
+        return ("slice", ax, b, e, -int(rng.integers(1, 4)))
+    return random_op(rng, shape)
+
+
 def out_shape(shape, op):
     k = op[0]
     if k == "transpose":
@@ -51,16 +68,20 @@ def out_shape(shape, op):
         return tuple(op[1])
     if k == "slice":
         s = list(shape)
-        s[op[1]] = -((op[2] - op[3]) // op[4])
+        s[op[1]] = -((op[2] - op[3]) // op[4])   # ceil((end - begin) / step), either sign of step
+        return tuple(s)
+    if k in ("repeat", "tile"):
+        s = list(shape)
+        s[op[1]] *= op[2]
         return tuple(s)
     if k == "pad":
         return tuple(l + s + h for l, s, h in zip(op[1], shape, op[2]))
     raise ValueError(k)
 
 
-def random_chain(seed, max_ops=5, n_src_max=3, max_volume=20000):
-    """Returns (src_shapes, ops)."""
-    rng = np.random.default_rng(seed)
+def random_chain(seed, max_ops=5, n_src_max=3, max_volume=20000, extended=False):
+    """Returns (src_shapes, ops).  extended: also repeat, tile and negative-step slices."""
+    rng = np.random.default_rng(seed if not extended else [seed, 77])
     shape = random_shape(rng)
     ops, src_shapes = [], [shape]
     if rng.random() < 0.3:
@@ -76,7 +97,7 @@ def random_chain(seed, max_ops=5, n_src_max=3, max_volume=20000):
         s[ax] = sum(t[ax] for t in src_shapes)
         shape = tuple(s)
     for _ in range(int(rng.integers(1, max_ops + 1))):
-        op = random_op(rng, shape)
+        op = random_op_ext(rng, shape) if extended else random_op(rng, shape)
         ns = out_shape(shape, op)
         if int(np.prod(ns)) > max_volume or len(ns) > 8:
             continue

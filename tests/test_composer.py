@@ -21,7 +21,15 @@ def _iota_sources(shapes, es):
     return srcs
 
 
-def _check_map(m, srcs, want, expect_strided=None):
+def _distinct_data_elements(srcs, ops, want):
+    """Distinct source elements a chain reads, from the oracle alone: positions whose value
+    follows a change of every source value are data, and iota sources make values = addresses."""
+    other = [(~s) for s in srcs]
+    data = oracle.run_chain(other, ops) != want
+    return len(np.unique(want[data]))
+
+
+def _check_map(m, srcs, want, expect_strided=None, ops=None):
     info = B.amap_describe(m)
     assert B.dst_shape(m) == want.shape
     got_prog = B.amap_eval_host(m, srcs, mode=1)
@@ -33,7 +41,10 @@ def _check_map(m, srcs, want, expect_strided=None):
         assert np.array_equal(got, want), "strided pieces"
         assert B.amap_check_cover(m) == (0, 0)
         assert info.write_bytes == want.nbytes
-        assert info.min_read_bytes + info.fill_bytes == want.nbytes
+        if ops is None:
+            assert info.min_read_bytes + info.fill_bytes == want.nbytes
+    if ops is not None:
+        assert info.min_read_bytes == _distinct_data_elements(srcs, ops, want) * want.dtype.itemsize
 
 
 @pytest.mark.parametrize("name", synth.WORKLOAD_NAMES)
@@ -77,6 +88,16 @@ def test_random_chains(seed):
     want = oracle.run_chain(srcs, ops)
     m = B.amap_compose(src_shapes, es, ops)
     _check_map(m, srcs, want)
+
+
+@pytest.mark.parametrize("seed", range(300))
+def test_random_chains_with_repeat_tile_and_downward_slices(seed):
+    src_shapes, ops = chains.random_chain(seed, extended=True)
+    es = 2 if seed % 2 else 4
+    srcs = _iota_sources(src_shapes, es)
+    want = oracle.run_chain(srcs, ops)
+    m = B.amap_compose(src_shapes, es, ops)
+    _check_map(m, srcs, want, ops=ops)
 
 
 def test_random_chains_mostly_strided():
@@ -164,10 +185,49 @@ def test_inverse_closed_forms():
     assert np.array_equal(B.amap_eval_host(ti, [B.amap_eval_host(t, [xs])]), xs)
 
 
+def test_repeat_tile_closed_forms():
+    x = _iota_sources([(3, 4, 5)], 4)[0]
+    s = B.amap_source(0, (3, 4, 5), 4)
+    # every r-th element of a repeat is the input; the map algebra cancels the division
+    m = B.amap_slice(B.amap_repeat(s, 1, 3), 1, 2, 12, 3)
+    assert np.array_equal(B.amap_eval_host(m, [x], mode=2), x)
+    info = B.amap_describe(m)
+    assert (info.n_pieces, info.min_read_bytes) == (1, x.nbytes)
+    # one block of a tile is the input
+    m = B.amap_slice(B.amap_tile(s, 2, 4), 2, 10, 15, 1)
+    assert np.array_equal(B.amap_eval_host(m, [x], mode=2), x)
+    assert B.amap_describe(m).n_pieces == 1
+    # broadcast: tile of an extent-1 axis, 7 copies read 12 elements
+    b = B.amap_tile(B.amap_reshape(B.amap_slice(s, 2, 1, 2, 1), (3, 1, 4)), 1, 7)
+    info = B.amap_describe(b)
+    assert (info.min_read_bytes, info.write_bytes) == (12 * 4, 84 * 4)
+    assert np.array_equal(B.amap_eval_host(b, [x]), np.broadcast_to(x[:, :, 1].reshape(3, 1, 4), (3, 7, 4)))
+    # repeat = reshape / tile / reshape, both forms give the same table
+    r1 = B.amap_repeat(s, 2, 2)
+    r2 = B.amap_reshape(B.amap_tile(B.amap_reshape(s, (3, 4, 5, 1)), 3, 2), (3, 4, 10))
+    assert np.array_equal(B.amap_eval_host(r1, [x], mode=2), B.amap_eval_host(r2, [x], mode=2))
+    assert np.array_equal(B.amap_eval_host(r1, [x]), np.repeat(x, 2, axis=2))
+    # reversing an axis twice cancels to the identity piece
+    f = B.amap_slice(B.amap_slice(s, 1, 3, -1, -1), 1, 3, -1, -1)
+    assert np.array_equal(B.amap_eval_host(f, [x], mode=2), x)
+    assert B.amap_describe(f).kernel_id == B.AMAP_K_ROWS
+
+
+def test_inverse_of_reversed_axes():
+    x = _iota_sources([(4, 6, 5)], 4)[0]
+    ops = [("slice", 1, 5, -1, -1), ("transpose", (2, 0, 1)), ("slice", 0, 4, -1, -1), ("reshape", (10, 12))]
+    m = B.amap_compose([(4, 6, 5)], 4, ops)
+    y = oracle.run_chain([x], ops)
+    inv = B.amap_inverse(m)
+    assert np.array_equal(B.amap_eval_host(inv, [y], mode=1), x)
+    assert np.array_equal(B.amap_eval_host(inv, [y], mode=2), x)
+
+
 def test_inverse_refuses_non_bijections():
     s = B.amap_source(0, (4, 6), 4)
     for m in [B.amap_slice(s, 1, 0, 3, 1), B.amap_pad(s, (0, 1), (0, 0), 0),
-              B.amap_concat([s, s], 0)]:
+              B.amap_concat([s, s], 0), B.amap_repeat(s, 0, 2), B.amap_tile(s, 1, 3),
+              B.amap_slice(s, 1, 5, 1, -1)]:
         with pytest.raises(B.AmapError) as e:
             B.amap_inverse(m)
         assert e.value.status == B.AMAP_E_UNSUPPORTED
@@ -187,6 +247,13 @@ def test_error_paths():
         (lambda: B.amap_slice(s, 1, 3, 3, 1), B.AMAP_E_SHAPE),
         (lambda: B.amap_slice(s, 1, 0, 7, 1), B.AMAP_E_SHAPE),
         (lambda: B.amap_slice(s, 1, 0, 6, 0), B.AMAP_E_SHAPE),
+        (lambda: B.amap_slice(s, 1, 2, 2, -1), B.AMAP_E_SHAPE),
+        (lambda: B.amap_slice(s, 1, 6, 0, -1), B.AMAP_E_SHAPE),
+        (lambda: B.amap_slice(s, 1, 3, -2, -1), B.AMAP_E_SHAPE),
+        (lambda: B.amap_repeat(s, 2, 2), B.AMAP_E_INVALID),
+        (lambda: B.amap_repeat(s, 0, 0), B.AMAP_E_SHAPE),
+        (lambda: B.amap_tile(s, -1, 2), B.AMAP_E_INVALID),
+        (lambda: B.amap_tile(s, 0, 0), B.AMAP_E_SHAPE),
         (lambda: B.amap_pad(s, (0, -1), (0, 0)), B.AMAP_E_SHAPE),
         (lambda: B.amap_concat([s, B.amap_source(1, (5, 7), 4)], 0), B.AMAP_E_SHAPE),
         (lambda: B.amap_concat([s, B.amap_source(1, (4, 6), 2)], 0), B.AMAP_E_INVALID),

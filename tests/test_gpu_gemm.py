@@ -99,6 +99,8 @@ CASES = [
     ((2, 8, 128, 8), [("transpose", (0, 2, 1, 3)), ("reshape", (256, 64))]),     # 8-element runs (one vector)
     ((300, 128), [("slice", 0, 22, 278, 1)]),                                    # base offset in the source
     ((2, 256, 2, 64), [("transpose", (0, 1, 3, 2)), ("transpose", (0, 1, 3, 2)), ("reshape", (512, 128))]),
+    ((64, 128), [("repeat", 0, 4)]),                                             # every A row read by 4 output rows
+    ((2, 128, 64), [("slice", 1, 127, -1, -1), ("tile", 0, 2), ("reshape", (512, 64))]),  # rows walked backwards, tiled
 ]
 
 

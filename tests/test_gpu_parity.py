@@ -98,6 +98,31 @@ def test_random_chains(dev, block):
         _run_families(dev, m, srcs, oracle.run_chain(srcs, ops), min_ran=2)
 
 
+@pytest.mark.parametrize("block", range(4))
+def test_random_chains_with_repeat_tile_and_downward_slices(dev, block):
+    for seed in range(block * 40, block * 40 + 40):
+        print(f"[gpu] extended random chain seed {seed}", flush=True)
+        src_shapes, ops = chains.random_chain(seed, extended=True)
+        es = 2 if seed % 2 else 4
+        srcs = [synth.random_bits(s, es, 2000 + seed + i) for i, s in enumerate(src_shapes)]
+        m = B.amap_compose(src_shapes, es, ops)
+        _run_families(dev, m, srcs, oracle.run_chain(srcs, ops), min_ran=2)
+
+
+def test_repeat_tile_at_bandwidth_sizes(dev):
+    """Several tiles and a ragged tail per kernel family, with re-read source elements."""
+    cases = [
+        ((16, 200, 72), 2, [("repeat", 0, 3), ("transpose", (0, 2, 1))]),
+        ((16, 200, 72), 2, [("transpose", (0, 2, 1)), ("tile", 1, 2), ("slice", 2, 199, -1, -1)]),
+        ((64, 1, 520), 4, [("tile", 1, 33), ("pad", (0, 1, 0), (0, 0, 8), 0xDEADBEEF)]),
+    ]
+    for shape, es, ops in cases:
+        print(f"[gpu] repeat/tile case {shape} {ops}", flush=True)
+        srcs = [synth.random_bits(shape, es, 11)]
+        m = B.amap_compose([shape], es, ops)
+        _run_families(dev, m, srcs, oracle.run_chain(srcs, ops), min_ran=3)
+
+
 @pytest.mark.parametrize("case", range(len(ALIGNED)))
 def test_aligned_shapes(dev, case):
     shape, es, ops = ALIGNED[case]

@@ -45,6 +45,14 @@ def test_random_chain_plans(seed):
         _replay_all(m)
 
 
+@pytest.mark.parametrize("seed", range(200))
+def test_random_chain_plans_with_repeat_tile_and_downward_slices(seed):
+    src_shapes, ops = chains.random_chain(seed, extended=True)
+    m = B.amap_compose(src_shapes, 2 if seed % 2 else 4, ops)
+    if B.amap_describe(m).strided:
+        _replay_all(m)
+
+
 # shapes with aligned inner extents so that the vector / tile paths are planned
 ALIGNED = [
     ((3, 40, 24), 2, [("transpose", (0, 2, 1))]),
@@ -56,6 +64,14 @@ ALIGNED = [
     ((2, 3, 64, 8), 2, [("transpose", (0, 2, 1, 3)), ("reshape", (2, 64, 24))]),
     ((7, 33, 65), 4, [("transpose", (2, 0, 1))]),
     ((5, 264, 40), 2, [("slice", 1, 8, 264, 2), ("transpose", (0, 2, 1))]),
+    # repeat / tile / downward slices: loops with source stride 0 and negative source strides
+    ((4, 24, 64), 2, [("repeat", 1, 3), ("transpose", (0, 2, 1))]),              # stride-0 loop inside P
+    ((4, 24, 64), 2, [("tile", 0, 3), ("transpose", (0, 2, 1))]),                # stride-0 batch loop
+    ((6, 1, 128), 4, [("tile", 1, 40)]),                                         # broadcast, row copy
+    ((3, 48, 40), 2, [("slice", 1, 47, -1, -1), ("transpose", (0, 2, 1))]),      # P walks the source backwards
+    ((3, 48, 40), 2, [("slice", 2, 39, -1, -1)]),                                # reversed contiguous axis
+    ((3, 48, 40), 4, [("slice", 0, 2, -1, -2), ("repeat", 2, 2), ("tile", 1, 2)]),
+    ((5, 16, 72), 2, [("transpose", (0, 2, 1)), ("repeat", 2, 4), ("pad", (0, 0, 8), (0, 0, 8), 3)]),
 ]
 
 
