@@ -177,6 +177,62 @@ amap_status amap_check_cover(const amap_t *m, int64_t *unwritten, int64_t *overw
  * lets the device indexing be verified on a machine without a GPU. */
 amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64_t *n_errors);
 
+/* ---- data-movement elimination over an operator graph (host only) ---------
+ * Section 2.1 applied to a whole program: tensors are either materialised
+ * (graph inputs, results of compute operators) or defined by a layout operator,
+ * i.e. by a load/store pair whose load feeds its store.  amap_graph_eliminate
+ * repeats the rewrite of eq. 3 / eq. 4 until no load reads a tensor defined by
+ * such a pair: every load of a compute operator, and every graph output, ends
+ * up reading materialised tensors through one composed map, and the
+ * intermediate tensors and the copies that defined them disappear.
+ * Compute operators are opaque here: the graph records only what they read
+ * and the shape of what they produce. */
+typedef struct amap_graph amap_graph_t;
+
+amap_status amap_graph_create(amap_graph_t **out);
+void amap_graph_free(amap_graph_t *g);
+
+/* A tensor that exists in memory before the graph runs.  *tensor receives its id. */
+amap_status amap_graph_input(amap_graph_t *g, int rank, const int64_t *shape, amap_elem es, int *tensor);
+
+/* tensor = op(inputs): a layout operator (CONCAT takes n_inputs >= 1 tensors, every other kind one). */
+amap_status amap_graph_op(amap_graph_t *g, const amap_op *op, const int *inputs, int n_inputs, int *tensor);
+
+/* An opaque compute operator reading n_inputs tensors (in this order: input slot k = inputs[k])
+ * and producing one materialised tensor of the given shape. */
+amap_status amap_graph_compute(amap_graph_t *g, const int *inputs, int n_inputs, int rank, const int64_t *shape,
+                               amap_elem es, int *tensor);
+
+/* The tensor must exist in memory when the graph has run. */
+amap_status amap_graph_output(amap_graph_t *g, int tensor);
+
+typedef struct {
+    int n_layout_ops;            /* layout operators in the graph */
+    int n_pairs;                 /* load/store pairs they stand for (a concat of k inputs is k pairs) */
+    int n_pairs_left;            /* pairs still executed afterwards: one per source of every graph output
+                                    that has to be materialised through a composed map */
+    int n_loads;                 /* loads of compute operators + graph outputs, = composed maps produced */
+    int n_rewrites;              /* applications of eq. 4 (one load rewritten past one eliminated tensor) */
+    int n_alias_outputs;         /* graph outputs whose composed map is the identity of one tensor: no copy left */
+    int64_t moved_bytes_before;  /* bytes read + written by all layout operators, one at a time */
+    int64_t moved_bytes_after;   /* bytes read + written by the composed maps of the graph outputs */
+    int64_t intermediate_bytes;  /* storage of the tensors that no longer exist */
+    int n_mapped_loads;          /* compute-operator loads whose composed map is not the identity of a tensor */
+    int64_t mapped_load_bytes;   /* bytes read + written if each of those is materialised by one composed copy
+                                    (a consumer that fuses the map into its operand load moves none of them) */
+} amap_graph_report;
+
+/* Run data-movement elimination to its fixed point.  Call once, after the graph is complete. */
+amap_status amap_graph_eliminate(amap_graph_t *g, amap_graph_report *report);
+
+/* Load number `index` (0 .. n_loads-1) after elimination.  consumer = tensor id of the compute
+ * operator that issues it, slot = which of its inputs; for a graph output consumer = -1 and
+ * slot = the output tensor's id.  *map is a NEW map (caller frees) whose source ids 0 .. *n_src-1
+ * stand for the materialised tensors src_tensors[0 .. *n_src-1] (room for 16 entries; maps that
+ * read more are refused with AMAP_E_UNSUPPORTED). */
+amap_status amap_graph_load(const amap_graph_t *g, int index, int *consumer, int *slot, amap_t **map,
+                            int *src_tensors, int *n_src);
+
 /* ---- execution (device pointers; asynchronous on `stream`) --------------
  * `stream` is a hipStream_t passed as void* (NULL = the default stream).
  * No allocation, no synchronisation, no host access to device memory. */

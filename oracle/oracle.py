@@ -231,6 +231,32 @@ def run_chain(srcs, ops, keep_intermediates=False):
     return (xs[0], inter) if keep_intermediates else xs[0]
 
 
+def run_graph(nodes, inputs, compute):
+    """Run an operator graph the un-optimised way: every node one at a time, every
+    tensor materialised.  nodes: ("input", shape) | ("op", op, [ids]) |
+    ("compute", kind, [ids], shape), node i defines tensor i; inputs: arrays for the
+    "input" nodes in order; compute(kind, arrays, shape) stands in for the opaque
+    compute operators.  Returns the list of all tensors."""
+    it = iter(inputs)
+    t = []
+    for n in nodes:
+        if n[0] == "input":
+            x = np.ascontiguousarray(next(it))
+            if x.shape != tuple(n[1]):
+                raise OracleError("graph input has the wrong shape")
+            t.append(x)
+        elif n[0] == "op":
+            t.append(apply_op([t[i] for i in n[2]], n[1])[0])
+        elif n[0] == "compute":
+            y = np.ascontiguousarray(compute(n[1], [t[i] for i in n[2]], tuple(n[3])))
+            if y.shape != tuple(n[3]):
+                raise OracleError("compute stand-in returned the wrong shape")
+            t.append(y)
+        else:
+            raise OracleError(f"unknown node {n[0]}")
+    return t
+
+
 def gemm_bf16(a_bits, w_bits):
     a = np.ascontiguousarray(a_bits, dtype=np.uint16)
     w = np.ascontiguousarray(w_bits, dtype=np.uint16)

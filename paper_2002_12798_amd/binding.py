@@ -30,6 +30,8 @@ EXPORTS = [
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
     "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_kernel",
     "amap_gemm_fused", "amap_status_str", "amap_last_error",
+    "amap_graph_create", "amap_graph_free", "amap_graph_input", "amap_graph_op", "amap_graph_compute",
+    "amap_graph_output", "amap_graph_eliminate", "amap_graph_load",
 ]
 
 
@@ -89,6 +91,26 @@ _L.amap_status_str.argtypes = [C.c_int]
 _L.amap_status_str.restype = C.c_char_p
 
 _L.amap_last_error.restype = C.c_char_p
+
+
+
+class amap_graph_report(C.Structure):
+    _fields_ = [("n_layout_ops", C.c_int), ("n_pairs", C.c_int), ("n_pairs_left", C.c_int), ("n_loads", C.c_int),
+                ("n_rewrites", C.c_int), ("n_alias_outputs", C.c_int), ("moved_bytes_before", C.c_int64),
+                ("moved_bytes_after", C.c_int64), ("intermediate_bytes", C.c_int64), ("n_mapped_loads", C.c_int),
+                ("mapped_load_bytes", C.c_int64)]
+
+
+_ip = C.POINTER(C.c_int)
+_L.amap_graph_create.argtypes = [_pp]
+_L.amap_graph_free.argtypes = [_vp]
+_L.amap_graph_free.restype = None
+_L.amap_graph_input.argtypes = [_vp, C.c_int, _i64p, C.c_int, _ip]
+_L.amap_graph_op.argtypes = [_vp, C.POINTER(amap_op), _ip, C.c_int, _ip]
+_L.amap_graph_compute.argtypes = [_vp, _ip, C.c_int, C.c_int, _i64p, C.c_int, _ip]
+_L.amap_graph_output.argtypes = [_vp, C.c_int]
+_L.amap_graph_eliminate.argtypes = [_vp, C.POINTER(amap_graph_report)]
+_L.amap_graph_load.argtypes = [_vp, C.c_int, _ip, _ip, _pp, _ip, _ip]
 
 raw = _L  # the raw CDLL, for callers that pre-marshal their arguments
 
@@ -257,9 +279,15 @@ def amap_eval_host(m, srcs, mode=0):
     dt = {2: np.uint16, 4: np.uint32}[info.elem_size]
     arrs = [None if s is None else np.ascontiguousarray(s).view(dt) for s in srcs]
     for i, a in enumerate(arrs):
-        if a is not None and a.size != int(np.prod(amap_source_shape(m, i))):
+        if a is None or i >= info.n_src:
+            continue
+        try:
+            want = int(np.prod(amap_source_shape(m, i)))
+        except AmapError:
+            continue  # an id the map no longer reads
+        if a.size != want:
             raise AmapError(AMAP_E_SHAPE, "amap_eval_host: source size")
-    ptrs = (C.c_void_p * max(1, info.n_src))(*[None if a is None else a.ctypes.data for a in arrs])
+    ptrs = (C.c_void_p * max(1, info.n_src, len(arrs)))(*[None if a is None else a.ctypes.data for a in arrs])
     out = np.empty(dst_shape(m), dtype=dt)
     _check(_L.amap_eval_host(m.handle, ptrs, out.ctypes.data, int(mode)), "amap_eval_host")
     return out
@@ -286,3 +314,54 @@ def amap_execute_kernel(src_ptrs, dst_ptr, m, stream, kernel_id):
 def amap_gemm_fused(a_src_ptr, a_map, w_ptr, n, out_ptr, stream=0):
     _check(_L.amap_gemm_fused(C.c_void_p(a_src_ptr), a_map.handle, C.c_void_p(w_ptr), int(n),
                               C.c_void_p(out_ptr), C.c_void_p(stream)), "amap_gemm_fused")
+
+
+class GraphDME:
+    """Owner of one amap_graph_t*.  Build from a synth.Graph-style node list, run
+    data-movement elimination, then read the rewritten loads."""
+
+    def __init__(self, nodes, outputs, es):
+        h = C.c_void_p()
+        _check(_L.amap_graph_create(C.byref(h)), "amap_graph_create")
+        self._h = h
+        self.report = None
+        for n in nodes:
+            tid = C.c_int(-1)
+            if n[0] == "input":
+                _check(_L.amap_graph_input(h, len(n[1]), _i64(n[1]), int(es), C.byref(tid)), "amap_graph_input")
+            elif n[0] == "op":
+                _, _, cops, _, keep = marshal_chain([(1,)], es, [n[1]])
+                ins = (C.c_int * len(n[2]))(*n[2])
+                _check(_L.amap_graph_op(h, cops, ins, len(n[2]), C.byref(tid)), "amap_graph_op")
+                del keep
+            elif n[0] == "compute":
+                ins = (C.c_int * max(1, len(n[2])))(*n[2])
+                _check(_L.amap_graph_compute(h, ins, len(n[2]), len(n[3]), _i64(n[3]), int(es), C.byref(tid)),
+                       "amap_graph_compute")
+            else:
+                raise AmapError(AMAP_E_INVALID, f"unknown node {n[0]}")
+        for o in outputs:
+            _check(_L.amap_graph_output(h, int(o)), "amap_graph_output")
+
+    def eliminate(self):
+        rep = amap_graph_report()
+        _check(_L.amap_graph_eliminate(self._h, C.byref(rep)), "amap_graph_eliminate")
+        self.report = rep
+        return rep
+
+    def loads(self):
+        """[(consumer tensor or -1, slot, Map, [source tensor ids])] after eliminate()."""
+        out = []
+        for i in range(self.report.n_loads):
+            cons, slot, n_src = C.c_int(), C.c_int(), C.c_int()
+            m = C.c_void_p()
+            ids = (C.c_int * 16)()
+            _check(_L.amap_graph_load(self._h, i, C.byref(cons), C.byref(slot), C.byref(m), ids, C.byref(n_src)),
+                   "amap_graph_load")
+            out.append((cons.value, slot.value, Map(m.value), [ids[k] for k in range(n_src.value)]))
+        return out
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _L is not None:
+            _L.amap_graph_free(h)

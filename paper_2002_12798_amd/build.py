@@ -10,7 +10,8 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libamap.so")
 
-SOURCES = ["amap_compose.cpp", "amap_host.cpp", "amap_plan.cpp", "amap_plan_check.cpp", "amap_kernels.hip", "amap_gemm.hip"]
+SOURCES = ["amap_compose.cpp", "amap_graph.cpp", "amap_host.cpp", "amap_plan.cpp", "amap_plan_check.cpp", "amap_kernels.hip",
+           "amap_gemm.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",

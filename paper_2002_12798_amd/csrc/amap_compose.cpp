@@ -158,6 +158,16 @@ void finalise(amap &m) {
 
 // every builder ends here: derive the kernel-form pieces and the launch plan
 static void finish(amap &m) {
+    // a source that no piece reads any more (sliced away, say) is no longer an
+    // argument of the map: the caller need not supply it
+    if (m.strided && !m.pieces.empty()) {
+        std::vector<char> used(m.src_shapes.size(), 0);
+        for (const Piece &p : m.pieces)
+            if (!p.fill) used[(size_t)p.src] = 1;
+        for (size_t i = 0; i < used.size(); ++i)
+            if (!used[i]) m.src_shapes[i].clear();
+        while (!m.src_shapes.empty() && m.src_shapes.back().empty()) m.src_shapes.pop_back();
+    }
     finalise(m);
     attach_plan(m);
 }
@@ -514,6 +524,7 @@ extern "C" amap_status amap_tile(const amap_t *m, int axis, int64_t count, amap_
     auto n = unary_node(PNode::TILE, m, r->shape);
     n->axis = axis;
     n->count = E;
+    n->step = count;
     r->prog = n;
     r->strided = m->strided;
     if (count > 1 && volume_of(m->shape) > 0) r->injective = false;

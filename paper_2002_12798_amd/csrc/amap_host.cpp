@@ -87,7 +87,7 @@ int64_t amap_detail::distinct_source_elements(const amap &m) {
 extern "C" amap_status amap_eval_host(const amap_t *m, const void *const *src, void *dst, int mode) {
     if (!m || !dst || mode < 0 || mode > 2) return AMAP_E_INVALID;
     if (volume_of(m->shape) == 0) return AMAP_OK;
-    if (!src) return AMAP_E_INVALID;
+    if (!src && !m->src_shapes.empty()) return AMAP_E_INVALID;
     const int es = m->elem;
     const bool use_pieces = mode == 2 || (mode == 0 && m->strided);
     if (use_pieces) {

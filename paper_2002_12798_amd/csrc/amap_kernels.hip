@@ -405,7 +405,8 @@ amap_status launch_program(const amap *m, const Plan &plan, const void *const *s
     if (!plan.program_ok) return AMAP_E_UNSUPPORTED;
     SrcTable t;
     std::memset(&t, 0, sizeof(t));
-    for (int i = 0; i < plan.n_prog_src; ++i) t.p[i] = src[i];
+    // leaves of the program that no dst index reaches are not arguments of the map
+    for (int i = 0; i < plan.n_prog_src && i < (int)m->src_shapes.size(); ++i) t.p[i] = src[i];
     const uint32_t total = (uint32_t)volume_of(m->shape);
     const uint32_t grid = (total + kProgramThreads - 1) / kProgramThreads;
     if (m->elem == 2)
@@ -421,7 +422,7 @@ extern "C" amap_status amap_execute_kernel(const void *const *src, void *dst, co
                                            int kernel_id) {
     if (!map || kernel_id < -1 || kernel_id > AMAP_K_WAVE) return AMAP_E_INVALID;
     if (volume_of(map->shape) == 0) return AMAP_OK;
-    if (!src) return AMAP_E_INVALID;
+    if (!src && !map->src_shapes.empty()) return AMAP_E_INVALID;
     amap_status st = check_pointers(map, src, dst);
     if (st != AMAP_OK) return st;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);

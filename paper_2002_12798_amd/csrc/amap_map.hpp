@@ -34,7 +34,7 @@ struct PNode {
     std::vector<int> perm;       // TRANSPOSE
     int axis = 0;                // SLICE, CONCAT, REPEAT, TILE
     int64_t count = 1;           // REPEAT: r;  TILE: extent of the child's axis
-    int64_t begin = 0, step = 1; // SLICE
+    int64_t begin = 0, step = 1; // SLICE; TILE keeps its number of copies in step
     std::vector<int64_t> lo;     // PAD
     uint32_t fill = 0;           // PAD
     std::vector<std::shared_ptr<const PNode>> kids;

@@ -153,3 +153,72 @@ def split_qkv_ops(t: int, b: int = 16):
     in a slice of the leading axis and a reshape that drops it."""
     return [("reshape", (b, 512, 3, 12, 64)), ("transpose", (2, 0, 3, 1, 4)),
             ("slice", 0, t, t + 1, 1), ("reshape", (b, 12, 512, 64))]
+
+
+# ---- operator graphs for graph-level data-movement elimination (Section 2.1) ----
+# A graph is plain data: a list of nodes in topological order, node i defines tensor i.
+#   ("input", shape)                      a tensor that exists in memory
+#   ("op", op_tuple, [input tensor ids])  a layout operator (concat takes several inputs)
+#   ("compute", kind, [input ids], shape) an opaque compute operator producing `shape`
+# plus the list of graph outputs.  The compute kinds are stand-ins executed by the test
+# harness only: "add" (wrapping integer sum of same-shaped inputs) and "rowmix"
+# (A[M,K], W[K,K] -> out[m,n] = A[m,n] + W[0,n], wrapping): the library treats them as opaque.
+
+class Graph:
+    def __init__(self, elem_size=2):
+        self.elem_size = elem_size
+        self.nodes = []
+        self.outputs = []
+
+    def input(self, shape):
+        self.nodes.append(("input", tuple(shape)))
+        return len(self.nodes) - 1
+
+    def op(self, op, inputs):
+        self.nodes.append(("op", tuple(op), [int(i) for i in (inputs if isinstance(inputs, (list, tuple)) else [inputs])]))
+        return len(self.nodes) - 1
+
+    def compute(self, kind, inputs, shape):
+        self.nodes.append(("compute", kind, [int(i) for i in inputs], tuple(shape)))
+        return len(self.nodes) - 1
+
+    def output(self, t):
+        self.outputs.append(int(t))
+
+    def input_ids(self):
+        return [i for i, n in enumerate(self.nodes) if n[0] == "input"]
+
+
+def wavenet_like_graph(layers=10, batch=1, channels=32, steps=256, skip_steps=64, elem_size=2):
+    """A stack of dilated causal gated layers written the way a framework lowers them:
+    the shifted taps, the channel concat, the layout change in front of the 1x1
+    convolution (a matrix product here), the gate split and the skip slices are all
+    separate copy operators between the compute operators.  Stand-in for the paper's
+    Parallel WaveNet graph (whose load/store pair count the paper reports); shapes
+    [batch, channels, steps]."""
+    B, Cc, T = batch, channels, steps
+    g = Graph(elem_size)
+    x = g.input((B, Cc, T))
+    skips = []
+    for l in range(layers):
+        d = 1 << (l % 6)
+        w = g.input((2 * Cc, 2 * Cc))
+        p = g.op(("pad", (0, 0, d), (0, 0, 0), 0), x)                 # causal padding
+        tap0 = g.op(("slice", 2, 0, T, 1), p)                         # x[t - d]
+        tap1 = g.op(("slice", 2, d, T + d, 1), p)                     # x[t]
+        cat = g.op(("concat", 1), [tap0, tap1])                       # [B, 2C, T]
+        tr = g.op(("transpose", (0, 2, 1)), cat)                      # [B, T, 2C]
+        a = g.op(("reshape", (B * T, 2 * Cc)), tr)                    # rows of the matrix product
+        z = g.compute("rowmix", [a, w], (B * T, 2 * Cc))
+        zr = g.op(("reshape", (B, T, 2 * Cc)), z)
+        zt = g.op(("transpose", (0, 2, 1)), zr)                       # back to [B, 2C, T]
+        f = g.op(("slice", 1, 0, Cc, 1), zt)                          # filter half
+        gt = g.op(("slice", 1, Cc, 2 * Cc, 1), zt)                    # gate half
+        gated = g.compute("add", [f, gt], (B, Cc, T))
+        skips.append(g.op(("slice", 2, T - skip_steps, T, 1), gated))  # last steps feed the skip path
+        x = g.compute("add", [x, gated], (B, Cc, T))                  # residual
+    s = g.op(("concat", 1), skips)                                    # [B, layers*C, skip_steps]
+    out = g.op(("transpose", (0, 2, 1)), s)
+    g.output(out)
+    g.output(x)
+    return g

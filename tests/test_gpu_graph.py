@@ -1,0 +1,78 @@
+"""GPU parity of graph-level data-movement elimination: the optimised graph (only
+compute operators and the composed maps in front of them run; no layout operator
+is executed on its own) against the un-optimised graph on the CPU oracle."""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2002_12798_amd import binding as B
+from paper_2002_12798_amd import synth
+from tests.test_graph_dme import _inputs, _random_graph, standin
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    from paper_2002_12798_amd import device
+    device.require_gpu()
+    return device
+
+
+def _standin_device(kind, xs, shape):
+    if kind == "add":
+        acc = xs[0].clone()
+        for x in xs[1:]:
+            acc += x                      # integer tensors wrap like the numpy stand-in
+        return acc.reshape(shape)
+    if kind == "rowmix":
+        return (xs[0] + xs[1][0][None, :]).reshape(shape)
+    raise AssertionError(kind)
+
+
+def run_optimised(dev, g, inputs):
+    """Returns {tensor id: host array} for every compute result and graph output."""
+    import torch
+    dme = B.GraphDME(g.nodes, g.outputs, g.elem_size)
+    dme.eliminate()
+    by_consumer = {}
+    for cons, slot, m, ids in dme.loads():
+        by_consumer[(cons, slot)] = (m, ids)
+    mat, it, got = {}, iter(inputs), {}
+    for i, n in enumerate(g.nodes):
+        if n[0] == "input":
+            mat[i] = dev.to_device(next(it))
+        elif n[0] == "compute":
+            xs = []
+            for s in range(len(n[2])):
+                m, ids = by_consumer[(i, s)]
+                xs.append(dev.execute(m, [mat[k] for k in ids]))
+            mat[i] = _standin_device(n[1], xs, n[3]).contiguous()
+            got[i] = dev.to_host(mat[i])
+    for o in g.outputs:
+        m, ids = by_consumer[(-1, o)]
+        got[o] = dev.to_host(dev.execute(m, [mat[k] for k in ids]))
+    torch.cuda.synchronize()
+    return got
+
+
+def test_wavenet_like_graph_on_device(dev):
+    g = synth.wavenet_like_graph(layers=7, batch=2, channels=32, steps=512, skip_steps=64)
+    ins = _inputs(g, 21)
+    want = oracle.run_graph(g.nodes, ins, standin)
+    got = run_optimised(dev, g, ins)
+    assert set(g.outputs) <= set(got)
+    for i, arr in got.items():
+        assert np.array_equal(arr.view(want[i].dtype).reshape(want[i].shape), want[i]), i
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_graphs_on_device(dev, block):
+    for seed in range(block * 20, block * 20 + 20):
+        print(f"[gpu] random graph seed {seed}", flush=True)
+        g = _random_graph(seed)
+        ins = _inputs(g, 100 + seed)
+        want = oracle.run_graph(g.nodes, ins, standin)
+        got = run_optimised(dev, g, ins)
+        for i, arr in got.items():
+            assert np.array_equal(arr.view(want[i].dtype).reshape(want[i].shape), want[i]), (seed, i)

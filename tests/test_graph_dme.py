@@ -1,0 +1,178 @@
+"""Graph-level data-movement elimination (CPU only): after the fixed point every
+load of a compute operator and every graph output reads materialised tensors
+through one composed map, and evaluating that map on the oracle's materialised
+tensors reproduces, bit for bit, the tensor the un-optimised program would have
+put in front of that load."""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2002_12798_amd import binding as B
+from paper_2002_12798_amd import synth
+from tests import chains
+
+
+def standin(kind, xs, shape):
+    """The opaque compute operators of the test graphs (integer, so exact)."""
+    if kind == "add":
+        acc = xs[0].copy()
+        for x in xs[1:]:
+            acc = acc + x            # unsigned wrap-around
+        return acc.reshape(shape)
+    if kind == "rowmix":
+        a, w = xs
+        return (a + w[0][None, :]).reshape(shape)
+    raise AssertionError(kind)
+
+
+def _inputs(g, seed):
+    return [synth.random_bits(g.nodes[i][1], g.elem_size, seed + i) for i in g.input_ids()]
+
+
+def _check_loads(g, tensors, dme):
+    mat = {i for i, n in enumerate(g.nodes) if n[0] in ("input", "compute")}
+    seen = set()
+    for cons, slot, m, ids in dme.loads():
+        assert set(ids) <= mat, "a rewritten load still reads a tensor defined by a copy"
+        want = tensors[slot] if cons < 0 else tensors[g.nodes[cons][2][slot]]
+        got = B.amap_eval_host(m, [tensors[i] for i in ids])
+        assert got.shape == want.shape
+        assert np.array_equal(got, want), (cons, slot)
+        seen.add((cons, slot))
+    expect = {(c, s) for c, n in enumerate(g.nodes) if n[0] == "compute" for s in range(len(n[2]))}
+    expect |= {(-1, o) for o in g.outputs}
+    assert seen == expect
+
+
+def test_wavenet_like_graph():
+    layers, Bn, Cc, T, S = 4, 2, 8, 32, 8
+    g = synth.wavenet_like_graph(layers, Bn, Cc, T, S)
+    tensors = oracle.run_graph(g.nodes, _inputs(g, 5), standin)
+    dme = B.GraphDME(g.nodes, g.outputs, g.elem_size)
+    rep = dme.eliminate()
+    _check_loads(g, tensors, dme)
+    # per layer: pad, 2 taps, concat (2 pairs), transpose, reshape | reshape, transpose, 2 gate slices | skip slice
+    assert rep.n_layout_ops == 11 * layers + 2
+    assert rep.n_pairs == 12 * layers + layers + 1
+    assert rep.n_loads == 6 * layers + 2
+    # only the skip output is still copied, from one tensor per layer; the other output is a compute result
+    assert rep.n_pairs_left == layers and rep.n_alias_outputs == 0
+    es = g.elem_size
+    skip_bytes = Bn * layers * Cc * S * es
+    assert rep.moved_bytes_after == 2 * skip_bytes
+    per_layer_storage = (Bn * Cc * (T + 1)) + 2 * Bn * Cc * T + 3 * Bn * 2 * Cc * T + 2 * Bn * 2 * Cc * T \
+        + 2 * Bn * Cc * T + Bn * Cc * S
+    dil = sum((1 << (l % 6)) - 1 for l in range(layers)) * Bn * Cc    # padding grows with the dilation
+    assert rep.intermediate_bytes == (per_layer_storage * layers + dil + Bn * layers * Cc * S) * es
+    assert rep.moved_bytes_before > 10 * rep.moved_bytes_after
+    # the matrix-product operand is not an identity load (taps + concat + layout change): one per layer,
+    # and so are the two halves of the gate
+    assert rep.n_mapped_loads == 3 * layers
+
+
+def test_cancelling_chain_leaves_no_copy():
+    g = synth.Graph(4)
+    x = g.input((3, 4, 5))
+    t = g.op(("transpose", (2, 0, 1)), x)
+    r = g.op(("reshape", (5, 12)), t)
+    r2 = g.op(("reshape", (5, 3, 4)), r)
+    back = g.op(("transpose", (1, 2, 0)), r2)
+    g.output(back)
+    dme = B.GraphDME(g.nodes, g.outputs, 4)
+    rep = dme.eliminate()
+    assert (rep.n_pairs, rep.n_pairs_left, rep.n_alias_outputs, rep.moved_bytes_after) == (4, 0, 1, 0)
+    assert rep.intermediate_bytes == 4 * 60 * 4 and rep.n_rewrites == 4
+    tensors = oracle.run_graph(g.nodes, _inputs(g, 1), standin)
+    _check_loads(g, tensors, dme)
+    (cons, slot, m, ids), = dme.loads()
+    assert ids == [x] and B.amap_describe(m).n_pieces == 1
+
+
+def test_several_consumers_and_chains_through_compute():
+    g = synth.Graph(2)
+    a = g.input((4, 6))
+    b = g.input((4, 6))
+    at = g.op(("transpose", (1, 0)), a)                 # read by two compute operators and an output
+    bt = g.op(("transpose", (1, 0)), b)
+    s = g.compute("add", [at, bt], (6, 4))
+    st = g.op(("transpose", (1, 0)), s)                 # a chain that starts at a compute result
+    cat = g.op(("concat", 0), [st, a, b])
+    u = g.compute("add", [g.op(("slice", 0, 4, 8, 1), cat), a], (4, 6))   # slice of the concat = a again
+    g.output(at)
+    g.output(u)
+    g.output(g.op(("repeat", 1, 2), cat))
+    tensors = oracle.run_graph(g.nodes, _inputs(g, 9), standin)
+    dme = B.GraphDME(g.nodes, g.outputs, 2)
+    rep = dme.eliminate()
+    _check_loads(g, tensors, dme)
+    loads = {(c, s_): (m, ids) for c, s_, m, ids in dme.loads()}
+    m, ids = loads[(u, 0)]
+    assert ids == [a] and B.amap_describe(m).kernel_id == B.AMAP_K_ROWS and B.amap_describe(m).n_pieces == 1
+    assert rep.n_mapped_loads == 2           # at and bt into the first add; the slice-of-concat load is the identity
+    assert rep.n_pairs_left == 1 + 3         # at from a; the repeated concat from s, a, b
+
+
+def _random_graph(seed):
+    rng = np.random.default_rng(seed)
+    g = synth.Graph(2 if seed % 2 else 4)
+    shapes = {}
+    for _ in range(int(rng.integers(1, 4))):
+        s = chains.random_shape(rng, max_rank=3, max_extent=6)
+        shapes[g.input(s)] = s
+    for _ in range(int(rng.integers(3, 14))):
+        ids = list(shapes)
+        u = rng.random()
+        if u < 0.7:
+            t = int(rng.choice(ids))
+            op = chains.random_op_ext(rng, shapes[t])
+            ns = chains.out_shape(shapes[t], op)
+            if int(np.prod(ns)) > 4000 or int(np.prod(ns)) == 0:
+                continue
+            shapes[g.op(op, t)] = ns
+        elif u < 0.8:
+            t = int(rng.choice(ids))
+            same = [i for i in ids if shapes[i][1:] == shapes[t][1:] and len(shapes[i]) == len(shapes[t])]
+            pick = [int(v) for v in rng.choice(same, size=min(len(same), int(rng.integers(1, 4))))]
+            ns = (sum(shapes[i][0] for i in pick),) + tuple(shapes[t][1:])
+            shapes[g.op(("concat", 0), pick)] = ns
+        else:
+            t = int(rng.choice(ids))
+            same = [i for i in ids if shapes[i] == shapes[t]]
+            pick = [int(v) for v in rng.choice(same, size=min(len(same), 2), replace=False)]
+            shapes[g.compute("add", pick, shapes[t])] = shapes[t]
+    ids = list(shapes)
+    for o in set(int(v) for v in rng.choice(ids, size=min(3, len(ids)), replace=False)):
+        g.output(o)
+    return g
+
+
+@pytest.mark.parametrize("seed", range(120))
+def test_random_graphs(seed):
+    g = _random_graph(seed)
+    tensors = oracle.run_graph(g.nodes, _inputs(g, 100 + seed), standin)
+    dme = B.GraphDME(g.nodes, g.outputs, g.elem_size)
+    rep = dme.eliminate()
+    _check_loads(g, tensors, dme)
+    assert rep.n_layout_ops == sum(n[0] == "op" for n in g.nodes)
+    assert rep.n_pairs == sum(len(n[2]) for n in g.nodes if n[0] == "op")
+
+
+def test_graph_error_paths():
+    g = synth.Graph(4)
+    x = g.input((2, 3))
+    with pytest.raises(B.AmapError) as e:
+        B.GraphDME(g.nodes + [("op", ("transpose", (1, 0)), [5])], [], 4)
+    assert e.value.status == B.AMAP_E_INVALID
+    with pytest.raises(B.AmapError) as e:
+        B.GraphDME(g.nodes + [("op", ("reshape", (7,)), [x])], [], 4)
+    assert e.value.status == B.AMAP_E_SHAPE
+    with pytest.raises(B.AmapError) as e:
+        B.GraphDME(g.nodes + [("op", ("transpose", (1, 0)), [x, x])], [], 4)
+    assert e.value.status == B.AMAP_E_INVALID
+    with pytest.raises(B.AmapError) as e:
+        B.GraphDME(g.nodes, [3], 4)
+    assert e.value.status == B.AMAP_E_INVALID
+    d = B.GraphDME(g.nodes, [x], 4)
+    d.eliminate()
+    with pytest.raises(B.AmapError):
+        d.eliminate()                       # only once
