@@ -149,6 +149,59 @@ def bench_gemm(torch, device, B, synth, steps, warmup):
             "speedup_vs_unfused": round(u_gpu / f_gpu, 3), "dtype": "bf16 in, fp32 accumulate, bf16 out"}
 
 
+def bench_graph(torch, device, B, synth, steps, warmup):
+    """Graph-level data-movement elimination on the synthetic WaveNet-like graph: time of all
+    layout operators run one at a time (each a materialising copy) against the composed maps
+    that are left (non-identity loads of the compute operators + graph outputs).  The compute
+    operators themselves are the same on both sides and are not run."""
+    g = synth.wavenet_like_graph(layers=10, batch=8, channels=128, steps=4096, skip_steps=512)
+    es = g.elem_size
+    dme = B.GraphDME(g.nodes, g.outputs, es)
+    rep = dme.eliminate()
+    stream = C.c_void_p(device.current_stream())
+    dt = torch.int16 if es == 2 else torch.int32
+    shapes, buf = {}, {}
+    single = []   # (map, source ids, dst id) of every layout operator on its own
+    for i, n in enumerate(g.nodes):
+        if n[0] == "input":
+            shapes[i] = n[1]
+        elif n[0] == "compute":
+            shapes[i] = n[3]
+        else:
+            m = B.amap_compose([shapes[k] for k in n[2]], es, [n[1]])
+            shapes[i] = B.dst_shape(m)
+            single.append((m, n[2], i))
+        buf[i] = torch.zeros(shapes[i], dtype=dt, device="cuda")
+    composed = []  # (map, source ids, dst buffer)
+    for cons, slot, m, ids in dme.loads():
+        info = B.amap_describe(m)
+        ident = len(ids) == 1 and info.n_pieces == 1 and info.kernel_id == B.AMAP_K_ROWS and \
+            tuple(info.shape[k] for k in range(info.rank)) == tuple(shapes[ids[0]]) and info.fill_bytes == 0 and \
+            info.min_read_bytes == info.write_bytes
+        if cons >= 0 and ident:
+            continue
+        composed.append((m, ids, device.empty_dst(m)))
+
+    def run(items, dst_of):
+        for m, ids, d in items:
+            arr = (C.c_void_p * max(1, len(ids)))(*[buf[k].data_ptr() for k in ids])
+            st = B.raw.amap_execute(arr, C.c_void_p(dst_of(d).data_ptr()), m.handle, stream)
+            if st != 0:
+                raise RuntimeError(B.amap_status_str(st))
+
+    u_wall, u_gpu = _time_launches(torch, lambda _: run(single, lambda d: buf[d]), [None], steps, warmup)
+    o_wall, o_gpu = _time_launches(torch, lambda _: run(composed, lambda d: d), [None], steps, warmup)
+    return {"workload": "WaveNet-like graph, 10 gated layers, bf16 [8,128,4096] activations (synthetic)",
+            "layout_ops": rep.n_layout_ops, "pairs": rep.n_pairs, "pairs_left": rep.n_pairs_left,
+            "rewrites": rep.n_rewrites, "loads": rep.n_loads, "mapped_loads": rep.n_mapped_loads,
+            "moved_bytes_before": rep.moved_bytes_before,
+            "moved_bytes_after_fused_consumers": rep.moved_bytes_after,
+            "moved_bytes_after_materialised_loads": rep.moved_bytes_after + rep.mapped_load_bytes,
+            "intermediate_bytes_eliminated": rep.intermediate_bytes,
+            "kernels_before": len(single), "kernels_after": len(composed),
+            "before_ms": round(u_gpu, 4), "after_ms": round(o_gpu, 4), "speedup": round(u_gpu / o_gpu, 3)}
+
+
 def cpu_baseline(synth, name, min_bytes, budget_s=12.0):
     from oracle import oracle
     w = synth.workload(name)
@@ -211,6 +264,8 @@ def main():
                     help="launch only a plain copy (identity map) of 53,248,000 2-byte elements on cold buffers: "
                          "the known-size kernel that calibrates the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--gemm-only", action="store_true", help="time only the fused-prologue GEMM (cfg4)")
+    ap.add_argument("--next-only", action="store_true",
+                    help="time only the repeat / tile / reversed-axis workloads and the graph-level elimination")
     ap.add_argument("--fused-only", action="store_true",
                     help="launch nothing but the fused kernel on cold buffers (for a clean rocprofv3 kernel summary)")
     a = ap.parse_args()
@@ -241,6 +296,13 @@ def main():
         return
     if a.gemm_only:
         print(json.dumps(bench_gemm(torch, device, B, synth, a.steps, a.warmup)))
+        return
+    if a.next_only:
+        nxt = {}
+        for name in synth.NEXT_WORKLOAD_NAMES:
+            r = bench_workload(torch, device, B, synth, name, a.steps, a.warmup)
+            nxt[r["workload"]] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
+        print(json.dumps({"repeat_tile_reverse": nxt, "graph_dme": bench_graph(torch, device, B, synth, 10, 2)}))
         return
     if a.fused_only:
         a.no_extras = True
@@ -280,6 +342,12 @@ def main():
         out["cpu_baseline"] = cpu_baseline(synth, a.workload, main_res["min_bytes"])
         out["other_workloads"] = extras
         out["fused_gemm"] = bench_gemm(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
+        nxt = {}
+        for name in synth.NEXT_WORKLOAD_NAMES:
+            r = bench_workload(torch, device, B, synth, name, max(20, a.steps // 3), max(5, a.warmup // 3))
+            nxt[r["workload"]] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
+        out["repeat_tile_reverse"] = nxt
+        out["graph_dme"] = bench_graph(torch, device, B, synth, 10, 2)
     print(json.dumps(out))
 
 

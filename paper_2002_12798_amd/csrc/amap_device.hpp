@@ -78,6 +78,10 @@ struct DevPiece {
     // source, source strides and first P index.  group_n = 1: a plain piece.
     uint32_t group_n;
     uint32_t p_begin;
+    // ROWS only: every source element of the row is written 1 << rep_log times in
+    // a row (a repeat along the contiguous dimension); a lane then loads
+    // 1 / (1 << rep_log) of a vector and spreads it over a whole one.
+    uint32_t rep_log;
 };
 
 struct LaunchArgs {

@@ -117,6 +117,45 @@ __device__ __forceinline__ void rows_move(const DevPiece &P, char *dst, int es, 
     }
 }
 
+// The same for a row whose source elements are each repeated REP times in dst
+// (REP a power of two): the lane loads 16 / REP bytes and spreads them over
+// one 16-byte dst vector in registers.
+template <int ES, int REP, int NT>
+__device__ __forceinline__ void rows_expand(const DevPiece &P, char *dst, const uint32_t (&doff)[kRowsUnroll],
+                                            const uint32_t (&soff)[kRowsUnroll], const bool (&ok)[kRowsUnroll]) {
+    constexpr int SB = 16 / REP;           // source bytes per dst vector
+    constexpr int SW = SB >= 4 ? SB / 4 : 1;
+    uint32_t in[kRowsUnroll][SW];
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) {
+        const char *s = (const char *)P.src + (size_t)soff[u] * ES;
+        if (!ok[u]) {
+#pragma unroll
+            for (int k = 0; k < SW; ++k) in[u][k] = 0;
+        } else if constexpr (SB >= 4) {
+            gld<SB, (NT & PF_NT_LOAD) != 0>(in[u], s);
+        } else {
+            in[u][0] = *reinterpret_cast<const uint16_t *>(s);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) {
+        uint32_t out[4] = {0, 0, 0, 0};
+        if constexpr (ES == 4) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) out[i] = in[u][i / REP];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = i / REP;  // source element of dst element i
+                const uint32_t v = (in[u][e / 2] >> (16 * (e & 1))) & 0xFFFFu;
+                out[i / 2] |= v << (16 * (i & 1));
+            }
+        }
+        if (ok[u]) gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)doff[u] * ES, out);
+    }
+}
+
 template <int ES, int NT>
 __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t blk, uint32_t tid) {
     uint32_t doff[kRowsUnroll], soff[kRowsUnroll];
@@ -128,6 +167,16 @@ __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t
         const uint32_t r = base + u * threads;
         ok[u] = r < P.n_units;
         rows_offsets(P, r, doff[u], soff[u]);
+    }
+    if (P.rep_log) {  // the planner only sets it together with 16-byte dst vectors and a source
+        switch (P.rep_log) {
+        case 1: rows_expand<ES, 2, NT>(P, dst, doff, soff, ok); break;
+        case 2: rows_expand<ES, 4, NT>(P, dst, doff, soff, ok); break;
+        default:
+            if constexpr (ES == 2) rows_expand<2, 8, NT>(P, dst, doff, soff, ok);
+            break;
+        }
+        return;
     }
     switch (ES << P.vlog) {
     case 16: rows_move<16, NT>(P, dst, ES, doff, soff, ok); break;

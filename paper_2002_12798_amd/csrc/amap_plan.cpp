@@ -113,6 +113,44 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         if (k != iP) ds_others.push_back(kp.dims[k].ds);
         if (k != iQ && !kp.fill) ss_others.push_back(kp.dims[k].ss);
     }
+    // A repeat along the contiguous dimension: the innermost loop (dst stride 1)
+    // does not move in the source and the loop around it walks the source
+    // contiguously, so a dst row is the source row with every element written r
+    // times.  For r a power of two that fits a 16-byte vector the row kernel
+    // handles both loops as one loop over dst vectors.
+    if (family < 0 || family == AMAP_K_ROWS) {
+        const int inner = n - 1;
+        if (!kp.fill && n >= 2 && kp.dims[inner].ds == 1 && kp.dims[inner].ss == 0 && kp.dims[inner - 1].ss == 1 &&
+            kp.dims[inner - 1].ds == kp.dims[inner].extent) {
+            const int64_t r = kp.dims[inner].extent, cnt = kp.dims[inner - 1].extent;
+            const uint32_t V = vmax;
+            const bool pow2 = (r & (r - 1)) == 0;
+            std::vector<int64_t> dso, sso;
+            for (int k = 0; k < n - 2; ++k) {
+                dso.push_back(kp.dims[k].ds);
+                sso.push_back(kp.dims[k].ss);
+            }
+            if (pow2 && r >= 2 && r <= (int64_t)V && common_pow2(V, {cnt * r, kp.dbase}, dso) == V &&
+                common_pow2(V, {cnt * r}, {}) == V && (int64_t)common_pow2(V, {kp.sbase * r, cnt * r}, {}) == V) {
+                const int64_t sv = V / r;  // source elements per dst vector
+                bool ok = kp.sbase % sv == 0 && cnt % sv == 0;
+                for (int64_t x : sso) ok = ok && x % sv == 0;
+                if (ok) {
+                    KPiece merged = kp;
+                    merged.dims.pop_back();
+                    merged.dims.back() = KDim{cnt * r, 1, 1};
+                    fill_rows(dp, merged, V, nwlog);
+                    dp.loops[0].ss = (int32_t)sv;
+                    dp.rep_log = ilog2((uint32_t)r);
+                    vec_bytes = (int)(sv * es);
+                    if (line_aligned(es, {cnt * r, kp.dbase}, dso)) dp.flags |= PF_NT_STORE;
+                    if (line_aligned(es, {cnt, kp.sbase}, sso)) dp.flags |= PF_NT_LOAD;
+                    dp.flags &= (uint32_t)env_int("AMAP_NT", 3);
+                    return AMAP_K_ROWS;
+                }
+            }
+        }
+    }
     const bool rows_ok = iP >= 0 && (kp.fill || iP == iQ);
     const bool tile_shape = !kp.fill && iP >= 0 && iQ >= 0 && iP != iQ;
     uint32_t Vt = 1;

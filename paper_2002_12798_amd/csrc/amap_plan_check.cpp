@@ -54,7 +54,7 @@ struct Replay {
                 if (r >= P.n_units) continue;
                 uint32_t d, s;
                 rows_offsets(P, r, d, s);
-                for (uint32_t e = 0; e < V; ++e) write((int64_t)d + e, code_of(sid, (int64_t)s + e));
+                for (uint32_t e = 0; e < V; ++e) write((int64_t)d + e, code_of(sid, (int64_t)s + (e >> P.rep_log)));
             }
     }
 

@@ -136,6 +136,41 @@ def _cfg4():
                     make_w=lambda: f32_to_bf16_bits(normal_f32((1024, 4096), 4, 1, std=0.02)))
 
 
+# ---- workloads for the non-injective gathers and reversed axes (repeat, tile, negative step) ----
+def _up2x(n=32):
+    """Nearest-neighbour 2x up-sampling of an NCHW activation: repeat on H and on W."""
+    shp = (n, 256, 28, 28)
+    ops = [("repeat", 2, 2), ("repeat", 3, 2)]
+    return Workload("up2x" if n == 32 else f"up2x_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 5))])
+
+
+def _up2x_nhwc(n=32):
+    """The same up-sampling in NHWC: the repeated axes are outer, channel rows stay contiguous."""
+    shp = (n, 28, 28, 256)
+    ops = [("repeat", 1, 2), ("repeat", 2, 2)]
+    return Workload("up2x_nhwc" if n == 32 else f"up2x_nhwc_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 5, 1))])
+
+
+def _bcast(n=32):
+    """A per-channel vector broadcast to a whole NHWC activation (tile of extent-1 axes)."""
+    shp = (1, 1, 1, 256)
+    ops = [("tile", 0, n), ("tile", 1, 56), ("tile", 2, 56)]
+    return Workload("bcast" if n == 32 else f"bcast_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 6))])
+
+
+def _flip_seq(b=16):
+    """Sequence reversal of [b, 512, 768] (a slice with step -1 on the sequence axis)."""
+    shp = (b, 512, 768)
+    ops = [("slice", 1, 511, -1, -1)]
+    return Workload("flip_seq" if b == 16 else f"flip_seq_b{b}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 7))])
+
+
+NEXT_FACTORIES = {"up2x": _up2x, "up2x_nhwc": _up2x_nhwc, "bcast": _bcast, "flip_seq": _flip_seq}
+
 _FACTORIES = {
     "cfg0": _cfg0, "cfg1": _cfg1, "cfg2_fwd": _cfg2_fwd, "cfg2_rev": _cfg2_rev,
     "cfg3": _cfg3, "cfg4": _cfg4,
@@ -144,8 +179,11 @@ _FACTORIES = {
 WORKLOAD_NAMES = tuple(_FACTORIES)
 
 
+NEXT_WORKLOAD_NAMES = tuple(NEXT_FACTORIES)
+
+
 def workload(name: str, **kw) -> Workload:
-    return _FACTORIES[name](**kw)
+    return (_FACTORIES.get(name) or NEXT_FACTORIES[name])(**kw)
 
 
 def split_qkv_ops(t: int, b: int = 16):

@@ -72,6 +72,14 @@ ALIGNED = [
     ((3, 48, 40), 2, [("slice", 2, 39, -1, -1)]),                                # reversed contiguous axis
     ((3, 48, 40), 4, [("slice", 0, 2, -1, -2), ("repeat", 2, 2), ("tile", 1, 2)]),
     ((5, 16, 72), 2, [("transpose", (0, 2, 1)), ("repeat", 2, 4), ("pad", (0, 0, 8), (0, 0, 8), 3)]),
+    # repeat along the contiguous dimension by a power of two: the expanding row kernel
+    ((3, 20, 28), 2, [("repeat", 1, 2), ("repeat", 2, 2)]),
+    ((3, 20, 32), 2, [("repeat", 2, 4)]),
+    ((7, 9, 40), 2, [("repeat", 2, 8), ("slice", 1, 8, -1, -1)]),
+    ((3, 20, 28), 4, [("repeat", 2, 2), ("tile", 0, 2)]),
+    ((3, 20, 28), 4, [("repeat", 2, 4)]),
+    ((3, 20, 30), 2, [("repeat", 2, 2)]),          # 30 source elements per row: not a whole number of half vectors
+    ((3, 20, 28), 2, [("repeat", 2, 3)]),          # not a power of two
 ]
 
 
