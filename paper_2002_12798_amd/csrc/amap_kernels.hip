@@ -52,20 +52,36 @@ __device__ __forceinline__ void st(void *p, const uint32_t (&r)[VB / 4]) {
 // accesses are issued non-temporal (streaming; a compile-time choice, since
 // a run-time choice between the two forms is merged back into a plain access): the lines do not linger in the
 // per-XCD L2s, which shortens the write-back at the end of the kernel.
+// Loads may start at any element: the pointee types below carry 2-byte
+// alignment only, and the hardware (in the unaligned access mode every HSA
+// queue runs in) serves a 16-byte load from such an address with the same
+// instruction.  A composed map often reads a source run that is shifted by a
+// few elements against the 16-byte grid of dst (a slice offset, a dilated
+// tap); dst vectors stay aligned, so only the loads need this.
+typedef u32x4 u32x4_u __attribute__((aligned(2)));
+typedef u32x2 u32x2_u __attribute__((aligned(2)));
+typedef uint32_t u32_u __attribute__((aligned(2)));
 template <int VB, bool NT>
 __device__ __forceinline__ void gld(uint32_t (&r)[VB / 4], const void *p) {
-    if constexpr (NT) {
-        if constexpr (VB == 16) {
-            u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-            r[0] = v.x, r[1] = v.y, r[2] = v.z, r[3] = v.w;
-        } else if constexpr (VB == 8) {
-            u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
-            r[0] = v.x, r[1] = v.y;
-        } else {
-            r[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
-        }
+    if constexpr (VB == 16) {
+        u32x4 v;
+        if constexpr (NT)
+            v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+        else
+            v = *reinterpret_cast<const u32x4_u *>(p);
+        r[0] = v.x, r[1] = v.y, r[2] = v.z, r[3] = v.w;
+    } else if constexpr (VB == 8) {
+        u32x2 v;
+        if constexpr (NT)
+            v = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(p));
+        else
+            v = *reinterpret_cast<const u32x2_u *>(p);
+        r[0] = v.x, r[1] = v.y;
     } else {
-        ld<VB>(r, p);
+        if constexpr (NT)
+            r[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p));
+        else
+            r[0] = *reinterpret_cast<const u32_u *>(p);
     }
 }
 template <int VB, bool NT>

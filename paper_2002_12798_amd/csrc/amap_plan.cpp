@@ -153,11 +153,10 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     }
     const bool rows_ok = iP >= 0 && (kp.fill || iP == iQ);
     const bool tile_shape = !kp.fill && iP >= 0 && iQ >= 0 && iP != iQ;
+    // The vector width follows from the dst side (aligned 16-byte stores) and from
+    // the extents; source runs may start at any element (under-aligned loads).
     uint32_t Vt = 1;
-    if (tile_shape) {
-        Vt = common_pow2(vmax, {kp.dims[iP].extent, kp.dims[iQ].extent, kp.dbase, kp.sbase}, ds_others);
-        Vt = common_pow2(Vt, {}, ss_others);
-    }
+    if (tile_shape) Vt = common_pow2(vmax, {kp.dims[iP].extent, kp.dims[iQ].extent, kp.dbase}, ds_others);
     const bool tile_ok = tile_shape && Vt * es >= 4;
 
     int fam = family;
@@ -178,9 +177,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     }
     if (fam == AMAP_K_ROWS) {
         if (!rows_ok) return -1;
-        std::vector<int64_t> all = ds_others;
-        all.insert(all.end(), ss_others.begin(), ss_others.end());
-        uint32_t V = common_pow2(vmax, {kp.dims[iP].extent, kp.dbase, kp.fill ? 0 : kp.sbase}, all);
+        uint32_t V = common_pow2(vmax, {kp.dims[iP].extent, kp.dbase}, ds_others);
         fill_rows(dp, kp, V, nwlog);
         vec_bytes = (int)V * es;
         // streaming accesses where the piece touches only whole lines
@@ -453,13 +450,11 @@ static bool plan_group(const amap &m, const std::vector<Member> &g, int family, 
             s.src = reinterpret_cast<const void *>((uintptr_t)(kp.src + 1));
             s.sbase = (uint32_t)kp.sbase;
             s.ssP = (int32_t)mem.dims[iP].ss;
-            if (kp.sbase % V != 0 || mem.dims[iP].ss % V != 0) return false;
             std::vector<int64_t> bss;
             for (uint32_t k = 0; k < s.nloops; ++k) {
                 const int64_t ss = mem.dims[slot_dim[k]].ss;
                 // the Q chain must be the same contiguous chain in every source
                 if (k < s.nq && ss != head.loops[k].ss) return false;
-                if (k >= s.nq && ss % V != 0) return false;
                 s.loops[k].ss = (int32_t)ss;
                 if (k >= s.nq) bss.push_back(ss);
             }
@@ -582,7 +577,60 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
     return true;
 }
 
-bool plan_strided(const amap &m, int family, Plan &out) {
+// A transposing piece whose P or Q extent is not a whole number of vectors would
+// have to run element by element.  Cut it into a main part with whole vectors
+// and a thin tail (fewer than one vector wide), planned on their own.
+static std::vector<KPiece> split_ragged(const KPiece &kp, int es) {
+    std::vector<KPiece> out{kp};
+    if (kp.fill) return out;
+    const int64_t vmax = 16 / es;
+    int iP = -1, iQ = -1;
+    for (int k = 0; k < (int)kp.dims.size(); ++k) {
+        if (kp.dims[k].ds == 1) iP = k;
+        if (kp.dims[k].ss == 1) iQ = k;
+    }
+    if (iP < 0 || iQ < 0 || iP == iQ) return out;
+    std::vector<int64_t> ds_others;
+    for (int k = 0; k < (int)kp.dims.size(); ++k)
+        if (k != iP) ds_others.push_back(kp.dims[k].ds);
+    const int64_t V = common_pow2((uint32_t)vmax, {kp.dbase}, ds_others);  // what the dst side allows
+    if (V < 2) return out;
+    for (int dim : {iQ, iP}) {
+        std::vector<KPiece> next;
+        for (const KPiece &p : out) {
+            const int64_t E = p.dims[dim].extent, tail = E % V;
+            if (tail == 0 || E < 2 * V) {
+                next.push_back(p);
+                continue;
+            }
+            KPiece a = p, b = p;
+            a.dims[dim].extent = E - tail;
+            b.dims[dim].extent = tail;
+            b.dbase += (E - tail) * p.dims[dim].ds;
+            b.sbase += (E - tail) * p.dims[dim].ss;
+            next.push_back(std::move(a));
+            next.push_back(std::move(b));
+        }
+        out = std::move(next);
+    }
+    for (KPiece &p : out) {
+        std::vector<KDim> d;
+        for (const KDim &x : p.dims)
+            if (x.extent > 1) d.push_back(x);
+        p.dims = merge_loops(std::move(d));
+    }
+    return out;
+}
+
+bool plan_strided(const amap &m0, int family, Plan &out) {
+    amap m = m0;  // the planner's own piece list: ragged pieces cut into main part + tails
+    m.plan.reset();
+    if (m.strided && env_int("AMAP_SPLIT_RAGGED", 1)) {
+        std::vector<KPiece> ks;
+        for (const KPiece &kp : m0.kpieces)
+            for (KPiece &p : split_ragged(kp, m.elem)) ks.push_back(std::move(p));
+        if (ks.size() <= 4 * m0.kpieces.size() + 8) m.kpieces = std::move(ks);
+    }
     const int nw_env = env_int("AMAP_WAVES_LOG", -1);
     bool split_rows = false;
     if (nw_env >= 0 && nw_env <= 2) return plan_strided_nw(m, family, nw_env, out, split_rows);
