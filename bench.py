@@ -149,6 +149,47 @@ def bench_gemm(torch, device, B, synth, steps, warmup):
             "speedup_vs_unfused": round(u_gpu / f_gpu, 3), "dtype": "bf16 in, fp32 accumulate, bf16 out"}
 
 
+def bench_gemm_store(torch, device, B, synth, steps, warmup):
+    """QKV projection whose product is stored straight in the head-split layout of cfg2-fwd
+    ([3,16,12,512,64]) next to: plain product, then the cfg2-fwd map as its own kernel."""
+    w2 = synth.workload("cfg2_fwd")
+    M, K, N = 16 * 512, 768, 2304
+    a_map = B.amap_compose([(M, K)], 2, [])
+    out_map = B.amap_compose([(M, N)], 2, [("reshape", (16, 512, 2304))] + list(w2.ops))
+    stream = C.c_void_p(device.current_stream())
+    per_set = (M * K + K * N + 2 * M * N) * 2
+    sets = []
+    for i in range(max(2, -(-COLD_FOOTPRINT // per_set))):
+        g = torch.Generator(device="cuda").manual_seed(i)
+        sets.append((torch.randint(-16000, 16000, (M, K), dtype=torch.int16, device="cuda", generator=g),
+                     torch.randint(-16000, 16000, (K, N), dtype=torch.int16, device="cuda", generator=g),
+                     torch.empty((M, N), dtype=torch.int16, device="cuda"),
+                     torch.empty((M, N), dtype=torch.int16, device="cuda")))
+
+    def fused(s):
+        st = B.raw.amap_gemm_fused_store(C.c_void_p(s[0].data_ptr()), a_map.handle, C.c_void_p(s[1].data_ptr()),
+                                         C.c_int64(N), out_map.handle, C.c_void_p(s[3].data_ptr()), stream)
+        if st != 0:
+            raise RuntimeError(B.amap_status_str(st))
+
+    def unfused(s):
+        st = B.raw.amap_gemm_fused(C.c_void_p(s[0].data_ptr()), a_map.handle, C.c_void_p(s[1].data_ptr()),
+                                   C.c_int64(N), C.c_void_p(s[2].data_ptr()), stream)
+        arr = (C.c_void_p * 1)(s[2].data_ptr())
+        st = st or B.raw.amap_execute(arr, C.c_void_p(s[3].data_ptr()), out_map.handle, stream)
+        if st != 0:
+            raise RuntimeError(B.amap_status_str(st))
+
+    f_wall, f_gpu = _time_launches(torch, fused, sets, steps, warmup)
+    u_wall, u_gpu = _time_launches(torch, unfused, sets, steps, warmup)
+    flops = 2.0 * M * N * K
+    del sets
+    torch.cuda.empty_cache()
+    return {"workload": "QKV projection C[8192,2304] = A[8192,768] x W[768,2304] stored as [3,16,12,512,64]",
+            "fused_ms": round(f_gpu, 5), "fused_tflops": round(flops / f_gpu / 1e9, 1),
+            "unfused_ms": round(u_gpu, 5), "speedup_vs_unfused": round(u_gpu / f_gpu, 3)}
+
+
 def bench_graph(torch, device, B, synth, steps, warmup):
     """Graph-level data-movement elimination on the synthetic WaveNet-like graph: time of all
     layout operators run one at a time (each a materialising copy) against the composed maps
@@ -302,7 +343,8 @@ def main():
         for name in synth.NEXT_WORKLOAD_NAMES:
             r = bench_workload(torch, device, B, synth, name, a.steps, a.warmup)
             nxt[r["workload"]] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
-        print(json.dumps({"repeat_tile_reverse": nxt, "graph_dme": bench_graph(torch, device, B, synth, 10, 2)}))
+        print(json.dumps({"repeat_tile_reverse": nxt, "graph_dme": bench_graph(torch, device, B, synth, 10, 2),
+                          "fused_gemm_store": bench_gemm_store(torch, device, B, synth, a.steps, a.warmup)}))
         return
     if a.fused_only:
         a.no_extras = True
@@ -347,6 +389,7 @@ def main():
             r = bench_workload(torch, device, B, synth, name, max(20, a.steps // 3), max(5, a.warmup // 3))
             nxt[r["workload"]] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
         out["repeat_tile_reverse"] = nxt
+        out["fused_gemm_store"] = bench_gemm_store(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["graph_dme"] = bench_graph(torch, device, B, synth, 10, 2)
     print(json.dumps(out))
 

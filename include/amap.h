@@ -260,6 +260,16 @@ amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t 
 amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
                             void *out, void *stream);
 
+/* The same product with its store rewritten as well (the store side t_s[f_s(i)] = v of
+ * Section 2): out_map is the layout chain that would be applied to the product, as a map
+ * whose single source is the [M,N] product and whose dst is the final tensor.  It must be
+ * a bijection (amap_inverse turns it into the store map) with 8-element aligned contiguous
+ * runs along n; element (m, n) is written straight to its place in `out` (the final tensor,
+ * M*N elements) and the row-major product never exists.  Example: a QKV projection that
+ * writes the head-split layout [3, b, heads, seq, 64] directly. */
+amap_status amap_gemm_fused_store(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
+                                  const amap_t *out_map, void *out, void *stream);
+
 const char *amap_status_str(amap_status s);
 
 /* Text of the HIP error behind the last AMAP_E_HIP returned on this thread

@@ -29,7 +29,7 @@ EXPORTS = [
     "amap_concat",
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
     "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_kernel",
-    "amap_gemm_fused", "amap_status_str", "amap_last_error",
+    "amap_gemm_fused", "amap_gemm_fused_store", "amap_status_str", "amap_last_error",
     "amap_graph_create", "amap_graph_free", "amap_graph_input", "amap_graph_op", "amap_graph_compute",
     "amap_graph_output", "amap_graph_eliminate", "amap_graph_load",
 ]
@@ -87,6 +87,7 @@ _L.amap_plan_selfcheck.argtypes = [_vp, C.c_int, _i64p]
 _L.amap_execute.argtypes = [_pp, _vp, _vp, _vp]
 _L.amap_execute_kernel.argtypes = [_pp, _vp, _vp, _vp, C.c_int]
 _L.amap_gemm_fused.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp]
+_L.amap_gemm_fused_store.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp, _vp]
 _L.amap_status_str.argtypes = [C.c_int]
 _L.amap_status_str.restype = C.c_char_p
 
@@ -314,6 +315,11 @@ def amap_execute_kernel(src_ptrs, dst_ptr, m, stream, kernel_id):
 def amap_gemm_fused(a_src_ptr, a_map, w_ptr, n, out_ptr, stream=0):
     _check(_L.amap_gemm_fused(C.c_void_p(a_src_ptr), a_map.handle, C.c_void_p(w_ptr), int(n),
                               C.c_void_p(out_ptr), C.c_void_p(stream)), "amap_gemm_fused")
+
+
+def amap_gemm_fused_store(a_src_ptr, a_map, w_ptr, n, out_map, out_ptr, stream=0):
+    _check(_L.amap_gemm_fused_store(C.c_void_p(a_src_ptr), a_map.handle, C.c_void_p(w_ptr), int(n), out_map.handle,
+                                    C.c_void_p(out_ptr), C.c_void_p(stream)), "amap_gemm_fused_store")
 
 
 class GraphDME:

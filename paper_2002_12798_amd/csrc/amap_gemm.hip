@@ -17,6 +17,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 
 #include "amap_index.hpp"
 #include "amap_plan.hpp"
@@ -57,6 +58,10 @@ struct GemmArgs {
     uint32_t sbase;
     uint32_t tiles_m, tiles_n;
     Digits dm, dk;
+    // store side (Section 2, eq. "store"): element (m, n) of the product goes to
+    // out[obase + om(m) + on(n)]; store_mapped = 0 means the plain row-major C
+    uint32_t store_mapped, obase;
+    Digits om, on;
 };
 
 __device__ __forceinline__ uint32_t digits_offset(const Digits &d, uint32_t x) {
@@ -213,7 +218,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
     for (int i = 0; i < 16; ++i) {
         const uint32_t v = tid + 256u * i, row = v >> 4, cv = v & 15u;
         const u32x4 x = *reinterpret_cast<const u32x4 *>(smem + row * kCPitch + cv * 16);
-        __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + (size_t)(m0 + row) * g.N + n0 + cv * 8u));
+        size_t off = (size_t)(m0 + row) * g.N + n0 + cv * 8u;
+        if (g.store_mapped) off = g.obase + digits_offset(g.om, m0 + row) + digits_offset(g.on, n0 + cv * 8u);
+        __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + off));
     }
 }
 
@@ -240,8 +247,30 @@ bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d) {
 
 }  // namespace
 
-extern "C" amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N, void *out,
-                                       void *stream) {
+namespace {
+
+// 16-byte vectors along a dimension: its innermost digit must be contiguous on
+// the other side in runs of a multiple of 8 elements, everything else 8-aligned
+bool vector_runs(const Digits &inner, const Digits &outer, int64_t base) {
+    bool inner_ok = false;
+    for (uint32_t j = 0; j < inner.n; ++j) {
+        if (inner.mult[j] == 1)
+            inner_ok = inner.ss[j] == 1 && inner.ext[j] % 8 == 0;
+        else if (inner.ss[j] % 8 != 0 || inner.mult[j] % 8 != 0)
+            return false;
+    }
+    for (uint32_t j = 0; j < outer.n; ++j)
+        if (outer.ss[j] % 8 != 0) return false;
+    return inner_ok && base % 8 == 0;
+}
+
+bool overlaps(const void *a, int64_t an, const void *b, int64_t bn) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + (uintptr_t)bn && b0 < a0 + (uintptr_t)an;
+}
+
+amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, int64_t N, const amap_t *out_map,
+                        void *out, void *stream) {
     if (!A_src || !A_map || !W || !out || N <= 0) return AMAP_E_INVALID;
     if (((uintptr_t)A_src | (uintptr_t)W | (uintptr_t)out) & 15) return AMAP_E_INVALID;
     if (A_map->shape.size() != 2 || A_map->elem != 2) return AMAP_E_INVALID;
@@ -252,28 +281,30 @@ extern "C" amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, c
     const int64_t svol = volume_of(A_map->src_shapes[p.src]);
     if (svol >= (1ll << 31) || M * K >= (1ll << 31) || M * N >= (1ll << 40) || K * N >= (1ll << 31))
         return AMAP_E_UNSUPPORTED;
+    if (out_map && M * N >= (1ll << 31)) return AMAP_E_UNSUPPORTED;  // the store map works in 32-bit offsets
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
     if (!make_digits(p, 0, M, g.dm) || !make_digits(p, 1, K, g.dk)) return AMAP_E_UNSUPPORTED;
-    // 16-byte vectors along k: the innermost k digit must be contiguous in the
-    // source in runs of a multiple of 8 elements, everything else 8-aligned
-    bool inner_ok = false;
-    for (uint32_t j = 0; j < g.dk.n; ++j) {
-        if (g.dk.mult[j] == 1) {
-            inner_ok = g.dk.ss[j] == 1 && g.dk.ext[j] % 8 == 0;
-        } else if (g.dk.ss[j] % 8 != 0 || g.dk.mult[j] % 8 != 0) {
-            return AMAP_E_UNSUPPORTED;
-        }
-    }
-    for (uint32_t j = 0; j < g.dm.n; ++j)
-        if (g.dm.ss[j] % 8 != 0) return AMAP_E_UNSUPPORTED;
-    if (!inner_ok || p.sbase % 8 != 0) return AMAP_E_UNSUPPORTED;
+    if (!vector_runs(g.dk, g.dm, p.sbase)) return AMAP_E_UNSUPPORTED;
     const int64_t cbytes = M * N * 2;
-    auto overlaps = [](const void *a, int64_t an, const void *b, int64_t bn) {
-        const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
-        return a0 < b0 + (uintptr_t)bn && b0 < a0 + (uintptr_t)an;
-    };
     if (overlaps(out, cbytes, A_src, svol * 2) || overlaps(out, cbytes, W, K * N * 2)) return AMAP_E_ALIAS;
+    if (out_map) {
+        // the layout chain applied to the product, turned into a store map: the
+        // reverse of the chain's load map (Section 2.1), C index -> index of out
+        if (out_map->elem != 2 || out_map->src_shapes.size() != 1 || out_map->src_shapes[0].size() != 2 ||
+            out_map->src_shapes[0][0] != M || out_map->src_shapes[0][1] != N)
+            return AMAP_E_INVALID;
+        amap_t *rev = nullptr;
+        amap_status st = amap_inverse(out_map, &rev);
+        if (st != AMAP_OK) return st;  // not a bijection between the product and out
+        std::unique_ptr<amap> hold(rev);
+        if (!rev->strided || rev->pieces.size() != 1 || rev->pieces[0].fill) return AMAP_E_UNSUPPORTED;
+        const Piece &q = rev->pieces[0];
+        if (!make_digits(q, 0, M, g.om) || !make_digits(q, 1, N, g.on)) return AMAP_E_UNSUPPORTED;
+        if (!vector_runs(g.on, g.om, q.sbase)) return AMAP_E_UNSUPPORTED;
+        g.store_mapped = 1;
+        g.obase = (uint32_t)q.sbase;
+    }
 
     g.A_src = static_cast<const uint16_t *>(A_src);
     g.W = static_cast<const uint16_t *>(W);
@@ -303,4 +334,25 @@ extern "C" amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, c
         return AMAP_E_HIP;
     }
     return AMAP_OK;
+}
+
+}  // namespace
+
+extern "C" amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N, void *out,
+                                       void *stream) {
+    try {
+        return gemm_launch(A_src, A_map, W, N, nullptr, out, stream);
+    } catch (...) {
+        return AMAP_E_NOMEM;
+    }
+}
+
+extern "C" amap_status amap_gemm_fused_store(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
+                                             const amap_t *out_map, void *out, void *stream) {
+    if (!out_map) return AMAP_E_INVALID;
+    try {
+        return gemm_launch(A_src, A_map, W, N, out_map, out, stream);
+    } catch (...) {
+        return AMAP_E_NOMEM;
+    }
 }

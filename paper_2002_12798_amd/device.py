@@ -51,11 +51,17 @@ def execute(m, srcs, dst=None, kernel_id=None, stream=None) -> torch.Tensor:
     return dst
 
 
-def gemm_fused(a_src: torch.Tensor, a_map, w: torch.Tensor, out=None, stream=None) -> torch.Tensor:
+def gemm_fused(a_src: torch.Tensor, a_map, w: torch.Tensor, out=None, stream=None, out_map=None) -> torch.Tensor:
+    """out = A x W with A read through a_map; with out_map the product is stored through
+    that map (out then has out_map's dst shape)."""
     info = B.amap_describe(a_map)
     n = w.shape[1]
     if out is None:
-        out = torch.empty((info.shape[0], n), dtype=torch.int16, device=require_gpu())
-    B.amap_gemm_fused(a_src.data_ptr(), a_map, w.data_ptr(), n, out.data_ptr(),
-                      current_stream() if stream is None else stream)
+        shape = (info.shape[0], n) if out_map is None else B.dst_shape(out_map)
+        out = torch.empty(shape, dtype=torch.int16, device=require_gpu())
+    st = current_stream() if stream is None else stream
+    if out_map is None:
+        B.amap_gemm_fused(a_src.data_ptr(), a_map, w.data_ptr(), n, out.data_ptr(), st)
+    else:
+        B.amap_gemm_fused_store(a_src.data_ptr(), a_map, w.data_ptr(), n, out_map, out.data_ptr(), st)
     return out
