@@ -240,9 +240,20 @@ amap_status amap_graph_load(const amap_graph_t *g, int index, int *consumer, int
 /* dst[i] = src[src_id][g(i)] or fill, for every index i of dst: the rewritten
  * load v' = t_l[g'(i')] of eq. 4 executed for the whole chain by one kernel
  * per group of pieces (one launch for every map in the five workloads).
- * src has n_src entries, indexed by source id.  dst must not overlap any
- * source (AMAP_E_ALIAS).  dst is fully overwritten. */
+ * src has n_src entries, indexed by source id (entries of ids the map no longer
+ * reads may be NULL).  dst must not overlap any source (AMAP_E_ALIAS).  dst is
+ * fully overwritten.  Tensors may exceed 2^31 elements when the map has a
+ * strided form; AMAP_E_UNSUPPORTED if such a map needs the element-wise
+ * interpreter. */
 amap_status amap_execute(const void *const *src, void *dst, const amap_t *map, void *stream);
+
+/* Several maps over ONE source table executed together (a split: one tensor feeding
+ * several outputs, e.g. Q, K and V; eq. 4 applied to every consumer of the same t_l):
+ * dst[i] receives maps[i].  The pieces of all maps share launches, so n small outputs
+ * cost one launch, not n.  All maps must have the same element size; the dst buffers
+ * must not overlap each other or a source. */
+amap_status amap_execute_multi(const void *const *src, void *const *dst, const amap_t *const *maps, int n,
+                               void *stream);
 
 /* Same, with the kernel family forced (amap_kernel_id) instead of planned:
  * for A/B measurements and for tests of every family on every map.

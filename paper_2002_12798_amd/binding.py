@@ -28,7 +28,7 @@ EXPORTS = [
     "amap_source", "amap_transpose", "amap_reshape", "amap_slice", "amap_repeat", "amap_tile", "amap_pad",
     "amap_concat",
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
-    "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_kernel",
+    "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_multi", "amap_execute_kernel",
     "amap_gemm_fused", "amap_gemm_fused_store", "amap_status_str", "amap_last_error",
     "amap_graph_create", "amap_graph_free", "amap_graph_input", "amap_graph_op", "amap_graph_compute",
     "amap_graph_output", "amap_graph_eliminate", "amap_graph_load",
@@ -86,6 +86,7 @@ _L.amap_check_cover.argtypes = [_vp, _i64p, _i64p]
 _L.amap_plan_selfcheck.argtypes = [_vp, C.c_int, _i64p]
 _L.amap_execute.argtypes = [_pp, _vp, _vp, _vp]
 _L.amap_execute_kernel.argtypes = [_pp, _vp, _vp, _vp, C.c_int]
+_L.amap_execute_multi.argtypes = [_pp, _pp, _pp, C.c_int, _vp]
 _L.amap_gemm_fused.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp]
 _L.amap_gemm_fused_store.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp, _vp]
 _L.amap_status_str.argtypes = [C.c_int]
@@ -310,6 +311,13 @@ def amap_execute(src_ptrs, dst_ptr, m, stream=0, kernel_id=None):
 
 def amap_execute_kernel(src_ptrs, dst_ptr, m, stream, kernel_id):
     amap_execute(src_ptrs, dst_ptr, m, stream, kernel_id)
+
+
+def amap_execute_multi(src_ptrs, dst_ptrs, maps, stream=0):
+    """One source table, several (map, dst) pairs, packed into shared launches."""
+    handles = (C.c_void_p * len(maps))(*[m.handle for m in maps])
+    _check(_L.amap_execute_multi(_ptr_array(src_ptrs), _ptr_array(dst_ptrs), handles, len(maps), C.c_void_p(stream)),
+           "amap_execute_multi")
 
 
 def amap_gemm_fused(a_src_ptr, a_map, w_ptr, n, out_ptr, stream=0):

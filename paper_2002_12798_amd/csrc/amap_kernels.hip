@@ -307,12 +307,13 @@ __global__ __launch_bounds__(kMaxThreads) void amap_pieces_kernel(const LaunchAr
         if (args.p[k].n_blocks && b >= args.p[k].first_block) pi = k;
     const DevPiece &P = args.p[pi];
     const uint32_t local = b - P.first_block;
+    char *const d = dst + (size_t)P.dwin * ES;
     if (P.kind == PK_ROWS)
-        rows_body<ES, NT>(P, dst, local, threadIdx.x);
+        rows_body<ES, NT>(P, d, local, threadIdx.x);
     else if (P.kind == PK_TILE)
-        tile_dispatch<ES, true, NT, GROUPED>(P, dst, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
+        tile_dispatch<ES, true, NT, GROUPED>(P, d, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
     else
-        tile_dispatch<ES, false, NT, GROUPED>(P, dst, local, threadIdx.x, nullptr);
+        tile_dispatch<ES, false, NT, GROUPED>(P, d, local, threadIdx.x, nullptr);
 }
 
 // ------------------------------------------------------------------ program
@@ -431,18 +432,12 @@ amap_status check_pointers(const amap *m, const void *const *src, const void *ds
     return AMAP_OK;
 }
 
-amap_status launch_strided(const amap *m, const Plan &plan, const void *const *src, void *dst, hipStream_t stream) {
-    for (size_t i = 0; i < plan.launches.size(); ++i) {
-        LaunchArgs args = plan.launches[i];
-        bool grouped = false;
-        for (uint32_t k = 0; k < args.n_pieces; ++k) {
-            const uintptr_t id = (uintptr_t)args.p[k].src;
-            args.p[k].src = id ? src[id - 1] : nullptr;
-            grouped = grouped || (args.p[k].kind != PK_ROWS && args.p[k].group_n > 1);
-        }
-        const dim3 grid(plan.grid[i]), block(64u << args.nwlog);
-        const size_t lds = plan.lds_bytes[i];
-        char *d = (char *)dst;
+// one launch of the piece kernel; args.p[].src must already hold device pointers
+amap_status launch_pieces(const LaunchArgs &args, uint32_t blocks, size_t lds, int es, char *d, hipStream_t stream) {
+    bool grouped = false;
+    for (uint32_t k = 0; k < args.n_pieces; ++k)
+        grouped = grouped || (args.p[k].kind != PK_ROWS && args.p[k].group_n > 1);
+    const dim3 grid(blocks), block(64u << args.nwlog);
 #define AMAP_LAUNCH(ES, NT)                                                                                  \
     do {                                                                                                     \
         if (grouped)                                                                                         \
@@ -450,18 +445,33 @@ amap_status launch_strided(const amap *m, const Plan &plan, const void *const *s
         else                                                                                                 \
             hipLaunchKernelGGL((amap_pieces_kernel<ES, NT, false>), grid, block, lds, stream, args, d);      \
     } while (0)
-        switch ((m->elem == 2 ? 0 : 4) + (int)(args.nt & 3)) {
-        case 0: AMAP_LAUNCH(2, 0); break;
-        case 1: AMAP_LAUNCH(2, 1); break;
-        case 2: AMAP_LAUNCH(2, 2); break;
-        case 3: AMAP_LAUNCH(2, 3); break;
-        case 4: AMAP_LAUNCH(4, 0); break;
-        case 5: AMAP_LAUNCH(4, 1); break;
-        case 6: AMAP_LAUNCH(4, 2); break;
-        default: AMAP_LAUNCH(4, 3); break;
-        }
+    switch ((es == 2 ? 0 : 4) + (int)(args.nt & 3)) {
+    case 0: AMAP_LAUNCH(2, 0); break;
+    case 1: AMAP_LAUNCH(2, 1); break;
+    case 2: AMAP_LAUNCH(2, 2); break;
+    case 3: AMAP_LAUNCH(2, 3); break;
+    case 4: AMAP_LAUNCH(4, 0); break;
+    case 5: AMAP_LAUNCH(4, 1); break;
+    case 6: AMAP_LAUNCH(4, 2); break;
+    default: AMAP_LAUNCH(4, 3); break;
+    }
 #undef AMAP_LAUNCH
-        if (launch_failed("amap_pieces_kernel")) return AMAP_E_HIP;
+    return launch_failed("amap_pieces_kernel") ? AMAP_E_HIP : AMAP_OK;
+}
+
+void patch_sources(LaunchArgs &args, const void *const *src, int es) {
+    for (uint32_t k = 0; k < args.n_pieces; ++k) {
+        const uintptr_t id = (uintptr_t)args.p[k].src;
+        args.p[k].src = id ? (const char *)src[id - 1] + (size_t)args.p[k].swin * (size_t)es : nullptr;
+    }
+}
+
+amap_status launch_strided(const amap *m, const Plan &plan, const void *const *src, void *dst, hipStream_t stream) {
+    for (size_t i = 0; i < plan.launches.size(); ++i) {
+        LaunchArgs args = plan.launches[i];
+        patch_sources(args, src, m->elem);
+        amap_status st = launch_pieces(args, plan.grid[i], plan.lds_bytes[i], m->elem, (char *)dst, stream);
+        if (st != AMAP_OK) return st;
     }
     return AMAP_OK;
 }
@@ -494,8 +504,9 @@ extern "C" amap_status amap_execute_kernel(const void *const *src, void *dst, co
     try {
         if (kernel_id < 0) {
             const Plan *plan = plan_of(*map);
-            if (!plan || !plan->fits32) return AMAP_E_UNSUPPORTED;
+            if (!plan) return AMAP_E_UNSUPPORTED;
             if (plan->strided_ok) return launch_strided(map, *plan, src, dst, s);
+            if (!plan->fits32) return AMAP_E_UNSUPPORTED;  // the interpreter works in 32-bit indices
             return launch_program(map, *plan, src, dst, s);
         }
         Plan forced;
@@ -512,6 +523,90 @@ extern "C" amap_status amap_execute_kernel(const void *const *src, void *dst, co
 }
 
 extern "C" const char *amap_last_error(void) { return g_last_error; }
+
+// Several maps over one source table, each with its own dst, in as few launches
+// as their pieces fit: the pieces of all maps are packed into shared launches,
+// every piece carrying the offset of its own dst from the lowest dst address.
+extern "C" amap_status amap_execute_multi(const void *const *src, void *const *dst, const amap_t *const *maps, int n,
+                                          void *stream) {
+    if (!dst || !maps || n < 1) return AMAP_E_INVALID;
+    for (int i = 0; i < n; ++i)
+        if (!maps[i] || !dst[i]) return AMAP_E_INVALID;
+    const int es = maps[0]->elem;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    try {
+        uintptr_t base = UINTPTR_MAX;
+        for (int i = 0; i < n; ++i) {
+            const amap *m = maps[i];
+            if (m->elem != es) return AMAP_E_INVALID;
+            if (volume_of(m->shape) == 0) continue;
+            if (!src && !m->src_shapes.empty()) return AMAP_E_INVALID;
+            amap_status st = check_pointers(m, src, dst[i]);
+            if (st != AMAP_OK) return st;
+            for (int j = 0; j < i; ++j)
+                if (volume_of(maps[j]->shape) > 0 &&
+                    overlaps(dst[i], volume_of(m->shape) * es, dst[j], volume_of(maps[j]->shape) * es))
+                    return AMAP_E_ALIAS;
+            base = std::min(base, (uintptr_t)dst[i]);
+        }
+        if (base == UINTPTR_MAX) return AMAP_OK;  // nothing to write
+        LaunchArgs cur;
+        uint32_t blocks = 0, lds = 0;
+        std::memset(&cur, 0, sizeof(cur));
+        auto flush = [&]() -> amap_status {
+            if (cur.n_pieces == 0) return AMAP_OK;
+            amap_status st = launch_pieces(cur, blocks, lds, es, reinterpret_cast<char *>(base), s);
+            std::memset(&cur, 0, sizeof(cur));
+            blocks = 0;
+            lds = 0;
+            return st;
+        };
+        for (int i = 0; i < n; ++i) {
+            const amap *m = maps[i];
+            if (volume_of(m->shape) == 0) continue;
+            const Plan *plan = plan_of(*m);
+            if (!plan) return AMAP_E_UNSUPPORTED;
+            if (!plan->strided_ok) {  // no strided form: this one runs on its own, through the interpreter
+                amap_status st = flush();
+                if (st != AMAP_OK) return st;
+                if (!plan->fits32) return AMAP_E_UNSUPPORTED;
+                st = launch_program(m, *plan, src, dst[i], s);
+                if (st != AMAP_OK) return st;
+                continue;
+            }
+            const uint64_t shift = ((uintptr_t)dst[i] - base) / (uint64_t)es;  // dst pointers are 16-byte aligned
+            for (size_t j = 0; j < plan->launches.size(); ++j) {
+                LaunchArgs a = plan->launches[j];
+                patch_sources(a, src, es);
+                const bool fits = cur.n_pieces == 0 ||
+                                  (cur.nwlog == a.nwlog && cur.n_pieces + a.n_pieces <= (uint32_t)kMaxPiecesPerLaunch &&
+                                   (uint64_t)blocks + plan->grid[j] < (1u << 31));
+                if (!fits) {
+                    amap_status st = flush();
+                    if (st != AMAP_OK) return st;
+                }
+                if (cur.n_pieces == 0) {
+                    cur.nwlog = a.nwlog;
+                    cur.nt = a.nt;
+                } else {
+                    cur.nt &= a.nt;
+                }
+                cur.xcd_remap |= a.xcd_remap;
+                for (uint32_t k = 0; k < a.n_pieces; ++k) {
+                    DevPiece p = a.p[k];
+                    p.first_block += blocks;
+                    p.dwin += shift;
+                    cur.p[cur.n_pieces++] = p;
+                }
+                blocks += plan->grid[j];
+                lds = std::max<uint32_t>(lds, plan->lds_bytes[j]);
+            }
+        }
+        return flush();
+    } catch (...) {
+        return AMAP_E_NOMEM;
+    }
+}
 
 extern "C" amap_status amap_execute(const void *const *src, void *dst, const amap_t *map, void *stream) {
     return amap_execute_kernel(src, dst, map, stream, -1);

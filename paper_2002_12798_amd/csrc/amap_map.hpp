@@ -76,6 +76,10 @@ struct KPiece {
     uint32_t fill_bits = 0;
     int src = -1;
     int64_t dbase = 0, sbase = 0;
+    // Set by the launch planner only: element offsets of the piece's window on
+    // either side.  Once set, dbase / sbase are relative to them, so that every
+    // offset inside the piece fits 32 bits even in tensors of 2^31 elements and more.
+    int64_t dwin = 0, swin = 0;
     std::vector<KDim> dims;
     int64_t volume() const {
         int64_t v = 1;

@@ -100,6 +100,8 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     dp.fill = replicate_fill(kp.fill_bits, es);
     dp.dbase = (uint32_t)kp.dbase;
     dp.sbase = (uint32_t)kp.sbase;
+    dp.dwin = (uint64_t)kp.dwin;
+    dp.swin = (uint64_t)kp.swin;
     dp.group_n = 1;
     lds = 0;
     const int n = (int)kp.dims.size();
@@ -449,6 +451,7 @@ static bool plan_group(const amap &m, const std::vector<Member> &g, int family, 
         } else {
             s.src = reinterpret_cast<const void *>((uintptr_t)(kp.src + 1));
             s.sbase = (uint32_t)kp.sbase;
+            s.swin = (uint64_t)kp.swin;
             s.ssP = (int32_t)mem.dims[iP].ss;
             std::vector<int64_t> bss;
             for (uint32_t k = 0; k < s.nloops; ++k) {
@@ -481,7 +484,7 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
     out.fits32 = volume_of(m.shape) < (1ll << 31);
     for (const auto &s : m.src_shapes)
         if (!s.empty() && volume_of(s) >= (1ll << 31)) out.fits32 = false;
-    if (!m.strided || !out.fits32) return false;
+    if (!m.strided) return false;
     // workgroup size: single wavefronts balance small problems over the
     // 256 compute units and keep the tail short; large problems amortise
     // dispatch with 4 wavefronts per workgroup
@@ -539,7 +542,7 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
     };
     // groups of pieces that are neighbours along the dst-contiguous dimension
     std::vector<char> grouped(m.kpieces.size(), 0);
-    if ((family < 0 || family == AMAP_K_TILE || family == AMAP_K_WAVE) && env_int("AMAP_GROUPS", 1)) {
+    if ((family < 0 || family == AMAP_K_TILE || family == AMAP_K_WAVE) && env_int("AMAP_GROUPS", 1) && !out.windowed) {
         std::vector<char> in_group;
         for (const auto &g : find_groups(m, in_group)) {
             std::vector<DevPiece> dps;
@@ -622,6 +625,70 @@ static std::vector<KPiece> split_ragged(const KPiece &kp, int es) {
     return out;
 }
 
+// Largest span (in elements) a piece may cover on either side: offsets inside a
+// piece are 32-bit.  Lowering it (tests) makes small tensors take the path of
+// tensors with 2^31 elements and more.
+static int64_t span_limit() {
+    const int bits = env_int("AMAP_MAX_SPAN_LOG2", 31);
+    return 1ll << std::min(31, std::max(8, bits));
+}
+
+// Give every piece a window (a 64-bit origin on each side, multiples of 64
+// elements so that vector and line alignment are unchanged) and cut pieces
+// that span more than the limit along the loop that contributes most.
+static bool window_pieces(std::vector<KPiece> &ks, int64_t limit) {
+    std::vector<KPiece> out;
+    std::vector<KPiece> work(ks.rbegin(), ks.rend());
+    while (!work.empty()) {
+        KPiece p = std::move(work.back());
+        work.pop_back();
+        int64_t dspan = 0, s_lo = 0, s_hi = 0, worst = -1;
+        int at = -1;
+        for (int k = 0; k < (int)p.dims.size(); ++k) {
+            const KDim &d = p.dims[k];
+            const int64_t dd = (d.extent - 1) * d.ds, ss = (d.extent - 1) * d.ss;
+            dspan += dd;
+            (ss < 0 ? s_lo : s_hi) += ss;
+            const int64_t c = std::max(dd, ss < 0 ? -ss : ss);
+            if (d.extent > 1 && c > worst) {
+                worst = c;
+                at = k;
+            }
+        }
+        // 64 elements of slack for the rounding of the window origin, one vector for masked lanes
+        if (dspan + 128 < limit && (p.fill || s_hi - s_lo + 128 < limit)) {
+            p.dwin = p.dbase / 64 * 64;
+            p.dbase -= p.dwin;
+            if (!p.fill) {
+                const int64_t lo = p.sbase + s_lo;
+                p.swin = lo / 64 * 64;
+                p.sbase -= p.swin;
+            }
+            out.push_back(std::move(p));
+            continue;
+        }
+        if (at < 0 || out.size() + work.size() > 100000) return false;
+        // cut loop `at` in two; keep the first part a whole number of vectors where it is the row loop
+        const KDim d = p.dims[at];
+        int64_t half = d.extent / 2;
+        if (half > 64) half = half / 64 * 64;
+        KPiece a = p, b = p;
+        a.dims[at].extent = half;
+        b.dims[at].extent = d.extent - half;
+        b.dbase += half * d.ds;
+        b.sbase += half * d.ss;
+        for (KPiece *q : {&b, &a}) {
+            std::vector<KDim> dd;
+            for (const KDim &x : q->dims)
+                if (x.extent > 1) dd.push_back(x);
+            q->dims = merge_loops(std::move(dd));
+            work.push_back(std::move(*q));
+        }
+    }
+    ks = std::move(out);
+    return true;
+}
+
 bool plan_strided(const amap &m0, int family, Plan &out) {
     amap m = m0;  // the planner's own piece list: ragged pieces cut into main part + tails
     m.plan.reset();
@@ -630,6 +697,21 @@ bool plan_strided(const amap &m0, int family, Plan &out) {
         for (const KPiece &kp : m0.kpieces)
             for (KPiece &p : split_ragged(kp, m.elem)) ks.push_back(std::move(p));
         if (ks.size() <= 4 * m0.kpieces.size() + 8) m.kpieces = std::move(ks);
+    }
+    out.windowed = false;
+    if (m.strided) {
+        const int64_t limit = span_limit();
+        bool big = volume_of(m.shape) >= limit;
+        for (const auto &s : m.src_shapes)
+            if (!s.empty() && volume_of(s) >= limit) big = true;
+        if (big) {
+            if (!window_pieces(m.kpieces, limit)) {
+                out.strided_ok = false;
+                out.fits32 = false;
+                return false;
+            }
+            out.windowed = true;
+        }
     }
     const int nw_env = env_int("AMAP_WAVES_LOG", -1);
     bool split_rows = false;

@@ -11,6 +11,7 @@ namespace amap_detail {
 struct Plan {
     bool fits32 = true;                         // every tensor has < 2^31 elements
     bool strided_ok = false;                    // launches[] is valid
+    bool windowed = false;                      // pieces carry 64-bit window origins (a tensor exceeds 32-bit offsets)
     std::vector<amap_dev::LaunchArgs> launches; // DevPiece::src holds (source id + 1) until launch
     std::vector<uint32_t> grid;                 // workgroups per launch
     std::vector<uint32_t> lds_bytes;            // dynamic LDS per launch

@@ -54,7 +54,8 @@ struct Replay {
                 if (r >= P.n_units) continue;
                 uint32_t d, s;
                 rows_offsets(P, r, d, s);
-                for (uint32_t e = 0; e < V; ++e) write((int64_t)d + e, code_of(sid, (int64_t)s + (e >> P.rep_log)));
+                for (uint32_t e = 0; e < V; ++e)
+                    write((int64_t)P.dwin + d + e, code_of(sid, (int64_t)P.swin + s + (e >> P.rep_log)));
             }
     }
 
@@ -77,7 +78,7 @@ struct Replay {
             for (uint32_t j = 0; j < V; ++j) {
                 // out[j] = elements along P (i = 0..V-1) at Q position w0 + j: in[i].elem[j]
                 for (uint32_t i = 0; i < V; ++i) {
-                    const int64_t code = code_of(sid, (int64_t)L.soff + (int64_t)i * L.ssP + j);
+                    const int64_t code = code_of(sid, (int64_t)(&P)[L.sub].swin + L.soff + (int64_t)i * L.ssP + j);
                     if (use_lds) {
                         const uint64_t slot = tile_lds_slot(G, vlog, L.r0 + j, L.pvl);
                         const uint64_t at = slot * V + i;
@@ -86,7 +87,7 @@ struct Replay {
                         else
                             lds[at] = code;
                     } else {
-                        write((int64_t)G.db + q_chain_offset(P, L.w0 + j) + L.p + i, code);
+                        write((int64_t)P.dwin + G.db + q_chain_offset(P, L.w0 + j) + L.p + i, code);
                     }
                 }
             }
@@ -102,7 +103,7 @@ struct Replay {
                     ++errors;
                     continue;
                 }
-                write((int64_t)S.doff + i, lds[at]);
+                write((int64_t)P.dwin + S.doff + i, lds[at]);
             }
         }
     }

@@ -51,6 +51,15 @@ def execute(m, srcs, dst=None, kernel_id=None, stream=None) -> torch.Tensor:
     return dst
 
 
+def execute_multi(maps, srcs, dsts=None, stream=None):
+    """dsts[i] <- maps[i](srcs), all maps in shared launches; returns the dst tensors."""
+    if dsts is None:
+        dsts = [empty_dst(m) for m in maps]
+    B.amap_execute_multi([0 if s is None else s.data_ptr() for s in srcs], [d.data_ptr() for d in dsts], maps,
+                         current_stream() if stream is None else stream)
+    return dsts
+
+
 def gemm_fused(a_src: torch.Tensor, a_map, w: torch.Tensor, out=None, stream=None, out_map=None) -> torch.Tensor:
     """out = A x W with A read through a_map; with out_map the product is stored through
     that map (out then has out_map's dst shape)."""

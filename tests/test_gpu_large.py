@@ -1,0 +1,107 @@
+"""GPU parity beyond 32-bit offsets: tensors of more than 2^31 elements (pieces run in 64-bit
+windows), and the same code path forced on small tensors by lowering the span limit."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2002_12798_amd import binding as B
+from paper_2002_12798_amd import synth
+from tests import chains
+from tests.test_plan_replay import ALIGNED
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    from paper_2002_12798_amd import device
+    device.require_gpu()
+    return device
+
+
+def _run(dev, m, srcs, want):
+    import torch
+    dst = dev.empty_dst(m, fill=0x5A5A if want.dtype.itemsize == 2 else 0x5A5A5A5A)
+    dev.execute(m, [dev.to_device(s) for s in srcs], dst)
+    torch.cuda.synchronize()
+    got = dev.to_host(dst)
+    assert got.shape == want.shape
+    assert np.array_equal(got, want)
+
+
+def test_small_tensors_through_the_window_path(dev, monkeypatch):
+    monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "10")
+    for case, (shape, es, ops) in enumerate(ALIGNED):
+        print(f"[gpu] windowed aligned case {case}", flush=True)
+        srcs = [synth.random_bits(shape, es, 40 + case)]
+        _run(dev, B.amap_compose([shape], es, ops), srcs, oracle.run_chain(srcs, ops))
+    for seed in range(60):
+        print(f"[gpu] windowed random chain {seed}", flush=True)
+        src_shapes, ops = chains.random_chain(seed, extended=seed % 2 == 0, max_volume=60000)
+        es = 2 if seed % 3 else 4
+        srcs = [synth.random_bits(s, es, 3000 + seed + i) for i, s in enumerate(src_shapes)]
+        m = B.amap_compose(src_shapes, es, ops)
+        if B.amap_describe(m).strided:
+            _run(dev, m, srcs, oracle.run_chain(srcs, ops))
+    monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "14")
+    w = synth.workload("cfg1", n=1)
+    srcs = w.sources()
+    _run(dev, B.amap_compose(w.src_shapes, w.elem_size, w.ops), srcs, oracle.run_chain(srcs, w.ops))
+
+
+def _host_gib():
+    try:
+        return os.sysconf("SC_PHYS_PAGES") * os.sysconf("SC_PAGE_SIZE") / 2 ** 30
+    except (ValueError, OSError):
+        return 0.0
+
+
+_BIG = {}
+
+
+def _big_input(shape):
+    """x[r, c] = a 16-bit mix of r and c (wrapping uint16 arithmetic; built once, in slabs of rows):
+    neighbouring rows and columns differ, so a shifted or transposed index shows."""
+    if shape not in _BIG:
+        x = np.empty(shape, dtype=np.uint16)
+        col = (np.arange(shape[1], dtype=np.uint32) * 25173).astype(np.uint16)[None, :]
+        for r in range(0, shape[0], 4000):
+            rows = np.arange(r, min(r + 4000, shape[0]), dtype=np.uint32)
+            rmix = ((rows * 40503) ^ (rows >> 5)).astype(np.uint16)[:, None]
+            np.add(rmix, col, out=x[r:r + 4000])
+        _BIG[shape] = x
+    return _BIG[shape]
+
+
+@pytest.mark.parametrize("ops", [
+    [("slice", 1, 0, 32992, 1), ("slice", 0, 65999, -1, -1)],     # row copy, rows walked backwards
+    [("transpose", (1, 0))],                                      # tile transpose
+])
+def test_more_than_2_31_elements(dev, ops):
+    import torch
+    shape = (66000, 33000)                                         # 2.178e9 two-byte elements, 4.36 GB
+    free, _ = torch.cuda.mem_get_info()
+    if free < 12 * 2 ** 30 or _host_gib() < 40:
+        pytest.skip("needs 12 GiB of device memory and 40 GiB of host memory")
+    print(f"[gpu] large tensor {shape} {ops}", flush=True)
+    x = _big_input(shape)
+    m = B.amap_compose([shape], 2, ops)
+    info = B.amap_describe(m)
+    assert info.strided and info.write_bytes > 2 ** 32
+    oracle.set_threads(16)
+    try:
+        want = oracle.run_chain([x], ops)
+    finally:
+        oracle.set_threads(1)
+    d_src = dev.to_device(x)
+    dst = dev.execute(m, [d_src])
+    torch.cuda.synchronize()
+    got = dev.to_host(dst)
+    del d_src, dst
+    torch.cuda.empty_cache()
+    assert got.shape == want.shape
+    # compare in slabs to keep the temporaries small
+    for r in range(0, want.shape[0], 4096):
+        assert np.array_equal(got[r:r + 4096], want[r:r + 4096]), r

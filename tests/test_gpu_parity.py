@@ -185,3 +185,36 @@ def test_non_default_stream(dev):
         dst = dev.execute(m, d)
     s.synchronize()
     assert np.array_equal(dev.to_host(dst), want)
+
+
+def test_execute_multi_split_outputs(dev):
+    """One source, several outputs in one call: Q, K and V as separate tensors, then a mixed bag."""
+    import torch
+    w = synth.workload("cfg2_fwd", b=2)
+    srcs = w.sources()
+    maps = [B.amap_compose(w.src_shapes, 2, synth.split_qkv_ops(t, b=2)) for t in range(3)]
+    outs = dev.execute_multi(maps, [dev.to_device(srcs[0])])
+    torch.cuda.synchronize()
+    for t in range(3):
+        assert np.array_equal(dev.to_host(outs[t]), oracle.run_chain(srcs, synth.split_qkv_ops(t, b=2))), t
+    # maps of different kernel families, a fill-only one, an empty one and more pieces than one launch holds
+    shape = (6, 40, 72)
+    x = synth.random_bits(shape, 2, 123)
+    chains_ = [
+        [("transpose", (0, 2, 1))],
+        [("slice", 1, 39, -1, -1)],
+        [("pad", (1, 2, 3), (3, 2, 1), 0xBEEF)],
+        [("repeat", 2, 2), ("transpose", (2, 0, 1))],
+        [("slice", 0, 0, 1, 1), ("pad", (0, 1, 8), (0, 1, 8), 7), ("transpose", (0, 2, 1))],
+        [("reshape", (240, 72)), ("slice", 0, 3, 230, 7)],
+    ]
+    maps = [B.amap_compose([shape], 2, ops) for ops in chains_]
+    outs = dev.execute_multi(maps, [dev.to_device(x)])
+    torch.cuda.synchronize()
+    for ops, o in zip(chains_, outs):
+        assert np.array_equal(dev.to_host(o), oracle.run_chain([x], ops)), ops
+    # overlapping outputs are refused
+    d = dev.empty_dst(maps[0])
+    with pytest.raises(B.AmapError) as e:
+        B.amap_execute_multi([dev.to_device(x).data_ptr()], [d.data_ptr(), d.data_ptr()], [maps[0], maps[0]], 0)
+    assert e.value.status == B.AMAP_E_ALIAS

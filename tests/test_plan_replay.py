@@ -89,3 +89,37 @@ def test_aligned_plans(case):
     m = B.amap_compose([shape], es, ops)
     assert B.amap_describe(m).strided
     assert _replay_all(m) >= 2
+
+
+# ---- tensors beyond 32-bit offsets: every piece gets a 64-bit window origin and pieces that span
+# too much are cut.  The span limit is lowered so that small tensors take that path.
+
+@pytest.fixture
+def tiny_windows(monkeypatch):
+    monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "10")   # at most 1024 elements per piece and side
+    yield
+    monkeypatch.delenv("AMAP_MAX_SPAN_LOG2")
+
+
+def test_windowed_plans_of_aligned_cases(tiny_windows):
+    for shape, es, ops in ALIGNED:
+        m = B.amap_compose([shape], es, ops)
+        assert B.amap_describe(m).strided
+        assert _replay_all(m) >= 2, (shape, ops)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_windowed_plans_of_random_chains(tiny_windows, block):
+    for seed in range(block * 50, block * 50 + 50):
+        src_shapes, ops = chains.random_chain(seed, extended=seed % 2 == 0, max_volume=60000)
+        m = B.amap_compose(src_shapes, 2 if seed % 3 else 4, ops)
+        if B.amap_describe(m).strided:
+            _replay_all(m)
+
+
+def test_windowed_plans_of_scaled_workloads(monkeypatch):
+    monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "14")   # cfg1's channel loop moves 3136 source elements per step
+    for name, kw in [("cfg0", {}), ("cfg1", {"n": 1}), ("cfg2_fwd", {"b": 1}), ("cfg2_rev", {"b": 1}), ("cfg3", {"n": 1})]:
+        w = synth.workload(name, **kw)
+        m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
+        assert B.amap_plan_selfcheck(m, -1) == 0, name
