@@ -190,6 +190,43 @@ def bench_gemm_store(torch, device, B, synth, steps, warmup):
             "unfused_ms": round(u_gpu, 5), "speedup_vs_unfused": round(u_gpu / f_gpu, 3)}
 
 
+def bench_multi(torch, device, B, synth, steps, warmup):
+    """Q, K and V of cfg2-fwd as three separately allocated outputs: three amap_execute calls
+    against one amap_execute_multi call (the same pieces, packed into one launch)."""
+    w = synth.workload("cfg2_fwd")
+    maps = [B.amap_compose(w.src_shapes, 2, synth.split_qkv_ops(t)) for t in range(3)]
+    handles = (C.c_void_p * 3)(*[m.handle for m in maps])
+    stream = C.c_void_p(device.current_stream())
+    host = w.sources()
+    per_set = 2 * host[0].nbytes
+    sets = []
+    for _ in range(max(2, -(-COLD_FOOTPRINT // per_set))):
+        src = device.to_device(host[0])
+        dsts = [device.empty_dst(m) for m in maps]
+        sets.append((src, dsts, (C.c_void_p * 1)(src.data_ptr()), (C.c_void_p * 3)(*[d.data_ptr() for d in dsts])))
+
+    def separate(s):
+        for t in range(3):
+            st = B.raw.amap_execute(s[2], C.c_void_p(s[1][t].data_ptr()), maps[t].handle, stream)
+            if st != 0:
+                raise RuntimeError(B.amap_status_str(st))
+
+    def together(s):
+        st = B.raw.amap_execute_multi(s[2], s[3], handles, 3, stream)
+        if st != 0:
+            raise RuntimeError(B.amap_status_str(st))
+
+    s_wall, s_gpu = _time_launches(torch, separate, sets, steps, warmup)
+    t_wall, t_gpu = _time_launches(torch, together, sets, steps, warmup)
+    nbytes = 2 * host[0].nbytes
+    del sets
+    torch.cuda.empty_cache()
+    return {"workload": "cfg2-fwd head split into three separately allocated outputs [16,12,512,64]",
+            "min_bytes": nbytes, "three_calls_ms": round(s_gpu, 5), "three_calls_gbs": round(nbytes / s_gpu / 1e6, 1),
+            "one_multi_call_ms": round(t_gpu, 5), "one_multi_call_gbs": round(nbytes / t_gpu / 1e6, 1),
+            "speedup": round(s_gpu / t_gpu, 3)}
+
+
 def bench_graph(torch, device, B, synth, steps, warmup):
     """Graph-level data-movement elimination on the synthetic WaveNet-like graph: time of all
     layout operators run one at a time (each a materialising copy) against the composed maps
@@ -344,6 +381,7 @@ def main():
             r = bench_workload(torch, device, B, synth, name, a.steps, a.warmup)
             nxt[r["workload"]] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
         print(json.dumps({"repeat_tile_reverse": nxt, "graph_dme": bench_graph(torch, device, B, synth, 10, 2),
+                          "execute_multi": bench_multi(torch, device, B, synth, a.steps, a.warmup),
                           "fused_gemm_store": bench_gemm_store(torch, device, B, synth, a.steps, a.warmup)}))
         return
     if a.fused_only:
@@ -390,6 +428,7 @@ def main():
             nxt[r["workload"]] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
         out["repeat_tile_reverse"] = nxt
         out["fused_gemm_store"] = bench_gemm_store(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
+        out["execute_multi"] = bench_multi(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["graph_dme"] = bench_graph(torch, device, B, synth, 10, 2)
     print(json.dumps(out))
 
