@@ -137,12 +137,24 @@ def bench_gemm(torch, device, B, synth, steps, warmup):
         if st != 0:
             raise RuntimeError(B.amap_status_str(st))
 
+    # the same product with the weight kept transposed ([N,K], read through a transpose map):
+    # its k runs go to LDS as they are, no transposition in registers
+    wt_map = B.amap_compose([(N, K)], 2, [("transpose", (1, 0))])
+
+    def fused_wt(s):
+        st = B.raw.amap_gemm_mapped(C.c_void_p(s[0].data_ptr()), m.handle, C.c_void_p(s[1].data_ptr()), wt_map.handle,
+                                    None, C.c_void_p(s[2].data_ptr()), stream)
+        if st != 0:
+            raise RuntimeError(B.amap_status_str(st))
+
     f_wall, f_gpu = _time_launches(torch, fused, sets, steps, warmup)
     u_wall, u_gpu = _time_launches(torch, unfused, sets, steps, warmup)
+    t_wall, t_gpu = _time_launches(torch, fused_wt, sets, steps, warmup)
     flops = 2.0 * M * N * K
     del sets
     torch.cuda.empty_cache()
     return {"workload": "cfg4: C[8192,4096] = A[8192,1024] x W[1024,4096], A read through permute+reshape of [16,16,512,64]",
+            "fused_transposed_weight_ms": round(t_gpu, 5), "fused_transposed_weight_tflops": round(flops / t_gpu / 1e9, 1),
             "fused_ms": round(f_gpu, 5), "fused_tflops": round(flops / f_gpu / 1e9, 1),
             "mfma_peak_tflops": 2500.0, "frac_of_mfma_peak": round(flops / f_gpu / 1e9 / 2500.0, 4),
             "unfused_ms": round(u_gpu, 5), "unfused_tflops": round(flops / u_gpu / 1e9, 1),

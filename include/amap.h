@@ -281,6 +281,14 @@ amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *
 amap_status amap_gemm_fused_store(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
                                   const amap_t *out_map, void *out, void *stream);
 
+/* All three accesses of the product rewritten: A through A_map, W through W_map
+ * (dst shape [K,N], bf16, one source, no fill; its contiguous runs of a multiple of 8
+ * elements may lie along n, as in a row-major weight, or along k, as in a transposed
+ * [N,K] weight, which then needs no transposition on its way to the matrix cores), and
+ * the product stored through out_map if that is not NULL (as in amap_gemm_fused_store). */
+amap_status amap_gemm_mapped(const void *A_src, const amap_t *A_map, const void *W_src, const amap_t *W_map,
+                             const amap_t *out_map, void *out, void *stream);
+
 const char *amap_status_str(amap_status s);
 
 /* Text of the HIP error behind the last AMAP_E_HIP returned on this thread

@@ -29,7 +29,7 @@ EXPORTS = [
     "amap_concat",
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
     "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_multi", "amap_execute_kernel",
-    "amap_gemm_fused", "amap_gemm_fused_store", "amap_status_str", "amap_last_error",
+    "amap_gemm_fused", "amap_gemm_fused_store", "amap_gemm_mapped", "amap_status_str", "amap_last_error",
     "amap_graph_create", "amap_graph_free", "amap_graph_input", "amap_graph_op", "amap_graph_compute",
     "amap_graph_output", "amap_graph_eliminate", "amap_graph_load",
 ]
@@ -89,6 +89,7 @@ _L.amap_execute_kernel.argtypes = [_pp, _vp, _vp, _vp, C.c_int]
 _L.amap_execute_multi.argtypes = [_pp, _pp, _pp, C.c_int, _vp]
 _L.amap_gemm_fused.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp]
 _L.amap_gemm_fused_store.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp, _vp]
+_L.amap_gemm_mapped.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _L.amap_status_str.argtypes = [C.c_int]
 _L.amap_status_str.restype = C.c_char_p
 
@@ -328,6 +329,12 @@ def amap_gemm_fused(a_src_ptr, a_map, w_ptr, n, out_ptr, stream=0):
 def amap_gemm_fused_store(a_src_ptr, a_map, w_ptr, n, out_map, out_ptr, stream=0):
     _check(_L.amap_gemm_fused_store(C.c_void_p(a_src_ptr), a_map.handle, C.c_void_p(w_ptr), int(n), out_map.handle,
                                     C.c_void_p(out_ptr), C.c_void_p(stream)), "amap_gemm_fused_store")
+
+
+def amap_gemm_mapped(a_src_ptr, a_map, w_src_ptr, w_map, out_map, out_ptr, stream=0):
+    _check(_L.amap_gemm_mapped(C.c_void_p(a_src_ptr), a_map.handle, C.c_void_p(w_src_ptr), w_map.handle,
+                               out_map.handle if out_map is not None else None, C.c_void_p(out_ptr),
+                               C.c_void_p(stream)), "amap_gemm_mapped")
 
 
 class GraphDME:

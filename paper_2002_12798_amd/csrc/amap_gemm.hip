@@ -62,7 +62,16 @@ struct GemmArgs {
     // out[obase + om(m) + on(n)]; store_mapped = 0 means the plain row-major C
     uint32_t store_mapped, obase;
     Digits om, on;
+    // W read through a map as well: element (k, n) of W is W[wbase + wk(k) + wn(n)]
+    uint32_t wbase;
+    Digits wk, wn;
 };
+
+// How the W operand is fetched: plain row-major [K,N]; through a map whose
+// contiguous runs lie along n (same 4 x 8 blocks, transposed in registers); or
+// through a map whose runs lie along k (a transposed weight: vectors go to LDS
+// as they are, like the A operand).
+enum WMode { W_PLAIN = 0, W_MAPPED_N = 1, W_MAPPED_K = 2 };
 
 __device__ __forceinline__ uint32_t digits_offset(const Digits &d, uint32_t x) {
     uint32_t off = 0;
@@ -104,6 +113,7 @@ __device__ __forceinline__ void tile_of_block(uint32_t b, uint32_t tiles_m, uint
     }
 }
 
+template <int WM>
 __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmArgs g) {
     extern __shared__ uint4 smem_v[];
     char *smem = reinterpret_cast<char *>(smem_v);
@@ -120,9 +130,16 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
     uint32_t a_soff[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) a_soff[i] = g.sbase + digits_offset(g.dm, m0 + (tid >> 3) + 32u * i);
-    // ---- W assignment: one 4 k x 8 n block per lane and step
+    // ---- W assignment: one 4 k x 8 n block per lane and step (runs along n), or
+    // four vectors of 8 k for n rows tid / 8 + 32 i (runs along k)
     const uint32_t w_nb = tid & 15u, w_kq = tid >> 4;
     const uint16_t *w_ptr = g.W + (size_t)(w_kq * 4u) * g.N + n0 + w_nb * 8u;
+    uint32_t w_noff[4] = {0, 0, 0, 0};
+    if constexpr (WM == W_MAPPED_N) w_noff[0] = g.wbase + digits_offset(g.wn, n0 + w_nb * 8u);
+    if constexpr (WM == W_MAPPED_K) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w_noff[i] = g.wbase + digits_offset(g.wn, n0 + (tid >> 3) + 32u * i);
+    }
 
     u32x4 ra[8], rw[4];
     auto load_step = [&](uint32_t k0) {
@@ -130,14 +147,31 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             ra[i] = *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[i] + koff));
-        const uint16_t *w = w_ptr + (size_t)k0 * g.N;
+        if constexpr (WM == W_PLAIN) {
+            const uint16_t *w = w_ptr + (size_t)k0 * g.N;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rw[i] = *reinterpret_cast<const u32x4 *>(w + (size_t)i * g.N);
+            for (int i = 0; i < 4; ++i) rw[i] = *reinterpret_cast<const u32x4 *>(w + (size_t)i * g.N);
+        } else if constexpr (WM == W_MAPPED_N) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                rw[i] = *reinterpret_cast<const u32x4 *>(g.W + (size_t)(w_noff[0] + digits_offset(g.wk, k0 + w_kq * 4u + i)));
+        } else {
+            const uint32_t wkoff = digits_offset(g.wk, k0 + a_chunk * 8u);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) rw[i] = *reinterpret_cast<const u32x4 *>(g.W + (size_t)(w_noff[i] + wkoff));
+        }
     };
     auto store_step = [&]() {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             *reinterpret_cast<u32x4 *>(sa + tile_offset((tid >> 3) + 32u * i, a_chunk)) = ra[i];
+        if constexpr (WM == W_MAPPED_K) {
+            // already 8 consecutive k per n row: straight into the stage
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<u32x4 *>(sw + tile_offset((tid >> 3) + 32u * i, a_chunk)) = rw[i];
+            return;
+        }
         // rw[i] = W[k = 4 kq + i][n = 8 nb .. 8 nb + 7]; the MFMA wants, per n,
         // consecutive k: transpose the 4 x 8 block of 16-bit values in registers
         // and write 8 bytes (4 k) per n
@@ -269,8 +303,12 @@ bool overlaps(const void *a, int64_t an, const void *b, int64_t bn) {
     return a0 < b0 + (uintptr_t)bn && b0 < a0 + (uintptr_t)an;
 }
 
-amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, int64_t N, const amap_t *out_map,
-                        void *out, void *stream) {
+amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, int64_t N, const amap_t *W_map,
+                        const amap_t *out_map, void *out, void *stream) {
+    if (W_map) {
+        if (W_map->shape.size() != 2) return AMAP_E_INVALID;
+        N = W_map->shape[1];
+    }
     if (!A_src || !A_map || !W || !out || N <= 0) return AMAP_E_INVALID;
     if (((uintptr_t)A_src | (uintptr_t)W | (uintptr_t)out) & 15) return AMAP_E_INVALID;
     if (A_map->shape.size() != 2 || A_map->elem != 2) return AMAP_E_INVALID;
@@ -287,7 +325,25 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
     if (!make_digits(p, 0, M, g.dm) || !make_digits(p, 1, K, g.dk)) return AMAP_E_UNSUPPORTED;
     if (!vector_runs(g.dk, g.dm, p.sbase)) return AMAP_E_UNSUPPORTED;
     const int64_t cbytes = M * N * 2;
-    if (overlaps(out, cbytes, A_src, svol * 2) || overlaps(out, cbytes, W, K * N * 2)) return AMAP_E_ALIAS;
+    int wmode = W_PLAIN;
+    int64_t wvol = K * N;
+    if (W_map) {
+        // W[k,n] = W_src[g_w(k,n)]: the second consumer load of the product, rewritten like the first
+        if (W_map->elem != 2 || W_map->shape[0] != K) return AMAP_E_INVALID;
+        if (!W_map->strided || W_map->pieces.size() != 1 || W_map->pieces[0].fill) return AMAP_E_UNSUPPORTED;
+        const Piece &q = W_map->pieces[0];
+        wvol = volume_of(W_map->src_shapes[q.src]);
+        if (wvol >= (1ll << 31)) return AMAP_E_UNSUPPORTED;
+        if (!make_digits(q, 0, K, g.wk) || !make_digits(q, 1, N, g.wn)) return AMAP_E_UNSUPPORTED;
+        if (vector_runs(g.wn, g.wk, q.sbase))
+            wmode = W_MAPPED_N;
+        else if (vector_runs(g.wk, g.wn, q.sbase))
+            wmode = W_MAPPED_K;
+        else
+            return AMAP_E_UNSUPPORTED;
+        g.wbase = (uint32_t)q.sbase;
+    }
+    if (overlaps(out, cbytes, A_src, svol * 2) || overlaps(out, cbytes, W, wvol * 2)) return AMAP_E_ALIAS;
     if (out_map) {
         // the layout chain applied to the product, turned into a store map: the
         // reverse of the chain's load map (Section 2.1), C index -> index of out
@@ -318,16 +374,25 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
     const size_t lds = kLdsBytes;
     static thread_local bool attr_done = false;
     if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(amap_gemm_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-            (void)hipGetLastError();
-            set_last_error("amap_gemm_kernel: cannot reserve its LDS stage");
-            return AMAP_E_HIP;
+        for (const void *fn : {reinterpret_cast<const void *>(amap_gemm_kernel<W_PLAIN>),
+                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_N>),
+                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_K>)}) {
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+                (void)hipGetLastError();
+                set_last_error("amap_gemm_kernel: cannot reserve its LDS stage");
+                return AMAP_E_HIP;
+            }
         }
         attr_done = true;
     }
-    hipLaunchKernelGGL(amap_gemm_kernel, dim3(g.tiles_m * g.tiles_n), dim3(kGemmThreads), lds,
-                       reinterpret_cast<hipStream_t>(stream), g);
+    const dim3 grid(g.tiles_m * g.tiles_n), block(kGemmThreads);
+    hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+    if (wmode == W_PLAIN)
+        hipLaunchKernelGGL(amap_gemm_kernel<W_PLAIN>, grid, block, lds, hs, g);
+    else if (wmode == W_MAPPED_N)
+        hipLaunchKernelGGL(amap_gemm_kernel<W_MAPPED_N>, grid, block, lds, hs, g);
+    else
+        hipLaunchKernelGGL(amap_gemm_kernel<W_MAPPED_K>, grid, block, lds, hs, g);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_last_error("amap_gemm_kernel", hipGetErrorString(e));
@@ -341,7 +406,7 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
 extern "C" amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N, void *out,
                                        void *stream) {
     try {
-        return gemm_launch(A_src, A_map, W, N, nullptr, out, stream);
+        return gemm_launch(A_src, A_map, W, N, nullptr, nullptr, out, stream);
     } catch (...) {
         return AMAP_E_NOMEM;
     }
@@ -351,7 +416,17 @@ extern "C" amap_status amap_gemm_fused_store(const void *A_src, const amap_t *A_
                                              const amap_t *out_map, void *out, void *stream) {
     if (!out_map) return AMAP_E_INVALID;
     try {
-        return gemm_launch(A_src, A_map, W, N, out_map, out, stream);
+        return gemm_launch(A_src, A_map, W, N, nullptr, out_map, out, stream);
+    } catch (...) {
+        return AMAP_E_NOMEM;
+    }
+}
+
+extern "C" amap_status amap_gemm_mapped(const void *A_src, const amap_t *A_map, const void *W_src, const amap_t *W_map,
+                                        const amap_t *out_map, void *out, void *stream) {
+    if (!W_map) return AMAP_E_INVALID;
+    try {
+        return gemm_launch(A_src, A_map, W_src, 0, W_map, out_map, out, stream);
     } catch (...) {
         return AMAP_E_NOMEM;
     }

@@ -203,3 +203,61 @@ def test_store_map_error_paths(dev):
         with pytest.raises(B.AmapError) as e:
             B.amap_gemm_fused_store(a.data_ptr(), a_map, w.data_ptr(), 128, om, out.data_ptr(), 0)
         assert e.value.status == status, status
+
+
+# ---- W read through a map too
+
+W_CASES = [
+    # (W source shape, chain -> [K,N]); A is the identity of [256,K]
+    ((384, 128), [("transpose", (1, 0))]),                                         # transposed weight: runs along k
+    ((2, 64, 128), [("transpose", (1, 0, 2)), ("reshape", (64, 256))]),            # runs along n, two blocks per row
+    ((4, 128, 64), [("transpose", (1, 0, 2)), ("reshape", (128, 256)), ("transpose", (1, 0))]),  # [256,128]: runs of 64 along k
+    ((130, 128), [("slice", 0, 2, 130, 1)]),                                       # row-major weight at an offset
+    ((128, 256), [("transpose", (1, 0)), ("slice", 0, 255, -1, -1)]),              # runs along k, k walked backwards in blocks
+]
+
+
+@pytest.mark.parametrize("case", range(len(W_CASES)))
+def test_w_operand_through_a_map(dev, case):
+    import torch
+    w_shape, w_ops = W_CASES[case]
+    print(f"[gpu] mapped-W gemm case {case}", flush=True)
+    w_src = synth.f32_to_bf16_bits((np.random.default_rng(500 + case).standard_normal(w_shape) * 0.05).astype(np.float32))
+    w_map = B.amap_compose([w_shape], 2, w_ops)
+    K, N = B.dst_shape(w_map)
+    a = synth.f32_to_bf16_bits(np.random.default_rng(600 + case).standard_normal((256, K)).astype(np.float32))
+    a_map = B.amap_compose([(256, K)], 2, [])
+    out = torch.empty((256, N), dtype=torch.int16, device="cuda")
+    d_a, d_w = dev.to_device(a), dev.to_device(w_src)          # kept alive until the product has been read back
+    try:
+        B.amap_gemm_mapped(d_a.data_ptr(), a_map, d_w.data_ptr(), w_map, None, out.data_ptr(), 0)
+    except B.AmapError as e:
+        # the last case reverses k element by element: runs of one element along k, refused
+        assert case == len(W_CASES) - 1 and e.status == B.AMAP_E_UNSUPPORTED
+        return
+    torch.cuda.synchronize()
+    assert case != len(W_CASES) - 1
+    _check(dev.to_host(out), a, oracle.run_chain([w_src], w_ops))
+
+
+def test_all_three_accesses_mapped(dev):
+    """A, W and the store each through their own chain; against product-then-chain on the oracle."""
+    import torch
+    a_shape, a_ops = (2, 4, 128, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (256, 256))]
+    w_shape, w_ops = (256, 256), [("transpose", (1, 0))]
+    c_ops = [("reshape", (2, 128, 4, 64)), ("transpose", (2, 0, 1, 3))]
+    a_src = synth.f32_to_bf16_bits(np.random.default_rng(71).standard_normal(a_shape).astype(np.float32))
+    w_src = synth.f32_to_bf16_bits((np.random.default_rng(72).standard_normal(w_shape) * 0.05).astype(np.float32))
+    a_map, w_map = B.amap_compose([a_shape], 2, a_ops), B.amap_compose([w_shape], 2, w_ops)
+    out_map = B.amap_compose([(256, 256)], 2, c_ops)
+    out = dev.empty_dst(out_map)
+    d_a, d_w = dev.to_device(a_src), dev.to_device(w_src)
+    B.amap_gemm_mapped(d_a.data_ptr(), a_map, d_w.data_ptr(), w_map, out_map, out.data_ptr(), 0)
+    torch.cuda.synchronize()
+    prod = oracle.gemm_bf16(oracle.run_chain([a_src], a_ops), oracle.run_chain([w_src], w_ops))
+    want = oracle.run_chain([prod], c_ops)
+    got = dev.to_host(out)
+    g, r = synth.bf16_bits_to_f32(got).astype(np.float64), synth.bf16_bits_to_f32(want).astype(np.float64)
+    assert got.shape == want.shape and np.abs(g - r).max() <= TOL * np.abs(r).max()
+    ulp = np.maximum(np.abs(r), 2.0 ** -126) * 2.0 ** -7
+    assert np.mean(np.abs(g - r) <= ulp) > 0.999

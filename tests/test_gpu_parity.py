@@ -214,7 +214,7 @@ def test_execute_multi_split_outputs(dev):
     for ops, o in zip(chains_, outs):
         assert np.array_equal(dev.to_host(o), oracle.run_chain([x], ops)), ops
     # overlapping outputs are refused
-    d = dev.empty_dst(maps[0])
+    d, d_x = dev.empty_dst(maps[0]), dev.to_device(x)
     with pytest.raises(B.AmapError) as e:
-        B.amap_execute_multi([dev.to_device(x).data_ptr()], [d.data_ptr(), d.data_ptr()], [maps[0], maps[0]], 0)
+        B.amap_execute_multi([d_x.data_ptr()], [d.data_ptr(), d.data_ptr()], [maps[0], maps[0]], 0)
     assert e.value.status == B.AMAP_E_ALIAS
