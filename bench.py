@@ -239,6 +239,58 @@ def bench_multi(torch, device, B, synth, steps, warmup):
             "speedup": round(s_gpu / t_gpu, 3)}
 
 
+def bench_layout(torch, device, B, synth, steps, warmup):
+    """Global layout assignment on the synthetic ResNet-like graph: relayout copies (count, bytes,
+    time of running them as transpose maps) of the per-operator assignment against those left
+    after propagation.  The local assignment's copies are rebuilt here from the same rules."""
+    tensors, ops = synth.resnet_like_layout_graph(batch=32)
+    g = B.LayoutGraph()
+    for shape, fixed in tensors:
+        g.tensor(shape, 2, fixed)
+    for operands, outs, reqs, same in ops:
+        g.op(operands, outs, reqs, same)
+    rep = g.solve()
+    stream = C.c_void_p(device.current_stream())
+
+    def timed(maps):
+        work = []
+        for m in maps:
+            info = B.amap_describe(m)
+            src = torch.zeros(int(info.min_read_bytes // 2), dtype=torch.int16, device="cuda")
+            work.append((m, (C.c_void_p * 1)(src.data_ptr()), device.empty_dst(m), src))
+
+        def run(_):
+            for m, arr, dst, _src in work:
+                st = B.raw.amap_execute(arr, C.c_void_p(dst.data_ptr()), m.handle, stream)
+                if st != 0:
+                    raise RuntimeError(B.amap_status_str(st))
+        return _time_launches(torch, run, [None], steps, warmup)[1] if work else 0.0
+
+    glob = [m for _, _, _, m in g.copies()]
+    # per-operator assignment: canonical order unless the operator asks for another one
+    canon = lambda t: tuple(range(len(tensors[t][0])))
+    written = {}
+    for operands, outs, reqs, same in ops:
+        for si, t in enumerate(operands):
+            if outs[si]:
+                written[t] = tuple(reqs[si]) if reqs and reqs[si] is not None else canon(t)
+    local = []
+    for operands, outs, reqs, same in ops:
+        for si, t in enumerate(operands):
+            if outs[si]:
+                continue
+            have = written.get(t, tensors[t][1] or canon(t))
+            need = tuple(reqs[si]) if reqs and reqs[si] is not None else canon(t)
+            if tuple(have) != need:
+                shape = tensors[t][0]
+                local.append(B.amap_transpose(B.amap_source(0, [shape[k] for k in have], 2), [have.index(d) for d in need]))
+    return {"workload": "ResNet-like graph, 36 convolutions, bf16 activations, batch 32 (synthetic)",
+            "copies_local": rep.n_copies_local, "copy_bytes_local": rep.copy_bytes_local,
+            "copies_global": rep.n_copies_global, "copy_bytes_global": rep.copy_bytes_global,
+            "sweeps": rep.n_sweeps, "local_copies_rebuilt": len(local),
+            "local_ms": round(timed(local), 4), "global_ms": round(timed(glob), 4)}
+
+
 def bench_graph(torch, device, B, synth, steps, warmup):
     """Graph-level data-movement elimination on the synthetic WaveNet-like graph: time of all
     layout operators run one at a time (each a materialising copy) against the composed maps
@@ -405,6 +457,7 @@ def main():
             nxt[r["workload"]] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
         print(json.dumps({"repeat_tile_reverse": nxt, "graph_dme": bench_graph(torch, device, B, synth, 10, 2),
                           "execute_multi": bench_multi(torch, device, B, synth, a.steps, a.warmup),
+                          "layout_assignment": bench_layout(torch, device, B, synth, 10, 2),
                           "fused_gemm_store": bench_gemm_store(torch, device, B, synth, a.steps, a.warmup)}))
         return
     if a.fused_only:
@@ -453,6 +506,7 @@ def main():
         out["fused_gemm_store"] = bench_gemm_store(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["execute_multi"] = bench_multi(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["graph_dme"] = bench_graph(torch, device, B, synth, 10, 2)
+        out["layout_assignment"] = bench_layout(torch, device, B, synth, 10, 2)
     print(json.dumps(out))
 
 

@@ -233,6 +233,56 @@ amap_status amap_graph_eliminate(amap_graph_t *g, amap_graph_report *report);
 amap_status amap_graph_load(const amap_graph_t *g, int index, int *consumer, int *slot, amap_t **map,
                             int *src_tensors, int *n_src);
 
+/* ---- global layout assignment (host only) --------------------------------
+ * The GPU counterpart of the paper's global memory-bank mapping (Section 2.2).
+ * There the property propagated through the network is which tensor dimension
+ * is spread over the on-chip banks; here it is the order of a tensor's
+ * dimensions in HBM (which one is contiguous).  Operators with a restriction
+ * (matrix products, convolutions) seed the layouts of their operands,
+ * the layouts are propagated along the data dependencies through the
+ * unrestricted operators to a fixed point, and only where a tensor meets
+ * conflicting requirements is a copy t -> t' inserted, as a relayout map that
+ * amap_execute runs.  The result is compared with the local assignment
+ * (every operator on its own, unrestricted operators in the canonical order). */
+typedef struct amap_layout_graph amap_layout_graph_t;
+
+amap_status amap_layout_create(amap_layout_graph_t **out);
+void amap_layout_free(amap_layout_graph_t *g);
+
+/* A logical tensor.  An order lists the logical dimensions from the outermost to the
+ * innermost (contiguous) one in memory; {0,1,..} is the canonical order.
+ * fixed_order = NULL: free; else the order the tensor must have (graph inputs / outputs). */
+amap_status amap_layout_tensor(amap_layout_graph_t *g, int rank, const int64_t *shape, amap_elem es,
+                               const int32_t *fixed_order, int *tensor);
+
+/* An operator over n operands.  is_output[i] != 0 marks the tensors it produces.
+ * req_orders[i] = NULL: the operand is free; else the order this operator needs it in.
+ * same_layout != 0: all free operands of equal rank must share one order (element-wise
+ * operators, pooling); the operator takes whatever order reaches it. */
+amap_status amap_layout_op(amap_layout_graph_t *g, const int *operands, const int *is_output,
+                           const int32_t *const *req_orders, int n, int same_layout, int *op);
+
+typedef struct {
+    int n_copies_local;          /* copies the per-operator assignment needs */
+    int64_t copy_bytes_local;    /* bytes they read + write */
+    int n_copies_global;         /* copies left after propagation */
+    int64_t copy_bytes_global;
+    int n_sweeps;                /* sweeps over the operators until the propagation reached its fixed point */
+} amap_layout_report;
+
+amap_status amap_layout_solve(amap_layout_graph_t *g, amap_layout_report *report);
+
+/* After amap_layout_solve: the order assigned to a tensor (rank entries). */
+amap_status amap_layout_order(const amap_layout_graph_t *g, int tensor, int32_t *order);
+
+/* Copy number `index` (0 .. n_copies_global-1) of the global assignment: operator `op` reads or
+ * writes operand `slot` (tensor `tensor`) in another order than the tensor has in memory.
+ * *map is a NEW map (caller frees) from the tensor as stored (source 0, its dimensions in the
+ * assigned order) to the order the operator needs; for an output operand the copy runs the other
+ * way and *map goes from what the operator wrote to the tensor as stored. */
+amap_status amap_layout_copy(const amap_layout_graph_t *g, int index, int *op, int *slot, int *tensor,
+                             amap_t **map);
+
 /* ---- execution (device pointers; asynchronous on `stream`) --------------
  * `stream` is a hipStream_t passed as void* (NULL = the default stream).
  * No allocation, no synchronisation, no host access to device memory. */

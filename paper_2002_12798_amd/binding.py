@@ -32,6 +32,8 @@ EXPORTS = [
     "amap_gemm_fused", "amap_gemm_fused_store", "amap_gemm_mapped", "amap_status_str", "amap_last_error",
     "amap_graph_create", "amap_graph_free", "amap_graph_input", "amap_graph_op", "amap_graph_compute",
     "amap_graph_output", "amap_graph_eliminate", "amap_graph_load",
+    "amap_layout_create", "amap_layout_free", "amap_layout_tensor", "amap_layout_op", "amap_layout_solve",
+    "amap_layout_order", "amap_layout_copy",
 ]
 
 
@@ -114,6 +116,22 @@ _L.amap_graph_compute.argtypes = [_vp, _ip, C.c_int, C.c_int, _i64p, C.c_int, _i
 _L.amap_graph_output.argtypes = [_vp, C.c_int]
 _L.amap_graph_eliminate.argtypes = [_vp, C.POINTER(amap_graph_report)]
 _L.amap_graph_load.argtypes = [_vp, C.c_int, _ip, _ip, _pp, _ip, _ip]
+
+
+
+class amap_layout_report(C.Structure):
+    _fields_ = [("n_copies_local", C.c_int), ("copy_bytes_local", C.c_int64), ("n_copies_global", C.c_int),
+                ("copy_bytes_global", C.c_int64), ("n_sweeps", C.c_int)]
+
+
+_L.amap_layout_create.argtypes = [_pp]
+_L.amap_layout_free.argtypes = [_vp]
+_L.amap_layout_free.restype = None
+_L.amap_layout_tensor.argtypes = [_vp, C.c_int, _i64p, C.c_int, _i32p, _ip]
+_L.amap_layout_op.argtypes = [_vp, _ip, _ip, C.POINTER(_i32p), C.c_int, C.c_int, _ip]
+_L.amap_layout_solve.argtypes = [_vp, C.POINTER(amap_layout_report)]
+_L.amap_layout_order.argtypes = [_vp, C.c_int, _i32p]
+_L.amap_layout_copy.argtypes = [_vp, C.c_int, _ip, _ip, _ip, _pp]
 
 raw = _L  # the raw CDLL, for callers that pre-marshal their arguments
 
@@ -386,3 +404,58 @@ class GraphDME:
         h, self._h = getattr(self, "_h", None), None
         if h and _L is not None:
             _L.amap_graph_free(h)
+
+
+class LayoutGraph:
+    """Owner of one amap_layout_graph_t* (global layout assignment)."""
+
+    def __init__(self):
+        h = C.c_void_p()
+        _check(_L.amap_layout_create(C.byref(h)), "amap_layout_create")
+        self._h = h
+        self.ranks = []
+        self.report = None
+
+    def tensor(self, shape, es, fixed_order=None):
+        tid = C.c_int(-1)
+        fo = None if fixed_order is None else (C.c_int32 * len(fixed_order))(*[int(v) for v in fixed_order])
+        _check(_L.amap_layout_tensor(self._h, len(shape), _i64(shape), int(es), fo, C.byref(tid)), "amap_layout_tensor")
+        self.ranks.append(len(shape))
+        return tid.value
+
+    def op(self, operands, is_output, req_orders=None, same_layout=False):
+        """operands: tensor ids; is_output: flags; req_orders: per operand None or a permutation."""
+        n = len(operands)
+        req_orders = req_orders or [None] * n
+        keep = [None if r is None else (C.c_int32 * len(r))(*[int(v) for v in r]) for r in req_orders]
+        arr = (_i32p * n)(*[None if k is None else C.cast(k, _i32p) for k in keep])
+        oid = C.c_int(-1)
+        _check(_L.amap_layout_op(self._h, (C.c_int * n)(*operands), (C.c_int * n)(*[int(bool(v)) for v in is_output]),
+                                 arr, n, int(bool(same_layout)), C.byref(oid)), "amap_layout_op")
+        return oid.value
+
+    def solve(self):
+        rep = amap_layout_report()
+        _check(_L.amap_layout_solve(self._h, C.byref(rep)), "amap_layout_solve")
+        self.report = rep
+        return rep
+
+    def order(self, tensor):
+        o = (C.c_int32 * AMAP_MAX_RANK)()
+        _check(_L.amap_layout_order(self._h, int(tensor), o), "amap_layout_order")
+        return tuple(o[k] for k in range(self.ranks[tensor]))
+
+    def copies(self):
+        """[(op, slot, tensor, Map)] of the global assignment."""
+        out = []
+        for i in range(self.report.n_copies_global):
+            op, slot, t = C.c_int(), C.c_int(), C.c_int()
+            m = C.c_void_p()
+            _check(_L.amap_layout_copy(self._h, i, C.byref(op), C.byref(slot), C.byref(t), C.byref(m)), "amap_layout_copy")
+            out.append((op.value, slot.value, t.value, Map(m.value)))
+        return out
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and _L is not None:
+            _L.amap_layout_free(h)

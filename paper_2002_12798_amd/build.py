@@ -10,7 +10,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libamap.so")
 
-SOURCES = ["amap_compose.cpp", "amap_graph.cpp", "amap_host.cpp", "amap_plan.cpp", "amap_plan_check.cpp", "amap_kernels.hip",
+SOURCES = ["amap_compose.cpp", "amap_graph.cpp", "amap_layout.cpp", "amap_host.cpp", "amap_plan.cpp", "amap_plan_check.cpp", "amap_kernels.hip",
            "amap_gemm.hip"]
 
 FLAGS = [

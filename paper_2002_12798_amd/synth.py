@@ -260,3 +260,58 @@ def wavenet_like_graph(layers=10, batch=1, channels=32, steps=256, skip_steps=64
     g.output(out)
     g.output(x)
     return g
+
+
+# ---- operator graphs for the global layout assignment (Section 2.2) ----
+# Plain data again: tensors = [(shape, fixed order or None)], ops = [(operands, is_output flags,
+# required orders (None = free), same_layout)].  Logical activations are [N, C, H, W]; a
+# convolution asks for channels innermost (order 0,2,3,1) on its input and output, a matrix
+# product for row-major operands; normalisation / activation / residual add / pooling take
+# any order as long as their operands agree.
+
+NHWC = (0, 2, 3, 1)
+
+
+def resnet_like_layout_graph(batch=32, stages=((64, 56, 3), (128, 28, 4), (256, 14, 6), (512, 7, 3)), classes=1000):
+    """Basic residual blocks (two convolutions, normalisation and activation after each, a
+    residual add) in four stages, global pooling and a classifier.  The network input is
+    given in the canonical [N, C, H, W] order.  Stand-in for the paper's ResNet-50 run."""
+    tensors, ops = [], []
+
+    def tensor(shape, fixed=None):
+        tensors.append((tuple(shape), fixed))
+        return len(tensors) - 1
+
+    def conv(x, cout, hw):
+        y = tensor((batch, cout, hw, hw))
+        ops.append(([x, y], [0, 1], [NHWC, NHWC], False))
+        return y
+
+    def same(ins, shape):
+        y = tensor(shape)
+        ops.append((list(ins) + [y], [0] * len(ins) + [1], None, True))
+        return y
+
+    x = tensor((batch, 3, 224, 224), fixed=(0, 1, 2, 3))
+    x = conv(x, 64, 112)                                    # stem
+    x = same([x], (batch, 64, 112, 112))                    # normalisation + activation
+    x = same([x], (batch, 64, 56, 56))                      # pooling
+    cin = 64
+    for cout, hw, blocks in stages:
+        for b in range(blocks):
+            shp = (batch, cout, hw, hw)
+            skip = x if cin == cout else conv(x, cout, hw)  # projection on the skip path when the width changes
+            y = conv(x, cout, hw)
+            y = same([y], shp)
+            y = conv(y, cout, hw)
+            y = same([y], shp)
+            x = same([y, skip], shp)                        # residual add
+            x = same([x], shp)
+            cin = cout
+    p = same([x], (batch, cin, 1, 1))                       # global average pooling
+    flat = tensor((batch, cin))
+    ops.append(([p, flat], [0, 1], None, False))            # flatten (free on both sides)
+    w = tensor((cin, classes), fixed=(0, 1))
+    logits = tensor((batch, classes), fixed=(0, 1))
+    ops.append(([flat, w, logits], [0, 0, 1], [(0, 1), (0, 1), (0, 1)], False))
+    return tensors, ops

@@ -115,3 +115,26 @@ def test_composed_maps_replay_from_a_hip_graph(dev):
         for (_, _, d), want in zip(work, eager):
             assert np.array_equal(dev.to_host(d), want), rep
     del gen
+
+
+def test_relayout_copies_of_the_global_assignment_on_device(dev):
+    """The copies the global layout assignment leaves are transpose maps; run them on the GPU."""
+    import torch
+    from tests.test_layout import _build
+    shp = (4, 24, 10, 12)
+    tensors = [(shp, (0, 1, 2, 3)), (shp, None), (shp, None), (shp, None), (shp, (0, 3, 1, 2))]
+    ops = [([0, 1], [0, 1], [synth.NHWC, synth.NHWC], False), ([1, 2], [0, 1], None, True),
+           ([2, 3], [0, 1], [(0, 1, 2, 3), (0, 1, 2, 3)], False), ([3, 4], [0, 1], None, True)]
+    g = _build(tensors, ops)
+    rep = g.solve()
+    assert rep.n_copies_global >= 2
+    logical = synth.random_bits(shp, 2, 31)
+    for op, slot, t, m in g.copies():
+        have = g.order(t)
+        reqs = ops[op][2]
+        need = reqs[slot] if reqs is not None and reqs[slot] is not None else g.order(ops[op][0][0])
+        src_order, dst_order = (need, have) if ops[op][1][slot] else (have, need)
+        stored = oracle.transpose(logical, src_order)
+        got = dev.to_host(dev.execute(m, [dev.to_device(stored)]))
+        torch.cuda.synchronize()
+        assert np.array_equal(got, oracle.transpose(logical, dst_order)), (op, slot)
