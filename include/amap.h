@@ -316,8 +316,9 @@ amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t 
  * materialised.  A_map: dst shape [M,K], 2-byte elements (bf16), one source,
  * no fill pieces.  W: [K,N] row-major bf16.  out: [M,N] row-major bf16,
  * fp32 accumulation, round-to-nearest-even on output.
- * Needs M % 256 == 0, N % 128 == 0, K % 64 == 0 and 8-element aligned
- * contiguous runs along k in the map, else AMAP_E_UNSUPPORTED. */
+ * Needs N % 8 == 0, K % 8 == 0 and 8-element aligned contiguous runs along k
+ * in the map, else AMAP_E_UNSUPPORTED; M, N and K need not be whole numbers of
+ * the 256 x 128 x 64 tiles (edge tiles are clamped on load, masked on store). */
 amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
                             void *out, void *stream);
 

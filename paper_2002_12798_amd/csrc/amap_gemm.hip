@@ -113,7 +113,10 @@ __device__ __forceinline__ void tile_of_block(uint32_t b, uint32_t tiles_m, uint
     }
 }
 
-template <int WM>
+// EDGE: M, N or K is not a whole number of tiles.  Rows past M are clamped for the
+// loads and skipped by the stores, vectors past K or N are replaced by zeros, so the
+// extra lanes neither read outside the operands nor contribute to a kept result.
+template <int WM, bool EDGE>
 __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmArgs g) {
     extern __shared__ uint4 smem_v[];
     char *smem = reinterpret_cast<char *>(smem_v);
@@ -129,36 +132,55 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
     const uint32_t a_chunk = tid & 7u;
     uint32_t a_soff[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) a_soff[i] = g.sbase + digits_offset(g.dm, m0 + (tid >> 3) + 32u * i);
+    for (int i = 0; i < 8; ++i) {
+        uint32_t row = m0 + (tid >> 3) + 32u * i;
+        if constexpr (EDGE) row = row < g.M ? row : g.M - 1;
+        a_soff[i] = g.sbase + digits_offset(g.dm, row);
+    }
     // ---- W assignment: one 4 k x 8 n block per lane and step (runs along n), or
     // four vectors of 8 k for n rows tid / 8 + 32 i (runs along k)
     const uint32_t w_nb = tid & 15u, w_kq = tid >> 4;
     const uint16_t *w_ptr = g.W + (size_t)(w_kq * 4u) * g.N + n0 + w_nb * 8u;
     uint32_t w_noff[4] = {0, 0, 0, 0};
-    if constexpr (WM == W_MAPPED_N) w_noff[0] = g.wbase + digits_offset(g.wn, n0 + w_nb * 8u);
+    const bool w_n_ok = !EDGE || n0 + w_nb * 8u < g.N;  // this lane's 8 n of W exist
+    if constexpr (WM == W_MAPPED_N) w_noff[0] = g.wbase + digits_offset(g.wn, w_n_ok ? n0 + w_nb * 8u : 0u);
     if constexpr (WM == W_MAPPED_K) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w_noff[i] = g.wbase + digits_offset(g.wn, n0 + (tid >> 3) + 32u * i);
+        for (int i = 0; i < 4; ++i) {
+            uint32_t n = n0 + (tid >> 3) + 32u * i;
+            if constexpr (EDGE) n = n < g.N ? n : g.N - 1;
+            w_noff[i] = g.wbase + digits_offset(g.wn, n);
+        }
     }
 
     u32x4 ra[8], rw[4];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
     auto load_step = [&](uint32_t k0) {
-        const uint32_t koff = digits_offset(g.dk, k0 + a_chunk * 8u);
+        const uint32_t kc = k0 + a_chunk * 8u;
+        const bool kc_ok = !EDGE || kc < g.K;
+        const uint32_t koff = digits_offset(g.dk, kc_ok ? kc : 0u);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            ra[i] = *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[i] + koff));
+            ra[i] = kc_ok ? *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[i] + koff)) : zero4;
         if constexpr (WM == W_PLAIN) {
             const uint16_t *w = w_ptr + (size_t)k0 * g.N;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) rw[i] = *reinterpret_cast<const u32x4 *>(w + (size_t)i * g.N);
+            for (int i = 0; i < 4; ++i) {
+                const bool ok = !EDGE || (w_n_ok && k0 + w_kq * 4u + i < g.K);
+                rw[i] = ok ? *reinterpret_cast<const u32x4 *>(w + (size_t)i * g.N) : zero4;
+            }
         } else if constexpr (WM == W_MAPPED_N) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                rw[i] = *reinterpret_cast<const u32x4 *>(g.W + (size_t)(w_noff[0] + digits_offset(g.wk, k0 + w_kq * 4u + i)));
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t k = k0 + w_kq * 4u + i;
+                const bool ok = !EDGE || (w_n_ok && k < g.K);
+                rw[i] = ok ? *reinterpret_cast<const u32x4 *>(g.W + (size_t)(w_noff[0] + digits_offset(g.wk, k))) : zero4;
+            }
         } else {
-            const uint32_t wkoff = digits_offset(g.wk, k0 + a_chunk * 8u);
+            const uint32_t wkoff = digits_offset(g.wk, kc_ok ? kc : 0u);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) rw[i] = *reinterpret_cast<const u32x4 *>(g.W + (size_t)(w_noff[i] + wkoff));
+            for (int i = 0; i < 4; ++i)
+                rw[i] = kc_ok ? *reinterpret_cast<const u32x4 *>(g.W + (size_t)(w_noff[i] + wkoff)) : zero4;
         }
     };
     auto store_step = [&]() {
@@ -195,7 +217,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
 
     const uint32_t wm = wave >> 1, wn = wave & 1u;
     const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
-    const uint32_t steps = g.K / BK;
+    const uint32_t steps = (g.K + BK - 1) / BK;
 
     load_step(0);
     store_step();
@@ -252,6 +274,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
     for (int i = 0; i < 16; ++i) {
         const uint32_t v = tid + 256u * i, row = v >> 4, cv = v & 15u;
         const u32x4 x = *reinterpret_cast<const u32x4 *>(smem + row * kCPitch + cv * 16);
+        if constexpr (EDGE) {
+            if (m0 + row >= g.M || n0 + cv * 8u >= g.N) continue;
+        }
         size_t off = (size_t)(m0 + row) * g.N + n0 + cv * 8u;
         if (g.store_mapped) off = g.obase + digits_offset(g.om, m0 + row) + digits_offset(g.on, n0 + cv * 8u);
         __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + off));
@@ -313,7 +338,9 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
     if (((uintptr_t)A_src | (uintptr_t)W | (uintptr_t)out) & 15) return AMAP_E_INVALID;
     if (A_map->shape.size() != 2 || A_map->elem != 2) return AMAP_E_INVALID;
     const int64_t M = A_map->shape[0], K = A_map->shape[1];
-    if (M % BM || N % BN || K % BK || M == 0 || K == 0) return AMAP_E_UNSUPPORTED;
+    if (M == 0 || K == 0) return AMAP_E_UNSUPPORTED;
+    if (N % 8 || K % 8) return AMAP_E_UNSUPPORTED;  // 16-byte vectors along n and k
+    const bool edge = M % BM || N % BN || K % BK;
     if (!A_map->strided || A_map->pieces.size() != 1 || A_map->pieces[0].fill) return AMAP_E_UNSUPPORTED;
     const Piece &p = A_map->pieces[0];
     const int64_t svol = volume_of(A_map->src_shapes[p.src]);
@@ -369,14 +396,17 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
     g.N = (uint32_t)N;
     g.K = (uint32_t)K;
     g.sbase = (uint32_t)p.sbase;
-    g.tiles_m = (uint32_t)(M / BM);
-    g.tiles_n = (uint32_t)(N / BN);
+    g.tiles_m = (uint32_t)((M + BM - 1) / BM);
+    g.tiles_n = (uint32_t)((N + BN - 1) / BN);
     const size_t lds = kLdsBytes;
     static thread_local bool attr_done = false;
     if (!attr_done) {
-        for (const void *fn : {reinterpret_cast<const void *>(amap_gemm_kernel<W_PLAIN>),
-                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_N>),
-                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_K>)}) {
+        for (const void *fn : {reinterpret_cast<const void *>(amap_gemm_kernel<W_PLAIN, false>),
+                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_N, false>),
+                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_K, false>),
+                               reinterpret_cast<const void *>(amap_gemm_kernel<W_PLAIN, true>),
+                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_N, true>),
+                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_K, true>)}) {
             if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
                 (void)hipGetLastError();
                 set_last_error("amap_gemm_kernel: cannot reserve its LDS stage");
@@ -387,12 +417,20 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
     }
     const dim3 grid(g.tiles_m * g.tiles_n), block(kGemmThreads);
     hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+#define AMAP_GEMM(WM)                                                                        \
+    do {                                                                                     \
+        if (edge)                                                                            \
+            hipLaunchKernelGGL((amap_gemm_kernel<WM, true>), grid, block, lds, hs, g);       \
+        else                                                                                 \
+            hipLaunchKernelGGL((amap_gemm_kernel<WM, false>), grid, block, lds, hs, g);      \
+    } while (0)
     if (wmode == W_PLAIN)
-        hipLaunchKernelGGL(amap_gemm_kernel<W_PLAIN>, grid, block, lds, hs, g);
+        AMAP_GEMM(W_PLAIN);
     else if (wmode == W_MAPPED_N)
-        hipLaunchKernelGGL(amap_gemm_kernel<W_MAPPED_N>, grid, block, lds, hs, g);
+        AMAP_GEMM(W_MAPPED_N);
     else
-        hipLaunchKernelGGL(amap_gemm_kernel<W_MAPPED_K>, grid, block, lds, hs, g);
+        AMAP_GEMM(W_MAPPED_K);
+#undef AMAP_GEMM
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_last_error("amap_gemm_kernel", hipGetErrorString(e));

@@ -129,9 +129,8 @@ def test_unsupported_and_error_paths(dev):
                           (y if o is None else o).data_ptr(), 0)
 
     for m, n, status in [
-        (B.amap_compose([(200, 64)], 2, []), 256, B.AMAP_E_UNSUPPORTED),                    # M % 256
-        (B.amap_compose([(256, 72)], 2, []), 256, B.AMAP_E_UNSUPPORTED),                    # K % 64
-        (B.amap_compose([(256, 64)], 2, []), 200, B.AMAP_E_UNSUPPORTED),                    # N % 256
+        (B.amap_compose([(256, 68)], 2, []), 256, B.AMAP_E_UNSUPPORTED),                    # K % 8
+        (B.amap_compose([(256, 64)], 2, []), 196, B.AMAP_E_UNSUPPORTED),                    # N % 8
         (B.amap_compose([(256, 64)], 4, []), 256, B.AMAP_E_INVALID),                        # not 2-byte
         (B.amap_compose([(4, 256, 64)], 2, []), 256, B.AMAP_E_INVALID),                     # not a matrix
         (B.amap_compose([(256, 60)], 2, [("pad", (0, 0), (0, 4), 0)]), 256, B.AMAP_E_UNSUPPORTED),  # fill piece
@@ -149,6 +148,38 @@ def test_unsupported_and_error_paths(dev):
         B.amap_gemm_fused(x.data_ptr() + 2, m, w.data_ptr(), 256, y.data_ptr(), 0)
     assert e.value.status == B.AMAP_E_INVALID
     torch.cuda.synchronize()
+
+
+EDGE_CASES = [
+    # M, K, N not whole numbers of 256 x 64 x 128 tiles; (A source shape, chain -> [M,K]), N
+    (((200, 64), []), 128),                                                    # M edge only
+    (((256, 72), []), 128),                                                    # K edge only
+    (((256, 64), []), 200),                                                    # N edge only
+    (((8, 8), []), 8),                                                         # everything smaller than one tile
+    (((3, 100, 40), [("transpose", (1, 0, 2)), ("reshape", (100, 120))]), 136),  # mapped A, all three edges
+    (((700, 200), [("slice", 0, 699, -1, -1)]), 264),                          # several tiles and an edge each way
+]
+
+
+@pytest.mark.parametrize("case", range(len(EDGE_CASES)))
+def test_edge_tiles(dev, case):
+    (shape, ops), N = EDGE_CASES[case]
+    print(f"[gpu] gemm edge case {case}", flush=True)
+    src = synth.f32_to_bf16_bits(np.random.default_rng(700 + case).standard_normal(shape).astype(np.float32))
+    a = oracle.run_chain([src], ops)
+    K = a.shape[1]
+    w = synth.f32_to_bf16_bits((np.random.default_rng(800 + case).standard_normal((K, N)) * 0.05).astype(np.float32))
+    _check(_gemm(dev, src, shape, ops, w), a, w)
+    # transposed weight and a mapped store on the same shapes
+    import torch
+    a_map = B.amap_compose([shape], 2, ops)
+    w_map = B.amap_compose([(N, K)], 2, [("transpose", (1, 0))])
+    out_map = B.amap_compose([(a.shape[0], N)], 2, [("slice", 0, a.shape[0] - 1, -1, -1)])
+    d_src, d_wt = dev.to_device(src), dev.to_device(np.ascontiguousarray(w.T))
+    out = dev.empty_dst(out_map)
+    B.amap_gemm_mapped(d_src.data_ptr(), a_map, d_wt.data_ptr(), w_map, out_map, out.data_ptr(), 0)
+    torch.cuda.synchronize()
+    _check(dev.to_host(out)[::-1], a, w)
 
 
 # ---- store side: the product written through a layout chain (the paper's store map f_s)
