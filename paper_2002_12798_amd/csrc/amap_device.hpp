@@ -82,6 +82,10 @@ struct DevPiece {
     // a row (a repeat along the contiguous dimension); a lane then loads
     // 1 / (1 << rep_log) of a vector and spreads it over a whole one.
     uint32_t rep_log;
+    // ROWS only: the row walks the source backwards (a reversed contiguous axis).  Loop 0 has
+    // source stride -V; the lane loads the V elements that END at its source offset and
+    // reverses them in registers.
+    uint32_t rev;
     // Window of the piece in tensors too large for 32-bit offsets: dbase and every
     // dst offset are relative to element dwin of dst; swin likewise for the source
     // (the host folds it into `src` at launch).  0 for ordinary tensors.

@@ -172,6 +172,34 @@ __device__ __forceinline__ void rows_expand(const DevPiece &P, char *dst, const 
     }
 }
 
+// The same for a row read backwards: the lane loads the 16 bytes that end at its
+// source element and reverses the elements in registers.
+template <int ES, int NT>
+__device__ __forceinline__ void rows_reverse(const DevPiece &P, char *dst, const uint32_t (&doff)[kRowsUnroll],
+                                             const uint32_t (&soff)[kRowsUnroll], const bool (&ok)[kRowsUnroll]) {
+    constexpr uint32_t V = 16 / ES;
+    uint32_t in[kRowsUnroll][4];
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) {
+        if (ok[u]) {
+            gld<16, false>(in[u], (const char *)P.src + ((size_t)soff[u] - (V - 1)) * ES);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) in[u][k] = 0;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) {
+        uint32_t out[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t w = in[u][3 - k];
+            out[k] = ES == 4 ? w : ((w >> 16) | (w << 16));
+        }
+        if (ok[u]) gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)doff[u] * ES, out);
+    }
+}
+
 template <int ES, int NT>
 __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t blk, uint32_t tid) {
     uint32_t doff[kRowsUnroll], soff[kRowsUnroll];
@@ -183,6 +211,10 @@ __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t
         const uint32_t r = base + u * threads;
         ok[u] = r < P.n_units;
         rows_offsets(P, r, doff[u], soff[u]);
+    }
+    if (P.rev) {  // set only together with 16-byte dst vectors and a source
+        rows_reverse<ES, NT>(P, dst, doff, soff, ok);
+        return;
     }
     if (P.rep_log) {  // the planner only sets it together with 16-byte dst vectors and a source
         switch (P.rep_log) {

@@ -153,6 +153,22 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
             }
         }
     }
+    // A reversed contiguous axis: the dst-contiguous loop walks the source backwards one element
+    // at a time.  With whole 16-byte dst vectors the row kernel loads the mirrored vector and
+    // reverses it in registers.
+    if ((family < 0 || family == AMAP_K_ROWS) && !kp.fill && n >= 1 && kp.dims[n - 1].ds == 1 && kp.dims[n - 1].ss == -1) {
+        std::vector<int64_t> dso;
+        for (int k = 0; k < n - 1; ++k) dso.push_back(kp.dims[k].ds);
+        if (common_pow2(vmax, {kp.dims[n - 1].extent, kp.dbase}, dso) == vmax) {
+            fill_rows(dp, kp, vmax, nwlog);
+            dp.loops[0].ss = -(int32_t)vmax;
+            dp.rev = 1;
+            vec_bytes = 16;
+            if (line_aligned(es, {kp.dims[n - 1].extent, kp.dbase}, dso)) dp.flags |= PF_NT_STORE;
+            dp.flags &= (uint32_t)env_int("AMAP_NT", 3);
+            return AMAP_K_ROWS;
+        }
+    }
     const bool rows_ok = iP >= 0 && (kp.fill || iP == iQ);
     const bool tile_shape = !kp.fill && iP >= 0 && iQ >= 0 && iP != iQ;
     // The vector width follows from the dst side (aligned 16-byte stores) and from

@@ -55,7 +55,7 @@ struct Replay {
                 uint32_t d, s;
                 rows_offsets(P, r, d, s);
                 for (uint32_t e = 0; e < V; ++e)
-                    write((int64_t)P.dwin + d + e, code_of(sid, (int64_t)P.swin + s + (e >> P.rep_log)));
+                    write((int64_t)P.dwin + d + e, code_of(sid, P.rev ? (int64_t)P.swin + s - e : (int64_t)P.swin + s + (e >> P.rep_log)));
             }
     }
 

@@ -80,6 +80,11 @@ ALIGNED = [
     ((3, 20, 28), 4, [("repeat", 2, 4)]),
     ((3, 20, 30), 2, [("repeat", 2, 2)]),          # 30 source elements per row: not a whole number of half vectors
     ((3, 20, 28), 2, [("repeat", 2, 3)]),          # not a power of two
+    # reversed contiguous axis: mirrored vector loads
+    ((5, 12, 64), 2, [("slice", 2, 63, -1, -1)]),
+    ((5, 12, 64), 4, [("slice", 2, 63, -1, -1), ("slice", 1, 11, -1, -1)]),
+    ((5, 12, 72), 2, [("slice", 2, 67, 3, -1)]),   # 64 of 72 elements, ending inside the row
+    ((5, 12, 64), 2, [("slice", 2, 63, -1, -1), ("pad", (0, 0, 8), (0, 0, 8), 1)]),
 ]
 
 
