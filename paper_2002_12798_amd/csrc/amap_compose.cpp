@@ -172,10 +172,6 @@ static void finish(amap &m) {
     attach_plan(m);
 }
 
-namespace amap_detail {
-
-}  // namespace amap_detail
-
 // ---------------------------------------------------------------- helpers
 
 static amap *clone_header(const amap *m) {

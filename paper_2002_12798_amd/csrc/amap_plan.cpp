@@ -94,7 +94,7 @@ static void fill_rows(DevPiece &dp, const KPiece &kp, uint32_t V, uint32_t nwlog
 static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlog, DevPiece &dp, uint32_t &lds,
                       int &vec_bytes, std::vector<int> *slot_dim = nullptr) {
     const int es = m.elem;
-    const uint32_t vmax = 16 / es;
+    const uint32_t vmax = (uint32_t)std::min(16, std::max(es, env_int("AMAP_VEC_BYTES", 16))) / es;
     std::memset(&dp, 0, sizeof(dp));
     dp.src = kp.fill ? nullptr : reinterpret_cast<const void *>((uintptr_t)(kp.src + 1));
     dp.fill = replicate_fill(kp.fill_bits, es);
@@ -535,7 +535,7 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
         out.lds_bytes.push_back(lds_max);
         std::memset(&cur, 0, sizeof(cur));
         cur.nwlog = nwlog;
-            blocks = 0;
+        blocks = 0;
         lds_max = 0;
     };
     auto emit = [&](const std::vector<DevPiece> &dps, uint32_t lds, int vb, int fam, int64_t vol) {
