@@ -218,3 +218,22 @@ def test_execute_multi_split_outputs(dev):
     with pytest.raises(B.AmapError) as e:
         B.amap_execute_multi([d_x.data_ptr()], [d.data_ptr(), d.data_ptr()], [maps[0], maps[0]], 0)
     assert e.value.status == B.AMAP_E_ALIAS
+
+
+def test_rank_8_and_many_pieces(dev):
+    """The rank limit, and maps with more pieces than one launch holds (several launches per call)."""
+    shape = (2, 3, 2, 4, 2, 3, 2, 8)
+    ops = [("transpose", (7, 0, 6, 1, 5, 2, 4, 3)), ("slice", 3, 1, 3, 1), ("pad", (0,) * 7 + (1,), (1,) + (0,) * 7, 0x1234)]
+    x = synth.random_bits(shape, 2, 5)
+    m = B.amap_compose([shape], 2, ops)
+    assert B.amap_describe(m).rank == 8
+    _run_families(dev, m, [x], oracle.run_chain([x], ops), min_ran=2)
+    # 24 sources concatenated along the axis that becomes contiguous, then padded: 24 copy pieces + fills
+    shapes = [(6, 8 * (1 + i % 3), 40) for i in range(24)]
+    srcs = [synth.random_bits(s, 4, 50 + i) for i, s in enumerate(shapes)]
+    ops = [("concat", 1), ("transpose", (0, 2, 1)), ("pad", (1, 0, 0), (0, 3, 8), 0xFEEDF00D)]
+    m = B.amap_compose(shapes, 4, ops)
+    info = B.amap_describe(m)
+    assert info.strided and info.n_pieces > 24 and info.n_src == 24
+    _run_families(dev, m, srcs, oracle.run_chain(srcs, ops), families=[None, B.AMAP_K_ELEMENT, B.AMAP_K_TILE, B.AMAP_K_WAVE],
+                  min_ran=2)
