@@ -223,6 +223,50 @@ def bench_gemm_store(torch, device, B, synth, steps, warmup):
             "unfused_ms": round(u_gpu, 5), "speedup_vs_unfused": round(u_gpu / f_gpu, 3)}
 
 
+def bench_gemm_nchw(torch, device, B, synth, steps, warmup):
+    """Pointwise convolution on a channel-major activation: the NCHW -> NHWC transposition of
+    cfg1 (without its padding) folded into the A operand of the product with a [256,512] weight,
+    next to: transposition as its own kernel, then the same GEMM on the NHWC copy."""
+    n, c, h, wd, N = 32, 256, 56, 56, 512
+    a_map = B.amap_compose([(n, c, h, wd)], 2, [("transpose", (0, 2, 3, 1)), ("reshape", (n * h * wd, c))])
+    M, K = B.dst_shape(a_map)
+    ident = B.amap_compose([(M, K)], 2, [])
+    stream = C.c_void_p(device.current_stream())
+    per_set = (2 * M * K + K * N + M * N) * 2
+    sets = []
+    for i in range(max(2, -(-COLD_FOOTPRINT // per_set))):
+        g = torch.Generator(device="cuda").manual_seed(40 + i)
+        sets.append((torch.randn((n, c, h, wd), device="cuda", generator=g).bfloat16().view(torch.int16),
+                     (0.05 * torch.randn((K, N), device="cuda", generator=g)).bfloat16().view(torch.int16),
+                     torch.empty((M, N), dtype=torch.int16, device="cuda"),
+                     torch.empty((M, K), dtype=torch.int16, device="cuda")))
+
+    def fused(s):
+        st = B.raw.amap_gemm_fused(C.c_void_p(s[0].data_ptr()), a_map.handle, C.c_void_p(s[1].data_ptr()),
+                                   C.c_int64(N), C.c_void_p(s[2].data_ptr()), stream)
+        if st != 0:
+            raise RuntimeError(B.amap_status_str(st))
+
+    def unfused(s):
+        arr = (C.c_void_p * 1)(s[0].data_ptr())
+        st = B.raw.amap_execute(arr, C.c_void_p(s[3].data_ptr()), a_map.handle, stream)
+        st = st or B.raw.amap_gemm_fused(C.c_void_p(s[3].data_ptr()), ident.handle, C.c_void_p(s[1].data_ptr()),
+                                         C.c_int64(N), C.c_void_p(s[2].data_ptr()), stream)
+        if st != 0:
+            raise RuntimeError(B.amap_status_str(st))
+
+    f_wall, f_gpu = _time_launches(torch, fused, sets, steps, warmup)
+    u_wall, u_gpu = _time_launches(torch, unfused, sets, steps, warmup)
+    flops = 2.0 * M * N * K
+    min_bytes = (M * K + K * N + M * N) * 2
+    del sets
+    torch.cuda.empty_cache()
+    return {"workload": "pointwise convolution C[100352,512] = NHWC view of x[32,256,56,56] (runs along m) x W[256,512]",
+            "fused_ms": round(f_gpu, 5), "fused_tflops": round(flops / f_gpu / 1e9, 1),
+            "fused_gbs": round(min_bytes / f_gpu / 1e6, 1),
+            "unfused_ms": round(u_gpu, 5), "speedup_vs_unfused": round(u_gpu / f_gpu, 3)}
+
+
 def bench_multi(torch, device, B, synth, steps, warmup):
     """Q, K and V of cfg2-fwd as three separately allocated outputs: three amap_execute calls
     against one amap_execute_multi call (the same pieces, packed into one launch)."""
@@ -479,7 +523,8 @@ def main():
         print(json.dumps({"repeat_tile_reverse": nxt, "graph_dme": bench_graph(torch, device, B, synth, 10, 2),
                           "execute_multi": bench_multi(torch, device, B, synth, a.steps, a.warmup),
                           "layout_assignment": bench_layout(torch, device, B, synth, 10, 2),
-                          "fused_gemm_store": bench_gemm_store(torch, device, B, synth, a.steps, a.warmup)}))
+                          "fused_gemm_store": bench_gemm_store(torch, device, B, synth, a.steps, a.warmup),
+                          "fused_gemm_nchw": bench_gemm_nchw(torch, device, B, synth, a.steps, a.warmup)}))
         return
     if a.fused_only:
         a.no_extras = True
@@ -526,6 +571,7 @@ def main():
             nxt[r["workload"]] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
         out["repeat_tile_reverse"] = nxt
         out["fused_gemm_store"] = bench_gemm_store(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
+        out["fused_gemm_nchw"] = bench_gemm_nchw(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["execute_multi"] = bench_multi(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["graph_dme"] = bench_graph(torch, device, B, synth, 10, 2)
         out["layout_assignment"] = bench_layout(torch, device, B, synth, 10, 2)

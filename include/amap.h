@@ -316,9 +316,13 @@ amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t 
  * materialised.  A_map: dst shape [M,K], 2-byte elements (bf16), one source,
  * no fill pieces.  W: [K,N] row-major bf16.  out: [M,N] row-major bf16,
  * fp32 accumulation, round-to-nearest-even on output.
- * Needs N % 8 == 0, K % 8 == 0 and 8-element aligned contiguous runs along k
- * in the map, else AMAP_E_UNSUPPORTED; M, N and K need not be whole numbers of
- * the 256 x 128 x 64 tiles (edge tiles are clamped on load, masked on store). */
+ * Needs N % 8 == 0, K % 8 == 0 and 8-element aligned contiguous source runs in
+ * the map, either along k (a row-major operand behind permutes and reshapes) or,
+ * with M % 8 == 0, along m (an operand kept transposed, a channel-major activation
+ * read as the [N*H*W, C] matrix of a pointwise convolution: 4 k x 8 m blocks are
+ * transposed on their way to the matrix cores), else AMAP_E_UNSUPPORTED; M, N and K
+ * need not be whole numbers of the 256 x 128 x 64 tiles (edge tiles are clamped on
+ * load, masked on store). */
 amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
                             void *out, void *stream);
 

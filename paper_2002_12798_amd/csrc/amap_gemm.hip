@@ -73,6 +73,12 @@ struct GemmArgs {
 // as they are, like the A operand).
 enum WMode { W_PLAIN = 0, W_MAPPED_N = 1, W_MAPPED_K = 2 };
 
+// How the A operand is fetched: 16-byte runs of the source along k (vectors go to
+// LDS as they are), or along m (an operand kept transposed, or a channel-major
+// activation feeding a pointwise convolution: 4 k x 8 m blocks, transposed in
+// registers like the W operand whose runs lie along n).
+enum AMode { A_RUNS_K = 0, A_RUNS_M = 1 };
+
 __device__ __forceinline__ uint32_t digits_offset(const Digits &d, uint32_t x) {
     uint32_t off = 0;
     for (uint32_t j = 0; j < d.n; ++j) {
@@ -89,6 +95,20 @@ __device__ __forceinline__ uint32_t digits_offset(const Digits &d, uint32_t x) {
 // rows 8 apart that the W transposition writes both spread over the banks.
 __device__ __forceinline__ uint32_t tile_offset(uint32_t row, uint32_t chunk) {
     return row * 128u + ((chunk ^ (row & 7u) ^ ((row >> 3) & 7u)) << 4);
+}
+
+// r[i] = eight consecutive rows (m or n) of the operand at k = 4 kq + i.  The MFMA wants, per
+// row, consecutive k: transpose the 4 x 8 block of 16-bit values in registers and write
+// 8 bytes (4 k) per row of the stage.
+__device__ __forceinline__ void store_transposed(char *stage, const u32x4 *r, uint32_t row0, uint32_t kq) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t a0 = r[0][j >> 1], a1 = r[1][j >> 1], a2 = r[2][j >> 1], a3 = r[3][j >> 1];
+        u32x2 o;
+        o.x = (j & 1) ? ((a0 >> 16) | (a1 & 0xFFFF0000u)) : ((a0 & 0xFFFFu) | (a1 << 16));
+        o.y = (j & 1) ? ((a2 >> 16) | (a3 & 0xFFFF0000u)) : ((a2 & 0xFFFFu) | (a3 << 16));
+        *reinterpret_cast<u32x2 *>(stage + tile_offset(row0 + j, kq >> 1) + (kq & 1u) * 8u) = o;
+    }
 }
 
 // two fp32 -> two bf16 (round to nearest even; the hardware conversion of gfx950)
@@ -116,7 +136,7 @@ __device__ __forceinline__ void tile_of_block(uint32_t b, uint32_t tiles_m, uint
 // EDGE: M, N or K is not a whole number of tiles.  Rows past M are clamped for the
 // loads and skipped by the stores, vectors past K or N are replaced by zeros, so the
 // extra lanes neither read outside the operands nor contribute to a kept result.
-template <int WM, bool EDGE>
+template <int AM, int WM, bool EDGE>
 __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmArgs g) {
     extern __shared__ uint4 smem_v[];
     char *smem = reinterpret_cast<char *>(smem_v);
@@ -127,15 +147,22 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, tm, tn);
     const uint32_t m0 = tm * BM, n0 = tn * BN;
 
-    // ---- A prologue assignment: 8 vectors of 8 k per lane and step:
-    // vector v = tid + 256 i -> row v / 8 of the tile, k chunk v % 8
+    // ---- A prologue assignment.  Runs along k: 8 vectors of 8 k per lane and step,
+    // vector v = tid + 256 i -> row v / 8 of the tile, k chunk v % 8.  Runs along m: two
+    // 4 k x 8 m blocks per lane and step, m block tid % 32, k rows 4 (tid / 32 + 8 h) + i.
     const uint32_t a_chunk = tid & 7u;
+    const uint32_t a_mb = tid & 31u, a_kq = tid >> 5;
+    const bool a_m_ok = !EDGE || m0 + a_mb * 8u < g.M;  // this lane's 8 m of A exist
     uint32_t a_soff[8];
+    if constexpr (AM == A_RUNS_K) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        uint32_t row = m0 + (tid >> 3) + 32u * i;
-        if constexpr (EDGE) row = row < g.M ? row : g.M - 1;
-        a_soff[i] = g.sbase + digits_offset(g.dm, row);
+        for (int i = 0; i < 8; ++i) {
+            uint32_t row = m0 + (tid >> 3) + 32u * i;
+            if constexpr (EDGE) row = row < g.M ? row : g.M - 1;
+            a_soff[i] = g.sbase + digits_offset(g.dm, row);
+        }
+    } else {
+        a_soff[0] = g.sbase + digits_offset(g.dm, a_m_ok ? m0 + a_mb * 8u : 0u);
     }
     // ---- W assignment: one 4 k x 8 n block per lane and step (runs along n), or
     // four vectors of 8 k for n rows tid / 8 + 32 i (runs along k)
@@ -158,10 +185,19 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
     auto load_step = [&](uint32_t k0) {
         const uint32_t kc = k0 + a_chunk * 8u;
         const bool kc_ok = !EDGE || kc < g.K;
-        const uint32_t koff = digits_offset(g.dk, kc_ok ? kc : 0u);
+        if constexpr (AM == A_RUNS_K) {
+            const uint32_t koff = digits_offset(g.dk, kc_ok ? kc : 0u);
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            ra[i] = kc_ok ? *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[i] + koff)) : zero4;
+            for (int i = 0; i < 8; ++i)
+                ra[i] = kc_ok ? *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[i] + koff)) : zero4;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t k = k0 + 4u * (a_kq + 8u * (i >> 2)) + (i & 3);
+                const bool ok = !EDGE || (a_m_ok && k < g.K);
+                ra[i] = ok ? *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[0] + digits_offset(g.dk, ok ? k : 0u))) : zero4;
+            }
+        }
         if constexpr (WM == W_PLAIN) {
             const uint16_t *w = w_ptr + (size_t)k0 * g.N;
 #pragma unroll
@@ -184,9 +220,14 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
         }
     };
     auto store_step = [&]() {
+        if constexpr (AM == A_RUNS_K) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<u32x4 *>(sa + tile_offset((tid >> 3) + 32u * i, a_chunk)) = ra[i];
+            for (int i = 0; i < 8; ++i)
+                *reinterpret_cast<u32x4 *>(sa + tile_offset((tid >> 3) + 32u * i, a_chunk)) = ra[i];
+        } else {
+            store_transposed(sa, ra, a_mb * 8u, a_kq);
+            store_transposed(sa, ra + 4, a_mb * 8u, a_kq + 8u);
+        }
         if constexpr (WM == W_MAPPED_K) {
             // already 8 consecutive k per n row: straight into the stage
 #pragma unroll
@@ -194,17 +235,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
                 *reinterpret_cast<u32x4 *>(sw + tile_offset((tid >> 3) + 32u * i, a_chunk)) = rw[i];
             return;
         }
-        // rw[i] = W[k = 4 kq + i][n = 8 nb .. 8 nb + 7]; the MFMA wants, per n,
-        // consecutive k: transpose the 4 x 8 block of 16-bit values in registers
-        // and write 8 bytes (4 k) per n
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t a0 = rw[0][j >> 1], a1 = rw[1][j >> 1], a2 = rw[2][j >> 1], a3 = rw[3][j >> 1];
-            u32x2 o;
-            o.x = (j & 1) ? ((a0 >> 16) | (a1 & 0xFFFF0000u)) : ((a0 & 0xFFFFu) | (a1 << 16));
-            o.y = (j & 1) ? ((a2 >> 16) | (a3 & 0xFFFF0000u)) : ((a2 & 0xFFFFu) | (a3 << 16));
-            *reinterpret_cast<u32x2 *>(sw + tile_offset(w_nb * 8u + j, w_kq >> 1) + (w_kq & 1u) * 8u) = o;
-        }
+        // rw[i] = W[k = 4 kq + i][n = 8 nb .. 8 nb + 7]
+        store_transposed(sw, rw, w_nb * 8u, w_kq);
     };
 
     f32x16 acc[4][2];
@@ -289,6 +321,18 @@ bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d) {
     std::vector<IterDim> its;
     for (const IterDim &it : p.it)
         if (it.dim == dim) its.push_back(it);
+    // loops that continue one another on both sides (h and w of an image plane kept whole)
+    // count as one digit: fewer divisions, and longer contiguous runs for the vector check
+    std::sort(its.begin(), its.end(), [](const IterDim &x, const IterDim &y) { return x.mult < y.mult; });
+    for (size_t i = 0; i + 1 < its.size();) {
+        const IterDim &in = its[i], &out = its[i + 1];
+        if (out.mult == in.mult * in.extent && out.sstride == in.sstride * in.extent) {
+            its[i].extent *= out.extent;
+            its.erase(its.begin() + i + 1);
+        } else {
+            ++i;
+        }
+    }
     if (its.size() > (size_t)kMaxDigits) return false;
     int64_t covered = 1;
     for (const IterDim &it : its) covered *= it.extent;
@@ -350,7 +394,11 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
     if (!make_digits(p, 0, M, g.dm) || !make_digits(p, 1, K, g.dk)) return AMAP_E_UNSUPPORTED;
-    if (!vector_runs(g.dk, g.dm, p.sbase)) return AMAP_E_UNSUPPORTED;
+    int amode = A_RUNS_K;
+    if (!vector_runs(g.dk, g.dm, p.sbase)) {
+        if (M % 8 || !vector_runs(g.dm, g.dk, p.sbase)) return AMAP_E_UNSUPPORTED;
+        amode = A_RUNS_M;
+    }
     const int64_t cbytes = M * N * 2;
     int wmode = W_PLAIN;
     int64_t wvol = K * N;
@@ -401,12 +449,15 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
     const size_t lds = kLdsBytes;
     static thread_local bool attr_done = false;
     if (!attr_done) {
-        for (const void *fn : {reinterpret_cast<const void *>(amap_gemm_kernel<W_PLAIN, false>),
-                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_N, false>),
-                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_K, false>),
-                               reinterpret_cast<const void *>(amap_gemm_kernel<W_PLAIN, true>),
-                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_N, true>),
-                               reinterpret_cast<const void *>(amap_gemm_kernel<W_MAPPED_K, true>)}) {
+#define AMAP_GEMM_FN(AM, WM, E) reinterpret_cast<const void *>(amap_gemm_kernel<AM, WM, E>)
+        for (const void *fn :
+             {AMAP_GEMM_FN(A_RUNS_K, W_PLAIN, false), AMAP_GEMM_FN(A_RUNS_K, W_MAPPED_N, false),
+              AMAP_GEMM_FN(A_RUNS_K, W_MAPPED_K, false), AMAP_GEMM_FN(A_RUNS_K, W_PLAIN, true),
+              AMAP_GEMM_FN(A_RUNS_K, W_MAPPED_N, true), AMAP_GEMM_FN(A_RUNS_K, W_MAPPED_K, true),
+              AMAP_GEMM_FN(A_RUNS_M, W_PLAIN, false), AMAP_GEMM_FN(A_RUNS_M, W_MAPPED_N, false),
+              AMAP_GEMM_FN(A_RUNS_M, W_MAPPED_K, false), AMAP_GEMM_FN(A_RUNS_M, W_PLAIN, true),
+              AMAP_GEMM_FN(A_RUNS_M, W_MAPPED_N, true), AMAP_GEMM_FN(A_RUNS_M, W_MAPPED_K, true)}) {
+#undef AMAP_GEMM_FN
             if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
                 (void)hipGetLastError();
                 set_last_error("amap_gemm_kernel: cannot reserve its LDS stage");
@@ -417,12 +468,16 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
     }
     const dim3 grid(g.tiles_m * g.tiles_n), block(kGemmThreads);
     hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
-#define AMAP_GEMM(WM)                                                                        \
-    do {                                                                                     \
-        if (edge)                                                                            \
-            hipLaunchKernelGGL((amap_gemm_kernel<WM, true>), grid, block, lds, hs, g);       \
-        else                                                                                 \
-            hipLaunchKernelGGL((amap_gemm_kernel<WM, false>), grid, block, lds, hs, g);      \
+#define AMAP_GEMM(WM)                                                                                  \
+    do {                                                                                               \
+        if (amode == A_RUNS_K && edge)                                                                 \
+            hipLaunchKernelGGL((amap_gemm_kernel<A_RUNS_K, WM, true>), grid, block, lds, hs, g);       \
+        else if (amode == A_RUNS_K)                                                                    \
+            hipLaunchKernelGGL((amap_gemm_kernel<A_RUNS_K, WM, false>), grid, block, lds, hs, g);      \
+        else if (edge)                                                                                 \
+            hipLaunchKernelGGL((amap_gemm_kernel<A_RUNS_M, WM, true>), grid, block, lds, hs, g);       \
+        else                                                                                           \
+            hipLaunchKernelGGL((amap_gemm_kernel<A_RUNS_M, WM, false>), grid, block, lds, hs, g);      \
     } while (0)
     if (wmode == W_PLAIN)
         AMAP_GEMM(W_PLAIN);

@@ -134,7 +134,8 @@ def test_unsupported_and_error_paths(dev):
         (B.amap_compose([(256, 64)], 4, []), 256, B.AMAP_E_INVALID),                        # not 2-byte
         (B.amap_compose([(4, 256, 64)], 2, []), 256, B.AMAP_E_INVALID),                     # not a matrix
         (B.amap_compose([(256, 60)], 2, [("pad", (0, 0), (0, 4), 0)]), 256, B.AMAP_E_UNSUPPORTED),  # fill piece
-        (B.amap_compose([(64, 256)], 2, [("transpose", (1, 0))]), 256, B.AMAP_E_UNSUPPORTED),       # k not contiguous
+        (B.amap_compose([(64, 252)], 2, [("transpose", (1, 0))]), 256, B.AMAP_E_UNSUPPORTED),       # runs along m, M % 8
+        (B.amap_compose([(64, 512)], 2, [("transpose", (1, 0)), ("slice", 0, 0, 512, 2)]), 256, B.AMAP_E_UNSUPPORTED),  # no runs at all
         (B.amap_compose([(256, 128)], 2, [("slice", 1, 0, 128, 2)]), 256, B.AMAP_E_UNSUPPORTED),    # strided k
     ]:
         with pytest.raises(B.AmapError) as e:
@@ -292,3 +293,51 @@ def test_all_three_accesses_mapped(dev):
     assert got.shape == want.shape and np.abs(g - r).max() <= TOL * np.abs(r).max()
     ulp = np.maximum(np.abs(r), 2.0 ** -126) * 2.0 ** -7
     assert np.mean(np.abs(g - r) <= ulp) > 0.999
+
+
+# ---- A whose contiguous runs lie along m: a transposed operand, a channel-major activation
+
+A_M_CASES = [
+    # (A source shape, chain -> [M,K]), N
+    (((64, 256), [("transpose", (1, 0))]), 128),                                              # A kept as [K,M]
+    (((2, 64, 16, 16), [("transpose", (0, 2, 3, 1)), ("reshape", (512, 64))]), 256),          # NCHW into a pointwise convolution
+    (((3, 40, 10, 12), [("transpose", (0, 2, 3, 1)), ("reshape", (360, 40))]), 136),          # the same with an edge in M, K and N
+    (((128, 304), [("slice", 1, 24, 280, 1), ("transpose", (1, 0))]), 128),                   # runs start at an offset
+    (((192, 8), [("transpose", (1, 0))]), 8),                                                 # smaller than one tile
+    (((2, 72, 264), [("transpose", (0, 2, 1)), ("reshape", (528, 72))]), 384),                # several tiles each way
+]
+
+
+@pytest.mark.parametrize("case", range(len(A_M_CASES)))
+def test_a_operand_with_runs_along_m(dev, case):
+    import torch
+    (shape, ops), N = A_M_CASES[case]
+    print(f"[gpu] m-major A gemm case {case}", flush=True)
+    src = synth.f32_to_bf16_bits(np.random.default_rng(900 + case).standard_normal(shape).astype(np.float32))
+    a = oracle.run_chain([src], ops)
+    M, K = a.shape
+    w = synth.f32_to_bf16_bits((np.random.default_rng(950 + case).standard_normal((K, N)) * 0.05).astype(np.float32))
+    _check(_gemm(dev, src, shape, ops, w), a, w)
+    # with the weight kept transposed and the product stored through a chain as well
+    a_map = B.amap_compose([shape], 2, ops)
+    w_map = B.amap_compose([(N, K)], 2, [("transpose", (1, 0))])
+    out_map = B.amap_compose([(M, N)], 2, [("slice", 0, M - 1, -1, -1)])
+    d_src, d_wt = dev.to_device(src), dev.to_device(np.ascontiguousarray(w.T))
+    out = dev.empty_dst(out_map)
+    B.amap_gemm_mapped(d_src.data_ptr(), a_map, d_wt.data_ptr(), w_map, out_map, out.data_ptr(), 0)
+    torch.cuda.synchronize()
+    _check(dev.to_host(out)[::-1], a, w)
+
+
+def test_m_major_identity_weight_is_exact(dev):
+    """W = permutation matrix: every output is one A element, so the transposing prologue
+    must reproduce A bit for bit (values of zeros aside)."""
+    shape, ops = (2, 128, 8, 32), [("transpose", (0, 2, 3, 1)), ("reshape", (512, 128))]
+    src = synth.f32_to_bf16_bits(np.random.default_rng(31).standard_normal(shape).astype(np.float32))
+    cols = (np.arange(128) * 5 + 3) % 128
+    wf = np.zeros((128, 128), dtype=np.float32)
+    wf[np.arange(128), cols] = 1.0
+    got = _gemm(dev, src, shape, ops, synth.f32_to_bf16_bits(wf))
+    a = oracle.run_chain([src], ops)
+    nz = (a & 0x7FFF) != 0
+    assert np.array_equal(got[:, cols][nz], a[nz])
