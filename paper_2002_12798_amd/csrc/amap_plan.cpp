@@ -90,6 +90,17 @@ static void fill_rows(DevPiece &dp, const KPiece &kp, uint32_t V, uint32_t nwlog
     dp.n_blocks = (uint32_t)((vol + chunk - 1) / chunk);
 }
 
+// Streaming (non-temporal) accesses a piece may use.  A loop that stands still in the source
+// (repeat, tile, broadcast) reads the same lines again and again: those loads must stay
+// cached (a [1,1,1,256] row tiled 100,352 times ran 14.0 us with streaming loads, 11.0 us without).
+static uint32_t nt_mask(const KPiece &kp) {
+    uint32_t mask = (uint32_t)env_int("AMAP_NT", 3);
+    if (!kp.fill)
+        for (const KDim &d : kp.dims)
+            if (d.ss == 0 && d.extent > 1) mask &= ~(uint32_t)PF_NT_LOAD;
+    return mask;
+}
+
 // returns the family used (amap_kernel_id) or -1 if the forced family cannot run the piece
 static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlog, DevPiece &dp, uint32_t &lds,
                       int &vec_bytes, std::vector<int> *slot_dim = nullptr) {
@@ -147,7 +158,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
                     vec_bytes = (int)(sv * es);
                     if (line_aligned(es, {cnt * r, kp.dbase}, dso)) dp.flags |= PF_NT_STORE;
                     if (line_aligned(es, {cnt, kp.sbase}, sso)) dp.flags |= PF_NT_LOAD;
-                    dp.flags &= (uint32_t)env_int("AMAP_NT", 3);
+                    dp.flags &= nt_mask(kp);
                     return AMAP_K_ROWS;
                 }
             }
@@ -165,7 +176,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
             dp.rev = 1;
             vec_bytes = 16;
             if (line_aligned(es, {kp.dims[n - 1].extent, kp.dbase}, dso)) dp.flags |= PF_NT_STORE;
-            dp.flags &= (uint32_t)env_int("AMAP_NT", 3);
+            dp.flags &= nt_mask(kp);
             return AMAP_K_ROWS;
         }
     }
@@ -202,7 +213,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         if (line_aligned(es, {kp.dims[iP].extent, kp.dbase}, ds_others)) dp.flags |= PF_NT_STORE;
         // a fill piece loads nothing, so it never vetoes streaming loads for its launch
         if (kp.fill || line_aligned(es, {kp.dims[iP].extent, kp.sbase}, ss_others)) dp.flags |= PF_NT_LOAD;
-        dp.flags &= (uint32_t)env_int("AMAP_NT", 3);
+        dp.flags &= nt_mask(kp);
         return fam;
     }
     if (fam != AMAP_K_TILE && fam != AMAP_K_WAVE) return -1;
@@ -312,7 +323,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         for (uint32_t k = 0; k < dp.nq; ++k) batch_ds.push_back(dp.loops[k].ds);
         if (line_aligned(es, {dp.eP, (int64_t)LP * V, kp.dbase}, batch_ds)) dp.flags |= PF_NT_STORE;
         if (line_aligned(es, {EQ, (int64_t)LQ * V, kp.sbase, dp.ssP}, batch_ss)) dp.flags |= PF_NT_LOAD;
-        dp.flags &= (uint32_t)env_int("AMAP_NT", 3);
+        dp.flags &= nt_mask(kp);
     }
     vec_bytes = (int)V * es;
     return fam;
