@@ -283,6 +283,51 @@ def bench_gemm_nchw(torch, device, B, synth, steps, warmup):
             "unfused_ms": round(u_gpu, 5), "speedup_vs_unfused": round(u_gpu / f_gpu, 3)}
 
 
+def bench_gemm_gather(torch, device, B, synth, steps, warmup):
+    """Inception-style block end: the channel concat of four NCHW branches (cfg3's shapes at batch 128)
+    and the NCHW -> NHWC transposition folded into the A operand of the following pointwise
+    convolution, next to: cfg3's fused concat+transposition kernel, then the GEMM on its output."""
+    w = synth.workload("cfg3", n=128)
+    N = 256
+    a_map = B.amap_compose(w.src_shapes, 2, list(w.ops) + [("reshape", (128 * 28 * 28, 320))])
+    M, K = B.dst_shape(a_map)
+    ident = B.amap_compose([(M, K)], 2, [])
+    stream = C.c_void_p(device.current_stream())
+    per_set = (2 * M * K + K * N + M * N) * 2
+    sets = []
+    for i in range(max(2, -(-COLD_FOOTPRINT // per_set))):
+        g = torch.Generator(device="cuda").manual_seed(60 + i)
+        srcs = [torch.randn(tuple(s), device="cuda", generator=g).bfloat16().view(torch.int16) for s in w.src_shapes]
+        sets.append((srcs, (0.05 * torch.randn((K, N), device="cuda", generator=g)).bfloat16().view(torch.int16),
+                     torch.empty((M, N), dtype=torch.int16, device="cuda"),
+                     torch.empty((M, K), dtype=torch.int16, device="cuda"),
+                     (C.c_void_p * len(srcs))(*[t.data_ptr() for t in srcs])))
+
+    def fused(s):
+        st = B.raw.amap_gemm_gather(s[4], a_map.handle, C.c_void_p(s[1].data_ptr()), None, C.c_int64(N), None,
+                                    C.c_void_p(s[2].data_ptr()), stream)
+        if st != 0:
+            raise RuntimeError(B.amap_status_str(st))
+
+    def unfused(s):
+        st = B.raw.amap_execute(s[4], C.c_void_p(s[3].data_ptr()), a_map.handle, stream)
+        st = st or B.raw.amap_gemm_fused(C.c_void_p(s[3].data_ptr()), ident.handle, C.c_void_p(s[1].data_ptr()),
+                                         C.c_int64(N), C.c_void_p(s[2].data_ptr()), stream)
+        if st != 0:
+            raise RuntimeError(B.amap_status_str(st))
+
+    f_gpu, u_gpu = _time_legs(torch, [fused, unfused], sets, steps, warmup)
+    flops = 2.0 * M * N * K
+    min_bytes = (M * K + K * N + M * N) * 2
+    del sets
+    torch.cuda.empty_cache()
+    return {"workload": "pointwise convolution C[100352,256] on the channel concat of four NCHW branches "
+                        "[128,{64,96,128,32},28,28] (A gathered from four sources, runs along m)",
+            "fused_ms": round(f_gpu, 5), "fused_tflops": round(flops / f_gpu / 1e9, 1),
+            "fused_gbs": round(min_bytes / f_gpu / 1e6, 1),
+            "unfused_ms": round(u_gpu, 5), "speedup_vs_unfused": round(u_gpu / f_gpu, 3)}
+
+
 def bench_multi(torch, device, B, synth, steps, warmup):
     """Q, K and V of cfg2-fwd as three separately allocated outputs: three amap_execute calls
     against one amap_execute_multi call (the same pieces, packed into one launch)."""
@@ -540,7 +585,8 @@ def main():
                           "execute_multi": bench_multi(torch, device, B, synth, a.steps, a.warmup),
                           "layout_assignment": bench_layout(torch, device, B, synth, 10, 2),
                           "fused_gemm_store": bench_gemm_store(torch, device, B, synth, a.steps, a.warmup),
-                          "fused_gemm_nchw": bench_gemm_nchw(torch, device, B, synth, a.steps, a.warmup)}))
+                          "fused_gemm_nchw": bench_gemm_nchw(torch, device, B, synth, a.steps, a.warmup),
+                          "fused_gemm_gather": bench_gemm_gather(torch, device, B, synth, a.steps, a.warmup)}))
         return
     if a.fused_only:
         a.no_extras = True
@@ -588,6 +634,7 @@ def main():
         out["repeat_tile_reverse"] = nxt
         out["fused_gemm_store"] = bench_gemm_store(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["fused_gemm_nchw"] = bench_gemm_nchw(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
+        out["fused_gemm_gather"] = bench_gemm_gather(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["execute_multi"] = bench_multi(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["graph_dme"] = bench_graph(torch, device, B, synth, 10, 2)
         out["layout_assignment"] = bench_layout(torch, device, B, synth, 10, 2)

@@ -344,6 +344,20 @@ amap_status amap_gemm_fused_store(const void *A_src, const amap_t *A_map, const 
 amap_status amap_gemm_mapped(const void *A_src, const amap_t *A_map, const void *W_src, const amap_t *W_map,
                              const amap_t *out_map, void *out, void *stream);
 
+/* The product with A gathered from several sources: a concat along the reduction dimension
+ * (channel concat of the branches of an inception block in front of a pointwise convolution,
+ * skip connections) rewritten into the consumer load, eq. 4 once per concat operand, so the
+ * concatenated tensor never exists.  A_map may have up to 8 sources and one piece per range
+ * of k; A_srcs is indexed by the map's source ids (device pointers, 16-byte aligned).  Every
+ * piece must span all of m, the pieces must follow one another along k, all with their
+ * 8-element runs the same way round: along k, then every range but the last must end at a
+ * multiple of 64, or along m, then at a multiple of 32 (a k-step, or half of one, reads one
+ * source).  W_map NULL: W_src is the row-major [K,N] weight and N its width; else as in
+ * amap_gemm_mapped and N is ignored.  out_map as in amap_gemm_fused_store, or NULL.
+ * A single-piece A_map is accepted as well.  AMAP_E_UNSUPPORTED for any other piece structure. */
+amap_status amap_gemm_gather(const void *const *A_srcs, const amap_t *A_map, const void *W_src, const amap_t *W_map,
+                             int64_t N, const amap_t *out_map, void *out, void *stream);
+
 const char *amap_status_str(amap_status s);
 
 /* Text of the HIP error behind the last AMAP_E_HIP returned on this thread

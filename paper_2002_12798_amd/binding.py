@@ -29,7 +29,7 @@ EXPORTS = [
     "amap_concat",
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
     "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_multi", "amap_execute_kernel",
-    "amap_gemm_fused", "amap_gemm_fused_store", "amap_gemm_mapped", "amap_status_str", "amap_last_error",
+    "amap_gemm_fused", "amap_gemm_fused_store", "amap_gemm_mapped", "amap_gemm_gather", "amap_status_str", "amap_last_error",
     "amap_graph_create", "amap_graph_free", "amap_graph_input", "amap_graph_op", "amap_graph_compute",
     "amap_graph_output", "amap_graph_eliminate", "amap_graph_load",
     "amap_layout_create", "amap_layout_free", "amap_layout_tensor", "amap_layout_op", "amap_layout_solve",
@@ -92,6 +92,7 @@ _L.amap_execute_multi.argtypes = [_pp, _pp, _pp, C.c_int, _vp]
 _L.amap_gemm_fused.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp]
 _L.amap_gemm_fused_store.argtypes = [_vp, _vp, _vp, C.c_int64, _vp, _vp, _vp]
 _L.amap_gemm_mapped.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_L.amap_gemm_gather.argtypes = [_pp, _vp, _vp, _vp, C.c_int64, _vp, _vp, _vp]
 _L.amap_status_str.argtypes = [C.c_int]
 _L.amap_status_str.restype = C.c_char_p
 
@@ -353,6 +354,14 @@ def amap_gemm_mapped(a_src_ptr, a_map, w_src_ptr, w_map, out_map, out_ptr, strea
     _check(_L.amap_gemm_mapped(C.c_void_p(a_src_ptr), a_map.handle, C.c_void_p(w_src_ptr), w_map.handle,
                                out_map.handle if out_map is not None else None, C.c_void_p(out_ptr),
                                C.c_void_p(stream)), "amap_gemm_mapped")
+
+
+def amap_gemm_gather(a_src_ptrs, a_map, w_src_ptr, w_map, n, out_map, out_ptr, stream=0):
+    """a_src_ptrs: device pointers by source id of a_map (None for ids the map does not use)."""
+    _check(_L.amap_gemm_gather(_ptr_array(a_src_ptrs), a_map.handle, C.c_void_p(w_src_ptr),
+                               w_map.handle if w_map is not None else None, int(n),
+                               out_map.handle if out_map is not None else None, C.c_void_p(out_ptr),
+                               C.c_void_p(stream)), "amap_gemm_gather")
 
 
 class GraphDME:

@@ -33,6 +33,7 @@ constexpr int kATileBytes = BM * BK * 2;  // 32 KiB
 constexpr int kCPitch = BN * 2 + 16;      // bytes per row of the staged output tile (padded against bank conflicts)
 constexpr int kLdsBytes = BM * kCPitch;   // 69,632 B: covers the operand stage (48 KiB) and the output stage
 constexpr int kMaxDigits = 4;
+constexpr int kMaxSeg = 8;  // sources of an A operand gathered along k
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -65,6 +66,15 @@ struct GemmArgs {
     // W read through a map as well: element (k, n) of W is W[wbase + wk(k) + wn(n)]
     uint32_t wbase;
     Digits wk, wn;
+    // A gathered from several sources, one per range of k (a concat along the reduction
+    // dimension that is never materialised): segment j covers k in [seg_kend[j-1], seg_kend[j])
+    // and reads seg_src[j] at seg_sbase[j] + seg_dm[j](m) + seg_dk[j](k - seg_kend[j-1]).
+    // n_seg <= 1: the single-source fields above are used instead.
+    uint32_t n_seg;
+    uint32_t seg_kend[kMaxSeg];
+    uint32_t seg_sbase[kMaxSeg];
+    const uint16_t *seg_src[kMaxSeg];
+    Digits seg_dm[kMaxSeg], seg_dk[kMaxSeg];
 };
 
 // How the W operand is fetched: plain row-major [K,N]; through a map whose
@@ -136,7 +146,9 @@ __device__ __forceinline__ void tile_of_block(uint32_t b, uint32_t tiles_m, uint
 // EDGE: M, N or K is not a whole number of tiles.  Rows past M are clamped for the
 // loads and skipped by the stores, vectors past K or N are replaced by zeros, so the
 // extra lanes neither read outside the operands nor contribute to a kept result.
-template <int AM, int WM, bool EDGE>
+// SEG: A is gathered from several sources along k (its own instances: the extra
+// bookkeeping in the load path costs the single-source kernels 4-6 % when it is a run-time branch).
+template <int AM, int WM, bool EDGE, bool SEG>
 __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmArgs g) {
     extern __shared__ uint4 smem_v[];
     char *smem = reinterpret_cast<char *>(smem_v);
@@ -154,14 +166,21 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
     const uint32_t a_mb = tid & 31u, a_kq = tid >> 5;
     const bool a_m_ok = !EDGE || m0 + a_mb * 8u < g.M;  // this lane's 8 m of A exist
     uint32_t a_soff[8];
-    if constexpr (AM == A_RUNS_K) {
+    constexpr bool segmented = SEG;
+    // state of the segmented load stream (runs along k): current segment, its first k, its source
+    uint32_t cur_seg = 0, seg_klo = 0;
+    const uint16_t *a_base = segmented ? g.seg_src[0] : g.A_src;
+    auto a_rows_of_segment = [&](uint32_t sg) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             uint32_t row = m0 + (tid >> 3) + 32u * i;
             if constexpr (EDGE) row = row < g.M ? row : g.M - 1;
-            a_soff[i] = g.sbase + digits_offset(g.dm, row);
+            a_soff[i] = segmented ? g.seg_sbase[sg] + digits_offset(g.seg_dm[sg], row) : g.sbase + digits_offset(g.dm, row);
         }
-    } else {
+    };
+    if constexpr (AM == A_RUNS_K) {
+        a_rows_of_segment(0);
+    } else if constexpr (!segmented) {
         a_soff[0] = g.sbase + digits_offset(g.dm, a_m_ok ? m0 + a_mb * 8u : 0u);
     }
     // ---- W assignment: one 4 k x 8 n block per lane and step (runs along n), or
@@ -186,16 +205,50 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
         const uint32_t kc = k0 + a_chunk * 8u;
         const bool kc_ok = !EDGE || kc < g.K;
         if constexpr (AM == A_RUNS_K) {
-            const uint32_t koff = digits_offset(g.dk, kc_ok ? kc : 0u);
+            uint32_t koff;
+            if constexpr (segmented) {
+                // segment ends are multiples of BK, so a whole step reads one source; steps come in
+                // increasing k, so the segment index only moves forward
+                uint32_t sg = cur_seg;
+                while (sg + 1 < g.n_seg && k0 >= g.seg_kend[sg]) ++sg;
+                if (sg != cur_seg) {
+                    cur_seg = sg;
+                    seg_klo = g.seg_kend[sg - 1];
+                    a_base = g.seg_src[sg];
+                    a_rows_of_segment(sg);
+                }
+                koff = digits_offset(g.seg_dk[sg], kc_ok ? kc - seg_klo : 0u);
+            } else {
+                koff = digits_offset(g.dk, kc_ok ? kc : 0u);
+            }
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                ra[i] = kc_ok ? *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[i] + koff)) : zero4;
-        } else {
+                ra[i] = kc_ok ? *reinterpret_cast<const u32x4 *>(a_base + (size_t)(a_soff[i] + koff)) : zero4;
+        } else if constexpr (!segmented) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const uint32_t k = k0 + 4u * (a_kq + 8u * (i >> 2)) + (i & 3);
                 const bool ok = !EDGE || (a_m_ok && k < g.K);
                 ra[i] = ok ? *reinterpret_cast<const u32x4 *>(g.A_src + (size_t)(a_soff[0] + digits_offset(g.dk, ok ? k : 0u))) : zero4;
+            }
+        } else {
+            // segment ends are multiples of 32: each half of the step (h) reads one source
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t kb = k0 + 32u * h;
+                uint32_t sg = 0;
+                while (sg + 1 < g.n_seg && kb >= g.seg_kend[sg]) ++sg;
+                const uint32_t klo = sg ? g.seg_kend[sg - 1] : 0u;
+                const uint16_t *base = g.seg_src[sg];
+                // this lane's 8 m in that source (decoded per half-step: registers are short here)
+                const uint32_t off = g.seg_sbase[sg] + digits_offset(g.seg_dm[sg], a_m_ok ? m0 + a_mb * 8u : 0u);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t k = kb + 4u * a_kq + i;
+                    const bool ok = !EDGE || (a_m_ok && k < g.K);
+                    ra[4 * h + i] =
+                        ok ? *reinterpret_cast<const u32x4 *>(base + (size_t)(off + digits_offset(g.seg_dk[sg], ok ? k - klo : 0u))) : zero4;
+                }
             }
         }
         if constexpr (WM == W_PLAIN) {
@@ -315,8 +368,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
     }
 }
 
-// Split the loops of one dst dimension of the A map into digits.
-bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d) {
+// Split the loops of one dst dimension of a piece into digits.  The piece must start at
+// index `lo` of that dimension and cover `extent` indices.
+bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d, int64_t lo = 0) {
     std::memset(&d, 0, sizeof(d));
     std::vector<IterDim> its;
     for (const IterDim &it : p.it)
@@ -336,7 +390,7 @@ bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d) {
     if (its.size() > (size_t)kMaxDigits) return false;
     int64_t covered = 1;
     for (const IterDim &it : its) covered *= it.extent;
-    if (covered != extent || p.lo[dim] != 0) return false;  // the piece must span the whole dimension
+    if (covered != extent || p.lo[dim] != lo) return false;
     for (const IterDim &it : its) {
         const uint32_t j = d.n++;
         d.mult[j] = (uint32_t)it.mult;
@@ -372,34 +426,79 @@ bool overlaps(const void *a, int64_t an, const void *b, int64_t bn) {
     return a0 < b0 + (uintptr_t)bn && b0 < a0 + (uintptr_t)an;
 }
 
-amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, int64_t N, const amap_t *W_map,
-                        const amap_t *out_map, void *out, void *stream) {
+// extent of a piece along one dst dimension
+int64_t piece_extent(const Piece &p, int dim) {
+    int64_t e = 1;
+    for (const IterDim &it : p.it)
+        if (it.dim == dim) e *= it.extent;
+    return e;
+}
+
+// A_srcs: by source id of A_map when `by_id`, else the one source of a single-piece map
+amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_map, const void *W, int64_t N,
+                        const amap_t *W_map, const amap_t *out_map, void *out, void *stream) {
     if (W_map) {
         if (W_map->shape.size() != 2) return AMAP_E_INVALID;
         N = W_map->shape[1];
     }
-    if (!A_src || !A_map || !W || !out || N <= 0) return AMAP_E_INVALID;
-    if (((uintptr_t)A_src | (uintptr_t)W | (uintptr_t)out) & 15) return AMAP_E_INVALID;
+    if (!A_srcs || !A_map || !W || !out || N <= 0) return AMAP_E_INVALID;
+    if (((uintptr_t)W | (uintptr_t)out) & 15) return AMAP_E_INVALID;
     if (A_map->shape.size() != 2 || A_map->elem != 2) return AMAP_E_INVALID;
     const int64_t M = A_map->shape[0], K = A_map->shape[1];
     if (M == 0 || K == 0) return AMAP_E_UNSUPPORTED;
     if (N % 8 || K % 8) return AMAP_E_UNSUPPORTED;  // 16-byte vectors along n and k
     const bool edge = M % BM || N % BN || K % BK;
-    if (!A_map->strided || A_map->pieces.size() != 1 || A_map->pieces[0].fill) return AMAP_E_UNSUPPORTED;
-    const Piece &p = A_map->pieces[0];
-    const int64_t svol = volume_of(A_map->src_shapes[p.src]);
-    if (svol >= (1ll << 31) || M * K >= (1ll << 31) || M * N >= (1ll << 40) || K * N >= (1ll << 31))
-        return AMAP_E_UNSUPPORTED;
+    if (!A_map->strided || A_map->pieces.empty()) return AMAP_E_UNSUPPORTED;
+    if (M * K >= (1ll << 31) || M * N >= (1ll << 40) || K * N >= (1ll << 31)) return AMAP_E_UNSUPPORTED;
     if (out_map && M * N >= (1ll << 31)) return AMAP_E_UNSUPPORTED;  // the store map works in 32-bit offsets
+    const int64_t cbytes = M * N * 2;
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
-    if (!make_digits(p, 0, M, g.dm) || !make_digits(p, 1, K, g.dk)) return AMAP_E_UNSUPPORTED;
-    int amode = A_RUNS_K;
-    if (!vector_runs(g.dk, g.dm, p.sbase)) {
-        if (M % 8 || !vector_runs(g.dm, g.dk, p.sbase)) return AMAP_E_UNSUPPORTED;
-        amode = A_RUNS_M;
+    // ---- the A operand: one piece, or one piece per range of k (segments, sorted by k)
+    std::vector<const Piece *> segs;
+    for (const Piece &q : A_map->pieces) segs.push_back(&q);
+    if (segs.size() > (size_t)kMaxSeg || (segs.size() > 1 && !by_id)) return AMAP_E_UNSUPPORTED;
+    std::sort(segs.begin(), segs.end(), [](const Piece *x, const Piece *y) { return x->lo[1] < y->lo[1]; });
+    int amode = -1;
+    int64_t k_at = 0;
+    for (size_t j = 0; j < segs.size(); ++j) {
+        const Piece &p = *segs[j];
+        if (p.fill) return AMAP_E_UNSUPPORTED;
+        const void *src = A_srcs[by_id ? p.src : 0];
+        if (!src || ((uintptr_t)src & 15)) return AMAP_E_INVALID;
+        const int64_t svol = volume_of(A_map->src_shapes[p.src]);
+        if (svol >= (1ll << 31)) return AMAP_E_UNSUPPORTED;
+        if (overlaps(out, cbytes, src, svol * 2)) return AMAP_E_ALIAS;
+        const int64_t kext = piece_extent(p, 1);
+        Digits dm, dk;
+        // every segment spans all of m and continues k where the one before ended
+        if (!make_digits(p, 0, M, dm) || !make_digits(p, 1, kext, dk, k_at)) return AMAP_E_UNSUPPORTED;
+        int mode = A_RUNS_K;
+        if (!vector_runs(dk, dm, p.sbase)) {
+            if (M % 8 || !vector_runs(dm, dk, p.sbase)) return AMAP_E_UNSUPPORTED;
+            mode = A_RUNS_M;
+        }
+        if (amode >= 0 && mode != amode) return AMAP_E_UNSUPPORTED;  // all segments the same way round
+        amode = mode;
+        k_at += kext;
+        // a k-step (64, runs along k) or half of one (32, runs along m) reads one source
+        if (j + 1 < segs.size() && k_at % (mode == A_RUNS_K ? BK : BK / 2)) return AMAP_E_UNSUPPORTED;
+        if (segs.size() == 1) {
+            g.A_src = static_cast<const uint16_t *>(src);
+            g.sbase = (uint32_t)p.sbase;
+            g.dm = dm;
+            g.dk = dk;
+        } else {
+            g.seg_src[j] = static_cast<const uint16_t *>(src);
+            g.seg_sbase[j] = (uint32_t)p.sbase;
+            g.seg_kend[j] = (uint32_t)k_at;
+            g.seg_dm[j] = dm;
+            g.seg_dk[j] = dk;
+        }
     }
-    const int64_t cbytes = M * N * 2;
+    if (k_at != K) return AMAP_E_UNSUPPORTED;
+    g.n_seg = (uint32_t)segs.size();
+    if (g.n_seg > 1) g.A_src = g.seg_src[0];
     int wmode = W_PLAIN;
     int64_t wvol = K * N;
     if (W_map) {
@@ -418,7 +517,7 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
             return AMAP_E_UNSUPPORTED;
         g.wbase = (uint32_t)q.sbase;
     }
-    if (overlaps(out, cbytes, A_src, svol * 2) || overlaps(out, cbytes, W, wvol * 2)) return AMAP_E_ALIAS;
+    if (overlaps(out, cbytes, W, wvol * 2)) return AMAP_E_ALIAS;
     if (out_map) {
         // the layout chain applied to the product, turned into a store map: the
         // reverse of the chain's load map (Section 2.1), C index -> index of out
@@ -437,19 +536,18 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
         g.obase = (uint32_t)q.sbase;
     }
 
-    g.A_src = static_cast<const uint16_t *>(A_src);
     g.W = static_cast<const uint16_t *>(W);
     g.C = static_cast<uint16_t *>(out);
     g.M = (uint32_t)M;
     g.N = (uint32_t)N;
     g.K = (uint32_t)K;
-    g.sbase = (uint32_t)p.sbase;
     g.tiles_m = (uint32_t)((M + BM - 1) / BM);
     g.tiles_n = (uint32_t)((N + BN - 1) / BN);
     const size_t lds = kLdsBytes;
     static thread_local bool attr_done = false;
     if (!attr_done) {
-#define AMAP_GEMM_FN(AM, WM, E) reinterpret_cast<const void *>(amap_gemm_kernel<AM, WM, E>)
+#define AMAP_GEMM_FN(AM, WM, E) \
+    reinterpret_cast<const void *>(amap_gemm_kernel<AM, WM, E, false>), reinterpret_cast<const void *>(amap_gemm_kernel<AM, WM, E, true>)
         for (const void *fn :
              {AMAP_GEMM_FN(A_RUNS_K, W_PLAIN, false), AMAP_GEMM_FN(A_RUNS_K, W_MAPPED_N, false),
               AMAP_GEMM_FN(A_RUNS_K, W_MAPPED_K, false), AMAP_GEMM_FN(A_RUNS_K, W_PLAIN, true),
@@ -468,16 +566,24 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
     }
     const dim3 grid(g.tiles_m * g.tiles_n), block(kGemmThreads);
     hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+    const bool seg = g.n_seg > 1;
+#define AMAP_GEMM_AWE(AM, WM, E)                                                                       \
+    do {                                                                                               \
+        if (seg)                                                                                       \
+            hipLaunchKernelGGL((amap_gemm_kernel<AM, WM, E, true>), grid, block, lds, hs, g);          \
+        else                                                                                           \
+            hipLaunchKernelGGL((amap_gemm_kernel<AM, WM, E, false>), grid, block, lds, hs, g);         \
+    } while (0)
 #define AMAP_GEMM(WM)                                                                                  \
     do {                                                                                               \
         if (amode == A_RUNS_K && edge)                                                                 \
-            hipLaunchKernelGGL((amap_gemm_kernel<A_RUNS_K, WM, true>), grid, block, lds, hs, g);       \
+            AMAP_GEMM_AWE(A_RUNS_K, WM, true);                                                         \
         else if (amode == A_RUNS_K)                                                                    \
-            hipLaunchKernelGGL((amap_gemm_kernel<A_RUNS_K, WM, false>), grid, block, lds, hs, g);      \
+            AMAP_GEMM_AWE(A_RUNS_K, WM, false);                                                        \
         else if (edge)                                                                                 \
-            hipLaunchKernelGGL((amap_gemm_kernel<A_RUNS_M, WM, true>), grid, block, lds, hs, g);       \
+            AMAP_GEMM_AWE(A_RUNS_M, WM, true);                                                         \
         else                                                                                           \
-            hipLaunchKernelGGL((amap_gemm_kernel<A_RUNS_M, WM, false>), grid, block, lds, hs, g);      \
+            AMAP_GEMM_AWE(A_RUNS_M, WM, false);                                                        \
     } while (0)
     if (wmode == W_PLAIN)
         AMAP_GEMM(W_PLAIN);
@@ -485,6 +591,7 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
         AMAP_GEMM(W_MAPPED_N);
     else
         AMAP_GEMM(W_MAPPED_K);
+#undef AMAP_GEMM_AWE
 #undef AMAP_GEMM
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -499,7 +606,7 @@ amap_status gemm_launch(const void *A_src, const amap_t *A_map, const void *W, i
 extern "C" amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N, void *out,
                                        void *stream) {
     try {
-        return gemm_launch(A_src, A_map, W, N, nullptr, nullptr, out, stream);
+        return gemm_launch(&A_src, false, A_map, W, N, nullptr, nullptr, out, stream);
     } catch (...) {
         return AMAP_E_NOMEM;
     }
@@ -509,7 +616,7 @@ extern "C" amap_status amap_gemm_fused_store(const void *A_src, const amap_t *A_
                                              const amap_t *out_map, void *out, void *stream) {
     if (!out_map) return AMAP_E_INVALID;
     try {
-        return gemm_launch(A_src, A_map, W, N, nullptr, out_map, out, stream);
+        return gemm_launch(&A_src, false, A_map, W, N, nullptr, out_map, out, stream);
     } catch (...) {
         return AMAP_E_NOMEM;
     }
@@ -519,7 +626,19 @@ extern "C" amap_status amap_gemm_mapped(const void *A_src, const amap_t *A_map, 
                                         const amap_t *out_map, void *out, void *stream) {
     if (!W_map) return AMAP_E_INVALID;
     try {
-        return gemm_launch(A_src, A_map, W_src, 0, W_map, out_map, out, stream);
+        return gemm_launch(&A_src, false, A_map, W_src, 0, W_map, out_map, out, stream);
+    } catch (...) {
+        return AMAP_E_NOMEM;
+    }
+}
+
+extern "C" amap_status amap_gemm_gather(const void *const *A_srcs, const amap_t *A_map, const void *W_src,
+                                        const amap_t *W_map, int64_t N, const amap_t *out_map, void *out, void *stream) {
+    if (!A_srcs || !A_map) return AMAP_E_INVALID;
+    for (const Piece &q : A_map->pieces)
+        if (!q.fill && (q.src < 0 || (size_t)q.src >= A_map->src_shapes.size())) return AMAP_E_INVALID;
+    try {
+        return gemm_launch(A_srcs, true, A_map, W_src, W_map ? 0 : N, W_map, out_map, out, stream);
     } catch (...) {
         return AMAP_E_NOMEM;
     }

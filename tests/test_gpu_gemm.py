@@ -341,3 +341,80 @@ def test_m_major_identity_weight_is_exact(dev):
     a = oracle.run_chain([src], ops)
     nz = (a & 0x7FFF) != 0
     assert np.array_equal(got[:, cols][nz], a[nz])
+
+
+# ---- A gathered from several sources: a concat along k that is never materialised
+
+GATHER_CASES = [
+    # source shapes, chain -> [M,K], N
+    ([(256, 64), (256, 128), (256, 64)], [("concat", 1)], 128),                                        # runs along k, ends at 64, 192
+    ([(2, 8, 16, 64), (2, 8, 16, 128)], [("concat", 3), ("reshape", (256, 192))], 256),                # NHWC branches
+    ([(2, 64, 16, 16), (2, 96, 16, 16), (2, 128, 16, 16), (2, 32, 16, 16)],
+     [("concat", 1), ("transpose", (0, 2, 3, 1)), ("reshape", (512, 320))], 128),                      # NCHW branches: runs along m
+    ([(3, 32, 10, 12), (3, 40, 10, 12)], [("concat", 1), ("transpose", (0, 2, 3, 1)), ("reshape", (360, 72))], 136),  # + edges
+    ([(200, 64), (200, 40)], [("concat", 1)], 72),                                                     # runs along k, edges
+    ([(520, 128)] * 8, [("concat", 1)], 384),                                                          # eight sources, several tiles
+]
+
+
+@pytest.mark.parametrize("case", range(len(GATHER_CASES)))
+def test_a_gathered_from_several_sources(dev, case):
+    import torch
+    shapes, ops, N = GATHER_CASES[case]
+    print(f"[gpu] gather gemm case {case}", flush=True)
+    rng = np.random.default_rng(1200 + case)
+    srcs = [synth.f32_to_bf16_bits(rng.standard_normal(s).astype(np.float32)) for s in shapes]
+    a = oracle.run_chain(srcs, ops)
+    M, K = a.shape
+    w = synth.f32_to_bf16_bits((rng.standard_normal((K, N)) * 0.05).astype(np.float32))
+    a_map = B.amap_compose(shapes, 2, ops)
+    d_srcs, d_w = [dev.to_device(s) for s in srcs], dev.to_device(w)
+    out = torch.empty((M, N), dtype=torch.int16, device="cuda")
+    B.amap_gemm_gather([t.data_ptr() for t in d_srcs], a_map, d_w.data_ptr(), None, N, None, out.data_ptr(), 0)
+    torch.cuda.synchronize()
+    _check(dev.to_host(out), a, w)
+    # transposed weight and mapped store on top
+    w_map = B.amap_compose([(N, K)], 2, [("transpose", (1, 0))])
+    out_map = B.amap_compose([(M, N)], 2, [("slice", 0, M - 1, -1, -1)])
+    d_wt = dev.to_device(np.ascontiguousarray(w.T))
+    out2 = dev.empty_dst(out_map)
+    B.amap_gemm_gather([t.data_ptr() for t in d_srcs], a_map, d_wt.data_ptr(), w_map, 0, out_map, out2.data_ptr(), 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(dev.to_host(out2)[::-1], dev.to_host(out))
+
+
+def test_gather_one_source_twice_and_error_paths(dev):
+    import torch
+    rng = np.random.default_rng(77)
+    x = synth.f32_to_bf16_bits(rng.standard_normal((256, 64)).astype(np.float32))
+    y = synth.f32_to_bf16_bits(rng.standard_normal((256, 64)).astype(np.float32))
+    sx, sy = B.amap_source(0, (256, 64), 2), B.amap_source(1, (256, 64), 2)
+    a_map = B.amap_concat([sx, sy, sx], 1)                      # [X | Y | X]: source 0 feeds two ranges of k
+    w = synth.f32_to_bf16_bits((rng.standard_normal((192, 128)) * 0.05).astype(np.float32))
+    d_x, d_y, d_w = dev.to_device(x), dev.to_device(y), dev.to_device(w)
+    out = torch.empty((256, 128), dtype=torch.int16, device="cuda")
+    B.amap_gemm_gather([d_x.data_ptr(), d_y.data_ptr()], a_map, d_w.data_ptr(), None, 128, None, out.data_ptr(), 0)
+    torch.cuda.synchronize()
+    _check(dev.to_host(out), np.concatenate([x, y, x], axis=1), w)
+
+    def refused(shapes, ops, status, ptrs=None):
+        m = B.amap_compose(shapes, 2, ops)
+        with pytest.raises(B.AmapError) as e:
+            B.amap_gemm_gather(ptrs or [d_x.data_ptr()] * len(shapes), m, d_w.data_ptr(), None, 128, None, out.data_ptr(), 0)
+        assert e.value.status == status, (e.value.status, status)
+
+    refused([(256, 32), (256, 96)], [("concat", 1)], B.AMAP_E_UNSUPPORTED)                  # range ends inside a k-step
+    refused([(128, 64), (128, 64)], [("concat", 0)], B.AMAP_E_UNSUPPORTED)                  # concat along m
+    refused([(256, 64), (256, 64)], [("concat", 1)], B.AMAP_E_INVALID, [d_x.data_ptr(), 0])  # a source pointer missing
+    refused([(256, 64)] * 9, [("concat", 1)], B.AMAP_E_UNSUPPORTED)                         # more than 8 ranges
+    # one source along k, the other along m
+    mixed = B.amap_concat([B.amap_source(0, (256, 64), 2), B.amap_transpose(B.amap_source(1, (64, 256), 2), (1, 0))], 1)
+    with pytest.raises(B.AmapError) as e:
+        B.amap_gemm_gather([d_x.data_ptr(), d_y.data_ptr()], mixed, d_w.data_ptr(), None, 128, None, out.data_ptr(), 0)
+    assert e.value.status == B.AMAP_E_UNSUPPORTED
+    # the single-source entry point refuses a gathered A
+    two = B.amap_compose([(256, 64), (256, 64)], 2, [("concat", 1)])
+    with pytest.raises(B.AmapError) as e:
+        B.amap_gemm_fused(d_x.data_ptr(), two, d_w.data_ptr(), 128, out.data_ptr(), 0)
+    assert e.value.status == B.AMAP_E_UNSUPPORTED
+    torch.cuda.synchronize()
