@@ -109,9 +109,10 @@ int64_t moved_bytes(const amap &m) {
     return info.min_read_bytes + info.write_bytes;
 }
 
-// the identity of exactly one whole tensor: executing it would be a plain copy
+// the identity of exactly one whole tensor, element for element in memory order (its shape may
+// differ: a reshape of a whole tensor is a view): executing it would be a plain copy
 bool is_identity(const amap &m, const std::vector<int64_t> &src_shape) {
-    if (!m.strided || m.kpieces.size() != 1 || m.kpieces[0].fill || m.shape != src_shape) return false;
+    if (!m.strided || m.kpieces.size() != 1 || m.kpieces[0].fill || volume_of(m.shape) != volume_of(src_shape)) return false;
     const KPiece &k = m.kpieces[0];
     if (k.dbase != 0 || k.sbase != 0) return false;
     if (volume_of(m.shape) <= 1) return true;

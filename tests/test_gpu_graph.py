@@ -138,3 +138,44 @@ def test_relayout_copies_of_the_global_assignment_on_device(dev):
         got = dev.to_host(dev.execute(m, [dev.to_device(stored)]))
         torch.cuda.synchronize()
         assert np.array_equal(got, oracle.transpose(logical, dst_order)), (op, slot)
+
+
+def test_concat_block_feeds_the_matrix_cores_without_copies(dev):
+    """Four channel-major branches -> concat -> NHWC -> rows of a pointwise convolution.  After
+    elimination the product's first operand is one map over the four branch tensors; it goes
+    straight into the GEMM's operand load (amap_gemm_gather), no copy kernel runs at all."""
+    import torch
+    n, h, w, chans, cout = 4, 16, 16, (64, 96, 128, 32), 128
+    g = synth.Graph(2)
+    branches = [g.input((n, c, h, w)) for c in chans]
+    wt = g.input((sum(chans), cout))
+    cat = g.op(("concat", 1), branches)
+    nhwc = g.op(("transpose", (0, 2, 3, 1)), cat)
+    rows = g.op(("reshape", (n * h * w, sum(chans))), nhwc)
+    z = g.compute("matmul", [rows, wt], (n * h * w, cout))
+    g.output(g.op(("reshape", (n, h, w, cout)), z))
+    rng = np.random.default_rng(5)
+    ins = [synth.f32_to_bf16_bits(rng.standard_normal((n, c, h, w)).astype(np.float32)) for c in chans]
+    ins.append(synth.f32_to_bf16_bits((rng.standard_normal((sum(chans), cout)) * 0.05).astype(np.float32)))
+    want = oracle.run_graph(g.nodes, ins, lambda kind, xs, shape: oracle.gemm_bf16(xs[0], xs[1]))
+
+    dme = B.GraphDME(g.nodes, g.outputs, g.elem_size)
+    rep = dme.eliminate()
+    # the product's output, reshaped, is a view: no pair left; only the A operand carries a map
+    assert rep.n_layout_ops == 4 and rep.n_pairs_left == 0 and rep.n_alias_outputs == 1 and rep.n_mapped_loads == 1
+    loads = {(cons, slot): (m, ids) for cons, slot, m, ids in dme.loads()}
+    mat = {i: dev.to_device(x) for i, x in zip(g.input_ids(), ins)}
+    a_map, a_ids = loads[(z, 0)]
+    w_map, w_ids = loads[(z, 1)]
+    assert sorted(a_ids) == sorted(branches) and w_ids == [wt]
+    out = torch.empty((n * h * w, cout), dtype=torch.int16, device="cuda")
+    B.amap_gemm_gather([mat[k].data_ptr() for k in a_ids], a_map, mat[wt].data_ptr(), None, cout, None,
+                       out.data_ptr(), 0)
+    torch.cuda.synchronize()
+    o_map, o_ids = loads[(-1, g.outputs[0])]
+    assert o_ids == [z]                                            # the output is the product, viewed as NHWC
+    got = synth.bf16_bits_to_f32(dev.to_host(out)).astype(np.float64)
+    ref = synth.bf16_bits_to_f32(want[z]).astype(np.float64)
+    assert np.abs(got - ref).max() <= 1e-2 * np.abs(ref).max()
+    ulp = np.maximum(np.abs(ref), 2.0 ** -126) * 2.0 ** -7
+    assert np.mean(np.abs(got - ref) <= ulp) > 0.999

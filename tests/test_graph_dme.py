@@ -88,6 +88,21 @@ def test_cancelling_chain_leaves_no_copy():
     assert ids == [x] and B.amap_describe(m).n_pieces == 1
 
 
+def test_reshape_of_a_whole_tensor_is_a_view():
+    """A reshape changes no address: an output or an operand that is only a reshaped tensor
+    needs no copy, whatever its shape says."""
+    g = synth.Graph(2)
+    x = g.input((4, 6))
+    c = g.compute("add", [g.op(("reshape", (2, 12)), x), g.op(("reshape", (2, 12)), x)], (2, 12))
+    g.output(g.op(("reshape", (3, 8)), c))
+    g.output(g.op(("transpose", (1, 0)), c))            # this one does move data
+    dme = B.GraphDME(g.nodes, g.outputs, 2)
+    rep = dme.eliminate()
+    assert (rep.n_alias_outputs, rep.n_pairs_left, rep.n_mapped_loads) == (1, 1, 0)
+    assert rep.moved_bytes_after == 2 * 24 * 2
+    _check_loads(g, oracle.run_graph(g.nodes, _inputs(g, 3), standin), dme)
+
+
 def test_several_consumers_and_chains_through_compute():
     g = synth.Graph(2)
     a = g.input((4, 6))
