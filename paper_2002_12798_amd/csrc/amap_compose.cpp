@@ -693,6 +693,20 @@ struct LinDim {
     int64_t extent, ds, ss;
 };
 
+// Loops (sorted by ds descending) that continue one another on both sides become one loop:
+// a tensor that is contiguous where it is read can then be re-split along any new shape.
+void merge_contiguous(std::vector<LinDim> &dims) {
+    for (size_t i = 0; i + 1 < dims.size();) {
+        const LinDim &a = dims[i], &b = dims[i + 1];
+        if (a.ds == b.ds * b.extent && a.ss == b.ss * b.extent) {
+            dims[i] = {a.extent * b.extent, b.ds, b.ss};
+            dims.erase(dims.begin() + i + 1);
+        } else {
+            ++i;
+        }
+    }
+}
+
 struct Redigit {
     std::vector<int64_t> shape, R;  // new shape and its row-major strides
     std::vector<int> cand;          // new dims with extent > 1, outermost first
@@ -753,7 +767,20 @@ struct Redigit {
                     acc += (n - 1) * m;
                     continue;
                 }
-                // loop j carries out of dimension d: cut its range into blocks
+                // loop j carries out of dimension d.  If it steps through whole multiples of the
+                // dimension (everything inside it stays below one step, the dimension is a whole
+                // number of steps, the loop a whole number of dimensions) it is two loops: one
+                // inside d and one that counts d's wrap-arounds, i.e. runs in an outer dimension.
+                if (acc < m && E % m == 0 && n % (E / m) == 0) {
+                    const int64_t q = E / m;
+                    std::vector<LinDim> two(dims.begin(), dims.begin() + j);
+                    two.push_back({n / q, dims[j].ds * q, dims[j].ss * q});
+                    two.push_back({q, dims[j].ds, dims[j].ss});
+                    two.insert(two.end(), dims.begin() + j + 1, dims.end());
+                    rec(L0, sbase, two);
+                    return;
+                }
+                // otherwise cut its range into blocks
                 split(L0, sbase, dims, j, lo[d], acc - lo[d], m, E);
                 return;
             }
@@ -863,6 +890,7 @@ extern "C" amap_status amap_reshape(const amap_t *m, int rank, const int64_t *sh
                 rd.ok = false;
                 break;
             }
+            merge_contiguous(dims);
             rd.proto = &p;
             rd.rec(L0, p.sbase, dims);
             if (!rd.ok) break;

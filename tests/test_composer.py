@@ -150,6 +150,25 @@ def test_misaligned_reshape_after_slice_splits_pieces():
     _check_map(m, [x], oracle.run_chain([x], ops), expect_strided=True)
 
 
+@pytest.mark.parametrize("shape,to", [((2, 12), (3, 8)), ((6, 4, 10), (5, 48)), ((7, 9), (3, 21)), ((7, 9), (63,)),
+                                      ((8, 8), (4, 4, 4)), ((4, 6), (2, 12)), ((3, 5, 7), (7, 15))])
+def test_reshape_of_a_contiguous_tensor_is_one_piece(shape, to):
+    """Loops that continue one another are merged and re-split along the new shape, so a
+    reshape across the old dimension boundaries of a whole tensor stays a single piece,
+    also behind a transposition that keeps the reshaped dimensions together."""
+    srcs = _iota_sources([shape], 4)
+    m = B.amap_compose([shape], 4, [("reshape", to)])
+    assert B.amap_describe(m).n_pieces == 1
+    _check_map(m, srcs, oracle.run_chain(srcs, [("reshape", to)]), expect_strided=True)
+    # two leading batch dimensions swapped, the rest reshaped across its boundaries
+    ops = [("transpose", (1, 0) + tuple(range(2, 2 + len(shape)))), ("reshape", (3, 2) + tuple(to))]
+    big = (2, 3) + tuple(shape)
+    srcs = _iota_sources([big], 4)
+    m = B.amap_compose([big], 4, ops)
+    assert B.amap_describe(m).n_pieces == 1
+    _check_map(m, srcs, oracle.run_chain(srcs, ops), expect_strided=True)
+
+
 def test_pad_then_flatten_and_step_slices():
     x = _iota_sources([(2, 3, 5, 6)], 2)[0]
     ops = [("pad", (0, 0, 1, 1), (0, 0, 1, 1), 7), ("reshape", (6, 56)), ("slice", 1, 3, 50, 3)]
