@@ -157,7 +157,90 @@ void finalise(amap &m) {
 }  // namespace amap_detail
 
 // every builder ends here: derive the kernel-form pieces and the launch plan
+// ---- merging of pieces
+//
+// A split followed by a concat of the parts, a tensor cut into slices that are processed the same
+// way and put together again: composition leaves one piece per part although the parts continue
+// one another.  Two pieces that are the same box displaced along ONE dst dimension, reading the
+// same source (or writing the same constant), are one piece with a longer, or a new, outermost
+// loop in that dimension.
+
+static bool same_loops(const std::vector<IterDim> &a, size_t a0, const std::vector<IterDim> &b, size_t b0, bool fill) {
+    if (a.size() - a0 != b.size() - b0) return false;
+    for (size_t i = a0, j = b0; i < a.size(); ++i, ++j)
+        if (a[i].extent != b[j].extent || a[i].mult != b[j].mult || (!fill && a[i].sstride != b[j].sstride)) return false;
+    return true;
+}
+
+// b lies after a along one dimension: extend a by b if the two form one box
+static bool absorb(Piece &a, const Piece &b, int rank) {
+    if (a.fill != b.fill || (a.fill ? a.fill_bits != b.fill_bits : a.src != b.src)) return false;
+    int d = -1;
+    for (int k = 0; k < rank; ++k)
+        if (a.lo[k] != b.lo[k]) {
+            if (d >= 0) return false;
+            d = k;
+        }
+    if (d < 0) return false;
+    const int64_t dlo = b.lo[d] - a.lo[d], ds = a.fill ? 0 : b.sbase - a.sbase;
+    if (dlo <= 0) return false;
+    std::vector<IterDim> ao, bo, ad, bd;  // loops outside dimension d, loops in it (outermost first)
+    for (const IterDim &it : a.it) (it.dim == d ? ad : ao).push_back(it);
+    for (const IterDim &it : b.it) (it.dim == d ? bd : bo).push_back(it);
+    if (!same_loops(ao, 0, bo, 0, a.fill)) return false;
+    for (size_t i = 0; i < ao.size(); ++i)
+        if (ao[i].dim != bo[i].dim) return false;
+    const bool f = a.fill;
+    if (!ad.empty() && ad.size() == bd.size() && same_loops(ad, 1, bd, 1, f) && ad[0].mult == bd[0].mult &&
+        (f || ad[0].sstride == bd[0].sstride) && dlo == ad[0].extent * ad[0].mult && ds == ad[0].extent * ad[0].sstride) {
+        ad[0].extent += bd[0].extent;  // b continues a's outermost loop
+    } else if (ad.size() == bd.size() + 1 && same_loops(ad, 1, bd, 0, f) && dlo == ad[0].extent * ad[0].mult &&
+               ds == ad[0].extent * ad[0].sstride) {
+        ad[0].extent += 1;             // b is one more iteration of it
+    } else if (bd.size() == ad.size() + 1 && same_loops(bd, 1, ad, 0, f) && dlo == bd[0].mult && ds == bd[0].sstride) {
+        ad.insert(ad.begin(), IterDim{bd[0].extent + 1, d, bd[0].mult, f ? 0 : bd[0].sstride});  // a is iteration 0 of b's loop
+    } else if (same_loops(ad, 0, bd, 0, f)) {
+        int64_t span = 0;
+        for (const IterDim &it : ad) span += (it.extent - 1) * it.mult;
+        if (dlo <= span) return false;  // interleaved boxes: not a loop nest
+        ad.insert(ad.begin(), IterDim{2, d, dlo, ds});  // two copies of the same box: a loop of two
+    } else {
+        return false;
+    }
+    a.it = ao;
+    a.it.insert(a.it.end(), ad.begin(), ad.end());
+    sort_iter(a);
+    return true;
+}
+
+static void merge_pieces(amap &m) {
+    const int rank = (int)m.shape.size();
+    std::vector<Piece> &P = m.pieces;
+    if (P.size() < 2 || P.size() > 1024) return;
+    // neighbours first: by source, then by origin
+    std::stable_sort(P.begin(), P.end(), [rank](const Piece &a, const Piece &b) {
+        if (a.fill != b.fill) return a.fill < b.fill;
+        if (!a.fill && a.src != b.src) return a.src < b.src;
+        for (int k = 0; k < rank; ++k)
+            if (a.lo[k] != b.lo[k]) return a.lo[k] < b.lo[k];
+        return false;
+    });
+    bool changed = true;
+    while (changed) {
+        changed = false;
+        for (size_t i = 0; i < P.size(); ++i)
+            for (size_t j = 0; j < P.size(); ++j) {
+                if (i == j || !absorb(P[i], P[j], rank)) continue;
+                P.erase(P.begin() + (ptrdiff_t)j);
+                if (j < i) --i;
+                j = (size_t)-1;  // the grown piece may now reach pieces it could not before
+                changed = true;
+            }
+    }
+}
+
 static void finish(amap &m) {
+    if (m.strided) merge_pieces(m);
     // a source that no piece reads any more (sliced away, say) is no longer an
     // argument of the map: the caller need not supply it
     if (m.strided && !m.pieces.empty()) {

@@ -455,8 +455,38 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
     // ---- the A operand: one piece, or one piece per range of k (segments, sorted by k)
+    // A piece whose k indices are not one interval (one source feeding two ranges of k is kept
+    // as one piece with an outer loop over the two) is taken apart along that loop.
+    std::vector<Piece> parts(A_map->pieces.begin(), A_map->pieces.end());
+    for (size_t i = 0; i < parts.size() && parts.size() <= (size_t)kMaxSeg; ++i) {
+        for (;;) {
+            std::vector<IterDim> kl;
+            for (const IterDim &it : parts[i].it)
+                if (it.dim == 1) kl.push_back(it);
+            std::sort(kl.begin(), kl.end(), [](const IterDim &x, const IterDim &y) { return x.mult < y.mult; });
+            int64_t run = 1;
+            bool dense = true;
+            for (const IterDim &it : kl) {
+                dense = dense && it.mult == run;
+                run *= it.extent;
+            }
+            if (dense || kl.back().extent + parts.size() - 1 > (size_t)kMaxSeg) break;
+            const IterDim outer = kl.back();
+            Piece rest = parts[i];
+            rest.it.erase(std::remove_if(rest.it.begin(), rest.it.end(),
+                                         [&](const IterDim &it) { return it.dim == 1 && it.mult == outer.mult; }),
+                          rest.it.end());
+            parts[i] = rest;
+            for (int64_t c = 1; c < outer.extent; ++c) {
+                Piece q = rest;
+                q.lo[1] += c * outer.mult;
+                q.sbase += c * outer.sstride;
+                parts.push_back(q);
+            }
+        }
+    }
     std::vector<const Piece *> segs;
-    for (const Piece &q : A_map->pieces) segs.push_back(&q);
+    for (const Piece &q : parts) segs.push_back(&q);
     if (segs.size() > (size_t)kMaxSeg || (segs.size() > 1 && !by_id)) return AMAP_E_UNSUPPORTED;
     std::sort(segs.begin(), segs.end(), [](const Piece *x, const Piece *y) { return x->lo[1] < y->lo[1]; });
     int amode = -1;

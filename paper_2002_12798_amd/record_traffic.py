@@ -17,7 +17,7 @@ import statistics
 import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-SOURCES = ["paper_2002_12798_amd/csrc/amap_kernels.hip", "paper_2002_12798_amd/csrc/amap_index.hpp",
+SOURCES = ["paper_2002_12798_amd/csrc/amap_kernels.hip", "paper_2002_12798_amd/csrc/amap_index.hpp", "paper_2002_12798_amd/csrc/amap_compose.cpp",
            "paper_2002_12798_amd/csrc/amap_plan.cpp", "paper_2002_12798_amd/csrc/amap_device.hpp"]
 COPY_BYTES = 106496000  # read and written per launch of `bench.py --copy-only`
 

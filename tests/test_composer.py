@@ -59,7 +59,7 @@ def test_workload_maps_small_values(name):
 def test_workload_piece_counts_and_bytes():
     exp = {  # name: (pieces, fill pieces, min read bytes, write bytes, fill bytes)
         "cfg0": (2, 1, 393216, 491520, 24576 * 4),
-        "cfg1": (5, 4, 51380224, 55115776, 1867776 * 2),
+        "cfg1": (3, 2, 51380224, 55115776, 1867776 * 2),   # top+bottom and left+right borders: one loop of two each
         "cfg2_fwd": (1, 0, 37748736, 37748736, 0),
         "cfg2_rev": (1, 0, 12582912, 12582912, 0),
         "cfg3": (4, 0, 16056320, 16056320, 0),
@@ -167,6 +167,42 @@ def test_reshape_of_a_contiguous_tensor_is_one_piece(shape, to):
     m = B.amap_compose([big], 4, ops)
     assert B.amap_describe(m).n_pieces == 1
     _check_map(m, srcs, oracle.run_chain(srcs, ops), expect_strided=True)
+
+
+def test_pieces_that_continue_one_another_are_merged():
+    """split + concat, slices processed alike and put together again, a source repeated by concat,
+    the two halves of a padding ring: pieces that are one box displaced along one dimension
+    become one piece (checked element by element against the operators run one at a time)."""
+    es = 4
+    x = _iota_sources([(4, 10)], es)[0]
+    sx = B.amap_source(0, (4, 10), es)
+
+    def check(m, want, n_pieces, distinct=None):
+        info = B.amap_describe(m)
+        assert info.n_pieces == n_pieces
+        if distinct is None:
+            _check_map(m, [x], want, expect_strided=True)
+            return
+        # the same source elements read more than once
+        assert np.array_equal(B.amap_eval_host(m, [x], mode=1), want) and np.array_equal(B.amap_eval_host(m, [x], mode=2), want)
+        assert B.amap_check_cover(m) == (0, 0) and info.min_read_bytes == distinct * es
+
+    check(B.amap_concat([B.amap_slice(sx, 1, 0, 4), B.amap_slice(sx, 1, 4, 10)], 1), x, 1)           # split, concat
+    check(B.amap_concat([B.amap_slice(sx, 0, 0, 1), B.amap_slice(sx, 0, 1, 2), B.amap_slice(sx, 0, 2, 4)], 0), x, 1)
+    check(B.amap_concat([B.amap_slice(sx, 1, 4, 10), B.amap_slice(sx, 1, 0, 4)], 1),
+          np.concatenate([x[:, 4:], x[:, :4]], axis=1), 2)                                         # a rotation stays two
+    check(B.amap_concat([sx, sx, sx], 0), np.concatenate([x, x, x], axis=0), 1, distinct=40)       # = tile
+    check(B.amap_concat([sx, B.amap_slice(sx, 0, 3, -1, -1), sx], 0), np.concatenate([x, x[::-1], x], axis=0), 2, distinct=40)
+    ring = B.amap_pad(B.amap_pad(sx, (1, 0), (1, 0), 7), (1, 0), (1, 0), 7)
+    check(ring, oracle.run_chain([x], [("pad", (2, 0), (2, 0), 7)]), 3)                             # data + two border loops
+    y = _iota_sources([(8, 6, 10)], es)[0]
+    sy = B.amap_source(0, (8, 6, 10), es)
+    m = B.amap_concat([B.amap_transpose(B.amap_slice(sy, 1, i, i + 1), (1, 0, 2)) for i in range(6)], 0)
+    assert B.amap_describe(m).n_pieces == 1
+    _check_map(m, [y], np.ascontiguousarray(y.transpose(1, 0, 2)), expect_strided=True)
+    # different constants do not merge
+    two = B.amap_pad(B.amap_pad(sx, (1, 0), (0, 0), 1), (0, 0), (1, 0), 2)
+    assert B.amap_describe(two).n_fill_pieces == 2
 
 
 def test_pad_then_flatten_and_step_slices():
