@@ -242,8 +242,11 @@ amap_status amap_graph_load(const amap_graph_t *g, int index, int *consumer, int
  * the layouts are propagated along the data dependencies through the
  * unrestricted operators to a fixed point, and only where a tensor meets
  * conflicting requirements is a copy t -> t' inserted, as a relayout map that
- * amap_execute runs.  The result is compared with the local assignment
- * (every operator on its own, unrestricted operators in the canonical order). */
+ * amap_execute runs.  The propagated assignment is then refined tensor by tensor
+ * for as long as the total copy bytes shrink (starting from the cheaper of it and
+ * the local assignment), so the result never costs more than the local assignment
+ * (every operator on its own, unrestricted operators in the canonical order), with
+ * which it is compared. */
 typedef struct amap_layout_graph amap_layout_graph_t;
 
 amap_status amap_layout_create(amap_layout_graph_t **out);

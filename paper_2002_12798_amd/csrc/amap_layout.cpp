@@ -208,21 +208,96 @@ extern "C" amap_status amap_layout_solve(amap_layout_graph_t *g, amap_layout_rep
     }
     for (LTensor &x : g->t)
         if (x.order.empty()) x.order = canonical((int)x.shape.size());
+
+    // ---- cost of an assignment, and the order an unrestricted operator works in
+    const size_t nt = g->t.size();
+    // the order of the free operands of one rank that leaves the fewest bytes to convert
+    auto work_order = [&](const LOp &o, size_t rank, const std::vector<Order> &ord) {
+        Order best;
+        int64_t best_cost = -1;
+        for (const LOperand &c : o.x) {
+            if (!c.req.empty() || g->t[c.tensor].shape.size() != rank) continue;
+            const Order &cand = ord[c.tensor];
+            int64_t cost = 0;
+            for (const LOperand &b : o.x)
+                if (b.req.empty() && g->t[b.tensor].shape.size() == rank && ord[b.tensor] != cand) cost += 2 * bytes_of(g->t[b.tensor]);
+            if (best_cost < 0 || cost < best_cost) {
+                best_cost = cost;
+                best = cand;
+            }
+        }
+        return best;
+    };
+    auto need_of = [&](const LOp &o, const LOperand &a, const std::vector<Order> &ord) {
+        if (!a.req.empty()) return a.req;
+        return o.same_layout ? work_order(o, g->t[a.tensor].shape.size(), ord) : Order();
+    };
+    auto cost_of = [&](const std::vector<Order> &ord) {
+        int64_t c = 0;
+        for (const LOp &o : g->ops)
+            for (const LOperand &a : o.x) {
+                const Order need = need_of(o, a, ord);
+                if (!need.empty() && need != ord[a.tensor]) c += 2 * bytes_of(g->t[a.tensor]);
+            }
+        return c;
+    };
+    std::vector<Order> ord(nt);
+    for (size_t ti = 0; ti < nt; ++ti) ord[ti] = g->t[ti].order;
+    // The propagation is a heuristic.  The per-operator assignment is an assignment too (every
+    // tensor stored the way its producer writes it): start from whichever of the two is cheaper ...
+    {
+        std::vector<Order> loc(nt);
+        for (size_t ti = 0; ti < nt; ++ti) {
+            const LTensor &x = g->t[ti];
+            loc[ti] = x.fixed ? x.order : canonical((int)x.shape.size());
+            if (!x.fixed && x.producer >= 0)
+                for (const LOperand &a : g->ops[x.producer].x)
+                    if (a.output && a.tensor == (int)ti && !a.req.empty()) loc[ti] = a.req;
+        }
+        if (cost_of(loc) < cost_of(ord)) ord = loc;
+    }
+    // ... and let every free tensor try the orders its operators ask for or its neighbours have,
+    // one tensor at a time, for as long as the total shrinks.
+    for (int sweep = 0; sweep < 16; ++sweep) {
+        bool better = false;
+        for (size_t ti = 0; ti < nt; ++ti) {
+            if (g->t[ti].fixed) continue;
+            std::vector<Order> cands;
+            for (const LOp &o : g->ops) {
+                bool mine = false;
+                for (const LOperand &a : o.x) mine = mine || a.tensor == (int)ti;
+                if (!mine) continue;
+                for (const LOperand &a : o.x) {
+                    if (a.tensor == (int)ti && !a.req.empty()) cands.push_back(a.req);
+                    if (a.tensor != (int)ti && a.req.empty() && o.same_layout &&
+                        g->t[a.tensor].shape.size() == g->t[ti].shape.size())
+                        cands.push_back(ord[a.tensor]);
+                }
+            }
+            int64_t cur = cost_of(ord);
+            for (const Order &c : cands) {
+                if (c == ord[ti]) continue;
+                const Order keep = ord[ti];
+                ord[ti] = c;
+                const int64_t now = cost_of(ord);
+                if (now < cur) {
+                    cur = now;
+                    better = true;
+                } else {
+                    ord[ti] = keep;
+                }
+            }
+        }
+        if (!better) break;
+    }
+    for (size_t ti = 0; ti < nt; ++ti) g->t[ti].order = ord[ti];
     // Conflicts: an operand whose operator needs another order than the tensor has.
     for (size_t oi = 0; oi < g->ops.size(); ++oi) {
         const LOp &o = g->ops[oi];
         for (size_t si = 0; si < o.x.size(); ++si) {
             const LOperand &a = o.x[si];
             const LTensor &x = g->t[a.tensor];
-            Order need = a.req;
-            if (need.empty() && o.same_layout) {
-                // the order the operator works in: that of its first free operand of this rank
-                for (const LOperand &b : o.x)
-                    if (b.req.empty() && g->t[b.tensor].shape.size() == x.shape.size()) {
-                        need = g->t[b.tensor].order;
-                        break;
-                    }
-            }
+            const Order need = need_of(o, a, ord);
             if (need.empty() || need == x.order) continue;
             LCopy c;
             c.op = (int)oi;

@@ -25,7 +25,9 @@ def _check_plan(tensors, ops, g):
     and every unrestricted operator sees one order per rank."""
     copies = {(op, slot): (t, m) for op, slot, t, m in g.copies()}
     for oi, (operands, outs, reqs, same) in enumerate(ops):
-        seen = {}
+        # an unrestricted operator works in the order of its operands that need no copy
+        seen = {len(tensors[t][0]): g.order(t) for si, t in enumerate(operands)
+                if same and (reqs is None or reqs[si] is None) and (oi, si) not in copies}
         for si, t in enumerate(operands):
             have = g.order(t)
             req = None if reqs is None else reqs[si]
@@ -131,3 +133,62 @@ def test_layout_error_paths():
     g.solve()
     with pytest.raises(B.AmapError):
         g.solve()
+
+
+def _random_layout_graph(seed):
+    """Small graphs of rank-2 tensors (two possible orders each), so that every assignment can be tried."""
+    rng = np.random.default_rng(seed)
+    orders = [(0, 1), (1, 0)]
+    tensors = [((int(rng.integers(2, 9)), int(rng.integers(2, 9))), orders[int(rng.integers(2))] if rng.random() < 0.7 else None)]
+    ops = []
+    for _ in range(int(rng.integers(3, 7))):
+        n_in = int(rng.integers(1, 3))
+        ins = [int(rng.integers(len(tensors))) for _ in range(n_in)]
+        restricted = rng.random() < 0.5
+        if not restricted:
+            shape = tensors[ins[0]][0]
+            ins = [t for t in ins if tensors[t][0] == shape] or ins[:1]   # element-wise: equal shapes
+        else:
+            shape = (int(rng.integers(2, 9)), int(rng.integers(2, 9)))
+        tensors.append((shape, orders[int(rng.integers(2))] if rng.random() < 0.15 else None))
+        operands = ins + [len(tensors) - 1]
+        outs = [0] * len(ins) + [1]
+        if restricted:
+            reqs = [orders[int(rng.integers(2))] if rng.random() < 0.8 else None for _ in operands]
+            ops.append((operands, outs, reqs, False))
+        else:
+            ops.append((operands, outs, None, True))
+    return tensors, ops
+
+
+def _assignment_cost(tensors, ops, order, es=2):
+    cost = 0
+    for operands, outs, reqs, same in ops:
+        if reqs is not None:
+            cost += sum(2 * es * int(np.prod(tensors[t][0])) for t, r in zip(operands, reqs) if r is not None and order[t] != r)
+        elif same:
+            cost += min(sum(2 * es * int(np.prod(tensors[t][0])) for t in operands if order[t] != o) for o in [(0, 1), (1, 0)])
+    return cost
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_global_assignment_between_the_optimum_and_the_local_one(seed):
+    """The propagation is a heuristic.  On graphs small enough to try every assignment its copy
+    bytes can never be below the true optimum (else a needed copy is missing) and should not
+    exceed what assigning every operator on its own costs."""
+    import itertools
+    tensors, ops = _random_layout_graph(seed)
+    g = _build(tensors, ops)
+    rep = g.solve()
+    _check_plan(tensors, ops, g)
+    free = [t for t, (_, fixed) in enumerate(tensors) if fixed is None]
+    best = None
+    for choice in itertools.product([(0, 1), (1, 0)], repeat=len(free)):
+        order = {t: fixed for t, (_, fixed) in enumerate(tensors)}
+        order.update(dict(zip(free, choice)))
+        c = _assignment_cost(tensors, ops, order)
+        best = c if best is None else min(best, c)
+    assert best <= rep.copy_bytes_global, (best, rep.copy_bytes_global)
+    assert rep.copy_bytes_global <= rep.copy_bytes_local, (rep.copy_bytes_global, rep.copy_bytes_local)
+    # the solver's own figure is the cost of the assignment it reports
+    assert rep.copy_bytes_global == _assignment_cost(tensors, ops, {t: g.order(t) for t in range(len(tensors))})
