@@ -237,3 +237,39 @@ def test_rank_8_and_many_pieces(dev):
     assert info.strided and info.n_pieces > 24 and info.n_src == 24
     _run_families(dev, m, srcs, oracle.run_chain(srcs, ops), families=[None, B.AMAP_K_ELEMENT, B.AMAP_K_TILE, B.AMAP_K_WAVE],
                   min_ran=2)
+
+
+def test_maps_whose_pieces_were_merged(dev):
+    """Maps built from many slices and concats, whose pieces the composer merges into loops
+    (also loops that walk the source backwards or stand still in it), in every kernel family."""
+    rng = np.random.default_rng(0)
+    xs = synth.random_bits((1000, 64), 2, 1)
+    x = B.amap_source(0, (1000, 64), 2)
+    perm = rng.permutation(1000)
+    gathered = B.amap_concat([B.amap_slice(x, 0, int(i), int(i) + 1) for i in perm], 0)
+    ys = synth.random_bits((8, 6, 40), 2, 2)
+    y = B.amap_source(0, (8, 6, 40), 2)
+    zs = synth.random_bits((64, 48), 4, 3)
+    z = B.amap_source(0, (64, 48), 4)
+    cases = [
+        ("split + concat", B.amap_concat([B.amap_slice(x, 0, i, i + 1) for i in range(1000)], 0), [xs], xs, 1),
+        ("rows in reverse order", B.amap_concat([B.amap_slice(x, 0, 999 - i, 1000 - i) for i in range(1000)], 0), [xs],
+         xs[::-1].copy(), 1),
+        ("row permutation", gathered, [xs], xs[perm], None),
+        ("row permutation, transposed", B.amap_transpose(gathered, (1, 0)), [xs], np.ascontiguousarray(xs[perm].T), None),
+        ("slices transposed, then concat", B.amap_concat([B.amap_transpose(B.amap_slice(y, 1, i, i + 1), (1, 0, 2))
+                                                           for i in range(6)], 0), [ys],
+         np.ascontiguousarray(ys.transpose(1, 0, 2)), 1),
+        ("padding in two steps", B.amap_pad(B.amap_pad(z, (1, 1), (1, 1), 5), (2, 3), (1, 0), 5), [zs],
+         oracle.run_chain([zs], [("pad", (3, 4), (2, 1), 5)]), None),
+        ("source, its mirror image, source", B.amap_concat([z, B.amap_slice(z, 0, 63, -1, -1), z], 0), [zs],
+         np.concatenate([zs, zs[::-1], zs], 0), 2),
+        ("de-interleave", B.amap_concat([B.amap_slice(z, 1, 0, 48, 2), B.amap_slice(z, 1, 1, 48, 2)], 1), [zs],
+         np.concatenate([zs[:, 0::2], zs[:, 1::2]], 1), 1),
+    ]
+    for name, m, srcs, want, n_pieces in cases:
+        print(f"[gpu] merged pieces: {name}", flush=True)
+        if n_pieces is not None:
+            assert B.amap_describe(m).n_pieces == n_pieces, name
+        assert B.amap_plan_selfcheck(m) == 0
+        _run_families(dev, m, srcs, want)
