@@ -198,6 +198,18 @@ amap_status amap_graph_input(amap_graph_t *g, int rank, const int64_t *shape, am
 /* tensor = op(inputs): a layout operator (CONCAT takes n_inputs >= 1 tensors, every other kind one). */
 amap_status amap_graph_op(amap_graph_t *g, const amap_op *op, const int *inputs, int n_inputs, int *tensor);
 
+/* A layout operator given as a map in load (gather) form: tensor[i] = inputs[src][map(i)], any
+ * composed map over n_inputs sources (source id k of the map reads inputs[k]; shapes and
+ * element size must agree with the graph tensors, else AMAP_E_SHAPE). */
+amap_status amap_graph_map(amap_graph_t *g, const amap_t *map, const int *inputs, int n_inputs, int *tensor);
+
+/* A layout operator given in store (scatter) form, the paper's t_s[f_s(i)] = t_l[i]: store_map
+ * has the shape of `input` as its dst shape and ONE source, whose shape is the shape of the tensor
+ * the operator writes; store_map(i) is where element i of the input goes.  The map is reversed on
+ * entry (Section 2.1), so it must be a bijection between the two tensors (AMAP_E_UNSUPPORTED
+ * otherwise, as for amap_inverse); from then on the operator is eliminated like the others. */
+amap_status amap_graph_store(amap_graph_t *g, const amap_t *store_map, int input, int *tensor);
+
 /* An opaque compute operator reading n_inputs tensors (in this order: input slot k = inputs[k])
  * and producing one materialised tensor of the given shape. */
 amap_status amap_graph_compute(amap_graph_t *g, const int *inputs, int n_inputs, int rank, const int64_t *shape,

@@ -231,6 +231,28 @@ def run_chain(srcs, ops, keep_intermediates=False):
     return (xs[0], inter) if keep_intermediates else xs[0]
 
 
+def store_form(x, chain, out_shape):
+    """A layout operator written as a store (Section 2, the store t_s[f_s(i)] = v): element i of x
+    goes to position f_s(i) of the output.  f_s is given as the operator chain that, applied to the
+    index space of the output, yields the shape of x; running the chain on the output's linear
+    indices gives f_s(i) for every i, and the store is executed as written, one element at a time."""
+    x = np.ascontiguousarray(x)
+    n = int(np.prod(out_shape))
+    where = run_chain([np.arange(n, dtype=np.uint32).reshape(out_shape)], list(chain))
+    if where.shape != x.shape:
+        raise OracleError("store map does not have the shape of the stored tensor")
+    out = np.empty(n, dtype=x.dtype)
+    written = np.zeros(n, dtype=bool)
+    for pos, v in zip(where.reshape(-1).tolist(), x.reshape(-1)):
+        if written[pos]:
+            raise OracleError("store map writes an element twice")
+        written[pos] = True
+        out[pos] = v
+    if not written.all():
+        raise OracleError("store map leaves elements of the output unwritten")
+    return out.reshape(out_shape)
+
+
 def run_graph(nodes, inputs, compute):
     """Run an operator graph the un-optimised way: every node one at a time, every
     tensor materialised.  nodes: ("input", shape) | ("op", op, [ids]) |
@@ -247,6 +269,8 @@ def run_graph(nodes, inputs, compute):
             t.append(x)
         elif n[0] == "op":
             t.append(apply_op([t[i] for i in n[2]], n[1])[0])
+        elif n[0] == "store":
+            t.append(store_form(t[n[2][0]], n[1], tuple(n[3])))
         elif n[0] == "compute":
             y = np.ascontiguousarray(compute(n[1], [t[i] for i in n[2]], tuple(n[3])))
             if y.shape != tuple(n[3]):

@@ -30,7 +30,8 @@ EXPORTS = [
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
     "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_multi", "amap_execute_kernel",
     "amap_gemm_fused", "amap_gemm_fused_store", "amap_gemm_mapped", "amap_gemm_gather", "amap_status_str", "amap_last_error",
-    "amap_graph_create", "amap_graph_free", "amap_graph_input", "amap_graph_op", "amap_graph_compute",
+    "amap_graph_create", "amap_graph_free", "amap_graph_input", "amap_graph_op", "amap_graph_map", "amap_graph_store",
+    "amap_graph_compute",
     "amap_graph_output", "amap_graph_eliminate", "amap_graph_load",
     "amap_layout_create", "amap_layout_free", "amap_layout_tensor", "amap_layout_op", "amap_layout_solve",
     "amap_layout_order", "amap_layout_copy",
@@ -113,6 +114,8 @@ _L.amap_graph_free.argtypes = [_vp]
 _L.amap_graph_free.restype = None
 _L.amap_graph_input.argtypes = [_vp, C.c_int, _i64p, C.c_int, _ip]
 _L.amap_graph_op.argtypes = [_vp, C.POINTER(amap_op), _ip, C.c_int, _ip]
+_L.amap_graph_map.argtypes = [_vp, _vp, _ip, C.c_int, _ip]
+_L.amap_graph_store.argtypes = [_vp, _vp, C.c_int, _ip]
 _L.amap_graph_compute.argtypes = [_vp, _ip, C.c_int, C.c_int, _i64p, C.c_int, _ip]
 _L.amap_graph_output.argtypes = [_vp, C.c_int]
 _L.amap_graph_eliminate.argtypes = [_vp, C.POINTER(amap_graph_report)]
@@ -382,6 +385,15 @@ class GraphDME:
                 ins = (C.c_int * len(n[2]))(*n[2])
                 _check(_L.amap_graph_op(h, cops, ins, len(n[2]), C.byref(tid)), "amap_graph_op")
                 del keep
+            elif n[0] == "store":
+                # ("store", chain, [input], out_shape): out[f_s(i)] = in[i], f_s = the chain applied to
+                # the index space of the OUTPUT, which must give the input's shape
+                sm = amap_compose([tuple(n[3])], es, list(n[1]))
+                _check(_L.amap_graph_store(h, sm.handle, int(n[2][0]), C.byref(tid)), "amap_graph_store")
+            elif n[0] == "map":
+                # ("map", Map, [inputs]): a layout operator given as a composed map in gather form
+                ins = (C.c_int * len(n[2]))(*n[2])
+                _check(_L.amap_graph_map(h, n[1].handle, ins, len(n[2]), C.byref(tid)), "amap_graph_map")
             elif n[0] == "compute":
                 ins = (C.c_int * max(1, len(n[2])))(*n[2])
                 _check(_L.amap_graph_compute(h, ins, len(n[2]), len(n[3]), _i64(n[3]), int(es), C.byref(tid)),

@@ -234,6 +234,49 @@ extern "C" amap_status amap_graph_op(amap_graph_t *g, const amap_op *op, const i
     GUARD_END
 }
 
+extern "C" amap_status amap_graph_map(amap_graph_t *g, const amap_t *m, const int *inputs, int n_inputs, int *tensor) {
+    GUARD_BEGIN
+    if (!g || !m || !m->prog || !inputs || n_inputs < 1 || !tensor || g->done) return AMAP_E_INVALID;
+    if (g->t.size() >= 4096) return AMAP_E_UNSUPPORTED;
+    for (int i = 0; i < n_inputs; ++i)
+        if (!valid_tensor(g, inputs[i])) return AMAP_E_INVALID;
+    // the operator's own program, re-applied on top of the graph tensors it reads
+    int used = 0;
+    const Leaf leaf = [&](int id, const std::vector<int64_t> &shape, int elem, amap **out) -> amap_status {
+        if (id < 0 || id >= n_inputs) return AMAP_E_INVALID;
+        const GTensor &x = g->t[inputs[id]];
+        if (x.shape != shape || x.elem != elem) return AMAP_E_SHAPE;
+        ++used;
+        return amap_source(inputs[id], (int)shape.size(), shape.data(), (amap_elem)elem, out);
+    };
+    amap *def = nullptr;
+    amap_status st = replay(m->prog.get(), m->elem, leaf, &def);
+    if (st != AMAP_OK) return st;
+    GTensor x;
+    x.kind = GTensor::LAYOUT;
+    x.shape = def->shape;
+    x.elem = def->elem;
+    x.pairs = std::max<int>(1, (int)sources_of(*def).size());
+    x.def.reset(def);
+    g->t.push_back(std::move(x));
+    *tensor = (int)g->t.size() - 1;
+    return AMAP_OK;
+    GUARD_END
+}
+
+extern "C" amap_status amap_graph_store(amap_graph_t *g, const amap_t *store_map, int input, int *tensor) {
+    GUARD_BEGIN
+    if (!g || !store_map || !tensor || g->done || !valid_tensor(g, input)) return AMAP_E_INVALID;
+    if (store_map->shape != g->t[input].shape || store_map->elem != g->t[input].elem) return AMAP_E_SHAPE;
+    // t_s[f_s(i)] = t_l[i]: reverse the store map (Section 2.1) and the operator is a load like the others
+    amap *rev = nullptr;
+    amap_status st = amap_inverse(store_map, &rev);
+    if (st != AMAP_OK) return st;
+    std::unique_ptr<amap> hold(rev);
+    return amap_graph_map(g, rev, &input, 1, tensor);
+    GUARD_END
+}
+
 extern "C" amap_status amap_graph_compute(amap_graph_t *g, const int *inputs, int n_inputs, int rank,
                                           const int64_t *shape, amap_elem es, int *tensor) {
     GUARD_BEGIN

@@ -216,6 +216,12 @@ class Graph:
         self.nodes.append(("op", tuple(op), [int(i) for i in (inputs if isinstance(inputs, (list, tuple)) else [inputs])]))
         return len(self.nodes) - 1
 
+    def store(self, chain, inp, out_shape):
+        """A layout operator in store form: out[f_s(i)] = in[i], where f_s is `chain` applied to the
+        index space of the output (the chain must turn out_shape into the input's shape)."""
+        self.nodes.append(("store", [tuple(o) for o in chain], [int(inp)], tuple(out_shape)))
+        return len(self.nodes) - 1
+
     def compute(self, kind, inputs, shape):
         self.nodes.append(("compute", kind, [int(i) for i in inputs], tuple(shape)))
         return len(self.nodes) - 1

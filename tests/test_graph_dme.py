@@ -127,6 +127,61 @@ def test_several_consumers_and_chains_through_compute():
     assert rep.n_pairs_left == 1 + 3         # at from a; the repeated concat from s, a, b
 
 
+def test_store_form_operators_are_reversed_and_eliminated():
+    """Operators written as stores (where each element goes) next to operators written as loads:
+    the store map is reversed on entry (Section 2.1) and from then on composes like any load."""
+    g = synth.Graph(2)
+    x = g.input((4, 6))
+    st = g.store([("transpose", (1, 0))], x, (6, 4))              # x[i,j] -> st[j,i]
+    back = g.op(("transpose", (1, 0)), st)                         # a load that undoes the store
+    c = g.compute("add", [back, x], (4, 6))
+    flat = g.store([("reshape", (4, 6)), ("slice", 1, 5, -1, -1)], c, (24,))   # c[i,j] -> flat[6 i + 5 - j]
+    g.output(flat)
+    g.output(st)
+    tensors = oracle.run_graph(g.nodes, _inputs(g, 4), standin)
+    assert np.array_equal(tensors[st], tensors[x].T) and np.array_equal(tensors[flat], tensors[c][:, ::-1].reshape(-1))
+    dme = B.GraphDME(g.nodes, g.outputs, 2)
+    rep = dme.eliminate()
+    _check_loads(g, tensors, dme)
+    # store + the load that undoes it: the add reads x itself, twice; both outputs still move data
+    assert (rep.n_layout_ops, rep.n_pairs, rep.n_mapped_loads, rep.n_alias_outputs, rep.n_pairs_left) == (3, 3, 0, 0, 2)
+    # not a bijection between input and output: refused like amap_inverse refuses it
+    bad = synth.Graph(2)
+    y = bad.input((4, 6))
+    bad.store([("slice", 0, 0, 4, 1)], y, (5, 6))
+    with pytest.raises(B.AmapError) as e:
+        B.GraphDME(bad.nodes, [], 2)
+    assert e.value.status == B.AMAP_E_UNSUPPORTED
+    bad2 = synth.Graph(2)
+    y = bad2.input((4, 6))
+    bad2.store([("transpose", (1, 0))], y, (4, 6))              # the map's dst shape is not the input's
+    with pytest.raises(B.AmapError) as e:
+        B.GraphDME(bad2.nodes, [], 2)
+    assert e.value.status == B.AMAP_E_SHAPE
+
+
+def test_operator_given_as_a_composed_map():
+    """amap_graph_map: a layout operator handed over as one composed map over several graph tensors."""
+    a_shape, b_shape = (3, 4), (5, 4)
+    m = B.amap_concat([B.amap_transpose(B.amap_source(0, a_shape, 2), (1, 0)),
+                       B.amap_transpose(B.amap_source(1, b_shape, 2), (1, 0))], 1)      # [4, 8]
+    nodes = [("input", a_shape), ("input", b_shape), ("map", m, [0, 1]), ("op", ("slice", 1, 3, 8, 1), [2]),
+             ("compute", "add", [3, 3], (4, 5))]
+    dme = B.GraphDME(nodes, [2], 2)
+    rep = dme.eliminate()
+    assert (rep.n_layout_ops, rep.n_pairs) == (2, 3)
+    a, b = synth.random_bits(a_shape, 2, 1), synth.random_bits(b_shape, 2, 2)
+    loads = {(c, s_): (mm, ids) for c, s_, mm, ids in dme.loads()}
+    mm, ids = loads[(4, 0)]
+    assert ids == [1]                                                                   # the slice keeps b's part only
+    assert np.array_equal(B.amap_eval_host(mm, [b]), b.T)
+    mm, ids = loads[(-1, 2)]
+    assert np.array_equal(B.amap_eval_host(mm, [a, b]), np.concatenate([a.T, b.T], 1))
+    with pytest.raises(B.AmapError) as e:                                               # shape of a graph tensor does not fit
+        B.GraphDME([("input", (3, 5)), ("input", b_shape), ("map", m, [0, 1])], [], 2)
+    assert e.value.status == B.AMAP_E_SHAPE
+
+
 def _random_graph(seed):
     rng = np.random.default_rng(seed)
     g = synth.Graph(2 if seed % 2 else 4)
@@ -137,7 +192,23 @@ def _random_graph(seed):
     for _ in range(int(rng.integers(3, 14))):
         ids = list(shapes)
         u = rng.random()
-        if u < 0.7:
+        if u < 0.12:
+            # a layout operator in store form: a random bijection given by where each element goes
+            t = int(rng.choice(ids))
+            sin = shapes[t]
+            perm = tuple(int(v) for v in rng.permutation(len(sin)))
+            mid = tuple(sin[perm.index(d)] for d in range(len(sin)))
+            chain, out_shape = [("transpose", perm)], mid
+            if rng.random() < 0.5 and int(np.prod(mid)) > 0:
+                chain, out_shape = [("reshape", mid)] + chain, (int(np.prod(mid)),)
+            if rng.random() < 0.5:
+                ax = int(rng.integers(len(sin)))
+                if sin[ax] > 0:
+                    chain = chain + [("slice", ax, sin[ax] - 1, -1, -1)]
+            if int(np.prod(sin)) == 0:
+                continue
+            shapes[g.store(chain, t, out_shape)] = tuple(out_shape)
+        elif u < 0.7:
             t = int(rng.choice(ids))
             op = chains.random_op_ext(rng, shapes[t])
             ns = chains.out_shape(shapes[t], op)
@@ -168,8 +239,8 @@ def test_random_graphs(seed):
     dme = B.GraphDME(g.nodes, g.outputs, g.elem_size)
     rep = dme.eliminate()
     _check_loads(g, tensors, dme)
-    assert rep.n_layout_ops == sum(n[0] == "op" for n in g.nodes)
-    assert rep.n_pairs == sum(len(n[2]) for n in g.nodes if n[0] == "op")
+    assert rep.n_layout_ops == sum(n[0] in ("op", "store") for n in g.nodes)
+    assert rep.n_pairs == sum(len(n[2]) for n in g.nodes if n[0] in ("op", "store"))
 
 
 def test_graph_error_paths():

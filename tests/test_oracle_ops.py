@@ -312,3 +312,37 @@ def test_threads_do_not_change_results():
     finally:
         oracle.set_threads(1)
     assert np.array_equal(a, b)
+
+
+def test_store_form_hand_worked_closed_forms_and_errors():
+    """The store t_s[f_s(i)] = v of Section 2 executed as written.  Pins: a hand-worked 2 x 3 example,
+    numpy's inverse permutation / flip / reshape as closed forms, gather-after-store = identity."""
+    x = np.array([[10, 20, 30], [40, 50, 60]], dtype=np.uint16)
+    # f_s = transposition of the [3,2] output's index space: element (i,j) of x goes to out[j,i]
+    out = oracle.store_form(x, [("transpose", (1, 0))], (3, 2))
+    assert out.tolist() == [[10, 40], [20, 50], [30, 60]]
+    # reversed rows of the output: x[i] goes to out[1 - i]
+    assert oracle.store_form(x, [("slice", 0, 1, -1, -1)], (2, 3)).tolist() == [[40, 50, 60], [10, 20, 30]]
+    rng = np.random.default_rng(0)
+    for shape in [(3, 4, 5), (2, 3, 2, 5), (7, 6)]:
+        y = synth.random_bits(shape, 4, 9)
+        for _ in range(6):
+            perm = tuple(int(p) for p in rng.permutation(len(shape)))
+            # the chain turns out_shape into y's shape, so out_shape is y's shape pulled back through perm
+            out_shape = tuple(shape[perm.index(d)] for d in range(len(shape)))
+            got = oracle.store_form(y, [("transpose", perm)], out_shape)
+            assert np.array_equal(got, np.transpose(y, np.argsort(perm)))
+            # reading the stored tensor back through the same chain gives the input again
+            assert np.array_equal(oracle.run_chain([got], [("transpose", perm)]), y)
+        flat = int(np.prod(shape))
+        got = oracle.store_form(y, [("reshape", shape)], (flat,))
+        assert np.array_equal(got, y.reshape(-1))
+        chain = [("reshape", shape), ("slice", 0, shape[0] - 1, -1, -1)]
+        got = oracle.store_form(y, chain, (flat,))
+        assert np.array_equal(got, y[::-1].reshape(-1)) and np.array_equal(oracle.run_chain([got], chain), y)
+    with pytest.raises(oracle.OracleError):
+        oracle.store_form(x, [("slice", 0, 0, 2, 1)], (3, 3))          # rows of the output never written
+    with pytest.raises(oracle.OracleError):
+        oracle.store_form(np.zeros((4, 3), np.uint16), [("repeat", 0, 2)], (2, 3))   # written twice
+    with pytest.raises(oracle.OracleError):
+        oracle.store_form(x, [("transpose", (1, 0))], (2, 3))          # wrong shape
