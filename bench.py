@@ -77,6 +77,22 @@ def _unfused_maps(B, w):
     return maps
 
 
+def _unfused_maps_views_free(B, w):
+    """The chain as a framework runs it at best: reshape and leading-dimension slices are views (they
+    cost nothing and are read through by the next copy), every other operator is one materialising copy."""
+    maps, shapes, pending = [], [tuple(s) for s in w.src_shapes], []
+    for op in w.ops:
+        cur = B.dst_shape(B.amap_compose(shapes, w.elem_size, pending)) if pending else shapes[0]
+        view = op[0] == "reshape" or (op[0] == "slice" and op[4] == 1 and all(e == 1 for e in cur[:op[1]]))
+        if view and len(shapes) == 1:
+            pending.append(op)
+            continue
+        m = B.amap_compose(shapes, w.elem_size, pending + [op])
+        maps.append(m)
+        shapes, pending = [B.dst_shape(m)], []
+    return maps
+
+
 def bench_workload(torch, device, B, synth, name, steps, warmup, with_unfused=True, with_hot=True, **kw):
     w = synth.workload(name, **kw)
     m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
@@ -136,6 +152,22 @@ def bench_workload(torch, device, B, synth, name, steps, warmup, with_unfused=Tr
         u_wall, u_gpu = _time_launches(torch, unfused, sets, max(10, steps // 4), max(2, warmup // 4))
         res.update({"unfused_ms": u_wall, "unfused_gbs": min_bytes / u_wall / 1e6, "unfused_ops": len(maps),
                     "speedup_vs_unfused": u_wall / wall_ms})
+        # the same with views free (what a framework's eager chain costs at best)
+        vmaps = _unfused_maps_views_free(B, w)
+        if vmaps:
+            vbufs = [device.empty_dst(mm) for mm in vmaps]   # trailing views may leave the last copy larger than dst
+
+            def views_free(s):
+                cur = s[2]
+                for mm, out in zip(vmaps, vbufs):
+                    st = B.raw.amap_execute(cur, C.c_void_p(out.data_ptr()), mm.handle, stream)
+                    if st != 0:
+                        raise RuntimeError(B.amap_status_str(st))
+                    cur = (C.c_void_p * 1)(out.data_ptr())
+
+            v_wall, v_gpu = _time_launches(torch, views_free, sets, max(10, steps // 4), max(2, warmup // 4))
+            res.update({"unfused_views_free_ms": v_wall, "unfused_views_free_copies": len(vmaps),
+                        "speedup_vs_unfused_views_free": v_wall / wall_ms})
     del sets
     torch.cuda.empty_cache()
     return res
