@@ -86,6 +86,12 @@ struct DevPiece {
     // source stride -V; the lane loads the V elements that END at its source offset and
     // reverses them in registers.
     uint32_t rev;
+    // ROWS only: gather.  The dst vectors tile a run that several loops cover jointly (they
+    // continue one another in dst), but the source is not contiguous along it (an innermost
+    // extent of 3, a repeat by 3, ...).  Loop 0 counts the 16-byte dst vectors of the run and does
+    // not move in the source; the run's own loops sit at the END of loops[] (loops[kMaxLoops - 1 - j],
+    // j < nq, innermost first) and give, element by element, the source offset of a dst position.
+    uint32_t gather;
     // Window of the piece in tensors too large for 32-bit offsets: dbase and every
     // dst offset are relative to element dwin of dst; swin likewise for the source
     // (the host folds it into `src` at launch).  0 for ordinary tensors.

@@ -65,6 +65,50 @@ AMAP_HD void rows_offsets(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_
     soff = s;
 }
 
+// ---- gather rows: position p of a run (see DevPiece::gather) -> source offset relative to the
+// offset rows_offsets returns, kept as a cursor that steps to the next position with carries
+struct GatherCursor {
+    uint32_t dig[4];
+    uint32_t off;
+};
+
+// NQ = number of loops of the run (P.nq, 1..4), a compile-time constant so that a run of one
+// loop steps with a single addition and a run of two with one carry.
+template <int NQ>
+AMAP_HD GatherCursor gather_begin(const DevPiece &P, uint32_t p) {
+    GatherCursor c;
+    c.off = 0;
+    c.dig[0] = c.dig[1] = c.dig[2] = c.dig[3] = 0;
+    for (int j = 0; j < NQ; ++j) {
+        const Loop &l = P.loops[kMaxLoops - 1 - j];
+        if (j == NQ - 1) {  // the outermost loop of the run never wraps
+            c.dig[j] = p;
+        } else {
+            const uint32_t q = fdiv(p, l.fd);
+            c.dig[j] = p - q * l.extent;
+            p = q;
+        }
+        c.off += c.dig[j] * (uint32_t)l.ss;
+    }
+    return c;
+}
+
+template <int NQ>
+AMAP_HD void gather_next(const DevPiece &P, GatherCursor &c) {
+    bool carry = true;
+    for (int j = 0; j < NQ; ++j) {
+        if (!carry) continue;
+        const Loop &l = P.loops[kMaxLoops - 1 - j];
+        c.off += (uint32_t)l.ss;
+        if (j == NQ - 1) break;
+        carry = ++c.dig[j] == l.extent;
+        if (carry) {
+            c.dig[j] = 0;
+            c.off -= l.extent * (uint32_t)l.ss;
+        }
+    }
+}
+
 // ---- tile kernels
 struct TileGeom {
     uint32_t tp, tq;      // tile coordinates along P and Q

@@ -200,6 +200,40 @@ __device__ __forceinline__ void rows_reverse(const DevPiece &P, char *dst, const
     }
 }
 
+// Gather rows: 16-byte dst vectors, every element fetched on its own through the run's loops.
+// The loads of neighbouring lanes and elements share cache lines, so they stay temporal.
+template <int ES, int NT, int NQ>
+__device__ __forceinline__ void rows_gather(const DevPiece &P, char *dst, uint32_t base, uint32_t threads,
+                                            const uint32_t (&doff)[kRowsUnroll], const uint32_t (&soff)[kRowsUnroll],
+                                            const bool (&ok)[kRowsUnroll]) {
+    constexpr int V = 16 / ES;
+    uint32_t out[kRowsUnroll][4];
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) out[u][k] = 0;
+        if (!ok[u]) continue;
+        const uint32_t r = base + u * threads;
+        const uint32_t rv = r - fdiv(r, P.loops[0].fd) * P.loops[0].extent;
+        GatherCursor c = gather_begin<NQ>(P, rv * V);
+        const char *s = (const char *)P.src;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            const uint32_t at = soff[u] + c.off;  // 32-bit wrap-around: strides may be negative
+            if constexpr (ES == 4) {
+                out[u][e] = *reinterpret_cast<const uint32_t *>(s + (size_t)at * 4);
+            } else {
+                const uint32_t v = *reinterpret_cast<const uint16_t *>(s + (size_t)at * 2);
+                out[u][e / 2] |= v << (16 * (e & 1));
+            }
+            if (e + 1 < V) gather_next<NQ>(P, c);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u)
+        if (ok[u]) gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)doff[u] * ES, out[u]);
+}
+
 template <int ES, int NT>
 __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t blk, uint32_t tid) {
     uint32_t doff[kRowsUnroll], soff[kRowsUnroll];
@@ -211,6 +245,15 @@ __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t
         const uint32_t r = base + u * threads;
         ok[u] = r < P.n_units;
         rows_offsets(P, r, doff[u], soff[u]);
+    }
+    if (P.gather) {  // set only together with 16-byte dst vectors and a source
+        switch (P.nq) {
+        case 1: rows_gather<ES, NT, 1>(P, dst, base, threads, doff, soff, ok); break;
+        case 2: rows_gather<ES, NT, 2>(P, dst, base, threads, doff, soff, ok); break;
+        case 3: rows_gather<ES, NT, 3>(P, dst, base, threads, doff, soff, ok); break;
+        default: rows_gather<ES, NT, 4>(P, dst, base, threads, doff, soff, ok); break;
+        }
+        return;
     }
     if (P.rev) {  // set only together with 16-byte dst vectors and a source
         rows_reverse<ES, NT>(P, dst, doff, soff, ok);

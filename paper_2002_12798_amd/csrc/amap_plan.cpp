@@ -101,6 +101,50 @@ static uint32_t nt_mask(const KPiece &kp) {
     return mask;
 }
 
+// Gather rows: the innermost loops of the piece (up to four) continue one another in dst, so
+// together they cover one long contiguous run, but the source is not contiguous along it: an
+// innermost extent of 3 (channels of an image), a repeat by 3, a source stride of 5.  The run is
+// written in aligned 16-byte vectors whose elements are fetched one by one.
+static bool plan_gather(const KPiece &kp, int es, uint32_t nwlog, DevPiece &dp) {
+    const int n = (int)kp.dims.size();
+    if (kp.fill || n == 0 || kp.dims[n - 1].ds != 1) return false;
+    int first = n - 1;  // the run's loops are dims[first .. n-1]
+    int64_t R = kp.dims[n - 1].extent;
+    while (first > 0 && n - first < 4 && kp.dims[first - 1].ds == R) {
+        --first;
+        R *= kp.dims[first].extent;
+    }
+    const uint32_t V = 16u / (uint32_t)es;
+    std::vector<int64_t> pre_ds;
+    for (int k = 0; k < first; ++k) pre_ds.push_back(kp.dims[k].ds);
+    if (common_pow2(V, {R, kp.dbase}, pre_ds) != V) return false;
+    if (1 + first + (n - first) > kMaxLoops) return false;
+    const int64_t chunk = (int64_t)(64u << nwlog) * kRowsUnroll;
+    dp.nwlog = nwlog;
+    dp.kind = PK_ROWS;
+    dp.vlog = ilog2(V);
+    dp.gather = 1;
+    dp.nq = (uint32_t)(n - first);
+    dp.nloops = 1 + (uint32_t)first;
+    int64_t vol = R / V;
+    dp.loops[0] = Loop{(uint32_t)(R / V), (int32_t)V, 0, make_fastdiv((uint32_t)(R / V))};
+    for (int k = 0; k < first; ++k) {
+        const KDim &d = kp.dims[first - 1 - k];  // innermost first
+        dp.loops[1 + k] = Loop{(uint32_t)d.extent, (int32_t)d.ds, (int32_t)d.ss, make_fastdiv((uint32_t)d.extent)};
+        vol *= d.extent;
+    }
+    for (int j = 0; j < n - first; ++j) {
+        const KDim &d = kp.dims[n - 1 - j];
+        dp.loops[kMaxLoops - 1 - j] = Loop{(uint32_t)d.extent, (int32_t)d.ds, (int32_t)d.ss, make_fastdiv((uint32_t)d.extent)};
+    }
+    if (vol >= (1ll << 31)) return false;
+    dp.n_units = (uint32_t)vol;
+    dp.n_blocks = (uint32_t)((vol + chunk - 1) / chunk);
+    if (line_aligned(es, {R, kp.dbase}, pre_ds)) dp.flags |= PF_NT_STORE;
+    dp.flags &= nt_mask(kp);
+    return true;
+}
+
 // returns the family used (amap_kernel_id) or -1 if the forced family cannot run the piece
 static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlog, DevPiece &dp, uint32_t &lds,
                       int &vec_bytes, std::vector<int> *slot_dim = nullptr) {
@@ -198,6 +242,23 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
             fam = AMAP_K_ELEMENT;
     }
     if (kp.fill && (fam == AMAP_K_TILE || fam == AMAP_K_WAVE)) fam = AMAP_K_ROWS;  // constants need no transpose
+    // Where the planned family would move 2- or 4-byte vectors only (or single elements), gathered
+    // 16-byte dst vectors are the better row form; a forced row family may use them as well.
+    if (!kp.fill && env_int("AMAP_GATHER", 1)) {
+        int64_t narrow = es;
+        if (fam == AMAP_K_ROWS && rows_ok) narrow = (int64_t)common_pow2(vmax, {kp.dims[iP].extent, kp.dbase}, ds_others) * es;
+        if ((fam == AMAP_K_TILE || fam == AMAP_K_WAVE) && tile_ok) narrow = (int64_t)Vt * es;
+        const bool planned_narrow = family < 0 && narrow < 8;
+        const bool forced_rows = family == AMAP_K_ROWS && (!rows_ok || narrow < 8);
+        if ((planned_narrow || forced_rows) && plan_gather(kp, es, nwlog, dp)) {
+            vec_bytes = 16;
+            return AMAP_K_ROWS;
+        }
+        // plan_gather may have touched dp before giving up
+        dp.gather = 0;
+        dp.nq = 0;
+        dp.flags = 0;
+    }
 
     if (fam == AMAP_K_ELEMENT) {
         fill_rows(dp, kp, 1, nwlog);

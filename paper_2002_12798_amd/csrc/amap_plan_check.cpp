@@ -54,6 +54,22 @@ struct Replay {
                 if (r >= P.n_units) continue;
                 uint32_t d, s;
                 rows_offsets(P, r, d, s);
+                if (P.gather) {
+                    const uint32_t rv = r - fdiv(r, P.loops[0].fd) * P.loops[0].extent;
+                    GatherCursor c = P.nq == 1 ? gather_begin<1>(P, rv * V) : P.nq == 2 ? gather_begin<2>(P, rv * V) : P.nq == 3 ? gather_begin<3>(P, rv * V) : gather_begin<4>(P, rv * V);
+                    for (uint32_t e = 0; e < V; ++e) {
+                        write((int64_t)P.dwin + d + e, code_of(sid, (int64_t)P.swin + (int64_t)(int32_t)(s + c.off)));
+                        if (P.nq == 1)
+                            gather_next<1>(P, c);
+                        else if (P.nq == 2)
+                            gather_next<2>(P, c);
+                        else if (P.nq == 3)
+                            gather_next<3>(P, c);
+                        else
+                            gather_next<4>(P, c);
+                    }
+                    continue;
+                }
                 for (uint32_t e = 0; e < V; ++e)
                     write((int64_t)P.dwin + d + e, code_of(sid, P.rev ? (int64_t)P.swin + s - e : (int64_t)P.swin + s + (e >> P.rep_log)));
             }

@@ -169,7 +169,26 @@ def _flip_seq(b=16):
                     lambda: [f32_to_bf16_bits(normal_f32(shp, 7))])
 
 
-NEXT_FACTORIES = {"up2x": _up2x, "up2x_nhwc": _up2x_nhwc, "bcast": _bcast, "flip_seq": _flip_seq}
+def _rgb_nhwc(n=64):
+    """A batch of 3-channel images from planar (NCHW) to interleaved (NHWC): the innermost dst
+    extent is 3, so no side of the transposition offers vectors."""
+    shp = (n, 3, 224, 224)
+    ops = [("transpose", (0, 2, 3, 1))]
+    return Workload("rgb_nhwc" if n == 64 else f"rgb_nhwc_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 8))])
+
+
+def _up3x(n=32):
+    """Nearest-neighbour up-sampling by 3 of [n,128,28,28] on H and W (repeats by a factor that
+    is no power of two, along the contiguous dimension too)."""
+    shp = (n, 128, 28, 28)
+    ops = [("repeat", 2, 3), ("repeat", 3, 3)]
+    return Workload("up3x" if n == 32 else f"up3x_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 9))])
+
+
+NEXT_FACTORIES = {"up2x": _up2x, "up2x_nhwc": _up2x_nhwc, "bcast": _bcast, "flip_seq": _flip_seq,
+                  "rgb_nhwc": _rgb_nhwc, "up3x": _up3x}
 
 _FACTORIES = {
     "cfg0": _cfg0, "cfg1": _cfg1, "cfg2_fwd": _cfg2_fwd, "cfg2_rev": _cfg2_rev,

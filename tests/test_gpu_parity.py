@@ -273,3 +273,20 @@ def test_maps_whose_pieces_were_merged(dev):
             assert B.amap_describe(m).n_pieces == n_pieces, name
         assert B.amap_plan_selfcheck(m) == 0
         _run_families(dev, m, srcs, want)
+
+
+def test_gathered_rows(dev):
+    """dst contiguous over several loops, source without vectors (3-channel images, repeats by 3,
+    a source stride of 5): gathered rows against the oracle, in every family that takes the map."""
+    from tests.test_plan_replay import GATHERED
+    for i, (shape, es, ops) in enumerate(GATHERED):
+        print(f"[gpu] gathered rows case {i}", flush=True)
+        x = synth.random_bits(shape, es, 40 + i)
+        _run_families(dev, B.amap_compose([shape], es, ops), [x], oracle.run_chain([x], ops))
+    for name, kw in (("rgb_nhwc", {"n": 3}), ("up3x", {"n": 2})):
+        print(f"[gpu] gathered rows workload {name}", flush=True)
+        w = synth.workload(name, **kw)
+        srcs = w.sources()
+        m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
+        assert B.amap_describe(m).vec_bytes == 16
+        _run_families(dev, m, srcs, oracle.run_chain(srcs, w.ops))

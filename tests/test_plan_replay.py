@@ -128,3 +128,36 @@ def test_windowed_plans_of_scaled_workloads(monkeypatch):
         w = synth.workload(name, **kw)
         m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
         assert B.amap_plan_selfcheck(m, -1) == 0, name
+
+
+# maps whose dst is contiguous over several loops while the source offers no vectors: planned as
+# gathered rows (16-byte dst vectors, one load per element)
+GATHERED = [
+    ((4, 3, 16, 24), 2, [("transpose", (0, 2, 3, 1))]),                       # planar image -> interleaved, 3 channels
+    ((4, 16, 24, 3), 2, [("transpose", (0, 3, 1, 2))]),                       # and back
+    ((4, 3, 16, 24), 4, [("transpose", (0, 2, 3, 1))]),
+    ((2, 5, 12, 8), 2, [("repeat", 3, 3)]),                                   # repeat by 3 along the contiguous dim
+    ((2, 4, 12, 8), 2, [("repeat", 2, 3), ("repeat", 3, 3)]),                 # up-sampling by 3: four loops in the run
+    ((64, 40, 5), 2, [("transpose", (0, 2, 1))]),                             # source stride 5
+    ((6, 8, 5), 4, [("transpose", (2, 0, 1)), ("slice", 1, 5, -1, -1)]),      # a loop of the run walks backwards
+    ((3, 7, 16), 2, [("transpose", (0, 2, 1)), ("pad", (0, 8, 0), (0, 0, 1), 7), ("slice", 2, 0, 8, 1)]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(GATHERED)))
+def test_gathered_rows_plans(case, monkeypatch):
+    shape, es, ops = GATHERED[case]
+    m = B.amap_compose([shape], es, ops)
+    info = B.amap_describe(m)
+    if case != len(GATHERED) - 1:
+        assert info.kernel_id == B.AMAP_K_ROWS and info.vec_bytes == 16, case
+    assert _replay_all(m) >= 2
+    # the same map with the gather form switched off falls back to narrower accesses and still replays
+    monkeypatch.setenv("AMAP_GATHER", "0")
+    m0 = B.amap_compose([shape], es, ops)
+    assert B.amap_describe(m0).vec_bytes < 16 or case == len(GATHERED) - 1
+    assert _replay_all(m0) >= 2
+    # windows (tensors cut for 32-bit offsets) on top of the gather form
+    monkeypatch.setenv("AMAP_GATHER", "1")
+    monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "9")
+    assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
