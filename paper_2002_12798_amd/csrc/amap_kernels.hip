@@ -234,6 +234,54 @@ __device__ __forceinline__ void rows_gather(const DevPiece &P, char *dst, uint32
         if (ok[u]) gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)doff[u] * ES, out[u]);
 }
 
+// Interleave / de-interleave rows (DevPiece::inter): E vectors in, E vectors out, shuffled in
+// registers.  With a[p][q] the value of plane p at position q of the unit (V positions), the
+// interleaved side holds a[p][q] at flat element q * E + p, the planar side at vector p, element q.
+template <int ES, int NT, int E, int DIR>
+__device__ __forceinline__ void rows_inter(const DevPiece &P, char *dst, const uint32_t (&doff)[kRowsUnroll],
+                                           const uint32_t (&soff)[kRowsUnroll], const bool (&ok)[kRowsUnroll]) {
+    constexpr int V = 16 / ES;
+    const uint32_t plane = (uint32_t)P.ssP;
+    auto get = [](const uint32_t (&r)[E][4], int flat) -> uint32_t {  // element `flat` of E consecutive vectors
+        const uint32_t w = r[flat / V][(flat % V) * ES / 4];
+        return ES == 4 ? w : ((w >> (16 * (flat & 1))) & 0xFFFFu);
+    };
+    auto put = [](uint32_t (&r)[E][4], int flat, uint32_t v) {
+        if constexpr (ES == 4)
+            r[flat / V][flat % V] = v;
+        else
+            r[flat / V][(flat % V) / 2] |= v << (16 * (flat & 1));
+    };
+    // one unit at a time: issuing the loads of two units before the first shuffle measured slower
+    // (16.9 against 13.1 us on a batch of 3-channel images) and costs registers of every other path
+#pragma unroll 1
+    for (int u = 0; u < kRowsUnroll; ++u) {
+        if (!ok[u]) continue;
+        uint32_t in[E][4], out[E][4];
+#pragma unroll
+        for (int p = 0; p < E; ++p) {
+            const uint32_t at = DIR == 1 ? soff[u] + (uint32_t)p * plane : soff[u] + (uint32_t)p * V;
+            gld<16, (NT & PF_NT_LOAD) != 0>(in[p], (const char *)P.src + (size_t)at * ES);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) out[p][k] = 0;
+        }
+#pragma unroll
+        for (int p = 0; p < E; ++p)
+#pragma unroll
+            for (int q = 0; q < V; ++q) {
+                if constexpr (DIR == 1)
+                    put(out, q * E + p, get(in, p * V + q));
+                else
+                    put(out, p * V + q, get(in, q * E + p));
+            }
+#pragma unroll
+        for (int p = 0; p < E; ++p) {
+            const uint32_t at = DIR == 1 ? doff[u] + (uint32_t)p * V : doff[u] + (uint32_t)p * plane;
+            gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)at * ES, out[p]);
+        }
+    }
+}
+
 template <int ES, int NT>
 __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t blk, uint32_t tid) {
     uint32_t doff[kRowsUnroll], soff[kRowsUnroll];
@@ -245,6 +293,24 @@ __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t
         const uint32_t r = base + u * threads;
         ok[u] = r < P.n_units;
         rows_offsets(P, r, doff[u], soff[u]);
+    }
+    if (P.inter) {  // set only together with 16-byte vectors on both sides and a source
+#define AMAP_INTER(E)                                                     \
+    case E:                                                               \
+        if (P.inter == 1)                                                 \
+            rows_inter<ES, NT, E, 1>(P, dst, doff, soff, ok);             \
+        else                                                              \
+            rows_inter<ES, NT, E, 2>(P, dst, doff, soff, ok);             \
+        break;
+        switch (P.eP) {
+            AMAP_INTER(3)
+            AMAP_INTER(5)
+            AMAP_INTER(6)
+            AMAP_INTER(7)
+        default: break;
+        }
+#undef AMAP_INTER
+        return;
     }
     if (P.gather) {  // set only together with 16-byte dst vectors and a source
         switch (P.nq) {

@@ -54,6 +54,16 @@ struct Replay {
                 if (r >= P.n_units) continue;
                 uint32_t d, s;
                 rows_offsets(P, r, d, s);
+                if (P.inter) {
+                    // V positions q of eP planes: interleaved side at q * eP + p, planar side at p * plane + q
+                    for (uint32_t pl = 0; pl < P.eP; ++pl)
+                        for (uint32_t q = 0; q < V; ++q) {
+                            const uint32_t il = q * P.eP + pl, pn = pl * (uint32_t)P.ssP + q;
+                            const uint32_t dd = P.inter == 1 ? d + il : d + pn, ss = P.inter == 1 ? s + pn : s + il;
+                            write((int64_t)P.dwin + dd, code_of(sid, (int64_t)P.swin + (int64_t)(int32_t)ss));
+                        }
+                    continue;
+                }
                 if (P.gather) {
                     const uint32_t rv = r - fdiv(r, P.loops[0].fd) * P.loops[0].extent;
                     GatherCursor c = P.nq == 1 ? gather_begin<1>(P, rv * V) : P.nq == 2 ? gather_begin<2>(P, rv * V) : P.nq == 3 ? gather_begin<3>(P, rv * V) : gather_begin<4>(P, rv * V);

@@ -278,11 +278,20 @@ def test_maps_whose_pieces_were_merged(dev):
 def test_gathered_rows(dev):
     """dst contiguous over several loops, source without vectors (3-channel images, repeats by 3,
     a source stride of 5): gathered rows against the oracle, in every family that takes the map."""
-    from tests.test_plan_replay import GATHERED
-    for i, (shape, es, ops) in enumerate(GATHERED):
+    from tests.test_plan_replay import GATHERED, INTERLEAVED
+    for i, (shape, es, ops) in enumerate(GATHERED + INTERLEAVED):
         print(f"[gpu] gathered rows case {i}", flush=True)
         x = synth.random_bits(shape, es, 40 + i)
         _run_families(dev, B.amap_compose([shape], es, ops), [x], oracle.run_chain([x], ops))
+    import os
+    os.environ["AMAP_INTER"] = "0"          # the same maps in the gathered form
+    try:
+        for i, (shape, es, ops) in enumerate(INTERLEAVED):
+            print(f"[gpu] interleaved case {i} as gathered rows", flush=True)
+            x = synth.random_bits(shape, es, 70 + i)
+            _run_families(dev, B.amap_compose([shape], es, ops), [x], oracle.run_chain([x], ops))
+    finally:
+        del os.environ["AMAP_INTER"]
     for name, kw in (("rgb_nhwc", {"n": 3}), ("up3x", {"n": 2})):
         print(f"[gpu] gathered rows workload {name}", flush=True)
         w = synth.workload(name, **kw)

@@ -161,3 +161,33 @@ def test_gathered_rows_plans(case, monkeypatch):
     monkeypatch.setenv("AMAP_GATHER", "1")
     monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "9")
     assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
+
+
+# a small odd number of planes innermost on one side, outer on the other: whole vectors both ways
+INTERLEAVED = [
+    ((4, 3, 16, 24), 2, [("transpose", (0, 2, 3, 1))]),                        # planar -> interleaved
+    ((4, 16, 24, 3), 2, [("transpose", (0, 3, 1, 2))]),                        # interleaved -> planar
+    ((4, 16, 24, 3), 4, [("transpose", (0, 3, 1, 2))]),
+    ((2, 5, 64), 2, [("transpose", (0, 2, 1))]),
+    ((2, 64, 5), 2, [("transpose", (0, 2, 1))]),
+    ((3, 6, 40), 2, [("transpose", (0, 2, 1))]),
+    ((3, 40, 7), 4, [("transpose", (0, 2, 1))]),
+    ((2, 7, 48), 2, [("transpose", (0, 2, 1)), ("slice", 1, 8, 40, 1)]),       # planes read at an offset
+    ((2, 3, 8, 16), 2, [("slice", 2, 7, -1, -1), ("transpose", (0, 2, 3, 1))]),  # rows of the image upside down
+    ((5, 3, 20), 2, [("transpose", (0, 2, 1))]),                               # 20 positions: no whole vectors -> other forms
+]
+
+
+@pytest.mark.parametrize("case", range(len(INTERLEAVED)))
+def test_interleaved_rows_plans(case, monkeypatch):
+    shape, es, ops = INTERLEAVED[case]
+    m = B.amap_compose([shape], es, ops)
+    info = B.amap_describe(m)
+    if case != len(INTERLEAVED) - 1:
+        assert info.kernel_id == B.AMAP_K_ROWS and info.vec_bytes == 16
+    assert _replay_all(m) >= 2
+    monkeypatch.setenv("AMAP_INTER", "0")           # the gathered form instead
+    assert _replay_all(B.amap_compose([shape], es, ops)) >= 2
+    monkeypatch.setenv("AMAP_INTER", "1")
+    monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "9")   # cut into windows
+    assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
