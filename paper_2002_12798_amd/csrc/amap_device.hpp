@@ -92,8 +92,8 @@ struct DevPiece {
     // not move in the source; the run's own loops sit at the END of loops[] (loops[kMaxLoops - 1 - j],
     // j < nq, innermost first) and give, element by element, the source offset of a dst position.
     uint32_t gather;
-    // ROWS only: interleave (1) / de-interleave (2) of eP = 3, 5, 6 or 7 planes (a planar image made
-    // interleaved and back).  A unit is one 16-byte vector of positions q per plane.  1: the lane
+    // ROWS only: interleave (1) / de-interleave (2) of eP = 2 .. 7 planes (a planar image made
+    // interleaved and back, a pixel shuffle).  A unit is one 16-byte vector of positions q per plane.  1: the lane
     // loads one vector from each of the eP planes (ssP elements apart in the source) and writes eP
     // consecutive dst vectors holding the positions' plane values side by side.  2: the reverse,
     // eP consecutive source vectors taken apart into one vector per plane, ssP elements apart in dst.

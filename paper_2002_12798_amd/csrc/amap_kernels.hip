@@ -303,7 +303,9 @@ __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t
             rows_inter<ES, NT, E, 2>(P, dst, doff, soff, ok);             \
         break;
         switch (P.eP) {
+            AMAP_INTER(2)
             AMAP_INTER(3)
+            AMAP_INTER(4)
             AMAP_INTER(5)
             AMAP_INTER(6)
             AMAP_INTER(7)

@@ -145,7 +145,8 @@ static bool plan_gather(const KPiece &kp, int es, uint32_t nwlog, DevPiece &dp) 
     return true;
 }
 
-// Interleave / de-interleave rows: a small odd number of planes (3 channels of an image) is the
+// Interleave / de-interleave rows: a small number of planes (3 channels of an image, the 2 x 2
+// sub-pixels of a pixel shuffle) is the
 // innermost dimension on one side and an outer one on the other, and the positions inside a plane
 // are contiguous on both sides.  Both sides then move whole 16-byte vectors: E per unit, shuffled
 // in registers (see DevPiece::inter).
@@ -153,7 +154,7 @@ static bool plan_inter(const KPiece &kp, int es, uint32_t nwlog, DevPiece &dp) {
     const int n = (int)kp.dims.size();
     if (kp.fill || n < 2 || kp.dims[n - 1].ds != 1) return false;
     const int64_t V = 16 / es;
-    auto planes_ok = [](int64_t e) { return e == 3 || e == 5 || e == 6 || e == 7; };
+    auto planes_ok = [](int64_t e) { return e >= 2 && e <= 7; };
     int iQ = -1, iP = -1, dir = 0;
     const KDim &last = kp.dims[n - 1];
     if (planes_ok(last.extent) && kp.dims[n - 2].ds == last.extent && kp.dims[n - 2].ss == 1) {

@@ -174,6 +174,9 @@ INTERLEAVED = [
     ((3, 40, 7), 4, [("transpose", (0, 2, 1))]),
     ((2, 7, 48), 2, [("transpose", (0, 2, 1)), ("slice", 1, 8, 40, 1)]),       # planes read at an offset
     ((2, 3, 8, 16), 2, [("slice", 2, 7, -1, -1), ("transpose", (0, 2, 3, 1))]),  # rows of the image upside down
+    ((2, 8, 6, 8), 2, [("reshape", (2, 2, 2, 2, 6, 8)), ("transpose", (0, 1, 4, 2, 5, 3)), ("reshape", (2, 2, 12, 16))]),   # pixel shuffle, r = 2
+    ((2, 2, 12, 16), 2, [("reshape", (2, 2, 6, 2, 8, 2)), ("transpose", (0, 1, 3, 5, 2, 4)), ("reshape", (2, 8, 6, 8))]),   # and back
+    ((3, 4, 32), 4, [("transpose", (0, 2, 1))]),                               # 4 planes of 4-byte elements
     ((5, 3, 20), 2, [("transpose", (0, 2, 1))]),                               # 20 positions: no whole vectors -> other forms
 ]
 
