@@ -203,6 +203,7 @@ static bool absorb(Piece &a, const Piece &b, int rank) {
         int64_t span = 0;
         for (const IterDim &it : ad) span += (it.extent - 1) * it.mult;
         if (dlo <= span) return false;  // interleaved boxes: not a loop nest
+        if ((int)a.it.size() >= kMaxRank) return false;  // one more loop than the kernels' loop nests hold
         ad.insert(ad.begin(), IterDim{2, d, dlo, ds});  // two copies of the same box: a loop of two
     } else {
         return false;

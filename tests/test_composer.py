@@ -200,6 +200,13 @@ def test_pieces_that_continue_one_another_are_merged():
     m = B.amap_concat([B.amap_transpose(B.amap_slice(sy, 1, i, i + 1), (1, 0, 2)) for i in range(6)], 0)
     assert B.amap_describe(m).n_pieces == 1
     _check_map(m, [y], np.ascontiguousarray(y.transpose(1, 0, 2)), expect_strided=True)
+    # a piece that already has as many loops as a launch holds is not given one more
+    shape8 = (2, 3, 2, 4, 2, 3, 2, 8)
+    t8 = B.amap_transpose(B.amap_source(0, shape8, es), (7, 0, 6, 1, 5, 2, 4, 3))
+    twice = B.amap_concat([t8, t8], 0)
+    assert B.amap_describe(twice).n_pieces == 2 and B.amap_plan_selfcheck(twice) == 0
+    halves = B.amap_concat([B.amap_slice(t8, 0, 0, 4), B.amap_slice(t8, 0, 4, 8)], 0)
+    assert B.amap_describe(halves).n_pieces == 1 and B.amap_plan_selfcheck(halves) == 0
     # different constants do not merge
     two = B.amap_pad(B.amap_pad(sx, (1, 0), (0, 0), 1), (0, 0), (1, 0), 2)
     assert B.amap_describe(two).n_fill_pieces == 2
