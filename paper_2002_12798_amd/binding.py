@@ -41,7 +41,9 @@ EXPORTS = [
 class AmapError(RuntimeError):
     def __init__(self, status, what):
         self.status = status
-        detail = f" [{_L.amap_last_error().decode()}]" if status == AMAP_E_HIP else ""
+        detail = ""
+        if status == AMAP_E_HIP or (status == AMAP_E_UNSUPPORTED and what.startswith("amap_gemm")):
+            detail = f" [{_L.amap_last_error().decode()}]"
         super().__init__(f"{what}: {_status_str(status)} (status {status}){detail}")
 
 

@@ -426,6 +426,12 @@ bool overlaps(const void *a, int64_t an, const void *b, int64_t bn) {
     return a0 < b0 + (uintptr_t)bn && b0 < a0 + (uintptr_t)an;
 }
 
+// AMAP_E_UNSUPPORTED with the reason left for amap_last_error
+amap_status unsupported(const char *why) {
+    set_last_error("unsupported", why);
+    return AMAP_E_UNSUPPORTED;
+}
+
 // extent of a piece along one dst dimension
 int64_t piece_extent(const Piece &p, int dim) {
     int64_t e = 1;
@@ -445,12 +451,12 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     if (((uintptr_t)W | (uintptr_t)out) & 15) return AMAP_E_INVALID;
     if (A_map->shape.size() != 2 || A_map->elem != 2) return AMAP_E_INVALID;
     const int64_t M = A_map->shape[0], K = A_map->shape[1];
-    if (M == 0 || K == 0) return AMAP_E_UNSUPPORTED;
-    if (N % 8 || K % 8) return AMAP_E_UNSUPPORTED;  // 16-byte vectors along n and k
+    if (M == 0 || K == 0) return unsupported("empty product");
+    if (N % 8 || K % 8) return unsupported("N and K must be multiples of 8");
     const bool edge = M % BM || N % BN || K % BK;
-    if (!A_map->strided || A_map->pieces.empty()) return AMAP_E_UNSUPPORTED;
-    if (M * K >= (1ll << 31) || M * N >= (1ll << 40) || K * N >= (1ll << 31)) return AMAP_E_UNSUPPORTED;
-    if (out_map && M * N >= (1ll << 31)) return AMAP_E_UNSUPPORTED;  // the store map works in 32-bit offsets
+    if (!A_map->strided || A_map->pieces.empty()) return unsupported("the A map has no strided form");
+    if (M * K >= (1ll << 31) || M * N >= (1ll << 40) || K * N >= (1ll << 31)) return unsupported("operand too large for 32-bit offsets");
+    if (out_map && M * N >= (1ll << 31)) return unsupported("product too large for a mapped store");
     const int64_t cbytes = M * N * 2;
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
@@ -487,32 +493,32 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     }
     std::vector<const Piece *> segs;
     for (const Piece &q : parts) segs.push_back(&q);
-    if (segs.size() > (size_t)kMaxSeg || (segs.size() > 1 && !by_id)) return AMAP_E_UNSUPPORTED;
+    if (segs.size() > (size_t)kMaxSeg || (segs.size() > 1 && !by_id)) return unsupported("the A map has several pieces (amap_gemm_gather takes up to 8, one per range of k)");
     std::sort(segs.begin(), segs.end(), [](const Piece *x, const Piece *y) { return x->lo[1] < y->lo[1]; });
     int amode = -1;
     int64_t k_at = 0;
     for (size_t j = 0; j < segs.size(); ++j) {
         const Piece &p = *segs[j];
-        if (p.fill) return AMAP_E_UNSUPPORTED;
+        if (p.fill) return unsupported("the A map has a fill piece (padding)");
         const void *src = A_srcs[by_id ? p.src : 0];
         if (!src || ((uintptr_t)src & 15)) return AMAP_E_INVALID;
         const int64_t svol = volume_of(A_map->src_shapes[p.src]);
-        if (svol >= (1ll << 31)) return AMAP_E_UNSUPPORTED;
+        if (svol >= (1ll << 31)) return unsupported("A source too large for 32-bit offsets");
         if (overlaps(out, cbytes, src, svol * 2)) return AMAP_E_ALIAS;
         const int64_t kext = piece_extent(p, 1);
         Digits dm, dk;
         // every segment spans all of m and continues k where the one before ended
-        if (!make_digits(p, 0, M, dm) || !make_digits(p, 1, kext, dk, k_at)) return AMAP_E_UNSUPPORTED;
+        if (!make_digits(p, 0, M, dm) || !make_digits(p, 1, kext, dk, k_at)) return unsupported("a piece of the A map does not span all of m, or the pieces do not follow one another along k");
         int mode = A_RUNS_K;
         if (!vector_runs(dk, dm, p.sbase)) {
-            if (M % 8 || !vector_runs(dm, dk, p.sbase)) return AMAP_E_UNSUPPORTED;
+            if (M % 8 || !vector_runs(dm, dk, p.sbase)) return unsupported("the A map has no 8-element aligned source runs along k or along m");
             mode = A_RUNS_M;
         }
-        if (amode >= 0 && mode != amode) return AMAP_E_UNSUPPORTED;  // all segments the same way round
+        if (amode >= 0 && mode != amode) return unsupported("the sources of A have their runs along different dimensions");
         amode = mode;
         k_at += kext;
         // a k-step (64, runs along k) or half of one (32, runs along m) reads one source
-        if (j + 1 < segs.size() && k_at % (mode == A_RUNS_K ? BK : BK / 2)) return AMAP_E_UNSUPPORTED;
+        if (j + 1 < segs.size() && k_at % (mode == A_RUNS_K ? BK : BK / 2)) return unsupported("a source of A ends inside a k-step (ranges must end at multiples of 64, or 32 with runs along m)");
         if (segs.size() == 1) {
             g.A_src = static_cast<const uint16_t *>(src);
             g.sbase = (uint32_t)p.sbase;
@@ -526,7 +532,7 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
             g.seg_dk[j] = dk;
         }
     }
-    if (k_at != K) return AMAP_E_UNSUPPORTED;
+    if (k_at != K) return unsupported("the pieces of the A map do not cover k");
     g.n_seg = (uint32_t)segs.size();
     if (g.n_seg > 1) g.A_src = g.seg_src[0];
     int wmode = W_PLAIN;
@@ -534,17 +540,17 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     if (W_map) {
         // W[k,n] = W_src[g_w(k,n)]: the second consumer load of the product, rewritten like the first
         if (W_map->elem != 2 || W_map->shape[0] != K) return AMAP_E_INVALID;
-        if (!W_map->strided || W_map->pieces.size() != 1 || W_map->pieces[0].fill) return AMAP_E_UNSUPPORTED;
+        if (!W_map->strided || W_map->pieces.size() != 1 || W_map->pieces[0].fill) return unsupported("the W map is not one fill-free strided piece");
         const Piece &q = W_map->pieces[0];
         wvol = volume_of(W_map->src_shapes[q.src]);
-        if (wvol >= (1ll << 31)) return AMAP_E_UNSUPPORTED;
-        if (!make_digits(q, 0, K, g.wk) || !make_digits(q, 1, N, g.wn)) return AMAP_E_UNSUPPORTED;
+        if (wvol >= (1ll << 31)) return unsupported("W source too large for 32-bit offsets");
+        if (!make_digits(q, 0, K, g.wk) || !make_digits(q, 1, N, g.wn)) return unsupported("the W map does not span [K,N]");
         if (vector_runs(g.wn, g.wk, q.sbase))
             wmode = W_MAPPED_N;
         else if (vector_runs(g.wk, g.wn, q.sbase))
             wmode = W_MAPPED_K;
         else
-            return AMAP_E_UNSUPPORTED;
+            return unsupported("the W map has no 8-element aligned source runs along n or along k");
         g.wbase = (uint32_t)q.sbase;
     }
     if (overlaps(out, cbytes, W, wvol * 2)) return AMAP_E_ALIAS;
@@ -556,12 +562,15 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
             return AMAP_E_INVALID;
         amap_t *rev = nullptr;
         amap_status st = amap_inverse(out_map, &rev);
-        if (st != AMAP_OK) return st;  // not a bijection between the product and out
+        if (st != AMAP_OK) {  // not a bijection between the product and out
+            set_last_error("unsupported", "the store map is not a bijection between the product and out");
+            return st;
+        }
         std::unique_ptr<amap> hold(rev);
-        if (!rev->strided || rev->pieces.size() != 1 || rev->pieces[0].fill) return AMAP_E_UNSUPPORTED;
+        if (!rev->strided || rev->pieces.size() != 1 || rev->pieces[0].fill) return unsupported("the reversed store map is not one strided piece");
         const Piece &q = rev->pieces[0];
-        if (!make_digits(q, 0, M, g.om) || !make_digits(q, 1, N, g.on)) return AMAP_E_UNSUPPORTED;
-        if (!vector_runs(g.on, g.om, q.sbase)) return AMAP_E_UNSUPPORTED;
+        if (!make_digits(q, 0, M, g.om) || !make_digits(q, 1, N, g.on)) return unsupported("the store map does not span [M,N]");
+        if (!vector_runs(g.on, g.om, q.sbase)) return unsupported("the store map has no 8-element aligned runs along n");
         g.store_mapped = 1;
         g.obase = (uint32_t)q.sbase;
     }

@@ -6,6 +6,7 @@ import sys
 import threading
 
 import numpy as np
+import pytest
 
 from oracle import oracle
 from paper_2002_12798_amd import binding as B
@@ -52,3 +53,20 @@ def test_builders_from_several_threads():
     for t in threads:
         t.join()
     assert not errors, errors
+
+
+def test_gemm_refusals_name_their_reason():
+    """The requirements of the GEMM entry points are checked on the host before anything is
+    launched; a refusal leaves its reason for amap_last_error (no GPU needed to get that far)."""
+    fake = [0x10000, 0x20000]           # aligned, never dereferenced: the calls return before any launch
+    cases = [
+        (B.amap_compose([(256, 68)], 2, []), 256, "multiples of 8"),
+        (B.amap_compose([(256, 128)], 2, [("slice", 1, 0, 128, 2)]), 256, "aligned source runs"),
+        (B.amap_compose([(256, 32), (256, 96)], 2, [("concat", 1)]), 64, "ends inside a k-step"),
+        (B.amap_compose([(128, 64), (128, 64)], 2, [("concat", 0)]), 64, "span all of m"),
+        (B.amap_compose([(256, 64)] * 9, 2, [("concat", 1)]), 64, "up to 8"),
+    ]
+    for m, n, word in cases:
+        with pytest.raises(B.AmapError) as e:
+            B.amap_gemm_gather(fake * 5, m, 0x900000, None, n, None, 0xA00000, 0)
+        assert e.value.status == B.AMAP_E_UNSUPPORTED and word in str(e.value), str(e.value)
