@@ -376,8 +376,8 @@ amap_status amap_gemm_gather(const void *const *A_srcs, const amap_t *A_map, con
 const char *amap_status_str(amap_status s);
 
 /* Text of the HIP error behind the last AMAP_E_HIP returned on this thread, or the reason
- * why one of the amap_gemm_* entry points last returned AMAP_E_UNSUPPORTED on this thread
- * (which requirement the maps did not meet); empty string if none. */
+ * why a device entry point (amap_execute*, amap_gemm_*) last returned AMAP_E_UNSUPPORTED on
+ * this thread (which requirement the maps did not meet); empty string if none. */
 const char *amap_last_error(void);
 
 #ifdef __cplusplus

@@ -42,7 +42,7 @@ class AmapError(RuntimeError):
     def __init__(self, status, what):
         self.status = status
         detail = ""
-        if status == AMAP_E_HIP or (status == AMAP_E_UNSUPPORTED and what.startswith("amap_gemm")):
+        if status == AMAP_E_HIP or (status == AMAP_E_UNSUPPORTED and what.startswith(("amap_gemm", "amap_execute"))):
             detail = f" [{_L.amap_last_error().decode()}]"
         super().__init__(f"{what}: {_status_str(status)} (status {status}){detail}")
 

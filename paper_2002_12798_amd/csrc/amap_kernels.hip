@@ -619,8 +619,15 @@ amap_status launch_strided(const amap *m, const Plan &plan, const void *const *s
     return AMAP_OK;
 }
 
+// AMAP_E_UNSUPPORTED with the reason left for amap_last_error
+amap_status refuse(const char *why) {
+    set_last_error("unsupported", why);
+    return AMAP_E_UNSUPPORTED;
+}
+
 amap_status launch_program(const amap *m, const Plan &plan, const void *const *src, void *dst, hipStream_t stream) {
-    if (!plan.program_ok) return AMAP_E_UNSUPPORTED;
+    if (!plan.program_ok)
+        return refuse("the map has no strided form and its operator program exceeds the interpreter (16 sources, 24 operators)");
     SrcTable t;
     std::memset(&t, 0, sizeof(t));
     // leaves of the program that no dst index reaches are not arguments of the map
@@ -647,18 +654,18 @@ extern "C" amap_status amap_execute_kernel(const void *const *src, void *dst, co
     try {
         if (kernel_id < 0) {
             const Plan *plan = plan_of(*map);
-            if (!plan) return AMAP_E_UNSUPPORTED;
+            if (!plan) return refuse("no launch plan");
             if (plan->strided_ok) return launch_strided(map, *plan, src, dst, s);
-            if (!plan->fits32) return AMAP_E_UNSUPPORTED;  // the interpreter works in 32-bit indices
+            if (!plan->fits32) return refuse("the map has no strided form and a tensor of 2^31 elements or more (the interpreter works in 32-bit indices)");
             return launch_program(map, *plan, src, dst, s);
         }
         Plan forced;
         if (kernel_id == AMAP_K_PROGRAM) {
             plan_strided(*map, -1, forced);  // sets fits32
-            if (!forced.fits32 || !plan_program(*map, forced)) return AMAP_E_UNSUPPORTED;
+            if (!forced.fits32 || !plan_program(*map, forced)) return refuse("the operator program exceeds the interpreter");
             return launch_program(map, forced, src, dst, s);
         }
-        if (!plan_strided(*map, kernel_id, forced)) return AMAP_E_UNSUPPORTED;
+        if (!plan_strided(*map, kernel_id, forced)) return refuse("the forced kernel family cannot execute this map");
         return launch_strided(map, forced, src, dst, s);
     } catch (...) {
         return AMAP_E_NOMEM;
@@ -708,11 +715,11 @@ extern "C" amap_status amap_execute_multi(const void *const *src, void *const *d
             const amap *m = maps[i];
             if (volume_of(m->shape) == 0) continue;
             const Plan *plan = plan_of(*m);
-            if (!plan) return AMAP_E_UNSUPPORTED;
+            if (!plan) return refuse("no launch plan");
             if (!plan->strided_ok) {  // no strided form: this one runs on its own, through the interpreter
                 amap_status st = flush();
                 if (st != AMAP_OK) return st;
-                if (!plan->fits32) return AMAP_E_UNSUPPORTED;
+                if (!plan->fits32) return refuse("a map without strided form over a tensor of 2^31 elements or more");
                 st = launch_program(m, *plan, src, dst[i], s);
                 if (st != AMAP_OK) return st;
                 continue;
