@@ -299,3 +299,39 @@ def test_gathered_rows(dev):
         m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
         assert B.amap_describe(m).vec_bytes == 16
         _run_families(dev, m, srcs, oracle.run_chain(srcs, w.ops))
+
+
+def test_one_map_executed_from_several_host_threads(dev):
+    """A map is immutable once built (its launch plan included), so host threads may execute the
+    same map at the same time, each on a stream of its own."""
+    import threading
+    import torch
+    w = synth.workload("cfg1", n=2)
+    srcs = w.sources()
+    m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
+    want = oracle.run_chain(srcs, w.ops)
+    d_srcs = [dev.to_device(s) for s in srcs]
+    torch.cuda.synchronize()
+    n_threads, reps = 4, 25
+    dsts = [[dev.empty_dst(m, fill=0x7777) for _ in range(reps)] for _ in range(n_threads)]
+    streams = [torch.cuda.Stream() for _ in range(n_threads)]
+    errors = []
+
+    def work(t):
+        try:
+            for r in range(reps):
+                B.amap_execute([s.data_ptr() for s in d_srcs], dsts[t][r].data_ptr(), m, streams[t].cuda_stream)
+            streams[t].synchronize()
+        except Exception as e:  # noqa: BLE001 - reported below
+            errors.append((t, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(n_threads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for t in range(n_threads):
+        for r in (0, reps - 1):
+            assert np.array_equal(dev.to_host(dsts[t][r]), want), (t, r)
