@@ -247,8 +247,9 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         if (!kp.fill && n >= 2 && kp.dims[inner].ds == 1 && kp.dims[inner].ss == 0 && kp.dims[inner - 1].ss == 1 &&
             kp.dims[inner - 1].ds == kp.dims[inner].extent) {
             const int64_t r = kp.dims[inner].extent, cnt = kp.dims[inner - 1].extent;
-            const uint32_t V = vmax;
-            const bool pow2 = (r & (r - 1)) == 0;
+            // the expanding row form always writes 16-byte dst vectors: not available under a narrower cap
+            const uint32_t V = 16u / (uint32_t)es;
+            const bool pow2 = (r & (r - 1)) == 0 && vmax == V;
             std::vector<int64_t> dso, sso;
             for (int k = 0; k < n - 2; ++k) {
                 dso.push_back(kp.dims[k].ds);
@@ -281,9 +282,11 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     if ((family < 0 || family == AMAP_K_ROWS) && !kp.fill && n >= 1 && kp.dims[n - 1].ds == 1 && kp.dims[n - 1].ss == -1) {
         std::vector<int64_t> dso;
         for (int k = 0; k < n - 1; ++k) dso.push_back(kp.dims[k].ds);
-        if (common_pow2(vmax, {kp.dims[n - 1].extent, kp.dbase}, dso) == vmax) {
-            fill_rows(dp, kp, vmax, nwlog);
-            dp.loops[0].ss = -(int32_t)vmax;
+        // the reversing row form always moves 16-byte vectors: not available under a narrower cap
+        const uint32_t V16 = 16u / (uint32_t)es;
+        if (vmax == V16 && common_pow2(V16, {kp.dims[n - 1].extent, kp.dbase}, dso) == V16) {
+            fill_rows(dp, kp, V16, nwlog);
+            dp.loops[0].ss = -(int32_t)V16;
             dp.rev = 1;
             vec_bytes = 16;
             if (line_aligned(es, {kp.dims[n - 1].extent, kp.dbase}, dso)) dp.flags |= PF_NT_STORE;
@@ -311,7 +314,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     if (kp.fill && (fam == AMAP_K_TILE || fam == AMAP_K_WAVE)) fam = AMAP_K_ROWS;  // constants need no transpose
     // Where the planned family would move 2- or 4-byte vectors only (or single elements), gathered
     // 16-byte dst vectors are the better row form; a forced row family may use them as well.
-    if (!kp.fill && env_int("AMAP_GATHER", 1)) {
+    if (!kp.fill && env_int("AMAP_GATHER", 1) && vmax * (uint32_t)es == 16) {  // both forms move 16-byte vectors only
         int64_t narrow = es;
         if (fam == AMAP_K_ROWS && rows_ok) narrow = (int64_t)common_pow2(vmax, {kp.dims[iP].extent, kp.dbase}, ds_others) * es;
         if ((fam == AMAP_K_TILE || fam == AMAP_K_WAVE) && tile_ok) narrow = (int64_t)Vt * es;

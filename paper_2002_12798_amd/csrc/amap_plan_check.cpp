@@ -46,7 +46,10 @@ struct Replay {
     }
 
     void rows(const DevPiece &P, int sid, uint32_t blk) {
-        const uint32_t V = 1u << P.vlog;
+        // the expanding, reversing, gathered and interleaving forms are written for 16-byte vectors whatever
+        // vlog says: replay what the kernel does, so that a plan with another width shows up as errors
+        const bool fixed16 = P.rev || P.rep_log || P.gather || P.inter;
+        const uint32_t V = fixed16 ? 16u / (uint32_t)m.elem : 1u << P.vlog;
         const uint32_t threads = 64u << P.nwlog;
         for (uint32_t tid = 0; tid < threads; ++tid)
             for (int u = 0; u < kRowsUnroll; ++u) {

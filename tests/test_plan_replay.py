@@ -194,3 +194,25 @@ def test_interleaved_rows_plans(case, monkeypatch):
     monkeypatch.setenv("AMAP_INTER", "1")
     monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "9")   # cut into windows
     assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
+
+
+FIXED_WIDTH_FORMS = [
+    ((4, 6, 16), 2, [("repeat", 2, 2)]),                      # expanded in registers
+    ((4, 6, 16), 4, [("repeat", 2, 4)]),
+    ((4, 6, 16), 2, [("slice", 2, 15, -1, -1)]),              # reversed in registers
+    ((3, 5, 8), 4, [("slice", 2, 7, -1, -1)]),
+]
+
+
+@pytest.mark.parametrize("cap", ["8", "4", "2"])
+def test_vector_cap_never_reaches_the_16_byte_row_forms(cap, monkeypatch):
+    """The expanding, reversing, gathered and interleaving row forms are written for 16-byte
+    vectors.  Under a narrower cap (a switch for A/B timing) the planner must pick other forms;
+    the replay walks those forms with the width the kernel uses, so a wrong plan shows as
+    out-of-bounds or doubly written elements (as it did: 772 errors for a repeat by 2 under an
+    8-byte cap before the planner checked the cap)."""
+    monkeypatch.setenv("AMAP_VEC_BYTES", cap)
+    for shape, es, ops in FIXED_WIDTH_FORMS + GATHERED + INTERLEAVED:
+        m = B.amap_compose([shape], es, ops)
+        assert B.amap_describe(m).vec_bytes <= max(int(cap), es), (shape, ops)
+        assert _replay_all(m) >= 1
