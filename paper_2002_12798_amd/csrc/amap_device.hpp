@@ -98,6 +98,9 @@ struct DevPiece {
     // consecutive dst vectors holding the positions' plane values side by side.  2: the reverse,
     // eP consecutive source vectors taken apart into one vector per plane, ssP elements apart in dst.
     // Loop 0 counts the units and carries the strides of a unit on both sides.
+    // 3 / 4: one plane only is kept (a slice with step eP = 2 along the contiguous dimension, 2-byte elements):
+    // the lane loads eP consecutive vectors and keeps the first (3) or the last (4) element of every
+    // group of eP; the window lies so that it never leaves the source.
     uint32_t inter;
     // Window of the piece in tensors too large for 32-bit offsets: dbase and every
     // dst offset are relative to element dwin of dst; swin likewise for the source

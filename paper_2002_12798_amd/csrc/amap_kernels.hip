@@ -265,6 +265,12 @@ __device__ __forceinline__ void rows_inter(const DevPiece &P, char *dst, const u
 #pragma unroll
             for (int k = 0; k < 4; ++k) out[p][k] = 0;
         }
+        if constexpr (DIR >= 3) {  // one plane kept: the first (3) or the last (4) element of every group of E
+#pragma unroll
+            for (int q = 0; q < V; ++q) put(out, q, get(in, q * E + (DIR == 3 ? 0 : E - 1)));
+            gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)doff[u] * ES, out[0]);
+            continue;
+        }
 #pragma unroll
         for (int p = 0; p < E; ++p)
 #pragma unroll
@@ -302,8 +308,19 @@ __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t
         else                                                              \
             rows_inter<ES, NT, E, 2>(P, dst, doff, soff, ok);             \
         break;
+#define AMAP_INTER_KEEP(E)                                                \
+    case E:                                                               \
+        if (P.inter == 1)                                                 \
+            rows_inter<ES, NT, E, 1>(P, dst, doff, soff, ok);             \
+        else if (P.inter == 2)                                            \
+            rows_inter<ES, NT, E, 2>(P, dst, doff, soff, ok);             \
+        else if (P.inter == 3)                                            \
+            rows_inter<ES, NT, E, 3>(P, dst, doff, soff, ok);             \
+        else                                                              \
+            rows_inter<ES, NT, E, 4>(P, dst, doff, soff, ok);             \
+        break;
         switch (P.eP) {
-            AMAP_INTER(2)
+            AMAP_INTER_KEEP(2)
             AMAP_INTER(3)
             AMAP_INTER(4)
             AMAP_INTER(5)
@@ -312,6 +329,7 @@ __device__ __forceinline__ void rows_body(const DevPiece &P, char *dst, uint32_t
         default: break;
         }
 #undef AMAP_INTER
+#undef AMAP_INTER_KEEP
         return;
     }
     if (P.gather) {  // set only together with 16-byte dst vectors and a source

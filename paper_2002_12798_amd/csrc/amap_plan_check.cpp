@@ -57,6 +57,17 @@ struct Replay {
                 if (r >= P.n_units) continue;
                 uint32_t d, s;
                 rows_offsets(P, r, d, s);
+                if (P.inter >= 3) {
+                    // one plane kept: position q reads element q * eP (+ eP - 1 for the last-of-group form)
+                    for (uint32_t q = 0; q < V; ++q) {
+                        const uint32_t ss = s + q * P.eP + (P.inter == 4 ? P.eP - 1 : 0u);
+                        write((int64_t)P.dwin + d + q, code_of(sid, (int64_t)P.swin + (int64_t)(int32_t)ss));
+                    }
+                    // the rest of the window is loaded too and must exist
+                    const int64_t first = (int64_t)P.swin + (int64_t)(int32_t)s, last = first + (int64_t)V * P.eP - 1;
+                    if (first < 0 || last >= src_vol[(size_t)sid]) ++errors;
+                    continue;
+                }
                 if (P.inter) {
                     // V positions q of eP planes: interleaved side at q * eP + p, planar side at p * plane + q
                     for (uint32_t pl = 0; pl < P.eP; ++pl)

@@ -301,6 +301,27 @@ def test_gathered_rows(dev):
         _run_families(dev, m, srcs, oracle.run_chain(srcs, w.ops))
 
 
+def test_keep_plane_rows(dev):
+    """A slice with a small step along the contiguous dimension (step 2 on 2-byte elements keeps one
+    plane of an interleaved source in registers, the rest is gathered):
+    every small case of the replay tests, then sizes of several blocks with a ragged last one."""
+    from tests.test_plan_replay import KEEP_PLANE
+    big = [
+        ((37, 5, 128), 2, [("slice", 2, 0, 128, 2)]),
+        ((37, 5, 128), 2, [("slice", 2, 1, 128, 2)]),
+        ((1031, 264), 4, [("slice", 1, 2, 264, 3)]),
+        ((1031, 264), 4, [("slice", 1, 0, 262, 3)]),
+        ((513, 1024), 2, [("slice", 1, 3, 1024, 4)]),
+        ((300, 520), 2, [("slice", 0, 299, -1, -1), ("slice", 1, 1, 520, 2), ("reshape", (300, 4, 65))]),
+    ]
+    for i, (shape, es, ops) in enumerate(KEEP_PLANE + big):
+        print(f"[gpu] keep-plane rows case {i}", flush=True)
+        x = synth.random_bits(shape, es, 90 + i)
+        m = B.amap_compose([shape], es, ops)
+        assert B.amap_plan_selfcheck(m) == 0
+        _run_families(dev, m, [x], oracle.run_chain([x], ops))
+
+
 def test_one_map_executed_from_several_host_threads(dev):
     """A map is immutable once built (its launch plan included), so host threads may execute the
     same map at the same time, each on a stream of its own."""

@@ -196,6 +196,38 @@ def test_interleaved_rows_plans(case, monkeypatch):
     assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
 
 
+# a slice with a small step along the contiguous dimension: with step 2 on 2-byte elements one plane of an
+# interleaved source is kept in registers; other steps and 4-byte elements use gathered rows
+KEEP_PLANE = [
+    ((4, 6, 64), 2, [("slice", 2, 0, 64, 2)]),      # window starts at the first kept element
+    ((4, 6, 64), 2, [("slice", 2, 1, 64, 2)]),      # last kept element is the tensor's last: window ends there
+    ((128,), 2, [("slice", 0, 1, 128, 2)]),
+    ((128,), 2, [("slice", 0, 0, 128, 2)]),
+    ((6, 48), 4, [("slice", 1, 0, 48, 3)]),
+    ((6, 48), 4, [("slice", 1, 1, 48, 3)]),
+    ((6, 48), 4, [("slice", 1, 2, 48, 3)]),
+    ((5, 3, 64), 2, [("slice", 2, 3, 64, 4)]),
+    ((5, 3, 66), 2, [("slice", 2, 2, 66, 2)]),      # rows of odd pitch in vectors
+    ((5, 64), 2, [("slice", 0, 4, -1, -1), ("slice", 1, 1, 64, 2)]),  # rows backwards
+    ((11,), 4, [("slice", 0, 0, 11, 3)]),           # neither window fits the source: gathered instead
+    ((4, 80), 2, [("slice", 1, 0, 80, 5)]),         # step 5: gathered
+    ((3, 2, 64), 2, [("slice", 2, 0, 64, 2), ("transpose", (1, 0, 2))]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(KEEP_PLANE)))
+def test_keep_plane_rows_plans(case, monkeypatch):
+    shape, es, ops = KEEP_PLANE[case]
+    m = B.amap_compose([shape], es, ops)
+    assert B.amap_describe(m).vec_bytes == 16
+    assert _replay_all(m) >= 1
+    monkeypatch.setenv("AMAP_INTER", "0")           # the gathered form instead
+    assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
+    monkeypatch.setenv("AMAP_INTER", "1")
+    monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "9")   # cut into windows
+    assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
+
+
 FIXED_WIDTH_FORMS = [
     ((4, 6, 16), 2, [("repeat", 2, 2)]),                      # expanded in registers
     ((4, 6, 16), 4, [("repeat", 2, 4)]),
@@ -212,7 +244,7 @@ def test_vector_cap_never_reaches_the_16_byte_row_forms(cap, monkeypatch):
     out-of-bounds or doubly written elements (as it did: 772 errors for a repeat by 2 under an
     8-byte cap before the planner checked the cap)."""
     monkeypatch.setenv("AMAP_VEC_BYTES", cap)
-    for shape, es, ops in FIXED_WIDTH_FORMS + GATHERED + INTERLEAVED:
+    for shape, es, ops in FIXED_WIDTH_FORMS + GATHERED + INTERLEAVED + KEEP_PLANE:
         m = B.amap_compose([shape], es, ops)
         assert B.amap_describe(m).vec_bytes <= max(int(cap), es), (shape, ops)
         assert _replay_all(m) >= 1
