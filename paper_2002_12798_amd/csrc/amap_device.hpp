@@ -38,7 +38,8 @@ struct Loop {
 enum PieceKind : uint32_t {
     PK_ROWS = 0,  // one lane per vector, dst order (also fill pieces and the element-wise form)
     PK_TILE = 1,  // P x Q tile, register micro-transpose, staged through LDS
-    PK_WAVE = 2   // P x Q tile per wavefront, register micro-transpose, no LDS
+    PK_WAVE = 2,  // P x Q tile per wavefront, register micro-transpose, no LDS
+    PK_FLAT = 3   // block of rows that is one contiguous run on one side, staged through LDS
 };
 
 enum PieceFlags : uint32_t {
@@ -102,6 +103,12 @@ struct DevPiece {
     // the lane loads eP consecutive vectors and keeps the first (3) or the last (4) element of every
     // group of eP; the window lies so that it never leaves the source.
     uint32_t inter;
+    // FLAT only.  An r x c matrix (r: EQ values, blocks of 64; c: eP values, any number) is contiguous
+    // on one side (offset r * eP + c) and has rows along r on the other (offset c * ssP + r).
+    // 1: the source is the contiguous side, 2: dst is.  tilesP = blocks along r; loops[0..nloops) = batch
+    // loops.  A workgroup moves the contiguous run of its block in 16-byte vectors into / out of LDS
+    // and serves the other side with 16-byte vectors along r whose elements it picks one by one.
+    uint32_t flat;
     // Window of the piece in tensors too large for 32-bit offsets: dbase and every
     // dst offset are relative to element dwin of dst; swin likewise for the source
     // (the host folds it into `src` at launch).  0 for ordinary tensors.

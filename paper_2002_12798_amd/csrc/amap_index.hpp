@@ -65,6 +65,31 @@ AMAP_HD void rows_offsets(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_
     soff = s;
 }
 
+// ---- flat tiles (see DevPiece::flat): workgroup t -> element offsets of its block on both sides
+// (of row r0, c = 0), and the number of rows in the block
+constexpr uint32_t kFlatRowsLog = 6;
+struct FlatUnit {
+    uint32_t doff, soff, rcount;
+};
+AMAP_HD FlatUnit flat_unit(const DevPiece &P, uint32_t t) {
+    uint32_t rest = fdiv(t, P.fdTP);
+    const uint32_t r0 = (t - rest * P.tilesP) << kFlatRowsLog;
+    uint32_t d = P.dbase, s = P.sbase;
+    for (uint32_t k = 0; k < P.nloops; ++k) {
+        const uint32_t q = fdiv(rest, P.loops[k].fd);
+        const uint32_t dig = rest - q * P.loops[k].extent;
+        d += dig * (uint32_t)P.loops[k].ds;
+        s += dig * (uint32_t)P.loops[k].ss;
+        rest = q;
+    }
+    FlatUnit u;
+    u.doff = d + (P.flat == 1 ? r0 : r0 * P.eP);
+    u.soff = s + (P.flat == 1 ? r0 * P.eP : r0);
+    const uint32_t left = P.EQ - r0;
+    u.rcount = left < (1u << kFlatRowsLog) ? left : (1u << kFlatRowsLog);
+    return u;
+}
+
 // ---- gather rows: position p of a run (see DevPiece::gather) -> source offset relative to the
 // offset rows_offsets returns, kept as a cursor that steps to the next position with carries
 struct GatherCursor {

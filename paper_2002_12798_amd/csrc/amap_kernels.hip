@@ -9,6 +9,7 @@
 
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 #include "amap_index.hpp"
 #include "amap_plan.hpp"
@@ -436,6 +437,84 @@ __device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t
     }
 }
 
+// ------------------------------------------------------------------ flat tiles
+// A block of 64 rows that is one contiguous run on one side (see DevPiece::flat).  The run passes
+// through LDS unchanged, in whole 16-byte vectors whatever the row length C is; the other side is
+// served with 16-byte vectors along r (8 or 16 lanes per row of 64 elements, so a wavefront covers
+// whole 128-byte row segments), whose elements are LDS accesses C elements apart.
+template <int ES, int NT>
+__device__ __forceinline__ void flat_body(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
+    constexpr int V = 16 / ES;
+    constexpr uint32_t VLOG = ES == 2 ? 3 : 2, RVLOG = kFlatRowsLog - VLOG;
+    constexpr int kBatch = 4;  // loads a lane has in flight
+    typedef typename std::conditional<ES == 2, uint16_t, uint32_t>::type elem_t;
+    const FlatUnit U = flat_unit(P, t);
+    const uint32_t C = P.eP, threads = 64u << P.nwlog, pitch = (uint32_t)P.ssP;
+    const uint32_t nflat = (U.rcount * C) >> VLOG, nstr = C << RVLOG;
+    elem_t *const lds = reinterpret_cast<elem_t *>(smem);
+    const char *const src = (const char *)P.src;
+
+    if (P.flat == 1) {
+        for (uint32_t i0 = tid; i0 < nflat; i0 += kBatch * threads) {
+            uint32_t v[kBatch][4];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const uint32_t i = i0 + b * threads;
+                if (i < nflat) gld<16, (NT & PF_NT_LOAD) != 0>(v[b], src + (size_t)(U.soff + i * V) * ES);
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const uint32_t i = i0 + b * threads;
+                if (i < nflat) st<16>(smem + (size_t)i * 16, v[b]);
+            }
+        }
+        __syncthreads();
+        for (uint32_t vi = tid; vi < nstr; vi += threads) {
+            const uint32_t rv = vi & ((1u << RVLOG) - 1), c = vi >> RVLOG;
+            if (rv * V >= U.rcount) continue;
+            uint32_t v[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int k = 0; k < V; ++k) {
+                const uint32_t x = lds[(rv * V + k) * C + c];
+                if constexpr (ES == 2)
+                    v[k / 2] |= x << (16 * (k & 1));
+                else
+                    v[k] = x;
+            }
+            gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)(U.doff + c * pitch + rv * V) * ES, v);
+        }
+    } else {
+        for (uint32_t v0 = tid; v0 < nstr; v0 += kBatch * threads) {
+            uint32_t v[kBatch][4];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const uint32_t vi = v0 + b * threads, rv = vi & ((1u << RVLOG) - 1), c = vi >> RVLOG;
+                if (vi < nstr && rv * V < U.rcount)
+                    gld<16, (NT & PF_NT_LOAD) != 0>(v[b], src + (size_t)(U.soff + c * pitch + rv * V) * ES);
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const uint32_t vi = v0 + b * threads, rv = vi & ((1u << RVLOG) - 1), c = vi >> RVLOG;
+                if (vi < nstr && rv * V < U.rcount) {
+#pragma unroll
+                    for (int k = 0; k < V; ++k) {
+                        if constexpr (ES == 2)
+                            lds[(rv * V + k) * C + c] = (uint16_t)(v[b][k / 2] >> (16 * (k & 1)));
+                        else
+                            lds[(rv * V + k) * C + c] = v[b][k];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        for (uint32_t i = tid; i < nflat; i += threads) {
+            uint32_t v[4];
+            ld<16>(v, smem + (size_t)i * 16);
+            gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)(U.doff + i * V) * ES, v);
+        }
+    }
+}
+
 template <int ES, bool USE_LDS, int NT, bool GROUPED>
 __device__ __forceinline__ void tile_dispatch(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
     if constexpr (ES == 2) {
@@ -473,6 +552,8 @@ __global__ __launch_bounds__(kMaxThreads) void amap_pieces_kernel(const LaunchAr
         rows_body<ES, NT>(P, d, local, threadIdx.x);
     else if (P.kind == PK_TILE)
         tile_dispatch<ES, true, NT, GROUPED>(P, d, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
+    else if (P.kind == PK_FLAT)
+        flat_body<ES, NT>(P, d, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
     else
         tile_dispatch<ES, false, NT, GROUPED>(P, d, local, threadIdx.x, nullptr);
 }

@@ -99,6 +99,64 @@ struct Replay {
             }
     }
 
+    // the two phases of a flat tile, lane by lane, with LDS as an array of codes
+    void flat(const DevPiece &P, int sid, uint32_t t, uint32_t lds_bytes) {
+        const uint32_t V = 16u / (uint32_t)m.elem, vlog = V == 8 ? 3 : 2, rvlog = kFlatRowsLog - vlog;
+        if (P.vlog != vlog || (P.flat != 1 && P.flat != 2) || P.EQ % V || t >= P.n_blocks) {
+            ++errors;
+            return;
+        }
+        const FlatUnit U = flat_unit(P, t);
+        const uint32_t C = P.eP, threads = 64u << P.nwlog;
+        const uint32_t nflat = (U.rcount * C) >> vlog, nstr = C << rvlog;
+        if ((uint64_t)nflat * 16 > lds_bytes) {
+            ++errors;
+            return;
+        }
+        std::vector<int64_t> lds((size_t)lds_bytes / (size_t)m.elem, kUnwritten);
+        auto lds_put = [&](uint64_t e, int64_t code) {
+            if (e >= lds.size() || lds[e] != kUnwritten)
+                ++errors;
+            else
+                lds[e] = code;
+        };
+        auto lds_get = [&](uint64_t e) -> int64_t {
+            if (e >= lds.size() || lds[e] == kUnwritten) {
+                ++errors;
+                return kFill;
+            }
+            return lds[e];
+        };
+        for (int phase = 0; phase < 2; ++phase)
+            for (uint32_t tid = 0; tid < threads; ++tid) {
+                const bool flat_side = (phase == 0) == (P.flat == 1);
+                if (flat_side) {
+                    for (uint32_t i = tid; i < nflat; i += threads)
+                        for (uint32_t k = 0; k < V; ++k) {
+                            const uint32_t e = i * V + k;
+                            if (P.flat == 2 && k == 0 && (P.dwin + U.doff + e) % V) ++errors;  // aligned dst vectors
+                            if (P.flat == 1)
+                                lds_put(e, code_of(sid, (int64_t)P.swin + (int64_t)(int32_t)(U.soff + e)));
+                            else
+                                write((int64_t)P.dwin + U.doff + e, lds_get(e));
+                        }
+                } else {
+                    for (uint32_t vi = tid; vi < nstr; vi += threads) {
+                        const uint32_t rv = vi & ((1u << rvlog) - 1), c = vi >> rvlog;
+                        if (rv * V >= U.rcount) continue;
+                        for (uint32_t k = 0; k < V; ++k) {
+                            const uint32_t e = (rv * V + k) * C + c, off = c * (uint32_t)P.ssP + rv * V + k;
+                            if (P.flat == 1 && k == 0 && (P.dwin + (uint32_t)(U.doff + off)) % V) ++errors;
+                            if (P.flat == 1)
+                                write((int64_t)P.dwin + (uint32_t)(U.doff + off), lds_get(e));
+                            else
+                                lds_put(e, code_of(sid, (int64_t)P.swin + (int64_t)(int32_t)(U.soff + off)));
+                        }
+                    }
+                }
+            }
+    }
+
     void tile(const DevPiece &P, uint32_t t, uint32_t lds_bytes) {
         const uint32_t vlog = P.vlog, V = 1u << vlog;
         const TileGeom G = tile_geometry(P, vlog, t);
@@ -189,6 +247,8 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
                 }
                 if (P.kind == PK_ROWS)
                     R.rows(P, sid, local);
+                else if (P.kind == PK_FLAT)
+                    R.flat(P, sid, local, plan->lds_bytes[li]);
                 else
                     R.tile(P, local, plan->lds_bytes[li]);
             }

@@ -322,6 +322,35 @@ def test_keep_plane_rows(dev):
         _run_families(dev, m, [x], oracle.run_chain([x], ops))
 
 
+def test_flat_tiles(dev):
+    """Transposing pieces that are contiguous on one side with a row length that offers no vectors
+    (7 x 7 positions per channel): blocks of 64 rows staged through LDS as one flat run, in both
+    directions, with a ragged last block, rows at a pitch and workgroups of 1 and 4 wavefronts."""
+    import os
+    from tests.test_plan_replay import FLAT
+    big = [
+        ((8, 2048, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),
+        ((8, 7, 7, 2048), 2, [("transpose", (0, 3, 1, 2))]),
+        ((5, 328, 9, 9), 4, [("transpose", (0, 2, 3, 1))]),
+        ((5, 9, 9, 328), 4, [("transpose", (0, 3, 1, 2))]),
+        ((3, 1000, 121), 2, [("slice", 1, 8, 1000, 1), ("transpose", (0, 2, 1))]),
+        ((3, 121, 1000), 2, [("slice", 2, 1, 993, 1), ("transpose", (0, 2, 1))]),
+    ]
+    for i, (shape, es, ops) in enumerate(FLAT + big):
+        x = synth.random_bits(shape, es, 110 + i)
+        want = oracle.run_chain([x], ops)
+        for waves in (None, "2"):
+            print(f"[gpu] flat tiles case {i} waves_log {waves}", flush=True)
+            if waves is not None:
+                os.environ["AMAP_WAVES_LOG"] = waves
+            try:
+                m = B.amap_compose([shape], es, ops)
+                assert B.amap_plan_selfcheck(m) == 0
+                _run_families(dev, m, [x], want)
+            finally:
+                os.environ.pop("AMAP_WAVES_LOG", None)
+
+
 def test_one_map_executed_from_several_host_threads(dev):
     """A map is immutable once built (its launch plan included), so host threads may execute the
     same map at the same time, each on a stream of its own."""

@@ -228,6 +228,42 @@ def test_keep_plane_rows_plans(case, monkeypatch):
     assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
 
 
+# a transposing piece that is contiguous on one side while that side's row length offers no vectors
+# (7 x 7 = 49 positions under 128 channels): blocks of 64 rows pass through LDS as one flat run
+FLAT = [
+    ((4, 128, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                          # the source is the flat side
+    ((4, 7, 7, 128), 2, [("transpose", (0, 3, 1, 2))]),                          # dst is
+    ((3, 72, 5, 5), 4, [("transpose", (0, 2, 3, 1))]),                           # last block of 8 rows
+    ((3, 5, 5, 72), 4, [("transpose", (0, 3, 1, 2))]),
+    ((2, 200, 9), 2, [("transpose", (0, 2, 1))]),
+    ((2, 9, 200), 2, [("transpose", (0, 2, 1))]),
+    ((4, 130, 7, 7), 2, [("slice", 1, 2, 130, 1), ("transpose", (0, 2, 3, 1))]),  # flat run starts at an odd 4 bytes
+    ((4, 7, 7, 136), 2, [("slice", 3, 0, 128, 1), ("transpose", (0, 3, 1, 2))]),  # source rows with a pitch
+    ((2, 64, 6, 3), 2, [("transpose", (0, 2, 3, 1))]),                           # 18 positions: pairs only
+    ((2, 3, 64, 5, 5), 2, [("transpose", (1, 0, 3, 4, 2))]),                     # batch loops in another order
+    ((2, 320, 3, 3), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),  # two loops on the flat side: other forms
+    ((2, 56, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                           # fewer than 64 rows: other forms
+]
+
+
+@pytest.mark.parametrize("case", range(len(FLAT)))
+def test_flat_tiles_plan(case, monkeypatch):
+    shape, es, ops = FLAT[case]
+    m = B.amap_compose([shape], es, ops)
+    info = B.amap_describe(m)
+    if case < len(FLAT) - 2:
+        assert info.vec_bytes == 16 and B.KERNEL_NAMES[info.kernel_id] == "tile"
+    assert _replay_all(m) >= 2
+    monkeypatch.setenv("AMAP_FLAT", "0")            # gathered rows / split tiles instead
+    assert _replay_all(B.amap_compose([shape], es, ops)) >= 2
+    monkeypatch.setenv("AMAP_FLAT", "1")
+    monkeypatch.setenv("AMAP_WAVES_LOG", "2")       # 4 wavefronts per workgroup
+    assert _replay_all(B.amap_compose([shape], es, ops)) >= 2
+    monkeypatch.delenv("AMAP_WAVES_LOG")
+    monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "11")  # cut into windows
+    assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
+
+
 FIXED_WIDTH_FORMS = [
     ((4, 6, 16), 2, [("repeat", 2, 2)]),                      # expanded in registers
     ((4, 6, 16), 4, [("repeat", 2, 4)]),
@@ -244,7 +280,7 @@ def test_vector_cap_never_reaches_the_16_byte_row_forms(cap, monkeypatch):
     out-of-bounds or doubly written elements (as it did: 772 errors for a repeat by 2 under an
     8-byte cap before the planner checked the cap)."""
     monkeypatch.setenv("AMAP_VEC_BYTES", cap)
-    for shape, es, ops in FIXED_WIDTH_FORMS + GATHERED + INTERLEAVED + KEEP_PLANE:
+    for shape, es, ops in FIXED_WIDTH_FORMS + GATHERED + INTERLEAVED + KEEP_PLANE + FLAT:
         m = B.amap_compose([shape], es, ops)
         assert B.amap_describe(m).vec_bytes <= max(int(cap), es), (shape, ops)
         assert _replay_all(m) >= 1
