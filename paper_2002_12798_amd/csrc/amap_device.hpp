@@ -104,9 +104,10 @@ struct DevPiece {
     // group of eP; the window lies so that it never leaves the source.
     uint32_t inter;
     // FLAT only.  An r x c matrix (r: EQ values, blocks of 64; c: eP values, any number) is contiguous
-    // on one side (offset r * eP + c) and has rows along r on the other (offset c * ssP + r).
-    // 1: the source is the contiguous side, 2: dst is.  tilesP = blocks along r; loops[0..nloops) = batch
-    // loops.  A workgroup moves the contiguous run of its block in 16-byte vectors into / out of LDS
+    // on one side (offset r * eP + c) and has rows along r on the other (offset f(c) + r, where c runs
+    // over the nq loops at the END of loops[], loops[kMaxLoops - 1 - j], innermost first, each with
+    // its own stride on that side).  1: the source is the contiguous side, 2: dst is.
+    // tilesP = blocks along r; loops[0..nloops) = batch loops.  A workgroup moves the contiguous run of its block in 16-byte vectors into / out of LDS
     // and serves the other side with 16-byte vectors along r whose elements it picks one by one.
     uint32_t flat;
     // Window of the piece in tensors too large for 32-bit offsets: dbase and every

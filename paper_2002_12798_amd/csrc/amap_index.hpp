@@ -90,6 +90,24 @@ AMAP_HD FlatUnit flat_unit(const DevPiece &P, uint32_t t) {
     return u;
 }
 
+// position c of a row -> element offset on the side where the row is not contiguous: the row's loops
+// sit at the end of loops[] (loops[kMaxLoops - 1 - j], j < nq, innermost first)
+AMAP_HD uint32_t flat_c_offset(const DevPiece &P, uint32_t c) {
+    uint32_t off = 0;
+    for (uint32_t j = 0; j < P.nq; ++j) {
+        const Loop &l = P.loops[kMaxLoops - 1 - j];
+        const uint32_t stride = (uint32_t)(P.flat == 1 ? l.ds : l.ss);
+        if (j + 1 == P.nq) {
+            off += c * stride;
+        } else {
+            const uint32_t q = fdiv(c, l.fd);
+            off += (c - q * l.extent) * stride;
+            c = q;
+        }
+    }
+    return off;
+}
+
 // ---- gather rows: position p of a run (see DevPiece::gather) -> source offset relative to the
 // offset rows_offsets returns, kept as a cursor that steps to the next position with carries
 struct GatherCursor {

@@ -449,7 +449,7 @@ __device__ __forceinline__ void flat_body(const DevPiece &P, char *dst, uint32_t
     constexpr int kBatch = 4;  // loads a lane has in flight
     typedef typename std::conditional<ES == 2, uint16_t, uint32_t>::type elem_t;
     const FlatUnit U = flat_unit(P, t);
-    const uint32_t C = P.eP, threads = 64u << P.nwlog, pitch = (uint32_t)P.ssP;
+    const uint32_t C = P.eP, threads = 64u << P.nwlog;
     const uint32_t nflat = (U.rcount * C) >> VLOG, nstr = C << RVLOG;
     elem_t *const lds = reinterpret_cast<elem_t *>(smem);
     const char *const src = (const char *)P.src;
@@ -481,7 +481,7 @@ __device__ __forceinline__ void flat_body(const DevPiece &P, char *dst, uint32_t
                 else
                     v[k] = x;
             }
-            gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)(U.doff + c * pitch + rv * V) * ES, v);
+            gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)(U.doff + flat_c_offset(P, c) + rv * V) * ES, v);
         }
     } else {
         for (uint32_t v0 = tid; v0 < nstr; v0 += kBatch * threads) {
@@ -490,7 +490,7 @@ __device__ __forceinline__ void flat_body(const DevPiece &P, char *dst, uint32_t
             for (int b = 0; b < kBatch; ++b) {
                 const uint32_t vi = v0 + b * threads, rv = vi & ((1u << RVLOG) - 1), c = vi >> RVLOG;
                 if (vi < nstr && rv * V < U.rcount)
-                    gld<16, (NT & PF_NT_LOAD) != 0>(v[b], src + (size_t)(U.soff + c * pitch + rv * V) * ES);
+                    gld<16, (NT & PF_NT_LOAD) != 0>(v[b], src + (size_t)(U.soff + flat_c_offset(P, c) + rv * V) * ES);
             }
 #pragma unroll
             for (int b = 0; b < kBatch; ++b) {

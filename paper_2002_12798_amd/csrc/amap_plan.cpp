@@ -280,60 +280,110 @@ static bool plan_inter(const KPiece &kp, int es, uint32_t nwlog, int64_t svol, D
 constexpr uint32_t kFlatRows = 64;
 constexpr uint32_t kFlatLdsBytes = 32768;
 
-static int flat_dir(const KPiece &kp, int es) {
-    if (kp.fill || (es != 2 && es != 4)) return 0;
+// The loops that continue the source-contiguous loop iQ in the source (x, then y of an image: one run of
+// H * W elements), innermost first, and the length of that run.  A tile vector along Q may straddle the
+// loops of the chain (every Q position gets its dst offset through the chain), so only the run's
+// length has to be a whole number of vectors.
+static std::vector<int> q_chain(const KPiece &kp, int iP, int iQ, int64_t &EQ) {
+    const int n = (int)kp.dims.size();
+    std::vector<int> chain{iQ};
+    EQ = kp.dims[iQ].extent;
+    for (bool grown = true; grown && chain.size() < 3;) {
+        grown = false;
+        for (int k = 0; k < n; ++k) {
+            if (k == iP || std::find(chain.begin(), chain.end(), k) != chain.end()) continue;
+            if (kp.dims[k].ss == EQ && EQ * kp.dims[k].extent < (1ll << 31)) {
+                chain.push_back(k);
+                EQ *= kp.dims[k].extent;
+                grown = true;
+                break;
+            }
+        }
+    }
+    return chain;
+}
+
+struct FlatShape {
+    int dir = 0;             // 0: the piece has no flat form
+    int iR = -1;             // the loop that is cut into blocks of kFlatRows
+    std::vector<int> chain;  // the loops that make up a row of the flat side, innermost first
+    int64_t C = 0, ER = 0;
+};
+
+// The row of the flat side may be several loops that continue one another on that side only (the
+// y and x loops of a 7 x 7 image that lands inside a padded image, or comes from a crop): on the other
+// side every loop of the chain has a stride of its own.
+static FlatShape flat_shape(const KPiece &kp, int es) {
+    FlatShape none, f;
+    if (kp.fill || (es != 2 && es != 4)) return none;
     const int n = (int)kp.dims.size();
     int iP = -1, iQ = -1;
     for (int k = 0; k < n; ++k) {
         if (kp.dims[k].ds == 1) iP = k;
         if (kp.dims[k].ss == 1) iQ = k;
     }
-    if (iP < 0 || iQ < 0 || iP == iQ || n - 2 > kMaxLoops) return 0;
+    if (iP < 0 || iQ < 0 || iP == iQ) return none;
     const int64_t V = 16 / es;
     const KDim &P = kp.dims[iP], &Q = kp.dims[iQ];
-    if (kp.dbase % V) return 0;
-    for (int k = 0; k < n; ++k)
-        if (k != iP && k != iQ && kp.dims[k].ds % V) return 0;
+    if (kp.dbase % V) return none;
     // only where the tile forms would move vectors of less than 16 bytes (with 8-byte vectors: 14.4 -> 10.4 us for
     // 196 positions under 1024 channels, 33.0 -> 21.2 us for rows of 100)
-    if ((int64_t)common_pow2((uint32_t)V, {P.extent, Q.extent}, {}) * es >= env_int("AMAP_FLAT_BELOW", 16)) return 0;
-    auto fits = [&](int64_t C, int64_t ER) {
+    int64_t EQc = Q.extent;
+    if (env_int("AMAP_TILE_CHAIN_VEC", 1)) q_chain(kp, iP, iQ, EQc);
+    if ((int64_t)common_pow2((uint32_t)V, {P.extent, EQc}, {}) * es >= env_int("AMAP_FLAT_BELOW", 16)) return none;
+    for (int dir = 1; dir <= 2; ++dir) {
+        // dir 1: rows are contiguous in the source, from Q outwards, until P's source stride is reached;
+        // dir 2: in dst, from P outwards, until Q's dst stride is reached
+        const int first = dir == 1 ? iQ : iP, iR = dir == 1 ? iP : iQ;
+        auto flat_stride = [&](int k) { return dir == 1 ? kp.dims[k].ss : kp.dims[k].ds; };
+        std::vector<int> chain{first};
+        int64_t C = kp.dims[first].extent;
+        while (flat_stride(iR) != C && chain.size() < 4) {
+            int next = -1;
+            for (int k = 0; k < n; ++k)
+                if (k != iR && std::find(chain.begin(), chain.end(), k) == chain.end() && kp.dims[k].extent > 1 && flat_stride(k) == C) next = k;
+            if (next < 0) break;
+            chain.push_back(next);
+            C *= kp.dims[next].extent;
+        }
+        if (flat_stride(iR) != C) continue;
+        const int64_t ER = kp.dims[iR].extent;
         // rows of 2 .. 7 elements belong to the interleaving row forms (a block of 64 such rows is too little work)
-        return C % V != 0 && C >= env_int("AMAP_FLAT_MIN_C", 8) && ER % V == 0 && ER >= (int64_t)kFlatRows && C * kFlatRows * es <= (int64_t)kFlatLdsBytes;
-    };
-    if (P.ss == Q.extent && Q.ds % V == 0 && fits(Q.extent, P.extent)) return 1;
-    if (Q.ds == P.extent && fits(P.extent, Q.extent)) return 2;
-    return 0;
+        if (C < env_int("AMAP_FLAT_MIN_C", 8) || ER % V || ER < (int64_t)kFlatRows || C * kFlatRows * es > (int64_t)kFlatLdsBytes) continue;
+        if (n - 1 > kMaxLoops) continue;  // batch loops + chain
+        bool ok = true;
+        for (int k = 0; k < n; ++k) {
+            const bool in_chain = std::find(chain.begin(), chain.end(), k) != chain.end();
+            if (k == iP || k == iR) continue;            // dst stride 1; in dir 2 the block loop walks dst in steps of C rows of whole vectors
+            if (dir == 2 && in_chain) continue;          // inside the flat dst run
+            if (kp.dims[k].ds % V) ok = false;           // batch loops on both sides, the chain's dst strides in dir 1
+        }
+        if (!ok) continue;
+        f.dir = dir, f.iR = iR, f.chain = chain, f.C = C, f.ER = ER;
+        return f;
+    }
+    return none;
 }
 
 static bool plan_flat(const KPiece &kp, int es, uint32_t nwlog, DevPiece &dp, uint32_t &lds) {
-    const int dir = flat_dir(kp, es);
-    if (!dir) return false;
+    const FlatShape f = flat_shape(kp, es);
+    if (!f.dir) return false;
     const int n = (int)kp.dims.size();
-    int iP = -1, iQ = -1;
-    for (int k = 0; k < n; ++k) {
-        if (kp.dims[k].ds == 1) iP = k;
-        if (kp.dims[k].ss == 1) iQ = k;
-    }
-    const KDim &P = kp.dims[iP], &Q = kp.dims[iQ];
     const int64_t V = 16 / es;
-    const int64_t C = dir == 1 ? Q.extent : P.extent, ER = dir == 1 ? P.extent : Q.extent;
-    const int64_t pitch = dir == 1 ? Q.ds : P.ss;  // from one c to the next on the side that is not flat
     dp.kind = PK_FLAT;
     dp.nwlog = nwlog;
     dp.vlog = ilog2((uint32_t)V);
     dp.inter = 0;
-    dp.flat = (uint32_t)dir;
-    dp.eP = (uint32_t)C;
-    dp.EQ = (uint32_t)ER;
-    dp.ssP = (int32_t)pitch;
-    dp.tilesP = (uint32_t)((ER + kFlatRows - 1) / kFlatRows);
+    dp.flat = (uint32_t)f.dir;
+    dp.eP = (uint32_t)f.C;
+    dp.EQ = (uint32_t)f.ER;
+    dp.tilesP = (uint32_t)((f.ER + kFlatRows - 1) / kFlatRows);
     dp.fdTP = make_fastdiv(dp.tilesP);
     int64_t nb = dp.tilesP;
     uint32_t nl = 0;
-    std::vector<int64_t> ds_o, ss_o;
+    std::vector<int64_t> ds_o, ss_o, chain_other;
     for (int k = n - 1; k >= 0; --k) {  // batch loops, innermost first
-        if (k == iP || k == iQ) continue;
+        if (k == f.iR || std::find(f.chain.begin(), f.chain.end(), k) != f.chain.end()) continue;
         const KDim &d = kp.dims[k];
         dp.loops[nl++] = Loop{(uint32_t)d.extent, (int32_t)d.ds, (int32_t)d.ss, make_fastdiv((uint32_t)d.extent)};
         nb *= d.extent;
@@ -341,16 +391,24 @@ static bool plan_flat(const KPiece &kp, int es, uint32_t nwlog, DevPiece &dp, ui
         ss_o.push_back(d.ss);
     }
     dp.nloops = nl;
+    dp.nq = (uint32_t)f.chain.size();
+    if (nl + dp.nq > (uint32_t)kMaxLoops) return false;
+    for (size_t j = 0; j < f.chain.size(); ++j) {  // the row's loops at the end of loops[], innermost first
+        const KDim &d = kp.dims[f.chain[j]];
+        dp.loops[kMaxLoops - 1 - j] = Loop{(uint32_t)d.extent, (int32_t)d.ds, (int32_t)d.ss, make_fastdiv((uint32_t)d.extent)};
+        chain_other.push_back(f.dir == 1 ? d.ds : d.ss);
+    }
     if (nb >= (1ll << 31)) return false;
     dp.n_blocks = (uint32_t)nb;
     dp.n_units = dp.n_blocks;
-    lds = (uint32_t)(C * kFlatRows * es);
+    lds = (uint32_t)(f.C * kFlatRows * es);
     // whole lines: blocks of kFlatRows rows are whole lines on the flat side (kFlatRows * C elements) and on the other
-    if (ER % kFlatRows == 0) {
+    if (f.ER % kFlatRows == 0) {
         const bool flat_dst = line_aligned(es, {kp.dbase}, ds_o), flat_src = line_aligned(es, {kp.sbase}, ss_o);
-        const bool rows_dst = line_aligned(es, {kp.dbase, pitch}, ds_o), rows_src = line_aligned(es, {kp.sbase, pitch}, ss_o);
-        if (dir == 1 ? rows_dst : flat_dst) dp.flags |= PF_NT_STORE;
-        if (dir == 1 ? flat_src : rows_src) dp.flags |= PF_NT_LOAD;
+        const bool rows_ok = line_aligned(es, {}, chain_other);
+        const bool rows_dst = rows_ok && line_aligned(es, {kp.dbase}, ds_o), rows_src = rows_ok && line_aligned(es, {kp.sbase}, ss_o);
+        if (f.dir == 1 ? rows_dst : flat_dst) dp.flags |= PF_NT_STORE;
+        if (f.dir == 1 ? flat_src : rows_src) dp.flags |= PF_NT_LOAD;
     }
     dp.flags &= nt_mask(kp);
     return true;
@@ -443,7 +501,11 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     // The vector width follows from the dst side (aligned 16-byte stores) and from
     // the extents; source runs may start at any element (under-aligned loads).
     uint32_t Vt = 1;
-    if (tile_shape) Vt = common_pow2(vmax, {kp.dims[iP].extent, kp.dims[iQ].extent, kp.dbase}, ds_others);
+    if (tile_shape) {
+        int64_t EQc = 0;
+        q_chain(kp, iP, iQ, EQc);
+        Vt = common_pow2(vmax, {kp.dims[iP].extent, env_int("AMAP_TILE_CHAIN_VEC", 1) ? EQc : kp.dims[iQ].extent, kp.dbase}, ds_others);
+    }
     const bool tile_ok = tile_shape && Vt * es >= 4;
 
     int fam = family;
@@ -478,6 +540,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
             return AMAP_K_TILE;
         }
         dp.flat = 0;
+        dp.nq = 0;
         dp.flags = 0;
         lds = 0;
         if ((planned_narrow || forced_rows) && plan_gather(kp, es, nwlog, dp)) {
@@ -516,20 +579,8 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     dp.vlog = ilog2(V);
     dp.eP = (uint32_t)kp.dims[iP].extent;
     dp.ssP = (int32_t)kp.dims[iP].ss;
-    std::vector<int> chain{iQ};
-    int64_t EQ = kp.dims[iQ].extent;
-    for (bool grown = true; grown && chain.size() < 3;) {
-        grown = false;
-        for (int k = 0; k < n; ++k) {
-            if (k == iP || std::find(chain.begin(), chain.end(), k) != chain.end()) continue;
-            if (kp.dims[k].ss == EQ && EQ * kp.dims[k].extent < (1ll << 31)) {
-                chain.push_back(k);
-                EQ *= kp.dims[k].extent;
-                grown = true;
-                break;
-            }
-        }
-    }
+    int64_t EQ = 0;
+    const std::vector<int> chain = q_chain(kp, iP, iQ, EQ);
     dp.EQ = (uint32_t)EQ;
     dp.nq = (uint32_t)chain.size();
     uint32_t nl = 0;
@@ -916,17 +967,20 @@ static std::vector<KPiece> split_ragged(const KPiece &kp, int es) {
         if (kp.dims[k].ss == 1) iQ = k;
     }
     if (iP < 0 || iQ < 0 || iP == iQ) return out;
-    if (env_int("AMAP_FLAT", 1) && env_int("AMAP_GATHER", 1) && env_int("AMAP_VEC_BYTES", 16) >= 16 && flat_dir(kp, es)) return out;  // a flat tile takes it whole
+    if (env_int("AMAP_FLAT", 1) && env_int("AMAP_GATHER", 1) && env_int("AMAP_VEC_BYTES", 16) >= 16 && flat_shape(kp, es).dir) return out;  // a flat tile takes it whole
     std::vector<int64_t> ds_others;
     for (int k = 0; k < (int)kp.dims.size(); ++k)
         if (k != iP) ds_others.push_back(kp.dims[k].ds);
     const int64_t V = common_pow2((uint32_t)vmax, {kp.dbase}, ds_others);  // what the dst side allows
     if (V < 2) return out;
+    int64_t EQc = 0;
+    q_chain(kp, iP, iQ, EQc);
+    const bool chain_whole = env_int("AMAP_TILE_CHAIN_VEC", 1) && EQc % V == 0;  // vectors may straddle the chain's loops
     for (int dim : {iQ, iP}) {
         std::vector<KPiece> next;
         for (const KPiece &p : out) {
             const int64_t E = p.dims[dim].extent, tail = E % V;
-            if (tail == 0 || E < 2 * V) {
+            if (tail == 0 || E < 2 * V || (dim == iQ && chain_whole)) {
                 next.push_back(p);
                 continue;
             }

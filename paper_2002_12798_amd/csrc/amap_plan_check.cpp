@@ -102,7 +102,7 @@ struct Replay {
     // the two phases of a flat tile, lane by lane, with LDS as an array of codes
     void flat(const DevPiece &P, int sid, uint32_t t, uint32_t lds_bytes) {
         const uint32_t V = 16u / (uint32_t)m.elem, vlog = V == 8 ? 3 : 2, rvlog = kFlatRowsLog - vlog;
-        if (P.vlog != vlog || (P.flat != 1 && P.flat != 2) || P.EQ % V || t >= P.n_blocks) {
+        if (P.vlog != vlog || (P.flat != 1 && P.flat != 2) || P.EQ % V || t >= P.n_blocks || P.nq < 1 || P.nq > 4 || P.nloops + P.nq > (uint32_t)kMaxLoops) {
             ++errors;
             return;
         }
@@ -145,7 +145,7 @@ struct Replay {
                         const uint32_t rv = vi & ((1u << rvlog) - 1), c = vi >> rvlog;
                         if (rv * V >= U.rcount) continue;
                         for (uint32_t k = 0; k < V; ++k) {
-                            const uint32_t e = (rv * V + k) * C + c, off = c * (uint32_t)P.ssP + rv * V + k;
+                            const uint32_t e = (rv * V + k) * C + c, off = flat_c_offset(P, c) + rv * V + k;
                             if (P.flat == 1 && k == 0 && (P.dwin + (uint32_t)(U.doff + off)) % V) ++errors;
                             if (P.flat == 1)
                                 write((int64_t)P.dwin + (uint32_t)(U.doff + off), lds_get(e));

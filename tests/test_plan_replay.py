@@ -241,7 +241,11 @@ FLAT = [
     ((4, 7, 7, 136), 2, [("slice", 3, 0, 128, 1), ("transpose", (0, 3, 1, 2))]),  # source rows with a pitch
     ((2, 64, 6, 3), 2, [("transpose", (0, 2, 3, 1))]),                           # 18 positions: pairs only
     ((2, 3, 64, 5, 5), 2, [("transpose", (1, 0, 3, 4, 2))]),                     # batch loops in another order
-    ((2, 320, 3, 3), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),  # two loops on the flat side: other forms
+    ((2, 320, 3, 3), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),  # into a padded image: the row is two loops
+    ((4, 128, 7, 7), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),
+    ((4, 9, 9, 128), 2, [("slice", 1, 1, 8, 1), ("slice", 2, 1, 8, 1), ("transpose", (0, 3, 1, 2))]),  # a crop made channel-major
+    ((2, 64, 3, 3, 3), 4, [("transpose", (0, 2, 3, 4, 1)), ("pad", (0, 1, 0, 1, 0), (0, 0, 1, 1, 0), 0)]),  # three loops
+    ((3, 72, 5, 6), 2, [("slice", 3, 5, -1, -1), ("transpose", (0, 2, 3, 1))]),   # x backwards: rows are no longer one run -> other forms or two loops
     ((2, 56, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                           # fewer than 64 rows: other forms
 ]
 
@@ -252,7 +256,8 @@ def test_flat_tiles_plan(case, monkeypatch):
     m = B.amap_compose([shape], es, ops)
     info = B.amap_describe(m)
     if case < len(FLAT) - 2:
-        assert info.vec_bytes == 16 and B.KERNEL_NAMES[info.kernel_id] == "tile"
+        # (the family reported is that of the largest piece: the border fill where the image is padded)
+        assert info.vec_bytes == 16 and (B.KERNEL_NAMES[info.kernel_id] == "tile" or "pad" in [o[0] for o in ops])
     assert _replay_all(m) >= 2
     monkeypatch.setenv("AMAP_FLAT", "0")            # gathered rows / split tiles instead
     assert _replay_all(B.amap_compose([shape], es, ops)) >= 2
@@ -261,6 +266,34 @@ def test_flat_tiles_plan(case, monkeypatch):
     assert _replay_all(B.amap_compose([shape], es, ops)) >= 2
     monkeypatch.delenv("AMAP_WAVES_LOG")
     monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "11")  # cut into windows
+    assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
+
+
+# tile vectors along a source run made of two loops (x then y of an image that lands in a padded one,
+# or with rows taken from a larger image): the run is a whole number of vectors, its rows are not
+STRADDLE = [
+    ((2, 64, 12, 12), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),
+    ((2, 64, 6, 6), 4, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),
+    ((2, 32, 28, 28), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),
+    ((3, 40, 4, 6, 4), 2, [("transpose", (0, 2, 3, 4, 1)), ("pad", (0, 0, 1, 1, 0), (0, 1, 0, 1, 0), 0)]),   # three loops: 96 positions
+]
+
+
+@pytest.mark.parametrize("case", range(len(STRADDLE)))
+def test_tile_vectors_straddle_the_loops_of_a_source_run(case, monkeypatch):
+    shape, es, ops = STRADDLE[case]
+    m = B.amap_compose([shape], es, ops)
+    assert B.amap_describe(m).vec_bytes == 16
+    assert _replay_all(m) >= 3
+    monkeypatch.setenv("AMAP_FLAT", "0")             # (short runs would pass through LDS as flat tiles otherwise)
+    assert B.amap_describe(m).vec_bytes == 16 and _replay_all(B.amap_compose([shape], es, ops)) >= 3
+    monkeypatch.setenv("AMAP_TILE_CHAIN_VEC", "0")   # vectors inside the innermost loop only
+    m0 = B.amap_compose([shape], es, ops)
+    assert B.amap_describe(m0).vec_bytes < 16
+    assert _replay_all(m0) >= 3
+    monkeypatch.setenv("AMAP_TILE_CHAIN_VEC", "1")
+    monkeypatch.setenv("AMAP_FLAT", "1")
+    monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "11")
     assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
 
 
