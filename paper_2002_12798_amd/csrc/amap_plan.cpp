@@ -278,7 +278,8 @@ static bool plan_inter(const KPiece &kp, int es, uint32_t nwlog, int64_t svol, D
 //   dir 1: the source is the flat side (P's source stride == Q's extent): r = P, c = Q
 //   dir 2: dst is the flat side (Q's dst stride == P's extent): r = Q, c = P
 constexpr uint32_t kFlatRows = 64;
-constexpr uint32_t kFlatLdsBytes = 32768;
+constexpr uint32_t kFlatLdsBytes = 65536;  // rows of 289 (17 x 17): 32.9 us as whole-vector part + tail, 24.8 us as flat tiles of 37 KiB
+constexpr uint32_t kFlatMinRows = 16;      // 48 channels of 7 x 7 images: 23.6 -> 12.5 us; 16 channels: 21.4 -> 11.6 us
 
 // The loops that continue the source-contiguous loop iQ in the source (x, then y of an image: one run of
 // H * W elements), innermost first, and the length of that run.  A tile vector along Q may straddle the
@@ -349,7 +350,7 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
         if (flat_stride(iR) != C) continue;
         const int64_t ER = kp.dims[iR].extent;
         // rows of 2 .. 7 elements belong to the interleaving row forms (a block of 64 such rows is too little work)
-        if (C < env_int("AMAP_FLAT_MIN_C", 8) || ER % V || ER < (int64_t)kFlatRows || C * kFlatRows * es > (int64_t)kFlatLdsBytes) continue;
+        if (C < env_int("AMAP_FLAT_MIN_C", 8) || ER % V || ER < (int64_t)env_int("AMAP_FLAT_MIN_ROWS", (int)kFlatMinRows) || C * std::min<int64_t>(ER, kFlatRows) * es > (int64_t)std::min(64, env_int("AMAP_FLAT_LDS_KB", (int)(kFlatLdsBytes >> 10))) * 1024) continue;
         if (n - 1 > kMaxLoops) continue;  // batch loops + chain
         bool ok = true;
         for (int k = 0; k < n; ++k) {
@@ -401,7 +402,7 @@ static bool plan_flat(const KPiece &kp, int es, uint32_t nwlog, DevPiece &dp, ui
     if (nb >= (1ll << 31)) return false;
     dp.n_blocks = (uint32_t)nb;
     dp.n_units = dp.n_blocks;
-    lds = (uint32_t)(f.C * kFlatRows * es);
+    lds = (uint32_t)(f.C * std::min<int64_t>(f.ER, kFlatRows) * es);
     // whole lines: blocks of kFlatRows rows are whole lines on the flat side (kFlatRows * C elements) and on the other
     if (f.ER % kFlatRows == 0) {
         const bool flat_dst = line_aligned(es, {kp.dbase}, ds_o), flat_src = line_aligned(es, {kp.sbase}, ss_o);
@@ -900,7 +901,7 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
         for (DevPiece d : dps) {
             // a flat tile of 8 KiB and more: few workgroups fit a compute unit, so each should bring 4 wavefronts
             // (rows of 81 elements: 9.1 -> 7.8 us, of 169: 10.9 -> 6.8 us; of 49 and fewer a single wavefront is faster)
-            if (d.kind == PK_FLAT && (uint64_t)d.eP * kFlatRows * m.elem >= 8192) split_rows = true;
+            if (d.kind == PK_FLAT && (uint64_t)d.eP * std::min(d.EQ, kFlatRows) * m.elem >= 8192) split_rows = true;
             if (d.kind != PK_ROWS && d.kind != PK_FLAT && d.n_blocks && d.tilesP > 1 && (d.eP * (uint64_t)m.elem) % 128 != 0) split_rows = true;
             d.first_block = blocks;
             cur.nt = cur.n_pieces == 0 ? d.flags : (cur.nt & d.flags);

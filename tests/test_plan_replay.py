@@ -245,8 +245,13 @@ FLAT = [
     ((4, 128, 7, 7), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),
     ((4, 9, 9, 128), 2, [("slice", 1, 1, 8, 1), ("slice", 2, 1, 8, 1), ("transpose", (0, 3, 1, 2))]),  # a crop made channel-major
     ((2, 64, 3, 3, 3), 4, [("transpose", (0, 2, 3, 4, 1)), ("pad", (0, 1, 0, 1, 0), (0, 0, 1, 1, 0), 0)]),  # three loops
-    ((3, 72, 5, 6), 2, [("slice", 3, 5, -1, -1), ("transpose", (0, 2, 3, 1))]),   # x backwards: rows are no longer one run -> other forms or two loops
-    ((2, 56, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                           # fewer than 64 rows: other forms
+    ((2, 56, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                           # fewer than 64 rows: one block of 56
+    ((5, 7, 7, 48), 2, [("transpose", (0, 3, 1, 2))]),
+    ((5, 16, 5, 5), 4, [("transpose", (0, 2, 3, 1))]),
+    ((2, 72, 17, 17), 2, [("transpose", (0, 2, 3, 1))]),                         # rows of 289: 37 KiB of LDS
+    ((2, 17, 17, 72), 2, [("transpose", (0, 3, 1, 2))]),
+    ((3, 72, 5, 6), 2, [("slice", 3, 5, -1, -1), ("transpose", (0, 2, 3, 1))]),   # x backwards: rows are no longer one run -> other forms
+    ((2, 8, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                            # 8 rows only: other forms
 ]
 
 
