@@ -103,7 +103,7 @@ struct DevPiece {
     // the lane loads eP consecutive vectors and keeps the first (3) or the last (4) element of every
     // group of eP; the window lies so that it never leaves the source.
     uint32_t inter;
-    // FLAT only.  An r x c matrix (r: EQ values, blocks of 64; c: eP values, any number) is contiguous
+    // FLAT only.  An r x c matrix (r: EQ values, blocks of 1 << lqlog = 16, 32 or 64; c: eP values, any number) is contiguous
     // on one side (offset r * eP + c) and has rows along r on the other (offset f(c) + r, where c runs
     // over the nq loops at the END of loops[], loops[kMaxLoops - 1 - j], innermost first, each with
     // its own stride on that side).  1: the source is the contiguous side, 2: dst is.

@@ -67,13 +67,13 @@ AMAP_HD void rows_offsets(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_
 
 // ---- flat tiles (see DevPiece::flat): workgroup t -> element offsets of its block on both sides
 // (of row r0, c = 0), and the number of rows in the block
-constexpr uint32_t kFlatRowsLog = 6;
+// rows per block = 1 << P.lqlog (16, 32 or 64: as many as fit LDS)
 struct FlatUnit {
     uint32_t doff, soff, rcount;
 };
 AMAP_HD FlatUnit flat_unit(const DevPiece &P, uint32_t t) {
     uint32_t rest = fdiv(t, P.fdTP);
-    const uint32_t r0 = (t - rest * P.tilesP) << kFlatRowsLog;
+    const uint32_t r0 = (t - rest * P.tilesP) << P.lqlog;
     uint32_t d = P.dbase, s = P.sbase;
     for (uint32_t k = 0; k < P.nloops; ++k) {
         const uint32_t q = fdiv(rest, P.loops[k].fd);
@@ -86,7 +86,7 @@ AMAP_HD FlatUnit flat_unit(const DevPiece &P, uint32_t t) {
     u.doff = d + (P.flat == 1 ? r0 : r0 * P.eP);
     u.soff = s + (P.flat == 1 ? r0 * P.eP : r0);
     const uint32_t left = P.EQ - r0;
-    u.rcount = left < (1u << kFlatRowsLog) ? left : (1u << kFlatRowsLog);
+    u.rcount = left < (1u << P.lqlog) ? left : (1u << P.lqlog);
     return u;
 }
 

@@ -445,7 +445,8 @@ __device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t
 template <int ES, int NT>
 __device__ __forceinline__ void flat_body(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
     constexpr int V = 16 / ES;
-    constexpr uint32_t VLOG = ES == 2 ? 3 : 2, RVLOG = kFlatRowsLog - VLOG;
+    constexpr uint32_t VLOG = ES == 2 ? 3 : 2;
+    const uint32_t RVLOG = P.lqlog - VLOG;  // log2(vectors per row of the block)
     constexpr int kBatch = 4;  // loads a lane has in flight
     typedef typename std::conditional<ES == 2, uint16_t, uint32_t>::type elem_t;
     const FlatUnit U = flat_unit(P, t);

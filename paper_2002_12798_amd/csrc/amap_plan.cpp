@@ -271,13 +271,12 @@ static bool plan_inter(const KPiece &kp, int es, uint32_t nwlog, int64_t svol, D
 
 // Flat tiles: a transposing piece whose P x Q matrix is contiguous on one side (rows follow one
 // another without a gap) while the extent C along that side's contiguous loop offers no 16-byte
-// vectors (49 = 7 x 7 positions of an image in channel-major order).  A workgroup takes kFlatRows rows of
-// the other loop: on the flat side that is ONE contiguous run of kFlatRows * C elements, moved in
+// vectors (49 = 7 x 7 positions of an image in channel-major order).  A workgroup takes 64 rows (32 or 16 where
+// 64 do not fit LDS) of the other loop: on the flat side that is ONE contiguous run of rows * C elements, moved in
 // whole vectors whatever C is; LDS holds the run, and the other side is served with 16-byte vectors
 // along its own contiguous loop, its elements picked from / put into LDS one by one.
 //   dir 1: the source is the flat side (P's source stride == Q's extent): r = P, c = Q
 //   dir 2: dst is the flat side (Q's dst stride == P's extent): r = Q, c = P
-constexpr uint32_t kFlatRows = 64;
 constexpr uint32_t kFlatLdsBytes = 65536;  // rows of 289 (17 x 17): 32.9 us as whole-vector part + tail, 24.8 us as flat tiles of 37 KiB
 constexpr uint32_t kFlatMinRows = 16;      // 48 channels of 7 x 7 images: 23.6 -> 12.5 us; 16 channels: 21.4 -> 11.6 us
 
@@ -306,9 +305,10 @@ static std::vector<int> q_chain(const KPiece &kp, int iP, int iQ, int64_t &EQ) {
 
 struct FlatShape {
     int dir = 0;             // 0: the piece has no flat form
-    int iR = -1;             // the loop that is cut into blocks of kFlatRows
+    int iR = -1;             // the loop that is cut into blocks of rows
     std::vector<int> chain;  // the loops that make up a row of the flat side, innermost first
     int64_t C = 0, ER = 0;
+    uint32_t rlog = 6;       // log2(rows per block)
 };
 
 // The row of the flat side may be several loops that continue one another on that side only (the
@@ -331,7 +331,8 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
     // 196 positions under 1024 channels, 33.0 -> 21.2 us for rows of 100)
     int64_t EQc = Q.extent;
     if (env_int("AMAP_TILE_CHAIN_VEC", 1)) q_chain(kp, iP, iQ, EQc);
-    if ((int64_t)common_pow2((uint32_t)V, {P.extent, EQc}, {}) * es >= env_int("AMAP_FLAT_BELOW", 16)) return none;
+    const int64_t tile_bytes = (int64_t)common_pow2((uint32_t)V, {P.extent, EQc}, {}) * es;
+    if (tile_bytes >= env_int("AMAP_FLAT_BELOW", 16)) return none;
     for (int dir = 1; dir <= 2; ++dir) {
         // dir 1: rows are contiguous in the source, from Q outwards, until P's source stride is reached;
         // dir 2: in dst, from P outwards, until Q's dst stride is reached
@@ -350,7 +351,15 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
         if (flat_stride(iR) != C) continue;
         const int64_t ER = kp.dims[iR].extent;
         // rows of 2 .. 7 elements belong to the interleaving row forms (a block of 64 such rows is too little work)
-        if (C < env_int("AMAP_FLAT_MIN_C", 8) || ER % V || ER < (int64_t)env_int("AMAP_FLAT_MIN_ROWS", (int)kFlatMinRows) || C * std::min<int64_t>(ER, kFlatRows) * es > (int64_t)std::min(64, env_int("AMAP_FLAT_LDS_KB", (int)(kFlatLdsBytes >> 10))) * 1024) continue;
+        if (C < env_int("AMAP_FLAT_MIN_C", 8) || ER % V || ER < (int64_t)env_int("AMAP_FLAT_MIN_ROWS", (int)kFlatMinRows)) continue;
+        // as many rows per block as fit LDS: 64, 32 or 16 (rows of 1225 = 35 x 35 positions: 16 at a time)
+        const int64_t lds_limit = (int64_t)std::min(64, env_int("AMAP_FLAT_LDS_KB", (int)(kFlatLdsBytes >> 10))) * 1024;
+        uint32_t rlog = 6;
+        // 16 rows at a time only against forms with vectors of less than 8 bytes (rows of 1225: 216.2 -> 27.8 us);
+        // against tiles with 8-byte vectors they lose (rows of 1444: 13.2 -> 21.1 us), 32 rows still win (676: 17.6 -> 15.6 us)
+        const uint32_t rlog_min = (uint32_t)std::max(4, std::min(6, env_int("AMAP_FLAT_MIN_RLOG", tile_bytes >= 8 ? 5 : 4)));
+        while (rlog > rlog_min && C * std::min<int64_t>(ER, 1ll << rlog) * es > lds_limit) --rlog;
+        if (C * std::min<int64_t>(ER, 1ll << rlog) * es > lds_limit) continue;
         if (n - 1 > kMaxLoops) continue;  // batch loops + chain
         bool ok = true;
         for (int k = 0; k < n; ++k) {
@@ -360,7 +369,7 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
             if (kp.dims[k].ds % V) ok = false;           // batch loops on both sides, the chain's dst strides in dir 1
         }
         if (!ok) continue;
-        f.dir = dir, f.iR = iR, f.chain = chain, f.C = C, f.ER = ER;
+        f.dir = dir, f.iR = iR, f.chain = chain, f.C = C, f.ER = ER, f.rlog = rlog;
         return f;
     }
     return none;
@@ -378,7 +387,9 @@ static bool plan_flat(const KPiece &kp, int es, uint32_t nwlog, DevPiece &dp, ui
     dp.flat = (uint32_t)f.dir;
     dp.eP = (uint32_t)f.C;
     dp.EQ = (uint32_t)f.ER;
-    dp.tilesP = (uint32_t)((f.ER + kFlatRows - 1) / kFlatRows);
+    const int64_t rows = 1ll << f.rlog;
+    dp.lqlog = f.rlog;
+    dp.tilesP = (uint32_t)((f.ER + rows - 1) / rows);
     dp.fdTP = make_fastdiv(dp.tilesP);
     int64_t nb = dp.tilesP;
     uint32_t nl = 0;
@@ -402,11 +413,11 @@ static bool plan_flat(const KPiece &kp, int es, uint32_t nwlog, DevPiece &dp, ui
     if (nb >= (1ll << 31)) return false;
     dp.n_blocks = (uint32_t)nb;
     dp.n_units = dp.n_blocks;
-    lds = (uint32_t)(f.C * std::min<int64_t>(f.ER, kFlatRows) * es);
-    // whole lines: blocks of kFlatRows rows are whole lines on the flat side (kFlatRows * C elements) and on the other
-    if (f.ER % kFlatRows == 0) {
-        const bool flat_dst = line_aligned(es, {kp.dbase}, ds_o), flat_src = line_aligned(es, {kp.sbase}, ss_o);
-        const bool rows_ok = line_aligned(es, {}, chain_other);
+    lds = (uint32_t)(f.C * std::min<int64_t>(f.ER, rows) * es);
+    // streaming accesses where every block covers whole lines on that side
+    if (f.ER % rows == 0) {
+        const bool flat_dst = line_aligned(es, {kp.dbase, rows * f.C}, ds_o), flat_src = line_aligned(es, {kp.sbase, rows * f.C}, ss_o);
+        const bool rows_ok = line_aligned(es, {rows}, chain_other);
         const bool rows_dst = rows_ok && line_aligned(es, {kp.dbase}, ds_o), rows_src = rows_ok && line_aligned(es, {kp.sbase}, ss_o);
         if (f.dir == 1 ? rows_dst : flat_dst) dp.flags |= PF_NT_STORE;
         if (f.dir == 1 ? flat_src : rows_src) dp.flags |= PF_NT_LOAD;
@@ -901,7 +912,7 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
         for (DevPiece d : dps) {
             // a flat tile of 8 KiB and more: few workgroups fit a compute unit, so each should bring 4 wavefronts
             // (rows of 81 elements: 9.1 -> 7.8 us, of 169: 10.9 -> 6.8 us; of 49 and fewer a single wavefront is faster)
-            if (d.kind == PK_FLAT && (uint64_t)d.eP * std::min(d.EQ, kFlatRows) * m.elem >= 8192) split_rows = true;
+            if (d.kind == PK_FLAT && (uint64_t)d.eP * std::min(d.EQ, 1u << d.lqlog) * m.elem >= 8192) split_rows = true;
             if (d.kind != PK_ROWS && d.kind != PK_FLAT && d.n_blocks && d.tilesP > 1 && (d.eP * (uint64_t)m.elem) % 128 != 0) split_rows = true;
             d.first_block = blocks;
             cur.nt = cur.n_pieces == 0 ? d.flags : (cur.nt & d.flags);

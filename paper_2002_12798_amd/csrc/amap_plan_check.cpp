@@ -101,8 +101,8 @@ struct Replay {
 
     // the two phases of a flat tile, lane by lane, with LDS as an array of codes
     void flat(const DevPiece &P, int sid, uint32_t t, uint32_t lds_bytes) {
-        const uint32_t V = 16u / (uint32_t)m.elem, vlog = V == 8 ? 3 : 2, rvlog = kFlatRowsLog - vlog;
-        if (P.vlog != vlog || (P.flat != 1 && P.flat != 2) || P.EQ % V || t >= P.n_blocks || P.nq < 1 || P.nq > 4 || P.nloops + P.nq > (uint32_t)kMaxLoops) {
+        const uint32_t V = 16u / (uint32_t)m.elem, vlog = V == 8 ? 3 : 2, rvlog = P.lqlog - vlog;
+        if (P.lqlog < 4 || P.lqlog > 6 || P.vlog != vlog || (P.flat != 1 && P.flat != 2) || P.EQ % V || t >= P.n_blocks || P.nq < 1 || P.nq > 4 || P.nloops + P.nq > (uint32_t)kMaxLoops) {
             ++errors;
             return;
         }

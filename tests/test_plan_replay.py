@@ -250,6 +250,10 @@ FLAT = [
     ((5, 16, 5, 5), 4, [("transpose", (0, 2, 3, 1))]),
     ((2, 72, 17, 17), 2, [("transpose", (0, 2, 3, 1))]),                         # rows of 289: 37 KiB of LDS
     ((2, 17, 17, 72), 2, [("transpose", (0, 3, 1, 2))]),
+    ((2, 48, 35, 35), 2, [("transpose", (0, 2, 3, 1))]),                         # rows of 1225: 16 rows per block
+    ((2, 35, 35, 48), 2, [("transpose", (0, 3, 1, 2))]),
+    ((2, 40, 23, 23), 4, [("transpose", (0, 2, 3, 1))]),                         # rows of 529 x 4 bytes: 16 rows per block
+    ((2, 26, 26, 96), 2, [("transpose", (0, 3, 1, 2))]),                         # rows of 676: 32 rows per block
     ((3, 72, 5, 6), 2, [("slice", 3, 5, -1, -1), ("transpose", (0, 2, 3, 1))]),   # x backwards: rows are no longer one run -> other forms
     ((2, 8, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                            # 8 rows only: other forms
 ]
