@@ -110,6 +110,14 @@ struct DevPiece {
     // tilesP = blocks along r; loops[0..nloops) = batch loops.  A workgroup moves the contiguous run of its block in 16-byte vectors into / out of LDS
     // and serves the other side with 16-byte vectors along r whose elements it picks one by one.
     uint32_t flat;
+    // FLAT, column-blocked ("ragged") form, for rows too long for LDS: rag_cb > 0.  A workgroup takes
+    // rows x rag_cb elements (tilesQ blocks along c, the fastest-running part of the workgroup index).  On
+    // the contiguous side a row segment starts at any element: loads take 16-byte vectors from the segment's
+    // start (under-aligned) and single elements at its end; stores take the aligned 16-byte slots the
+    // segment covers (rag_s = rag_cb / V + 1 of them), whole where the slot lies inside the segment and
+    // element by element at the two ends.  LDS rows are rag_w elements apart.
+    uint32_t rag_cb, rag_w, rag_s;
+    FastDiv fd_rag_s;
     // Window of the piece in tensors too large for 32-bit offsets: dbase and every
     // dst offset are relative to element dwin of dst; swin likewise for the source
     // (the host folds it into `src` at launch).  0 for ordinary tensors.

@@ -90,6 +90,34 @@ AMAP_HD FlatUnit flat_unit(const DevPiece &P, uint32_t t) {
     return u;
 }
 
+// column-blocked form: workgroup t -> block (rows from r0, columns from c0), offsets of (r0, c0)
+struct RagUnit {
+    uint32_t doff, soff, rcount, c0, ccount;
+};
+AMAP_HD RagUnit rag_unit(const DevPiece &P, uint32_t t) {
+    uint32_t rest = fdiv(t, P.fdTQ);
+    const uint32_t c0 = (t - rest * P.tilesQ) * P.rag_cb;
+    const uint32_t t2 = rest;
+    rest = fdiv(t2, P.fdTP);
+    const uint32_t r0 = (t2 - rest * P.tilesP) << P.lqlog;
+    uint32_t d = P.dbase, s = P.sbase;
+    for (uint32_t k = 0; k < P.nloops; ++k) {
+        const uint32_t q = fdiv(rest, P.loops[k].fd);
+        const uint32_t dig = rest - q * P.loops[k].extent;
+        d += dig * (uint32_t)P.loops[k].ds;
+        s += dig * (uint32_t)P.loops[k].ss;
+        rest = q;
+    }
+    RagUnit u;
+    u.doff = d + (P.flat == 1 ? r0 : r0 * P.eP + c0);
+    u.soff = s + (P.flat == 1 ? r0 * P.eP + c0 : r0);
+    const uint32_t rleft = P.EQ - r0, cleft = P.eP - c0;
+    u.rcount = rleft < (1u << P.lqlog) ? rleft : (1u << P.lqlog);
+    u.c0 = c0;
+    u.ccount = cleft < P.rag_cb ? cleft : P.rag_cb;
+    return u;
+}
+
 // position c of a row -> element offset on the side where the row is not contiguous: the row's loops
 // sit at the end of loops[] (loops[kMaxLoops - 1 - j], j < nq, innermost first)
 AMAP_HD uint32_t flat_c_offset(const DevPiece &P, uint32_t c) {

@@ -516,6 +516,97 @@ __device__ __forceinline__ void flat_body(const DevPiece &P, char *dst, uint32_t
     }
 }
 
+// The same for rows too long for LDS: blocks of rows x rag_cb columns (see DevPiece::rag_cb).
+template <int ES, int NT>
+__device__ __forceinline__ void rag_body(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
+    constexpr uint32_t V = 16 / ES;
+    constexpr uint32_t VLOG = ES == 2 ? 3 : 2;
+    const uint32_t RVLOG = P.lqlog - VLOG;
+    constexpr int kBatch = 4;
+    typedef typename std::conditional<ES == 2, uint16_t, uint32_t>::type elem_t;
+    const RagUnit U = rag_unit(P, t);
+    const uint32_t C = P.eP, W = P.rag_w, S = P.rag_s, threads = 64u << P.nwlog;
+    const uint32_t nrag = U.rcount * S, nstr = U.ccount << RVLOG;
+    elem_t *const lds = reinterpret_cast<elem_t *>(smem);
+    const char *const src = (const char *)P.src;
+
+    if (P.flat == 1) {
+        for (uint32_t item = tid; item < nrag; item += threads) {
+            const uint32_t r = fdiv(item, P.fd_rag_s), col = (item - r * S) * V;
+            if (col >= U.ccount) continue;
+            const uint32_t a = U.soff + r * C + col, at = r * W + col;
+            if (col + V <= U.ccount) {
+                uint32_t v[4];
+                gld<16, false>(v, src + (size_t)a * ES);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) reinterpret_cast<uint32_t *>(smem)[(at * ES) / 4 + k] = v[k];
+            } else {
+                for (uint32_t i = 0; col + i < U.ccount; ++i) lds[at + i] = reinterpret_cast<const elem_t *>(src)[a + i];
+            }
+        }
+        __syncthreads();
+        for (uint32_t vi = tid; vi < nstr; vi += threads) {
+            const uint32_t rv = vi & ((1u << RVLOG) - 1), c = vi >> RVLOG;
+            if (rv * V >= U.rcount) continue;
+            uint32_t v[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (uint32_t k = 0; k < V; ++k) {
+                const uint32_t x = lds[(rv * V + k) * W + c];
+                if constexpr (ES == 2)
+                    v[k / 2] |= x << (16 * (k & 1));
+                else
+                    v[k] = x;
+            }
+            gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)(U.doff + flat_c_offset(P, U.c0 + c) + rv * V) * ES, v);
+        }
+    } else {
+        for (uint32_t v0 = tid; v0 < nstr; v0 += kBatch * threads) {
+            uint32_t v[kBatch][4];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const uint32_t vi = v0 + b * threads, rv = vi & ((1u << RVLOG) - 1), c = vi >> RVLOG;
+                if (vi < nstr && rv * V < U.rcount)
+                    gld<16, (NT & PF_NT_LOAD) != 0>(v[b], src + (size_t)(U.soff + flat_c_offset(P, U.c0 + c) + rv * V) * ES);
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const uint32_t vi = v0 + b * threads, rv = vi & ((1u << RVLOG) - 1), c = vi >> RVLOG;
+                if (vi < nstr && rv * V < U.rcount) {
+#pragma unroll
+                    for (uint32_t k = 0; k < V; ++k) {
+                        if constexpr (ES == 2)
+                            lds[(rv * V + k) * W + c] = (uint16_t)(v[b][k / 2] >> (16 * (k & 1)));
+                        else
+                            lds[(rv * V + k) * W + c] = v[b][k];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        for (uint32_t item = tid; item < nrag; item += threads) {
+            const uint32_t r = fdiv(item, P.fd_rag_s), s = item - r * S;
+            const uint32_t a = U.doff + r * C;                 // first dst element of the row segment
+            const uint32_t x = (a & ~(V - 1)) + s * V;         // the aligned slot
+            const uint32_t lo = x > a ? x : a, hi = x + V < a + U.ccount ? x + V : a + U.ccount;
+            if (lo >= hi) continue;
+            if (hi - lo == V) {
+                uint32_t v[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (uint32_t k = 0; k < V; ++k) {
+                    const uint32_t e = lds[r * W + (x - a) + k];
+                    if constexpr (ES == 2)
+                        v[k / 2] |= e << (16 * (k & 1));
+                    else
+                        v[k] = e;
+                }
+                gst<16, false>(dst + (size_t)x * ES, v);
+            } else {
+                for (uint32_t p = lo; p < hi; ++p) reinterpret_cast<elem_t *>(dst)[p] = lds[r * W + (p - a)];
+            }
+        }
+    }
+}
+
 template <int ES, bool USE_LDS, int NT, bool GROUPED>
 __device__ __forceinline__ void tile_dispatch(const DevPiece &P, char *dst, uint32_t t, uint32_t tid, char *smem) {
     if constexpr (ES == 2) {
@@ -553,6 +644,8 @@ __global__ __launch_bounds__(kMaxThreads) void amap_pieces_kernel(const LaunchAr
         rows_body<ES, NT>(P, d, local, threadIdx.x);
     else if (P.kind == PK_TILE)
         tile_dispatch<ES, true, NT, GROUPED>(P, d, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
+    else if (P.kind == PK_FLAT && P.rag_cb)
+        rag_body<ES, NT>(P, d, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
     else if (P.kind == PK_FLAT)
         flat_body<ES, NT>(P, d, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
     else

@@ -19,6 +19,8 @@
 
 #include "amap_plan.hpp"
 
+#include <cstdio>
+
 using namespace amap_dev;
 
 namespace amap_detail {
@@ -309,6 +311,7 @@ struct FlatShape {
     std::vector<int> chain;  // the loops that make up a row of the flat side, innermost first
     int64_t C = 0, ER = 0;
     uint32_t rlog = 6;       // log2(rows per block)
+    int64_t cb = 0;          // > 0: column-blocked form with this many columns per block
 };
 
 // The row of the flat side may be several loops that continue one another on that side only (the
@@ -359,17 +362,26 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
         // against tiles with 8-byte vectors they lose (rows of 1444: 13.2 -> 21.1 us), 32 rows still win (676: 17.6 -> 15.6 us)
         const uint32_t rlog_min = (uint32_t)std::max(4, std::min(6, env_int("AMAP_FLAT_MIN_RLOG", tile_bytes >= 8 ? 5 : 4)));
         while (rlog > rlog_min && C * std::min<int64_t>(ER, 1ll << rlog) * es > lds_limit) --rlog;
-        if (C * std::min<int64_t>(ER, 1ll << rlog) * es > lds_limit) continue;
-        if (n - 1 > kMaxLoops) continue;  // batch loops + chain
-        bool ok = true;
-        for (int k = 0; k < n; ++k) {
-            const bool in_chain = std::find(chain.begin(), chain.end(), k) != chain.end();
-            if (k == iP || k == iR) continue;            // dst stride 1; in dir 2 the block loop walks dst in steps of C rows of whole vectors
-            if (dir == 2 && in_chain) continue;          // inside the flat dst run
-            if (kp.dims[k].ds % V) ok = false;           // batch loops on both sides, the chain's dst strides in dir 1
+        int64_t cb = 0;
+        // 128 columns per block (55 x 55 positions under 96 channels, towards channel-major: 24.4 us; 256 columns: 26.6 us;
+        // gathered rows: 178.8 us).  With the source as the contiguous side and a row of one loop, the cut into a
+        // whole-vector part and a one-element tail is as fast or faster (23.7 against 23.8 us; 75 x 75 fp32: 11.9 against
+        // 17.4 us), so there the blocked form is left to rows of several loops (padded or cropped images).
+        const int64_t cb_env = env_int("AMAP_FLAT_RAG_CB", 128);
+        const bool rag_ok = env_int("AMAP_FLAT_RAG", 1) && cb_env >= V && cb_env % V == 0 && cb_env * es <= 1024 && tile_bytes < 8 && ER >= 64;
+        const bool fits = C * std::min<int64_t>(ER, 1ll << rlog) * es <= lds_limit;
+        if (!fits) {
+            // rows too long for LDS: blocks of 64 rows x cb columns whose row segments start at any element
+            if (!rag_ok || !(dir == 2 || chain.size() > 1 || env_int("AMAP_FLAT_RAG", 1) >= 2)) continue;
+            rlog = 6;
+            cb = cb_env;
+        } else if (rag_ok && ((rlog == 4 && dir == 1) || (rlog < 6 && env_int("AMAP_FLAT_RAG", 1) >= 2))) {
+            // 16 rows at a time with the source as the contiguous side: the blocked form is faster
+            // (35 x 35 positions under 288 channels: 26.3 against 30.7 us; into a padded image 29.1 against 32.1 us)
+            rlog = 6;
+            cb = cb_env;
         }
-        if (!ok) continue;
-        f.dir = dir, f.iR = iR, f.chain = chain, f.C = C, f.ER = ER, f.rlog = rlog;
+        f.dir = dir, f.iR = iR, f.chain = chain, f.C = C, f.ER = ER, f.rlog = rlog, f.cb = cb;
         return f;
     }
     return none;
@@ -414,6 +426,21 @@ static bool plan_flat(const KPiece &kp, int es, uint32_t nwlog, DevPiece &dp, ui
     dp.n_blocks = (uint32_t)nb;
     dp.n_units = dp.n_blocks;
     lds = (uint32_t)(f.C * std::min<int64_t>(f.ER, rows) * es);
+    if (f.cb) {
+        dp.rag_cb = (uint32_t)f.cb;
+        dp.rag_w = (uint32_t)(f.cb + (es == 2 ? 2 : 1));  // LDS row stride: an odd number of dwords
+        dp.rag_s = (uint32_t)(f.cb / V + 1);
+        dp.fd_rag_s = make_fastdiv(dp.rag_s);
+        dp.tilesQ = (uint32_t)((f.C + f.cb - 1) / f.cb);
+        dp.fdTQ = make_fastdiv(dp.tilesQ);
+        nb *= dp.tilesQ;
+        if (nb >= (1ll << 31)) return false;
+        dp.n_blocks = (uint32_t)nb;
+        dp.n_units = dp.n_blocks;
+        lds = (uint32_t)(rows * dp.rag_w * es);
+        dp.flags = 0;
+        return true;
+    }
     // streaming accesses where every block covers whole lines on that side
     if (f.ER % rows == 0) {
         const bool flat_dst = line_aligned(es, {kp.dbase, rows * f.C}, ds_o), flat_src = line_aligned(es, {kp.sbase, rows * f.C}, ss_o);
@@ -552,6 +579,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
             return AMAP_K_TILE;
         }
         dp.flat = 0;
+        dp.rag_cb = 0;
         dp.nq = 0;
         dp.flags = 0;
         lds = 0;
@@ -905,14 +933,29 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
         blocks = 0;
         lds_max = 0;
     };
+    const bool trace = env_int("AMAP_PLAN_TRACE", 0) != 0;  // one line per planned piece on stderr
     auto emit = [&](const std::vector<DevPiece> &dps, uint32_t lds, int vb, int fam, int64_t vol) {
+        if (trace)
+            for (const DevPiece &d : dps) {
+                const char *form = d.kind == PK_TILE ? "tile" : d.kind == PK_WAVE ? "wave" : "rows";
+                if (d.kind == PK_FLAT) form = d.rag_cb ? (d.flat == 1 ? "flat-blocked-src" : "flat-blocked-dst") : (d.flat == 1 ? "flat-src" : "flat-dst");
+                if (d.kind == PK_ROWS) {
+                    if (!d.src) form = "rows-fill";
+                    if (d.rep_log) form = "rows-expand";
+                    if (d.rev) form = "rows-reverse";
+                    if (d.gather) form = "rows-gather";
+                    if (d.inter) form = d.inter == 1 ? "rows-interleave" : d.inter == 2 ? "rows-deinterleave" : "rows-keep-plane";
+                }
+                std::fprintf(stderr, "amap plan: %s vec_bytes=%d workgroups=%u lds=%u lanes=%u elements=%lld\n", form, vb, d.n_blocks, lds,
+                             64u << nwlog, (long long)vol);
+            }
         uint32_t nb = 0;
         for (const DevPiece &d : dps) nb += d.n_blocks;
         if (cur.n_pieces + dps.size() > (size_t)kMaxPiecesPerLaunch || (uint64_t)blocks + nb >= (1u << 31)) flush();
         for (DevPiece d : dps) {
             // a flat tile of 8 KiB and more: few workgroups fit a compute unit, so each should bring 4 wavefronts
             // (rows of 81 elements: 9.1 -> 7.8 us, of 169: 10.9 -> 6.8 us; of 49 and fewer a single wavefront is faster)
-            if (d.kind == PK_FLAT && (uint64_t)d.eP * std::min(d.EQ, 1u << d.lqlog) * m.elem >= 8192) split_rows = true;
+            if (d.kind == PK_FLAT && ((uint64_t)d.eP * std::min(d.EQ, 1u << d.lqlog) * m.elem >= 8192 || d.rag_cb)) split_rows = true;
             if (d.kind != PK_ROWS && d.kind != PK_FLAT && d.n_blocks && d.tilesP > 1 && (d.eP * (uint64_t)m.elem) % 128 != 0) split_rows = true;
             d.first_block = blocks;
             cur.nt = cur.n_pieces == 0 ? d.flags : (cur.nt & d.flags);

@@ -99,6 +99,70 @@ struct Replay {
             }
     }
 
+    // the column-blocked form of a flat tile
+    void rag(const DevPiece &P, int sid, uint32_t t, uint32_t lds_bytes) {
+        const uint32_t V = 16u / (uint32_t)m.elem, vlog = V == 8 ? 3 : 2, rvlog = P.lqlog - vlog;
+        if (P.lqlog != 6 || P.vlog != vlog || (P.flat != 1 && P.flat != 2) || P.EQ % V || t >= P.n_blocks || P.nq < 1 || P.nq > 4 ||
+            P.nloops + P.nq > (uint32_t)kMaxLoops || P.rag_cb % V || P.rag_s != P.rag_cb / V + 1 || P.rag_w < P.rag_cb || (P.rag_w * m.elem) % 4 ||
+            (uint64_t)P.rag_w * 64 * m.elem > lds_bytes || (uint64_t)P.tilesQ * P.rag_cb < P.eP) {
+            ++errors;
+            return;
+        }
+        const RagUnit U = rag_unit(P, t);
+        const uint32_t C = P.eP, W = P.rag_w, S = P.rag_s, threads = 64u << P.nwlog;
+        const uint32_t nrag = U.rcount * S, nstr = U.ccount << rvlog;
+        std::vector<int64_t> lds((size_t)lds_bytes / (size_t)m.elem, kUnwritten);
+        auto lds_put = [&](uint64_t e, int64_t code) {
+            if (e >= lds.size() || lds[e] != kUnwritten)
+                ++errors;
+            else
+                lds[e] = code;
+        };
+        auto lds_get = [&](uint64_t e) -> int64_t {
+            if (e >= lds.size() || lds[e] == kUnwritten) {
+                ++errors;
+                return kFill;
+            }
+            return lds[e];
+        };
+        for (int phase = 0; phase < 2; ++phase)
+            for (uint32_t tid = 0; tid < threads; ++tid) {
+                const bool rag_side = (phase == 0) == (P.flat == 1);
+                if (!rag_side) {
+                    for (uint32_t vi = tid; vi < nstr; vi += threads) {
+                        const uint32_t rv = vi & ((1u << rvlog) - 1), c = vi >> rvlog;
+                        if (rv * V >= U.rcount) continue;
+                        for (uint32_t k = 0; k < V; ++k) {
+                            const uint32_t e = (rv * V + k) * W + c, off = flat_c_offset(P, U.c0 + c) + rv * V + k;
+                            if (P.flat == 1 && k == 0 && (P.dwin + (uint32_t)(U.doff + off)) % V) ++errors;
+                            if (P.flat == 1)
+                                write((int64_t)P.dwin + (uint32_t)(U.doff + off), lds_get(e));
+                            else
+                                lds_put(e, code_of(sid, (int64_t)P.swin + (int64_t)(int32_t)(U.soff + off)));
+                        }
+                    }
+                } else if (P.flat == 1) {
+                    for (uint32_t item = tid; item < nrag; item += threads) {
+                        const uint32_t r = fdiv(item, P.fd_rag_s), col = (item - r * S) * V;
+                        if (col >= U.ccount) continue;
+                        const uint32_t a = U.soff + r * C + col, at = r * W + col;
+                        if ((at * (uint32_t)m.elem) % 4) ++errors;  // dword LDS stores
+                        for (uint32_t i = 0; i < V && col + i < U.ccount; ++i)
+                            lds_put(at + i, code_of(sid, (int64_t)P.swin + (int64_t)(int32_t)(a + i)));
+                    }
+                } else {
+                    for (uint32_t item = tid; item < nrag; item += threads) {
+                        const uint32_t r = fdiv(item, P.fd_rag_s), s = item - r * S;
+                        const uint32_t a = U.doff + r * C, x = (a & ~(V - 1)) + s * V;
+                        const uint32_t lo = x > a ? x : a, hi = x + V < a + U.ccount ? x + V : a + U.ccount;
+                        if (lo >= hi) continue;
+                        if (hi - lo == V && (P.dwin + x) % V) ++errors;
+                        for (uint32_t p = lo; p < hi; ++p) write((int64_t)P.dwin + p, lds_get(r * W + (p - a)));
+                    }
+                }
+            }
+    }
+
     // the two phases of a flat tile, lane by lane, with LDS as an array of codes
     void flat(const DevPiece &P, int sid, uint32_t t, uint32_t lds_bytes) {
         const uint32_t V = 16u / (uint32_t)m.elem, vlog = V == 8 ? 3 : 2, rvlog = P.lqlog - vlog;
@@ -247,6 +311,8 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
                 }
                 if (P.kind == PK_ROWS)
                     R.rows(P, sid, local);
+                else if (P.kind == PK_FLAT && P.rag_cb)
+                    R.rag(P, sid, local, plan->lds_bytes[li]);
                 else if (P.kind == PK_FLAT)
                     R.flat(P, sid, local, plan->lds_bytes[li]);
                 else

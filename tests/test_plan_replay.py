@@ -254,6 +254,10 @@ FLAT = [
     ((2, 35, 35, 48), 2, [("transpose", (0, 3, 1, 2))]),
     ((2, 40, 23, 23), 4, [("transpose", (0, 2, 3, 1))]),                         # rows of 529 x 4 bytes: 16 rows per block
     ((2, 26, 26, 96), 2, [("transpose", (0, 3, 1, 2))]),                         # rows of 676: 32 rows per block
+    ((2, 64, 75, 75), 4, [("transpose", (0, 2, 3, 1))]),                         # rows of 5625: too long for LDS (cut into two tile pieces)
+    ((2, 75, 75, 64), 4, [("transpose", (0, 3, 1, 2))]),                         # blocks of 64 rows x 128 columns
+    ((2, 72, 47, 47), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),   # 2209 positions into a padded image
+    ((2, 49, 49, 72), 2, [("slice", 1, 1, 48, 1), ("slice", 2, 1, 48, 1), ("transpose", (0, 3, 1, 2))]),
     ((3, 72, 5, 6), 2, [("slice", 3, 5, -1, -1), ("transpose", (0, 2, 3, 1))]),   # x backwards: rows are no longer one run -> other forms
     ((2, 8, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                            # 8 rows only: other forms
 ]
@@ -304,6 +308,38 @@ def test_tile_vectors_straddle_the_loops_of_a_source_run(case, monkeypatch):
     monkeypatch.setenv("AMAP_FLAT", "1")
     monkeypatch.setenv("AMAP_MAX_SPAN_LOG2", "11")
     assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
+
+
+def _forms(capfd, monkeypatch, shape, es, ops):
+    """The forms the planner picks, from its trace on stderr."""
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    capfd.readouterr()
+    m = B.amap_compose([shape], es, ops)
+    B.amap_describe(m)
+    err = capfd.readouterr().err
+    monkeypatch.delenv("AMAP_PLAN_TRACE")
+    return {line.split()[2] for line in err.splitlines() if line.startswith("amap plan:")}
+
+
+def test_planned_forms_of_the_special_cases(capfd, monkeypatch):
+    t = lambda *perm: [("transpose", perm)]
+    assert "flat-src" in _forms(capfd, monkeypatch, (4, 128, 7, 7), 2, t(0, 2, 3, 1))
+    assert "flat-dst" in _forms(capfd, monkeypatch, (4, 7, 7, 128), 2, t(0, 3, 1, 2))
+    assert "flat-src" in _forms(capfd, monkeypatch, (2, 48, 35, 35), 2, t(0, 2, 3, 1))
+    # long rows of one loop with the source as the contiguous side: whole-vector part + one-element tail
+    assert "tile" in _forms(capfd, monkeypatch, (2, 64, 75, 75), 4, t(0, 2, 3, 1))
+    assert "flat-blocked-src" in _forms(capfd, monkeypatch, (2, 72, 47, 47), 2, t(0, 2, 3, 1) + [("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)])
+    assert "flat-blocked-dst" in _forms(capfd, monkeypatch, (2, 75, 75, 64), 4, t(0, 3, 1, 2))
+    assert "flat-src" in _forms(capfd, monkeypatch, (4, 128, 7, 7), 2, t(0, 2, 3, 1) + [("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)])
+    assert "rows-keep-plane" in _forms(capfd, monkeypatch, (4, 6, 64), 2, [("slice", 2, 1, 64, 2)])
+    assert "rows-gather" in _forms(capfd, monkeypatch, (6, 48), 4, [("slice", 1, 1, 48, 3)])
+    assert "rows-interleave" in _forms(capfd, monkeypatch, (4, 3, 16, 24), 2, t(0, 2, 3, 1))
+    assert "rows-deinterleave" in _forms(capfd, monkeypatch, (4, 16, 24, 3), 2, t(0, 3, 1, 2))
+    assert "rows-expand" in _forms(capfd, monkeypatch, (4, 6, 16), 2, [("repeat", 2, 2)])
+    assert "rows-reverse" in _forms(capfd, monkeypatch, (4, 6, 16), 2, [("slice", 2, 15, -1, -1)])
+    assert "tile" in _forms(capfd, monkeypatch, (2, 64, 16, 16), 2, t(0, 2, 3, 1))
+    # 28 x 28 into a padded image: tile vectors of 16 bytes across image rows
+    assert _forms(capfd, monkeypatch, (2, 64, 28, 28), 2, t(0, 2, 3, 1) + [("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]) >= {"tile", "rows-fill"}
 
 
 FIXED_WIDTH_FORMS = [
