@@ -187,8 +187,43 @@ def _up3x(n=32):
                     lambda: [f32_to_bf16_bits(normal_f32(shp, 9))])
 
 
+def _s5_nhwc_pad(n=128):
+    """The chain of cfg1 at the last stage of the same network: [n,2048,7,7] channel-major to
+    channels-last with one pixel of zero padding.  49 positions per channel: no vectors along
+    the image on the source side."""
+    shp = (n, 2048, 7, 7)
+    ops = [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]
+    return Workload("s5_nhwc_pad" if n == 128 else f"s5_nhwc_pad_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 9))])
+
+
+def _s5_nchw_crop(n=128):
+    """The way back: the interior of a padded channels-last [n,9,9,2048] made channel-major."""
+    shp = (n, 9, 9, 2048)
+    ops = [("slice", 1, 1, 8, 1), ("slice", 2, 1, 8, 1), ("transpose", (0, 3, 1, 2))]
+    return Workload("s5_nchw_crop" if n == 128 else f"s5_nchw_crop_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 10))])
+
+
+def _i35_nchw(n=64):
+    """Channels-last [n,35,35,288] made channel-major: dst rows of 1225 elements, an odd number."""
+    shp = (n, 35, 35, 288)
+    ops = [("transpose", (0, 3, 1, 2))]
+    return Workload("i35_nchw" if n == 64 else f"i35_nchw_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 11))])
+
+
+def _i55_nchw(n=64):
+    """Channels-last [n,55,55,96] made channel-major: dst rows of 3025 elements, too long for LDS."""
+    shp = (n, 55, 55, 96)
+    ops = [("transpose", (0, 3, 1, 2))]
+    return Workload("i55_nchw" if n == 64 else f"i55_nchw_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 12))])
+
+
 NEXT_FACTORIES = {"up2x": _up2x, "up2x_nhwc": _up2x_nhwc, "bcast": _bcast, "flip_seq": _flip_seq,
-                  "rgb_nhwc": _rgb_nhwc, "up3x": _up3x}
+                  "rgb_nhwc": _rgb_nhwc, "up3x": _up3x,
+                  "s5_nhwc_pad": _s5_nhwc_pad, "s5_nchw_crop": _s5_nchw_crop, "i35_nchw": _i35_nchw, "i55_nchw": _i55_nchw}
 
 _FACTORIES = {
     "cfg0": _cfg0, "cfg1": _cfg1, "cfg2_fwd": _cfg2_fwd, "cfg2_rev": _cfg2_rev,

@@ -292,7 +292,8 @@ def test_gathered_rows(dev):
             _run_families(dev, B.amap_compose([shape], es, ops), [x], oracle.run_chain([x], ops))
     finally:
         del os.environ["AMAP_INTER"]
-    for name, kw in (("rgb_nhwc", {"n": 3}), ("up3x", {"n": 2})):
+    for name, kw in (("rgb_nhwc", {"n": 3}), ("up3x", {"n": 2}), ("s5_nhwc_pad", {"n": 3}), ("s5_nchw_crop", {"n": 3}),
+                     ("i35_nchw", {"n": 2}), ("i55_nchw", {"n": 2})):
         print(f"[gpu] gathered rows workload {name}", flush=True)
         w = synth.workload(name, **kw)
         srcs = w.sources()
