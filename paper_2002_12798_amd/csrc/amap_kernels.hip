@@ -565,8 +565,22 @@ __device__ __forceinline__ void rag_body(const DevPiece &P, char *dst, uint32_t 
 #pragma unroll
             for (int b = 0; b < kBatch; ++b) {
                 const uint32_t vi = v0 + b * threads, rv = vi & ((1u << RVLOG) - 1), c = vi >> RVLOG;
-                if (vi < nstr && rv * V < U.rcount)
-                    gld<16, (NT & PF_NT_LOAD) != 0>(v[b], src + (size_t)(U.soff + flat_c_offset(P, U.c0 + c) + rv * V) * ES);
+                if (vi < nstr && rv * V < U.rcount) {
+                    const uint32_t a = U.soff + flat_c_offset(P, U.c0 + c) + rv * V;
+                    if (rv * V + V <= U.rcount) {
+                        gld<16, (NT & PF_NT_LOAD) != 0>(v[b], src + (size_t)a * ES);
+                    } else {  // the last rows of a row count that is no whole number of vectors
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) v[b][k] = 0;
+                        for (uint32_t k = 0; rv * V + k < U.rcount; ++k) {
+                            const uint32_t e = reinterpret_cast<const elem_t *>(src)[a + k];
+                            if constexpr (ES == 2)
+                                v[b][k / 2] |= e << (16 * (k & 1));
+                            else
+                                v[b][k] = e;
+                        }
+                    }
+                }
             }
 #pragma unroll
             for (int b = 0; b < kBatch; ++b) {
@@ -574,6 +588,7 @@ __device__ __forceinline__ void rag_body(const DevPiece &P, char *dst, uint32_t 
                 if (vi < nstr && rv * V < U.rcount) {
 #pragma unroll
                     for (uint32_t k = 0; k < V; ++k) {
+                        if (rv * V + k >= U.rcount) break;
                         if constexpr (ES == 2)
                             lds[(rv * V + k) * W + c] = (uint16_t)(v[b][k / 2] >> (16 * (k & 1)));
                         else

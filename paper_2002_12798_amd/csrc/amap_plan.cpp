@@ -329,7 +329,6 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
     if (iP < 0 || iQ < 0 || iP == iQ) return none;
     const int64_t V = 16 / es;
     const KDim &P = kp.dims[iP], &Q = kp.dims[iQ];
-    if (kp.dbase % V) return none;
     // only where the tile forms would move vectors of less than 16 bytes (with 8-byte vectors: 14.4 -> 10.4 us for
     // 196 positions under 1024 channels, 33.0 -> 21.2 us for rows of 100)
     int64_t EQc = Q.extent;
@@ -354,7 +353,26 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
         if (flat_stride(iR) != C) continue;
         const int64_t ER = kp.dims[iR].extent;
         // rows of 2 .. 7 elements belong to the interleaving row forms (a block of 64 such rows is too little work)
-        if (C < env_int("AMAP_FLAT_MIN_C", 8) || ER % V || ER < (int64_t)env_int("AMAP_FLAT_MIN_ROWS", (int)kFlatMinRows)) continue;
+        if (C < env_int("AMAP_FLAT_MIN_C", 8) || ER < (int64_t)env_int("AMAP_FLAT_MIN_ROWS", (int)kFlatMinRows)) continue;
+        if (n - 1 > kMaxLoops) continue;  // batch loops + chain
+        // whole 16-byte vectors on the dst side and along the rows?  If not, only the blocked form with dst as
+        // the contiguous side remains: its stores take any alignment and its loads along the rows end element by element
+        // (a transposition of 4097 x 4099 elements: 74.8 us element by element)
+        bool aligned = kp.dbase % V == 0 && ER % V == 0;
+        for (int k = 0; k < n; ++k) {
+            const bool in_chain = std::find(chain.begin(), chain.end(), k) != chain.end();
+            if (k == iP || k == iR) continue;            // dst stride 1; in dir 2 the block loop walks dst in steps of C
+            if (dir == 2 && in_chain) continue;          // inside the flat dst run
+            if (kp.dims[k].ds % V) aligned = false;      // batch loops on both sides, the chain's dst strides in dir 1
+        }
+        if (!aligned) {
+            if (dir == 1) continue;
+            // where dst still offers vectors along P, the tile forms (cut into whole-vector part + tail) keep the piece
+            std::vector<int64_t> ds_all;
+            for (int k = 0; k < n; ++k)
+                if (k != iP) ds_all.push_back(kp.dims[k].ds);
+            if (common_pow2((uint32_t)V, {kp.dbase}, ds_all) >= 2) continue;
+        }
         // as many rows per block as fit LDS: 64, 32 or 16 (rows of 1225 = 35 x 35 positions: 16 at a time)
         const int64_t lds_limit = (int64_t)std::min(64, env_int("AMAP_FLAT_LDS_KB", (int)(kFlatLdsBytes >> 10))) * 1024;
         uint32_t rlog = 6;
@@ -369,7 +387,7 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
         // 17.4 us), so there the blocked form is left to rows of several loops (padded or cropped images).
         const int64_t cb_env = env_int("AMAP_FLAT_RAG_CB", 128);
         const bool rag_ok = env_int("AMAP_FLAT_RAG", 1) && cb_env >= V && cb_env % V == 0 && cb_env * es <= 1024 && tile_bytes < 8 && ER >= 64;
-        const bool fits = C * std::min<int64_t>(ER, 1ll << rlog) * es <= lds_limit;
+        const bool fits = aligned && C * std::min<int64_t>(ER, 1ll << rlog) * es <= lds_limit;
         if (!fits) {
             // rows too long for LDS: blocks of 64 rows x cb columns whose row segments start at any element
             if (!rag_ok || !(dir == 2 || chain.size() > 1 || env_int("AMAP_FLAT_RAG", 1) >= 2)) continue;
@@ -934,6 +952,7 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
         lds_max = 0;
     };
     const bool trace = env_int("AMAP_PLAN_TRACE", 0) != 0;  // one line per planned piece on stderr
+    if (trace) std::fprintf(stderr, "amap plan: begin (%zu pieces, family %d)\n", m.kpieces.size(), family);
     auto emit = [&](const std::vector<DevPiece> &dps, uint32_t lds, int vb, int fam, int64_t vol) {
         if (trace)
             for (const DevPiece &d : dps) {

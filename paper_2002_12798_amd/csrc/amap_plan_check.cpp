@@ -102,7 +102,7 @@ struct Replay {
     // the column-blocked form of a flat tile
     void rag(const DevPiece &P, int sid, uint32_t t, uint32_t lds_bytes) {
         const uint32_t V = 16u / (uint32_t)m.elem, vlog = V == 8 ? 3 : 2, rvlog = P.lqlog - vlog;
-        if (P.lqlog != 6 || P.vlog != vlog || (P.flat != 1 && P.flat != 2) || P.EQ % V || t >= P.n_blocks || P.nq < 1 || P.nq > 4 ||
+        if (P.lqlog != 6 || P.vlog != vlog || (P.flat != 1 && P.flat != 2) || (P.flat == 1 && P.EQ % V) || t >= P.n_blocks || P.nq < 1 || P.nq > 4 ||
             P.nloops + P.nq > (uint32_t)kMaxLoops || P.rag_cb % V || P.rag_s != P.rag_cb / V + 1 || P.rag_w < P.rag_cb || (P.rag_w * m.elem) % 4 ||
             (uint64_t)P.rag_w * 64 * m.elem > lds_bytes || (uint64_t)P.tilesQ * P.rag_cb < P.eP) {
             ++errors;
@@ -132,7 +132,7 @@ struct Replay {
                     for (uint32_t vi = tid; vi < nstr; vi += threads) {
                         const uint32_t rv = vi & ((1u << rvlog) - 1), c = vi >> rvlog;
                         if (rv * V >= U.rcount) continue;
-                        for (uint32_t k = 0; k < V; ++k) {
+                        for (uint32_t k = 0; k < V && rv * V + k < U.rcount; ++k) {
                             const uint32_t e = (rv * V + k) * W + c, off = flat_c_offset(P, U.c0 + c) + rv * V + k;
                             if (P.flat == 1 && k == 0 && (P.dwin + (uint32_t)(U.doff + off)) % V) ++errors;
                             if (P.flat == 1)

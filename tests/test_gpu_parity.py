@@ -328,7 +328,7 @@ def test_flat_tiles(dev):
     (7 x 7 positions per channel): blocks of 64 rows staged through LDS as one flat run, in both
     directions, with a ragged last block, rows at a pitch and workgroups of 1 and 4 wavefronts."""
     import os
-    from tests.test_plan_replay import FLAT, STRADDLE
+    from tests.test_plan_replay import FLAT, FLAT_OTHER, STRADDLE
     big = [
         ((8, 2048, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),
         ((8, 7, 7, 2048), 2, [("transpose", (0, 3, 1, 2))]),
@@ -338,7 +338,7 @@ def test_flat_tiles(dev):
         ((3, 121, 1000), 2, [("slice", 2, 1, 993, 1), ("transpose", (0, 2, 1))]),
     ]
     big.append(((4, 256, 28, 28), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]))  # tile vectors across image rows
-    for i, (shape, es, ops) in enumerate(FLAT + big + STRADDLE):
+    for i, (shape, es, ops) in enumerate(FLAT + FLAT_OTHER + big + STRADDLE):
         x = synth.random_bits(shape, es, 110 + i)
         want = oracle.run_chain([x], ops)
         for waves in (None, "2"):

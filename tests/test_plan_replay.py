@@ -258,17 +258,28 @@ FLAT = [
     ((2, 75, 75, 64), 4, [("transpose", (0, 3, 1, 2))]),                         # blocks of 64 rows x 128 columns
     ((2, 72, 47, 47), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),   # 2209 positions into a padded image
     ((2, 49, 49, 72), 2, [("slice", 1, 1, 48, 1), ("slice", 2, 1, 48, 1), ("transpose", (0, 3, 1, 2))]),
+    ((3, 7, 7, 64), 2, [("transpose", (0, 3, 1, 2)), ("pad", (0, 1, 0, 0), (0, 0, 0, 0), 0)]),     # dst run starts at element 49 of every image
+    ((67, 131), 2, [("transpose", (1, 0))]),                                     # both extents odd
+    ((2, 70, 9, 9), 4, [("transpose", (0, 2, 3, 1))]),                           # 70 rows of fp32: no whole vectors along the rows
+    ((2, 9, 9, 70), 4, [("transpose", (0, 3, 1, 2))]),
+]
+
+
+# neighbours of the flat forms that must take other forms
+FLAT_OTHER = [
+    ((3, 64, 7, 7), 2, [("transpose", (0, 2, 3, 1)), ("pad", (0, 0, 0, 1), (0, 0, 0, 0), 0)]),     # dst rows start at element 1: no flat form
     ((3, 72, 5, 6), 2, [("slice", 3, 5, -1, -1), ("transpose", (0, 2, 3, 1))]),   # x backwards: rows are no longer one run -> other forms
     ((2, 8, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                            # 8 rows only: other forms
 ]
 
 
-@pytest.mark.parametrize("case", range(len(FLAT)))
+@pytest.mark.parametrize("case", range(len(FLAT) + len(FLAT_OTHER)))
 def test_flat_tiles_plan(case, monkeypatch):
-    shape, es, ops = FLAT[case]
+    shape, es, ops = (FLAT + FLAT_OTHER)[case]
     m = B.amap_compose([shape], es, ops)
     info = B.amap_describe(m)
-    if case < len(FLAT) - 2:
+    # (fp32 rows that are no whole vectors on the dst side take other forms; the 49-element fill runs of the third start at odd elements)
+    if case < len(FLAT) and (shape, es) not in (((2, 70, 9, 9), 4), ((3, 7, 7, 64), 2)):
         # (the family reported is that of the largest piece: the border fill where the image is padded)
         assert info.vec_bytes == 16 and (B.KERNEL_NAMES[info.kernel_id] == "tile" or "pad" in [o[0] for o in ops])
     assert _replay_all(m) >= 2
@@ -318,7 +329,9 @@ def _forms(capfd, monkeypatch, shape, es, ops):
     B.amap_describe(m)
     err = capfd.readouterr().err
     monkeypatch.delenv("AMAP_PLAN_TRACE")
-    return {line.split()[2] for line in err.splitlines() if line.startswith("amap plan:")}
+    lines = [line for line in err.splitlines() if line.startswith("amap plan:")]
+    last = max(i for i, line in enumerate(lines) if line.split()[2] == "begin")   # the plan of the whole chain
+    return {line.split()[2] for line in lines[last + 1:]}
 
 
 def test_planned_forms_of_the_special_cases(capfd, monkeypatch):
@@ -331,6 +344,10 @@ def test_planned_forms_of_the_special_cases(capfd, monkeypatch):
     assert "flat-blocked-src" in _forms(capfd, monkeypatch, (2, 72, 47, 47), 2, t(0, 2, 3, 1) + [("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)])
     assert "flat-blocked-dst" in _forms(capfd, monkeypatch, (2, 75, 75, 64), 4, t(0, 3, 1, 2))
     assert "flat-src" in _forms(capfd, monkeypatch, (4, 128, 7, 7), 2, t(0, 2, 3, 1) + [("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)])
+    # dst not aligned to vectors, or a row count that is no whole number of vectors: blocked form towards the contiguous dst
+    assert "flat-blocked-dst" in _forms(capfd, monkeypatch, (3, 7, 7, 64), 2, t(0, 3, 1, 2) + [("pad", (0, 1, 0, 0), (0, 0, 0, 0), 0)])
+    assert "flat-blocked-dst" in _forms(capfd, monkeypatch, (67, 131), 2, t(1, 0))
+    assert not any(f.startswith("flat") for f in _forms(capfd, monkeypatch, (3, 64, 7, 7), 2, t(0, 2, 3, 1) + [("pad", (0, 0, 0, 1), (0, 0, 0, 0), 0)]))
     assert "rows-keep-plane" in _forms(capfd, monkeypatch, (4, 6, 64), 2, [("slice", 2, 1, 64, 2)])
     assert "rows-gather" in _forms(capfd, monkeypatch, (6, 48), 4, [("slice", 1, 1, 48, 3)])
     assert "rows-interleave" in _forms(capfd, monkeypatch, (4, 3, 16, 24), 2, t(0, 2, 3, 1))
@@ -358,7 +375,7 @@ def test_vector_cap_never_reaches_the_16_byte_row_forms(cap, monkeypatch):
     out-of-bounds or doubly written elements (as it did: 772 errors for a repeat by 2 under an
     8-byte cap before the planner checked the cap)."""
     monkeypatch.setenv("AMAP_VEC_BYTES", cap)
-    for shape, es, ops in FIXED_WIDTH_FORMS + GATHERED + INTERLEAVED + KEEP_PLANE + FLAT:
+    for shape, es, ops in FIXED_WIDTH_FORMS + GATHERED + INTERLEAVED + KEEP_PLANE + FLAT + FLAT_OTHER:
         m = B.amap_compose([shape], es, ops)
         assert B.amap_describe(m).vec_bytes <= max(int(cap), es), (shape, ops)
         assert _replay_all(m) >= 1
