@@ -592,7 +592,8 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         dp.sbase = (uint32_t)kp.sbase;
         const bool forced_tile = family == AMAP_K_TILE && (!tile_ok || narrow < 8);
         const bool planned_flat = family < 0 && narrow < env_int("AMAP_FLAT_BELOW", 16);
-        if ((planned_flat || forced_tile) && env_int("AMAP_FLAT", 1) && plan_flat(kp, es, nwlog, dp, lds)) {
+        // (slot_dim: the caller plans a group of pieces as one tile piece and needs the tile geometry proper)
+        if ((planned_flat || forced_tile) && !slot_dim && env_int("AMAP_FLAT", 1) && plan_flat(kp, es, nwlog, dp, lds)) {
             vec_bytes = 16;
             return AMAP_K_TILE;
         }

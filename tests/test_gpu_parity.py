@@ -353,6 +353,20 @@ def test_flat_tiles(dev):
                 os.environ.pop("AMAP_WAVES_LOG", None)
 
 
+def test_concat_of_odd_sized_images(dev):
+    """Channel concat of channel-major branches made channels-last (and the other way round) at image
+    sizes whose rows offer no vectors: every branch is a flat tile piece of its own."""
+    from tests.test_plan_replay import CONCAT_ODD_IMAGES
+    big = [([(4, c, 17, 17) for c in (192, 192, 192, 192)], 2, [("concat", 1), ("transpose", (0, 2, 3, 1))]),
+           ([(3, c, 35, 35) for c in (64, 64, 96, 32)], 2, [("concat", 1), ("transpose", (0, 2, 3, 1))])]
+    for i, (shapes, es, ops) in enumerate(CONCAT_ODD_IMAGES + big):
+        print(f"[gpu] concat of odd-sized images case {i}", flush=True)
+        xs = [synth.random_bits(sh, es, 200 + 10 * i + k) for k, sh in enumerate(shapes)]
+        m = B.amap_compose(shapes, es, ops)
+        assert B.amap_plan_selfcheck(m) == 0
+        _run_families(dev, m, xs, oracle.run_chain(xs, ops))
+
+
 def test_one_map_executed_from_several_host_threads(dev):
     """A map is immutable once built (its launch plan included), so host threads may execute the
     same map at the same time, each on a stream of its own."""

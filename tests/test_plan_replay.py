@@ -321,6 +321,26 @@ def test_tile_vectors_straddle_the_loops_of_a_source_run(case, monkeypatch):
     assert _replay_all(B.amap_compose([shape], es, ops)) >= 1
 
 
+CONCAT_ODD_IMAGES = [
+    ([(3, c, 17, 17) for c in (64, 96, 64, 32)], 2, [("concat", 1), ("transpose", (0, 2, 3, 1))]),
+    ([(3, c, 7, 7) for c in (64, 80, 128)], 2, [("concat", 1), ("transpose", (0, 2, 3, 1)), ("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]),
+    ([(2, c, 5, 5) for c in (32, 64)], 4, [("concat", 1), ("transpose", (0, 2, 3, 1))]),
+    ([(2, 9, 9, c) for c in (64, 72)], 2, [("concat", 3), ("transpose", (0, 3, 1, 2))]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(CONCAT_ODD_IMAGES)))
+def test_concat_of_images_with_rows_of_no_whole_vectors(case, monkeypatch):
+    """Pieces that are neighbours along the dst-contiguous dimension are first tried as one group of
+    tile pieces; where the image rows offer no vectors the group is not possible and every piece is
+    planned on its own (as a flat tile).  (Planning the group's head as a flat tile crashed the host.)"""
+    shapes, es, ops = CONCAT_ODD_IMAGES[case]
+    m = B.amap_compose(shapes, es, ops)
+    assert _replay_all(m) >= 2
+    monkeypatch.setenv("AMAP_WAVES_LOG", "2")
+    assert _replay_all(B.amap_compose(shapes, es, ops)) >= 2
+
+
 def _forms(capfd, monkeypatch, shape, es, ops):
     """The forms the planner picks, from its trace on stderr."""
     monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
