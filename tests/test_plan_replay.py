@@ -358,7 +358,10 @@ def test_planned_forms_of_the_special_cases(capfd, monkeypatch):
     t = lambda *perm: [("transpose", perm)]
     assert "flat-src" in _forms(capfd, monkeypatch, (4, 128, 7, 7), 2, t(0, 2, 3, 1))
     assert "flat-dst" in _forms(capfd, monkeypatch, (4, 7, 7, 128), 2, t(0, 3, 1, 2))
-    assert "flat-src" in _forms(capfd, monkeypatch, (2, 48, 35, 35), 2, t(0, 2, 3, 1))
+    # rows of 1225: few channels keep the cut into whole-vector part + tail, many take the blocked form; the way back 16-row blocks
+    assert "tile" in _forms(capfd, monkeypatch, (2, 48, 35, 35), 2, t(0, 2, 3, 1))
+    assert "flat-blocked-src" in _forms(capfd, monkeypatch, (2, 136, 35, 35), 2, t(0, 2, 3, 1))
+    assert "flat-dst" in _forms(capfd, monkeypatch, (2, 35, 35, 48), 2, t(0, 3, 1, 2))
     # long rows of one loop with the source as the contiguous side: whole-vector part + one-element tail
     assert "tile" in _forms(capfd, monkeypatch, (2, 64, 75, 75), 4, t(0, 2, 3, 1))
     assert "flat-blocked-src" in _forms(capfd, monkeypatch, (2, 72, 47, 47), 2, t(0, 2, 3, 1) + [("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)])
