@@ -213,6 +213,17 @@ def test_execute_multi_split_outputs(dev):
     torch.cuda.synchronize()
     for ops, o in zip(chains_, outs):
         assert np.array_equal(dev.to_host(o), oracle.run_chain([x], ops)), ops
+    # a channels-last tensor of 17 x 17 images split into four channel-major branches (flat tiles, in one launch
+    # with a plain row copy and a blocked flat tile of another source shape)
+    shape = (3, 17, 17, 256)
+    x = synth.random_bits(shape, 2, 124)
+    chains_ = [[("slice", 3, 64 * b, 64 * b + 64, 1), ("transpose", (0, 3, 1, 2))] for b in range(4)]
+    chains_ += [[("slice", 3, 0, 8, 1)], [("reshape", (3, 289, 256)), ("transpose", (0, 2, 1)), ("slice", 2, 1, 288, 1)]]
+    maps = [B.amap_compose([shape], 2, ops) for ops in chains_]
+    outs = dev.execute_multi(maps, [dev.to_device(x)])
+    torch.cuda.synchronize()
+    for ops, o in zip(chains_, outs):
+        assert np.array_equal(dev.to_host(o), oracle.run_chain([x], ops)), ops
     # overlapping outputs are refused
     d, d_x = dev.empty_dst(maps[0]), dev.to_device(x)
     with pytest.raises(B.AmapError) as e:
