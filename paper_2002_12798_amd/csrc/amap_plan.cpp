@@ -381,11 +381,11 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
         const uint32_t rlog_min = (uint32_t)std::max(4, std::min(6, env_int("AMAP_FLAT_MIN_RLOG", tile_bytes >= 8 ? 5 : 4)));
         while (rlog > rlog_min && C * std::min<int64_t>(ER, 1ll << rlog) * es > lds_limit) --rlog;
         int64_t cb = 0;
-        // 128 columns per block (55 x 55 positions under 96 channels, towards channel-major: 24.4 us; 256 columns: 26.6 us;
+        // 128 2-byte columns per block (55 x 55 positions under 96 channels, towards channel-major: 24.4 us; 256 columns: 26.6 us;
         // gathered rows: 178.8 us).  With the source as the contiguous side and a row of one loop, the cut into a
         // whole-vector part and a one-element tail is as fast or faster (23.7 against 23.8 us; 75 x 75 fp32: 11.9 against
         // 17.4 us), so there the blocked form is left to rows of several loops (padded or cropped images).
-        const int64_t cb_env = env_int("AMAP_FLAT_RAG_CB", 128);
+        const int64_t cb_env = env_int("AMAP_FLAT_RAG_CB", 256 / es);  // 256-byte row segments (fp32: 64 columns 15.5 us, 128 columns 17.2 us)
         const bool rag_ok = env_int("AMAP_FLAT_RAG", 1) && cb_env >= V && cb_env % V == 0 && cb_env * es <= 1024 && tile_bytes < 8 && ER >= 64;
         // long rows of one loop under few channels, the source contiguous: the cut into a whole-vector part and a
         // one-element tail is faster there (concat of 64 + 64 + 96 + 32 channels of 35 x 35 positions: 26.8 against 34.6 us)
