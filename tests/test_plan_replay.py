@@ -248,6 +248,8 @@ FLAT = [
     ((2, 56, 7, 7), 2, [("transpose", (0, 2, 3, 1))]),                           # fewer than 64 rows: one block of 56
     ((5, 7, 7, 48), 2, [("transpose", (0, 3, 1, 2))]),
     ((5, 16, 5, 5), 4, [("transpose", (0, 2, 3, 1))]),
+    ((2, 72, 511), 2, [("transpose", (0, 2, 1))]),                               # rows of 511: 65,408 bytes of LDS, the most a tile takes
+    ((2, 255, 136), 4, [("transpose", (0, 2, 1))]),                              # fp32, dst contiguous: 65,280 bytes
     ((2, 72, 17, 17), 2, [("transpose", (0, 2, 3, 1))]),                         # rows of 289: 37 KiB of LDS
     ((2, 17, 17, 72), 2, [("transpose", (0, 3, 1, 2))]),
     ((2, 48, 35, 35), 2, [("transpose", (0, 2, 3, 1))]),                         # rows of 1225: 16 rows per block
