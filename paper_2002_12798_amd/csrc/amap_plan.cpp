@@ -586,7 +586,8 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         if ((fam == AMAP_K_TILE || fam == AMAP_K_WAVE) && tile_ok) narrow = (int64_t)Vt * es;
         const bool planned_narrow = family < 0 && narrow < 8;
         const bool forced_rows = family == AMAP_K_ROWS && (!rows_ok || narrow < 8);
-        if ((planned_narrow || forced_rows) && env_int("AMAP_INTER", 1) && plan_inter(kp, es, nwlog, kp.src >= 0 && (size_t)kp.src < m.src_shapes.size() ? volume_of(m.src_shapes[(size_t)kp.src]) : 0, dp)) {
+        const int64_t svol = kp.src >= 0 && (size_t)kp.src < m.src_shapes.size() ? volume_of(m.src_shapes[(size_t)kp.src]) : 0;
+        if ((planned_narrow || forced_rows) && env_int("AMAP_INTER", 1) && plan_inter(kp, es, nwlog, svol, dp)) {
             vec_bytes = 16;
             return AMAP_K_ROWS;
         }
@@ -961,7 +962,8 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
         if (trace)
             for (const DevPiece &d : dps) {
                 const char *form = d.kind == PK_TILE ? "tile" : d.kind == PK_WAVE ? "wave" : "rows";
-                if (d.kind == PK_FLAT) form = d.rag_cb ? (d.flat == 1 ? "flat-blocked-src" : "flat-blocked-dst") : (d.flat == 1 ? "flat-src" : "flat-dst");
+                if (d.kind == PK_FLAT && d.rag_cb) form = d.flat == 1 ? "flat-blocked-src" : "flat-blocked-dst";
+                if (d.kind == PK_FLAT && !d.rag_cb) form = d.flat == 1 ? "flat-src" : "flat-dst";
                 if (d.kind == PK_ROWS) {
                     if (!d.src) form = "rows-fill";
                     if (d.rep_log) form = "rows-expand";
@@ -1045,7 +1047,9 @@ static std::vector<KPiece> split_ragged(const KPiece &kp, int es) {
         if (kp.dims[k].ss == 1) iQ = k;
     }
     if (iP < 0 || iQ < 0 || iP == iQ) return out;
-    if (env_int("AMAP_FLAT", 1) && env_int("AMAP_GATHER", 1) && env_int("AMAP_VEC_BYTES", 16) >= 16 && flat_shape(kp, es).dir) return out;  // a flat tile takes it whole
+    // a flat tile takes the piece whole (under the same switches as in plan_piece)
+    const bool flat_on = env_int("AMAP_FLAT", 1) && env_int("AMAP_GATHER", 1) && env_int("AMAP_VEC_BYTES", 16) >= 16;
+    if (flat_on && flat_shape(kp, es).dir) return out;
     std::vector<int64_t> ds_others;
     for (int k = 0; k < (int)kp.dims.size(); ++k)
         if (k != iP) ds_others.push_back(kp.dims[k].ds);
