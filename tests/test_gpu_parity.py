@@ -364,6 +364,34 @@ def test_flat_tiles(dev):
                 os.environ.pop("AMAP_WAVES_LOG", None)
 
 
+def test_random_transposing_maps(dev):
+    """Random transpositions with pads and crops around them (the generator of the replay tests):
+    the planned form and the forced tile family against the oracle, after the host replay of the
+    plan has found every access in bounds."""
+    import torch
+    from tests.test_plan_replay import _random_transposing_map
+    rng = np.random.default_rng(77)
+    ran = 0
+    for it in range(120):
+        shape, es, ops = _random_transposing_map(rng)
+        x = synth.random_bits(shape, es, 500 + it)
+        want = oracle.run_chain([x], ops)
+        m = B.amap_compose([shape], es, ops)
+        d_x = [dev.to_device(x)]
+        for fam in (None, B.AMAP_K_TILE):
+            try:
+                assert B.amap_plan_selfcheck(m, -1 if fam is None else fam) == 0, (shape, es, ops, fam)
+            except B.AmapError:
+                continue
+            print(f"[gpu] random transposing map {it} family {fam}: {shape} {es} {ops}", flush=True)
+            dst = dev.empty_dst(m, fill=0x5A5A if es == 2 else 0x5A5A5A5A)
+            dev.execute(m, d_x, dst, kernel_id=fam)
+            torch.cuda.synchronize()
+            assert np.array_equal(dev.to_host(dst).view(want.dtype).reshape(want.shape), want), (shape, es, ops, fam)
+            ran += 1
+    assert ran >= 150
+
+
 def test_concat_of_odd_sized_images(dev):
     """Channel concat of channel-major branches made channels-last (and the other way round) at image
     sizes whose rows offer no vectors: every branch is a flat tile piece of its own."""

@@ -384,6 +384,49 @@ def test_planned_forms_of_the_special_cases(capfd, monkeypatch):
     assert _forms(capfd, monkeypatch, (2, 64, 28, 28), 2, t(0, 2, 3, 1) + [("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0)]) >= {"tile", "rows-fill"}
 
 
+def _random_transposing_map(rng):
+    """A transposition of the two innermost axes with row lengths, row counts, batch loops, slices,
+    pads and crops drawn so that the flat tile forms, their neighbours and their fallbacks all occur."""
+    es = int(rng.choice([2, 4]))
+    v = 16 // es
+    c = int(rng.choice([9, 10, 11, 13, 18, 25, 27, 49, 50, 81, 121, 289, 625, 1225, 2209])) if rng.random() < 0.8 else int(rng.integers(8, 600))
+    er = v * int(rng.integers(16 // v, 40)) if rng.random() < 0.7 else int(rng.integers(16, 300))
+    nb = int(rng.integers(1, 4)) if c < 1000 else 1
+    if c > 1000:
+        er = min(er, 160)
+    ops = []
+    mode = rng.random()
+    if mode < 0.25:      # channel-major images into a padded channels-last tensor
+        h, w = int(rng.integers(2, 8)), int(rng.integers(2, 10))
+        shape = (nb, er, h, w)
+        ops = [("transpose", (0, 2, 3, 1)),
+               ("pad", (0, int(rng.integers(0, 3)), int(rng.integers(0, 3)), 0), (0, int(rng.integers(0, 3)), int(rng.integers(1, 3)), 0), 0)]
+    elif mode < 0.5:     # the crop of a padded channels-last tensor made channel-major
+        h, w, a, b = int(rng.integers(2, 8)), int(rng.integers(2, 10)), int(rng.integers(0, 3)), int(rng.integers(1, 3))
+        shape = (nb, h + a + 1, w + b + 1, er)
+        ops = [("slice", 1, a, a + h, 1), ("slice", 2, b, b + w, 1), ("transpose", (0, 3, 1, 2))]
+    else:
+        extra = int(rng.integers(0, 3 * v))
+        shape = (nb, er + extra, c) if mode < 0.75 else (nb, c, er + extra)
+        ax = 1 if mode < 0.75 else 2
+        if extra:
+            st = int(rng.integers(0, extra + 1))
+            ops.append(("slice", ax, st, st + er, 1))
+        ops.append(("transpose", (0, 2, 1)))
+    return shape, es, ops
+
+
+def test_random_transposing_maps_replay(monkeypatch):
+    rng = np.random.default_rng(2024)
+    for it in range(160):
+        shape, es, ops = _random_transposing_map(rng)
+        monkeypatch.delenv("AMAP_WAVES_LOG", raising=False)
+        if it % 3 == 0:
+            monkeypatch.setenv("AMAP_WAVES_LOG", str(it % 2 * 2))
+        m = B.amap_compose([shape], es, ops)
+        assert _replay_all(m) >= 1, (shape, es, ops)
+
+
 FIXED_WIDTH_FORMS = [
     ((4, 6, 16), 2, [("repeat", 2, 2)]),                      # expanded in registers
     ((4, 6, 16), 4, [("repeat", 2, 4)]),
