@@ -133,7 +133,8 @@ typedef enum {
     AMAP_K_PROGRAM = 0, /* element-wise interpreter of the operator program (any map)      */
     AMAP_K_ELEMENT = 1, /* element-wise over the strided pieces                             */
     AMAP_K_ROWS = 2,    /* both sides share their contiguous dimension: vector row copy     */
-    AMAP_K_TILE = 3,    /* contiguous dimension permuted: LDS-staged tile transpose         */
+    AMAP_K_TILE = 3,    /* contiguous dimension permuted: LDS-staged tile transpose (also the
+                           flat tiles: blocks of rows that are contiguous on one side)      */
     AMAP_K_WAVE = 4     /* small permute: in-register / cross-lane transpose, no LDS        */
 } amap_kernel_id;
 
@@ -154,6 +155,8 @@ typedef struct {
 } amap_info;
 
 amap_status amap_describe(const amap_t *m, amap_info *out);
+/* With AMAP_PLAN_TRACE=1 in the environment the planner also prints, on stderr, one line per
+ * planned piece (its form, vector bytes, workgroups, LDS bytes) whenever it plans a map. */
 
 /* Shape of source src_id as recorded in the map (rank returned in *rank). */
 amap_status amap_source_shape(const amap_t *m, int src_id, int *rank, int64_t *shape);
