@@ -250,6 +250,9 @@ FLAT = [
     ((5, 16, 5, 5), 4, [("transpose", (0, 2, 3, 1))]),
     ((2, 72, 511), 2, [("transpose", (0, 2, 1))]),                               # rows of 511: 65,408 bytes of LDS, the most a tile takes
     ((2, 255, 136), 4, [("transpose", (0, 2, 1))]),                              # fp32, dst contiguous: 65,280 bytes
+    ((3, 9, 9, 64), 2, [("slice", 1, 7, 0, -1), ("slice", 2, 1, 8, 1), ("slice", 0, 2, -1, -1), ("transpose", (0, 3, 1, 2))]),  # image rows and the batch backwards
+    ((3, 64, 7, 7), 2, [("slice", 0, 2, -1, -1), ("slice", 1, 63, -1, -1), ("transpose", (0, 2, 3, 1))]),                     # batch and channels backwards
+    ((1, 64, 25), 4, [("transpose", (0, 2, 1)), ("repeat", 0, 3)]),              # one image written three times
     ((2, 72, 17, 17), 2, [("transpose", (0, 2, 3, 1))]),                         # rows of 289: 37 KiB of LDS
     ((2, 17, 17, 72), 2, [("transpose", (0, 3, 1, 2))]),
     ((2, 48, 35, 35), 2, [("transpose", (0, 2, 3, 1))]),                         # rows of 1225: 16 rows per block
