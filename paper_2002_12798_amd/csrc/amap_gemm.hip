@@ -4,6 +4,7 @@
 // used to read the materialised chain output t_s reads the chain's source t_l
 // through g' instead, in its operand-load prologue, and t_s never exists.
 //
+// Two kernels.  amap_gemm_tile256_kernel (further down) takes the aligned common case; the general one:
 // Kernel shape (gfx950): 256 x 128 output tile per workgroup of 4 wavefronts,
 // each wavefront 128 x 64 = 4 x 2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (fp32
 // accumulate in 128 AGPRs), K stepped by 64 through one LDS stage with the
@@ -16,6 +17,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 
@@ -58,6 +60,7 @@ struct GemmArgs {
     uint32_t M, N, K;
     uint32_t sbase;
     uint32_t tiles_m, tiles_n;
+    uint32_t a_row_ss;  // tile256 kernel: source elements between consecutive m inside a 256-row tile
     Digits dm, dk;
     // store side (Section 2, eq. "store"): element (m, n) of the product goes to
     // out[obase + om(m) + on(n)]; store_mapped = 0 means the plain row-major C
@@ -368,6 +371,222 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The aligned case (M % 256 = N % 256 = 0, K % 64 = 0, K >= 128, row-major W, one source with its
+// runs along k, a tile's 256 rows inside one digit of m and a k-step inside one digit of k).
+// Same consumer load of eq. 4, different machine mapping:
+//   * 256 x 256 output tile per workgroup of 4 wavefronts (128 x 128 each: 16 MFMA tiles, 256
+//     accumulator registers), one workgroup per compute unit, persistent over its tiles;
+//   * both operands go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
+//     no staging registers, no LDS-write instructions); the lane -> address permutation applies the
+//     bank swizzle on the global side because such a load always fills 1 KiB of LDS in lane order;
+//   * W stays [k][n] in LDS and is read with the transposing LDS read (ds_read_b64_tr_b16), which
+//     hands every lane four consecutive k of one n: the MFMA operand layout without a register transpose;
+//   * two LDS stages of 64 k; the batch for step s + 2 is issued right after the barrier that frees
+//     its stage, laid between the MFMAs of the last quarter of step s, and the first loads of the
+//     workgroup's next tile are in flight while the current tile is written out;
+//   * every memory instruction sits at a fixed place between two MFMAs (scheduling barriers pin the
+//     order): one LDS read, or one LDS read and one load, per MFMA.
+constexpr int T2M = 256, T2N = 256, T2K = 64;
+constexpr int kT2Stage = 65536;            // A [256 rows][64 k] + W [64 k][256 n]
+constexpr int kT2WOff = 32768;             // W part of a stage
+constexpr int kT2Scratch = 2 * kT2Stage;   // output staging, 8 KiB per wavefront
+constexpr int kT2Lds = kT2Scratch + 32768; // 160 KiB: all of a compute unit's LDS
+
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) const u32x4 lds_u32x4;
+
+// all digits of one dimension, fixed trip count (unused digits have extent 1 and stride 0)
+__device__ __forceinline__ uint32_t digits_offset4(const Digits &d, uint32_t x) {
+    uint32_t off = 0;
+#pragma unroll
+    for (uint32_t j = 0; j < (uint32_t)kMaxDigits; ++j) {
+        const uint32_t q = fdiv(x, d.fmult[j]);
+        const uint32_t dig = q - fdiv(q, d.fext[j]) * d.ext[j];
+        off += dig * (uint32_t)d.ss[j];
+    }
+    return off;
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane i lands at lds_base + 16 i
+__device__ __forceinline__ void load_to_lds16(const void *base, uint32_t byte_off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_base) : "memory");
+}
+
+#define AMAP_PIN() __builtin_amdgcn_sched_barrier(0)
+
+template <bool STORE_MAPPED>
+__global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(const GemmArgs g) {
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t wm = wave >> 1, wn = wave & 1u;
+    const uint32_t steps = g.K / T2K;  // >= 2
+    const uint32_t ntiles = g.tiles_m * g.tiles_n;
+
+    // ---- load cursor: the k-step the next batch of loads fetches.
+    // A stage: 1 KiB block b = rows 8 b .. 8 b + 7, 128 B each; lane i of the load holds row 8 b + i / 8,
+    // physical chunk i % 8 = logical chunk ^ ((row >> 1) & 7).  W stage: block b = k rows 2 b, 2 b + 1,
+    // 512 B each; lane i holds row 2 b + i / 32, physical chunk i % 32 = logical chunk ^ ((k & 3) << 2).
+    // Wavefront w issues blocks 8 w .. 8 w + 7 of both.
+    uint32_t ld_tile = blockIdx.x, ld_k0 = 0;
+    const uint32_t a_chunk0 = (lane & 7u) ^ (lane >> 4);
+    const uint32_t w_kr = lane >> 5;
+    uint32_t a_lane[2], w_lane[2];   // per-lane byte offsets, block parity 0 / 1
+#pragma unroll
+    for (uint32_t par = 0; par < 2; ++par) {
+        a_lane[par] = 2u * ((64u * wave + (lane >> 3)) * g.a_row_ss + 8u * (a_chunk0 ^ (par << 2)));
+        w_lane[par] = 2u * ((16u * wave + w_kr) * g.N + 8u * ((lane & 31u) ^ (w_kr << 2) ^ (par << 3)));
+    }
+    uint32_t a_tile = 0, w_tile = 0;   // wave-uniform byte offsets of the cursor's tile
+    auto cursor_tile = [&]() __attribute__((always_inline)) {
+        uint32_t tm, tn;
+        tile_of_block(ld_tile, g.tiles_m, g.tiles_n, tm, tn);
+        a_tile = 2u * (g.sbase + digits_offset4(g.dm, tm * T2M));
+        w_tile = 2u * (tn * T2N);
+    };
+    uint32_t ka = 0, wk = 0;
+    auto loads_begin = [&]() __attribute__((always_inline)) {
+        ka = a_tile + 2u * digits_offset4(g.dk, ld_k0);
+        wk = w_tile + 2u * ld_k0 * g.N;
+    };
+    auto load_one = [&](uint32_t stage_base, int j, int which) __attribute__((always_inline)) {
+        if (which == 0)
+            load_to_lds16(g.A_src, a_lane[j & 1] + ka + 16u * j * g.a_row_ss, stage_base + (wave * 8u + j) * 1024u);
+        else
+            load_to_lds16(g.W, w_lane[j & 1] + wk + 4u * j * g.N, stage_base + kT2WOff + (wave * 8u + j) * 1024u);
+    };
+
+    // ---- fragment addresses (bytes from the start of a stage)
+    // A: row 128 wm + 32 i + lane % 32, logical chunk 2 kk + lane / 32
+    const uint32_t fa_addr0 = wm * 16384u + (lane & 31u) * 128u + (((lane >> 5) ^ ((lane >> 1) & 7u)) << 4);
+    // W: lane = 16 g + s supplies the 8 bytes at k = 16 kk + 8 (g >> 1) + s / 4 (+ 4), n = 128 wn + 32 jn + 16 (g & 1) + 4 (s % 4)
+    // and receives k = 16 kk + 8 (lane / 32) .. + 3 (+ 4) of n = 128 wn + 32 jn + lane % 32
+    const uint32_t gq = lane >> 4, sq = lane & 15u;
+    const uint32_t fw_base = kT2WOff + (8u * (gq >> 1) + (sq >> 2)) * 512u + wn * 256u + (2u * (gq & 1u) + ((sq >> 1) & 1u)) * 16u + (sq & 1u) * 8u;
+    uint32_t fw_addr[4];
+#pragma unroll
+    for (int jn = 0; jn < 4; ++jn) fw_addr[jn] = fw_base + (((uint32_t)jn ^ ((sq >> 2) & 3u)) << 6);
+
+    f32x16 acc[4][4];
+    bf16x8 fa[2][4];
+    bf16x4 fbl[2][4], fbh[2][4];
+    auto mf = [&](int set, int i, int jn) __attribute__((always_inline)) {
+        const bf16x8 b = __builtin_shufflevector(fbl[set][jn], fbh[set][jn], 0, 1, 2, 3, 4, 5, 6, 7);
+        // W fragment as the row operand: the 32 x 32 result is C^T, a lane holds four consecutive n of one row m
+        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, fa[set][i], acc[i][jn], 0, 0, 0);
+    };
+    // one of the 12 fragment reads of a k sub-step (4 of A, 8 of W)
+    auto rd = [&](int set, uint32_t stage_base, int kk, int r) __attribute__((always_inline)) {
+        if (r < 4) {
+            fa[set][r] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u32x4 *>(stage_base + (fa_addr0 ^ ((uint32_t)kk << 5)) + r * 4096u));
+        } else {
+            const uint32_t a = stage_base + fw_addr[(r - 4) >> 1] + kk * 8192u + ((r & 1) ? 2048u : 0u);
+            const bf16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(reinterpret_cast<__attribute__((address_space(3))) bf16x4 *>(a));
+            if (r & 1)
+                fbh[set][(r - 4) >> 1] = v;
+            else
+                fbl[set][(r - 4) >> 1] = v;
+        }
+    };
+    // 16 MFMAs on fragment set `set`; the 12 reads of the next sub-step go into the other set, one per MFMA;
+    // with `loads` the 16 loads of the cursor's k-step go out as well, one per MFMA
+    auto phase = [&](int set, uint32_t rd_stage, int rd_kk, bool reads, uint32_t ld_stage, bool loads) __attribute__((always_inline)) {
+        if (loads) loads_begin();
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            mf(set, s >> 2, s & 3);
+            if (reads && s < 12) rd(set ^ 1, rd_stage, rd_kk, s);
+            if (loads) load_one(ld_stage, s >> 1, s & 1);
+            AMAP_PIN();
+        }
+        if (loads) ld_k0 += T2K;
+    };
+    uint32_t cur = 0;
+    if (ld_tile < ntiles) {
+        cursor_tile();
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            loads_begin();
+#pragma unroll
+            for (int s = 0; s < 16; ++s) load_one(p * kT2Stage, s >> 1, s & 1);
+            ld_k0 += T2K;
+        }
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // the first step is there, the second may still be on its way
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int r = 0; r < 12; ++r) rd(0, 0, 0, r);
+    }
+    for (uint32_t c_tile = blockIdx.x; c_tile < ntiles; c_tile += gridDim.x) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        for (uint32_t ks = 0; ks < steps; ++ks) {
+            // one k-step on stage `cur`
+            AMAP_PIN();
+            phase(0, cur, 1, true, 0, false);
+            phase(1, cur, 2, true, 0, false);
+            phase(0, cur, 3, true, 0, false);
+            // every wavefront's reads of this stage are complete, and everyone's loads of the other stage
+            // have landed, before anyone goes on (the loads only count in vmcnt; the compiler does not know of them)
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            AMAP_PIN();
+            // last quarter: the fragments of the next step's first quarter come from the other stage (after
+            // the workgroup's last step they are stale and unused), and the cursor's k-step, two ahead of
+            // this one and possibly in the workgroup's next tile, is fetched into the stage just released
+            const bool issue = ld_tile < ntiles;
+            phase(1, kT2Stage - cur, 0, true, cur, issue);
+            if (issue && ld_k0 >= g.K) {
+                ld_k0 = 0;
+                ld_tile += gridDim.x;
+                if (ld_tile < ntiles) cursor_tile();
+            }
+            cur = kT2Stage - cur;
+        }
+
+        // ---- epilogue: this wavefront's 128 x 128 block, 32 rows at a time: rounded to bf16, through its
+        // own 8 KiB of LDS (16-byte chunks XOR-swizzled by the row, the 8-byte halves by row bit 4), then
+        // whole 256-byte row segments to memory.  Accumulator v of a tile in lane l: m = l % 32,
+        // n = 8 (v / 4) + 4 (l / 32) + v % 4.
+        uint32_t tm, tn;
+        tile_of_block(c_tile, g.tiles_m, g.tiles_n, tm, tn);
+        const uint32_t scr = kT2Scratch + wave * 8192u;
+        const uint32_t row_w = lane & 31u, half_w = lane >> 5;
+        const uint32_t m_base = tm * T2M + wm * 128u, n_lane = tn * T2N + wn * 128u + (lane & 15u) * 8u;
+        size_t col_off = n_lane;
+        if constexpr (STORE_MAPPED) col_off = g.obase + digits_offset4(g.on, n_lane);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int jn = 0; jn < 4; ++jn)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    u32x2 o;
+                    o.x = pack_bf16(acc[i][jn][4 * q], acc[i][jn][4 * q + 1]);
+                    o.y = pack_bf16(acc[i][jn][4 * q + 2], acc[i][jn][4 * q + 3]);
+                    const uint32_t chunk = (uint32_t)(jn * 4 + q) ^ (row_w & 15u);
+                    *reinterpret_cast<__attribute__((address_space(3))) u32x2 *>(scr + row_w * 256u + (chunk << 4) + ((half_w ^ (row_w >> 4)) << 3)) = o;
+                }
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const uint32_t row = 4u * p + (lane >> 4), chunk = lane & 15u;
+                u32x4 x = *reinterpret_cast<lds_u32x4 *>(scr + row * 256u + ((chunk ^ (row & 15u)) << 4));
+                if (p >= 4) x = u32x4{x.z, x.w, x.x, x.y};
+                const uint32_t m = m_base + i * 32u + row;
+                size_t off;
+                if constexpr (STORE_MAPPED)
+                    off = col_off + digits_offset4(g.om, m);
+                else
+                    off = (size_t)m * g.N + col_off;
+                __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + off));
+            }
+        }
+    }
+}
+
 // Split the loops of one dst dimension of a piece into digits.  The piece must start at
 // index `lo` of that dimension and cover `extent` indices.
 bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d, int64_t lo = 0) {
@@ -398,6 +617,12 @@ bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d, int64_t lo 
         d.ss[j] = (int32_t)it.sstride;
         d.fmult[j] = make_fastdiv(d.mult[j]);
         d.fext[j] = make_fastdiv(d.ext[j]);
+    }
+    // the rest as digits that contribute nothing, for decoders with a fixed trip count
+    for (uint32_t j = d.n; j < (uint32_t)kMaxDigits; ++j) {
+        d.mult[j] = d.ext[j] = 1;
+        d.ss[j] = 0;
+        d.fmult[j] = d.fext[j] = make_fastdiv(1);
     }
     return true;
 }
@@ -582,6 +807,50 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     g.K = (uint32_t)K;
     g.tiles_m = (uint32_t)((M + BM - 1) / BM);
     g.tiles_n = (uint32_t)((N + BN - 1) / BN);
+    hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+    // ---- the aligned common case runs on 256 x 256 tiles (see amap_gemm_tile256_kernel)
+    const char *t256 = std::getenv("AMAP_GEMM_TILE256");   // 0: always the general kernel (tests compare the two)
+    const bool tile256_on = !(t256 && t256[0] == '0');
+    if (tile256_on && amode == A_RUNS_K && segs.size() == 1 && wmode == W_PLAIN && M % T2M == 0 && N % T2N == 0 && K % T2K == 0 &&
+        K >= 2 * T2K && g.dm.mult[0] == 1 && g.dm.ext[0] % T2M == 0 && g.dk.mult[0] == 1 && g.dk.ss[0] == 1 && g.dk.ext[0] % T2K == 0) {
+        static thread_local int n_cu = 0;
+        if (n_cu == 0) {
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) {
+                (void)hipGetLastError();
+                n_cu = 0;
+                set_last_error("amap_gemm_tile256_kernel: cannot query the device");
+                return AMAP_E_HIP;
+            }
+            for (const void *fn : {reinterpret_cast<const void *>(amap_gemm_tile256_kernel<false>), reinterpret_cast<const void *>(amap_gemm_tile256_kernel<true>)})
+                if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kT2Lds) != hipSuccess) {
+                    (void)hipGetLastError();
+                    n_cu = 0;
+                    set_last_error("amap_gemm_tile256_kernel: cannot reserve its LDS stages");
+                    return AMAP_E_HIP;
+                }
+        }
+        if (const char *tr = std::getenv("AMAP_PLAN_TRACE"); tr && tr[0] != '0')
+            std::fprintf(stderr, "amap gemm: 256 x 256 tiles, %lld x %lld x %lld\n", (long long)M, (long long)N, (long long)K);
+        g.a_row_ss = (uint32_t)g.dm.ss[0];
+        g.tiles_m = (uint32_t)(M / T2M);
+        g.tiles_n = (uint32_t)(N / T2N);
+        const uint32_t ntiles = g.tiles_m * g.tiles_n;
+        const dim3 grid2(std::min<uint32_t>(ntiles, (uint32_t)n_cu)), block2(kGemmThreads);
+        (void)hipGetLastError();   // an earlier, unrelated error on this thread is not this launch's
+        if (g.store_mapped)
+            hipLaunchKernelGGL(amap_gemm_tile256_kernel<true>, grid2, block2, kT2Lds, hs, g);
+        else
+            hipLaunchKernelGGL(amap_gemm_tile256_kernel<false>, grid2, block2, kT2Lds, hs, g);
+        const hipError_t e2 = hipGetLastError();
+        if (e2 != hipSuccess) {
+            set_last_error("amap_gemm_tile256_kernel", hipGetErrorString(e2));
+            return AMAP_E_HIP;
+        }
+        return AMAP_OK;
+    }
+    if (const char *tr = std::getenv("AMAP_PLAN_TRACE"); tr && tr[0] != '0')
+        std::fprintf(stderr, "amap gemm: 256 x 128 tiles, %lld x %lld x %lld\n", (long long)M, (long long)N, (long long)K);
     const size_t lds = kLdsBytes;
     static thread_local bool attr_done = false;
     if (!attr_done) {
@@ -604,8 +873,8 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
         attr_done = true;
     }
     const dim3 grid(g.tiles_m * g.tiles_n), block(kGemmThreads);
-    hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
     const bool seg = g.n_seg > 1;
+    (void)hipGetLastError();   // an earlier, unrelated error on this thread is not this launch's
 #define AMAP_GEMM_AWE(AM, WM, E)                                                                       \
     do {                                                                                               \
         if (seg)                                                                                       \

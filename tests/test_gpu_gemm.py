@@ -418,3 +418,79 @@ def test_gather_one_source_twice_and_error_paths(dev):
         B.amap_gemm_fused(d_x.data_ptr(), two, d_w.data_ptr(), 128, out.data_ptr(), 0)
     assert e.value.status == B.AMAP_E_UNSUPPORTED
     torch.cuda.synchronize()
+
+
+# ---- the aligned case: 256 x 256 tiles, operands loaded straight into LDS (its own kernel)
+
+T256_CASES = [
+    # (A source shape, A chain -> [M,K]), N, chain on the product or None
+    (((512, 128), []), 256, None),                                                                 # two k-steps, 2 x 1 tiles
+    (((256, 192), []), 256, None),                                                                 # odd number of k-steps, one tile
+    (((2, 4, 256, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (512, 256))]), 512, None),        # head merge: 64-element runs
+    (((1024, 128), []), 1024, None),                                                               # 16 tiles
+    (((2, 1024, 2, 64), [("transpose", (0, 2, 1, 3)), ("slice", 2, 256, 768, 1), ("transpose", (0, 2, 1, 3)),
+                         ("reshape", (1024, 128))]), 256, None),                                   # base offset, rows 128 elements apart
+    (((512, 128), []), 768, [("reshape", (2, 256, 3, 4, 64)), ("transpose", (2, 0, 3, 1, 4))]),    # QKV head split on the store side
+    (((2, 2, 256, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (512, 128))]), 256,
+     [("reshape", (2, 256, 4, 64)), ("transpose", (2, 0, 1, 3))]),                                 # both sides mapped
+]
+
+
+@pytest.mark.parametrize("case", range(len(T256_CASES)))
+def test_tile256_kernel_vs_oracle_and_general_kernel(dev, case, monkeypatch, capfd):
+    import torch
+    (shape, a_ops), N, c_ops = T256_CASES[case]
+    print(f"[gpu] tile256 gemm case {case} {shape} N={N}", flush=True)
+    rng = np.random.default_rng(700 + case)
+    src = synth.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    a_map = B.amap_compose([shape], 2, a_ops)
+    M, K = B.dst_shape(a_map)
+    w = synth.f32_to_bf16_bits((rng.standard_normal((K, N)) * 0.05).astype(np.float32))
+    out_map = B.amap_compose([(M, N)], 2, c_ops) if c_ops else None
+    d_src, d_w = dev.to_device(src), dev.to_device(w)
+
+    def run():
+        out = dev.gemm_fused(d_src, a_map, d_w, out_map=out_map) if out_map else dev.gemm_fused(d_src, a_map, d_w)
+        torch.cuda.synchronize()
+        return dev.to_host(out)
+
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    capfd.readouterr()
+    got = run()
+    assert "256 x 256 tiles" in capfd.readouterr().err           # the kernel under test is the one that ran
+    monkeypatch.setenv("AMAP_GEMM_TILE256", "0")
+    general = run()
+    assert "256 x 128 tiles" in capfd.readouterr().err
+    monkeypatch.delenv("AMAP_GEMM_TILE256")
+    monkeypatch.delenv("AMAP_PLAN_TRACE")
+    a_bits = oracle.run_chain([src], a_ops) if a_ops else src
+    want = oracle.gemm_bf16(a_bits, w)
+    if c_ops:
+        want = oracle.run_chain([want], c_ops)
+    assert got.shape == want.shape
+    g, r = synth.bf16_bits_to_f32(got).astype(np.float64), synth.bf16_bits_to_f32(want).astype(np.float64)
+    assert np.abs(g - r).max() <= TOL * np.abs(r).max()
+    ulp = np.maximum(np.abs(r), 2.0 ** -126) * 2.0 ** -7
+    assert np.mean(np.abs(g - r) <= ulp) > 0.999
+    # both kernels add the same products in the same order (k ascending, 16 at a time in the same MFMA)
+    assert np.array_equal(got, general)
+
+
+def test_tile256_identity_weight_is_exact(dev, monkeypatch, capfd):
+    """W = shifted identity on the 256 x 256 kernel: C reproduces the mapped A bit for bit, so a wrong
+    lane -> address permutation of the LDS loads or of the transposing reads cannot hide in rounding."""
+    shape, ops = (2, 2, 256, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (512, 128))]
+    src = synth.f32_to_bf16_bits(np.random.default_rng(31).standard_normal(shape).astype(np.float32))
+    cols = (np.arange(128) * 5 + 3) % 256
+    wf = np.zeros((128, 256), dtype=np.float32)
+    wf[np.arange(128), cols] = 1.0
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    capfd.readouterr()
+    got = _gemm(dev, src, shape, ops, synth.f32_to_bf16_bits(wf))
+    assert "256 x 256 tiles" in capfd.readouterr().err
+    a = oracle.run_chain([src], ops)
+    nz = (a & 0x7FFF) != 0
+    assert np.array_equal(got[:, cols][nz], a[nz])
+    rest = np.ones(256, dtype=bool)
+    rest[cols] = False
+    assert not (got[:, rest] & 0x7FFF).any()
