@@ -320,13 +320,34 @@ def amap_eval_host(m, srcs, mode=0):
     return out
 
 
-def _ptr_array(ptrs):
-    return (C.c_void_p * max(1, len(ptrs)))(*[int(p) if p else None for p in ptrs])
+def _ptr_array(ptrs, n_min=0):
+    """Pointer table for the C side, padded with NULL up to n_min entries: the library reads one
+    entry per source id of the map and the ABI carries no count, so a short table must never be handed over."""
+    vals = [int(p) if p else None for p in ptrs]
+    vals += [None] * (max(1, n_min) - len(vals))
+    return (C.c_void_p * len(vals))(*vals)
+
+
+def _src_array(src_ptrs, maps, what):
+    """Source table sized to the maps it serves; a source id a map reads without a pointer is an error here,
+    before the library sees the table."""
+    n_src = 0
+    for m in maps:
+        info = amap_describe(m)
+        n_src = max(n_src, info.n_src)
+        for i in range(info.n_src):
+            try:
+                amap_source_shape(m, i)
+            except AmapError:
+                continue  # an id the map no longer reads
+            if i >= len(src_ptrs) or not src_ptrs[i]:
+                raise AmapError(AMAP_E_INVALID, f"{what}: no pointer for source {i}")
+    return _ptr_array(src_ptrs, n_src)
 
 
 def amap_execute(src_ptrs, dst_ptr, m, stream=0, kernel_id=None):
     """src_ptrs: device addresses (ints) indexed by source id; dst_ptr: device address."""
-    arr = _ptr_array(src_ptrs)
+    arr = _src_array(src_ptrs, [m], "amap_execute")
     if kernel_id is None:
         _check(_L.amap_execute(arr, C.c_void_p(dst_ptr), m.handle, C.c_void_p(stream)), "amap_execute")
     else:
@@ -341,7 +362,7 @@ def amap_execute_kernel(src_ptrs, dst_ptr, m, stream, kernel_id):
 def amap_execute_multi(src_ptrs, dst_ptrs, maps, stream=0):
     """One source table, several (map, dst) pairs, packed into shared launches."""
     handles = (C.c_void_p * len(maps))(*[m.handle for m in maps])
-    _check(_L.amap_execute_multi(_ptr_array(src_ptrs), _ptr_array(dst_ptrs), handles, len(maps), C.c_void_p(stream)),
+    _check(_L.amap_execute_multi(_src_array(src_ptrs, maps, "amap_execute_multi"), _ptr_array(dst_ptrs), handles, len(maps), C.c_void_p(stream)),
            "amap_execute_multi")
 
 
@@ -363,7 +384,7 @@ def amap_gemm_mapped(a_src_ptr, a_map, w_src_ptr, w_map, out_map, out_ptr, strea
 
 def amap_gemm_gather(a_src_ptrs, a_map, w_src_ptr, w_map, n, out_map, out_ptr, stream=0):
     """a_src_ptrs: device pointers by source id of a_map (None for ids the map does not use)."""
-    _check(_L.amap_gemm_gather(_ptr_array(a_src_ptrs), a_map.handle, C.c_void_p(w_src_ptr),
+    _check(_L.amap_gemm_gather(_ptr_array(a_src_ptrs, amap_describe(a_map).n_src), a_map.handle, C.c_void_p(w_src_ptr),
                                w_map.handle if w_map is not None else None, int(n),
                                out_map.handle if out_map is not None else None, C.c_void_p(out_ptr),
                                C.c_void_p(stream)), "amap_gemm_gather")

@@ -129,8 +129,6 @@ struct LaunchArgs {
     uint32_t nwlog;      // workgroup size = 64 << nwlog
     uint32_t nt;         // PieceFlags every piece of the launch agrees on
     uint32_t xcd_remap;  // 1: remap workgroup indices so each XCD gets a contiguous range
-    uint32_t n_fill_blocks;  // trailing workgroups (in logical order) that belong to fill pieces
-    uint32_t fill_stride;    // every fill_stride-th hardware workgroup runs a fill workgroup; 0 = keep them last
     DevPiece p[kMaxPiecesPerLaunch];
 };
 

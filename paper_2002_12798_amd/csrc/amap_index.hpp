@@ -33,22 +33,8 @@ AMAP_HD uint32_t xcd_remap(uint32_t b, uint32_t grid) {
     return x * q + (x < r ? x : r) + idx;
 }
 
-// Fill pieces only store.  Their workgroups sit at the end of the logical
-// block sequence; spread them evenly over the launch (every fill_stride-th
-// hardware workgroup is a fill workgroup) so that the constant stores overlap
-// with the copy tiles instead of forming a store-only tail.
-// grid = all workgroups, n_fill = trailing fill workgroups.  A bijection.
-AMAP_HD uint32_t fill_interleave(uint32_t h, uint32_t grid, uint32_t n_fill, uint32_t stride) {
-    if (stride == 0) return h;
-    const uint32_t slot = h / stride;
-    if (h - slot * stride == 0 && slot < n_fill) return grid - n_fill + slot;
-    const uint32_t before = (h + stride - 1) / stride;  // fill slots below h
-    return h - (before < n_fill ? before : n_fill);
-}
-
 AMAP_HD uint32_t logical_block(const LaunchArgs &a, uint32_t hw, uint32_t grid) {
-    const uint32_t b = a.xcd_remap ? xcd_remap(hw, grid) : hw;
-    return fill_interleave(b, grid, a.n_fill_blocks, a.fill_stride);
+    return a.xcd_remap ? xcd_remap(hw, grid) : hw;
 }
 
 // ---- row kernel: vector r of the piece (dst order) -> element offsets

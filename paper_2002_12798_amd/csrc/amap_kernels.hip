@@ -746,23 +746,17 @@ __global__ __launch_bounds__(kProgramThreads) void amap_program_kernel(const Pro
 
 // ------------------------------------------------------------------ host side
 
-thread_local char g_last_error[256] = "";
-}  // namespace
+// An error left on this thread by an earlier, unrelated HIP call must not be read as the failure
+// of the launch that follows: called right before every launch, launch_failed right after it.
+void clear_stale_error() { (void)hipGetLastError(); }
 
-void amap_detail::set_last_error(const char *what, const char *detail) {
-    if (detail)
-        std::snprintf(g_last_error, sizeof(g_last_error), "%s: %s", what, detail);
-    else
-        std::snprintf(g_last_error, sizeof(g_last_error), "%s", what);
-}
-
-namespace {
-
-// true if the launch just made (or an earlier call on this thread) left an error
+// true if the launch just made left an error
 bool launch_failed(const char *what) {
     const hipError_t e = hipGetLastError();
     if (e == hipSuccess) return false;
-    std::snprintf(g_last_error, sizeof(g_last_error), "%s: %s (%s)", what, hipGetErrorString(e), hipGetErrorName(e));
+    char detail[200];
+    std::snprintf(detail, sizeof(detail), "%s (%s)", hipGetErrorString(e), hipGetErrorName(e));
+    set_last_error(what, detail);
     return true;
 }
 
@@ -789,6 +783,7 @@ amap_status launch_pieces(const LaunchArgs &args, uint32_t blocks, size_t lds, i
     for (uint32_t k = 0; k < args.n_pieces; ++k)
         grouped = grouped || (args.p[k].kind != PK_ROWS && args.p[k].group_n > 1);
     const dim3 grid(blocks), block(64u << args.nwlog);
+    clear_stale_error();
 #define AMAP_LAUNCH(ES, NT)                                                                                  \
     do {                                                                                                     \
         if (grouped)                                                                                         \
@@ -842,6 +837,7 @@ amap_status launch_program(const amap *m, const Plan &plan, const void *const *s
     for (int i = 0; i < plan.n_prog_src && i < (int)m->src_shapes.size(); ++i) t.p[i] = src[i];
     const uint32_t total = (uint32_t)volume_of(m->shape);
     const uint32_t grid = (total + kProgramThreads - 1) / kProgramThreads;
+    clear_stale_error();
     if (m->elem == 2)
         hipLaunchKernelGGL(amap_program_kernel<2>, dim3(grid), dim3(kProgramThreads), 0, stream, plan.prog, t, (char *)dst, total);
     else
@@ -879,8 +875,6 @@ extern "C" amap_status amap_execute_kernel(const void *const *src, void *dst, co
         return AMAP_E_NOMEM;
     }
 }
-
-extern "C" const char *amap_last_error(void) { return g_last_error; }
 
 // Several maps over one source table, each with its own dst, in as few launches
 // as their pieces fit: the pieces of all maps are packed into shared launches,
@@ -970,48 +964,3 @@ extern "C" amap_status amap_execute(const void *const *src, void *dst, const ama
     return amap_execute_kernel(src, dst, map, stream, -1);
 }
 
-extern "C" amap_status amap_describe(const amap_t *m, amap_info *out) {
-    if (!m || !out) return AMAP_E_INVALID;
-    amap_info o;
-    std::memset(&o, 0, sizeof(o));
-    o.rank = (int)m->shape.size();
-    for (int k = 0; k < o.rank; ++k) o.shape[k] = m->shape[k];
-    o.elem_size = m->elem;
-    o.n_src = (int)m->src_shapes.size();
-    o.strided = m->strided ? 1 : 0;
-    o.write_bytes = volume_of(m->shape) * m->elem;
-    if (m->strided) {
-        o.n_pieces = (int)m->kpieces.size();
-        for (const KPiece &p : m->kpieces) {
-            if (p.fill) {
-                ++o.n_fill_pieces;
-                o.fill_bytes += p.volume() * m->elem;
-            } else {
-                o.min_read_bytes += p.volume() * m->elem;
-            }
-        }
-    } else {
-        // count the data elements by walking the program over dst
-        int64_t idx[kMaxRank] = {0};
-        const int rank = o.rank;
-        int64_t data = 0, vol = volume_of(m->shape);
-        for (int64_t L = 0; L < vol; ++L) {
-            int sid;
-            int64_t off;
-            uint32_t fill;
-            data += eval_program(m->prog.get(), idx, &sid, &off, &fill) ? 1 : 0;
-            for (int k = rank - 1; k >= 0; --k) {
-                if (++idx[k] < m->shape[k]) break;
-                idx[k] = 0;
-            }
-        }
-        o.min_read_bytes = data * m->elem;
-        o.fill_bytes = (vol - data) * m->elem;
-    }
-    if (!m->injective) o.min_read_bytes = distinct_source_elements(*m) * m->elem;
-    const Plan *plan = plan_of(*m);
-    o.kernel_id = plan ? plan->main_kernel : AMAP_K_PROGRAM;
-    o.vec_bytes = plan ? plan->min_vec_bytes : m->elem;
-    *out = o;
-    return AMAP_OK;
-}

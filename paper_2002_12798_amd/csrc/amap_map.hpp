@@ -100,6 +100,7 @@ struct amap {
     std::vector<amap_detail::Piece> pieces;
     std::vector<amap_detail::KPiece> kpieces;      // derived from pieces when strided
     std::shared_ptr<void> plan;                    // device launch plan (owned by the executor)
+    mutable int64_t distinct_reads = -1;           // distinct source elements read, once counted (see distinct_source_elements)
 };
 
 namespace amap_detail {
@@ -119,8 +120,11 @@ std::vector<KDim> merge_loops(std::vector<KDim> dims);
 // Recompute m.kpieces from m.pieces (no-op if not strided).
 void finalise(amap &m);
 
-// Number of distinct source elements a map reads (exact; marks one bit per
-// source element, walks the pieces or, without a strided form, the program).
+// Number of distinct source elements a map reads (exact).  Closed form when every source is read by
+// one piece whose moving loops cannot meet; otherwise one bit per source element is marked while the
+// pieces (or, without a strided form, the program) are walked: throws std::bad_alloc when the sources
+// hold more than kMaxDistinctBits elements.  The count is kept in the map.
+constexpr int64_t kMaxDistinctBits = int64_t(1) << 33;   // 1 GiB of marks
 int64_t distinct_source_elements(const amap &m);
 
 // Evaluate the operator program for one dst multi-index.

@@ -96,7 +96,7 @@ static void fill_rows(DevPiece &dp, const KPiece &kp, uint32_t V, uint32_t nwlog
 // (repeat, tile, broadcast) reads the same lines again and again: those loads must stay
 // cached (a [1,1,1,256] row tiled 100,352 times ran 14.0 us with streaming loads, 11.0 us without).
 static uint32_t nt_mask(const KPiece &kp) {
-    uint32_t mask = (uint32_t)env_int("AMAP_NT", 3);
+    uint32_t mask = PF_NT_LOAD | PF_NT_STORE;
     if (!kp.fill)
         for (const KDim &d : kp.dims)
             if (d.ss == 0 && d.extent > 1) mask &= ~(uint32_t)PF_NT_LOAD;
@@ -334,7 +334,7 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
     int64_t EQc = Q.extent;
     if (env_int("AMAP_TILE_CHAIN_VEC", 1)) q_chain(kp, iP, iQ, EQc);
     const int64_t tile_bytes = (int64_t)common_pow2((uint32_t)V, {P.extent, EQc}, {}) * es;
-    if (tile_bytes >= env_int("AMAP_FLAT_BELOW", 16)) return none;
+    if (tile_bytes >= 16) return none;
     for (int dir = 1; dir <= 2; ++dir) {
         // dir 1: rows are contiguous in the source, from Q outwards, until P's source stride is reached;
         // dir 2: in dst, from P outwards, until Q's dst stride is reached
@@ -353,7 +353,7 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
         if (flat_stride(iR) != C) continue;
         const int64_t ER = kp.dims[iR].extent;
         // rows of 2 .. 7 elements belong to the interleaving row forms (a block of 64 such rows is too little work)
-        if (C < env_int("AMAP_FLAT_MIN_C", 8) || ER < (int64_t)env_int("AMAP_FLAT_MIN_ROWS", (int)kFlatMinRows)) continue;
+        if (C < 8 || ER < (int64_t)kFlatMinRows) continue;
         if (n - 1 > kMaxLoops) continue;  // batch loops + chain
         // whole 16-byte vectors on the dst side and along the rows?  If not, only the blocked form with dst as
         // the contiguous side remains: its stores take any alignment and its loads along the rows end element by element
@@ -374,29 +374,29 @@ static FlatShape flat_shape(const KPiece &kp, int es) {
             if (common_pow2((uint32_t)V, {kp.dbase}, ds_all) >= 2) continue;
         }
         // as many rows per block as fit LDS: 64, 32 or 16 (rows of 1225 = 35 x 35 positions: 16 at a time)
-        const int64_t lds_limit = (int64_t)std::min(64, env_int("AMAP_FLAT_LDS_KB", (int)(kFlatLdsBytes >> 10))) * 1024;
+        const int64_t lds_limit = (int64_t)kFlatLdsBytes;
         uint32_t rlog = 6;
         // 16 rows at a time only against forms with vectors of less than 8 bytes (rows of 1225: 216.2 -> 27.8 us);
         // against tiles with 8-byte vectors they lose (rows of 1444: 13.2 -> 21.1 us), 32 rows still win (676: 17.6 -> 15.6 us)
-        const uint32_t rlog_min = (uint32_t)std::max(4, std::min(6, env_int("AMAP_FLAT_MIN_RLOG", tile_bytes >= 8 ? 5 : 4)));
+        const uint32_t rlog_min = tile_bytes >= 8 ? 5 : 4;
         while (rlog > rlog_min && C * std::min<int64_t>(ER, 1ll << rlog) * es > lds_limit) --rlog;
         int64_t cb = 0;
         // 128 2-byte columns per block (55 x 55 positions under 96 channels, towards channel-major: 24.4 us; 256 columns: 26.6 us;
         // gathered rows: 178.8 us).  With the source as the contiguous side and a row of one loop, the cut into a
         // whole-vector part and a one-element tail is as fast or faster (23.7 against 23.8 us; 75 x 75 fp32: 11.9 against
         // 17.4 us), so there the blocked form is left to rows of several loops (padded or cropped images).
-        const int64_t cb_env = env_int("AMAP_FLAT_RAG_CB", 256 / es);  // 256-byte row segments (fp32: 64 columns 15.5 us, 128 columns 17.2 us)
-        const bool rag_ok = env_int("AMAP_FLAT_RAG", 1) && cb_env >= V && cb_env % V == 0 && cb_env * es <= 1024 && tile_bytes < 8 && ER >= 64;
+        const int64_t cb_env = 256 / es;  // 256-byte row segments (fp32: 64 columns 15.5 us, 128 columns 17.2 us)
+        const bool rag_ok = cb_env >= V && cb_env % V == 0 && tile_bytes < 8 && ER >= 64;
         // long rows of one loop under few channels, the source contiguous: the cut into a whole-vector part and a
         // one-element tail is faster there (concat of 64 + 64 + 96 + 32 channels of 35 x 35 positions: 26.8 against 34.6 us)
-        if (dir == 1 && chain.size() == 1 && rlog == 4 && ER < 128 && env_int("AMAP_FLAT_RAG", 1) < 2) continue;
+        if (dir == 1 && chain.size() == 1 && rlog == 4 && ER < 128) continue;
         const bool fits = aligned && C * std::min<int64_t>(ER, 1ll << rlog) * es <= lds_limit;
         if (!fits) {
             // rows too long for LDS: blocks of 64 rows x cb columns whose row segments start at any element
-            if (!rag_ok || !(dir == 2 || chain.size() > 1 || env_int("AMAP_FLAT_RAG", 1) >= 2)) continue;
+            if (!rag_ok || !(dir == 2 || chain.size() > 1)) continue;
             rlog = 6;
             cb = cb_env;
-        } else if (rag_ok && ((rlog == 4 && dir == 1) || (rlog < 6 && env_int("AMAP_FLAT_RAG", 1) >= 2))) {
+        } else if (rag_ok && rlog == 4 && dir == 1) {
             // 16 rows at a time with the source as the contiguous side: the blocked form is faster
             // (35 x 35 positions under 288 channels: 26.3 against 30.7 us; into a padded image 29.1 against 32.1 us)
             rlog = 6;
@@ -573,7 +573,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         if (rows_ok)
             fam = AMAP_K_ROWS;
         else if (tile_ok)
-            fam = (int64_t)kp.dims[iP].extent * es <= env_int("AMAP_WAVE_MAX_P_BYTES", 64) ? AMAP_K_WAVE : AMAP_K_TILE;
+            fam = (int64_t)kp.dims[iP].extent * es <= 64 ? AMAP_K_WAVE : AMAP_K_TILE;
         else
             fam = AMAP_K_ELEMENT;
     }
@@ -595,7 +595,7 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         dp.flags = 0;
         dp.sbase = (uint32_t)kp.sbase;
         const bool forced_tile = family == AMAP_K_TILE && (!tile_ok || narrow < 8);
-        const bool planned_flat = family < 0 && narrow < env_int("AMAP_FLAT_BELOW", 16);
+        const bool planned_flat = family < 0 && narrow < 16;
         // (slot_dim: the caller plans a group of pieces as one tile piece and needs the tile geometry proper)
         if ((planned_flat || forced_tile) && !slot_dim && env_int("AMAP_FLAT", 1) && plan_flat(kp, es, nwlog, dp, lds)) {
             vec_bytes = 16;
@@ -677,11 +677,6 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
             LQ >>= 1;
     }
     if (LP * LQ < 64) LQ = 64 / LP;
-    int lq_env = env_int("AMAP_TILE_LQLOG", -1);
-    if (lq_env >= 0 && lq_env <= 6) {
-        LQ = 1u << lq_env;
-        LP = 64 / LQ;
-    }
     const uint64_t remP = (pv + LP - 1) / LP, remQ = (qv + LQ - 1) / LQ;
     const uint32_t NW = 1u << nwlog;
     uint32_t NWP;
@@ -697,8 +692,6 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
     // inside the row would leave partial lines to two workgroups, so let one
     // tile span the whole row if the workgroup is large enough
     if ((dp.eP * (uint64_t)es) % 128 != 0) NWP = std::min<uint32_t>(NW, pow2ceil(remP));
-    int nwp_env = env_int("AMAP_TILE_NWPLOG", -1);
-    if (nwp_env >= 0 && (uint32_t)nwp_env <= nwlog) NWP = 1u << nwp_env;
     dp.lqlog = ilog2(LQ);
     dp.nwplog = ilog2(NWP);
     dp.nwlog = nwlog;
@@ -905,7 +898,7 @@ static bool plan_group(const amap &m, const std::vector<Member> &g, int family, 
     out[0].group_n = (uint32_t)g.size();
     uint32_t flags = head.flags & PF_NT_STORE;
     if ((head.flags & PF_NT_LOAD) && nt_load) flags |= PF_NT_LOAD;
-    for (DevPiece &s : out) s.flags = flags & (uint32_t)env_int("AMAP_NT", 3);
+    for (DevPiece &s : out) s.flags = flags;
     return true;
 }
 
@@ -932,22 +925,14 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
     uint32_t blocks = 0, lds_max = 0;
     auto flush = [&]() {
         if (cur.n_pieces == 0) return;
-        // fill pieces come last in a launch: count their workgroups and spread them
-        uint32_t nf = 0;
-        for (uint32_t k = cur.n_pieces; k-- > 0 && cur.p[k].src == nullptr;) nf += cur.p[k].n_blocks;
-        cur.n_fill_blocks = nf;
         // XCD-aware order only where it pays: tile pieces whose source segments
         // are not line-aligned share lines between neighbouring tiles, and those
         // neighbours should meet in one L2 (measured +6..11 %); for aligned
         // streaming pieces the plain round-robin order is faster
-        int xr = env_int("AMAP_XCD_REMAP", -1);
-        if (xr < 0) {
-            xr = 0;
-            for (uint32_t k = 0; k < cur.n_pieces; ++k)
-                if (cur.p[k].kind != PK_ROWS && cur.p[k].src && !(cur.p[k].flags & PF_NT_LOAD)) xr = 1;
-        }
-        cur.xcd_remap = (uint32_t)xr;
-        cur.fill_stride = (nf > 0 && nf < blocks && env_int("AMAP_FILL_INTERLEAVE", 0)) ? blocks / nf : 0;
+        uint32_t xr = 0;
+        for (uint32_t k = 0; k < cur.n_pieces; ++k)
+            if (cur.p[k].kind != PK_ROWS && cur.p[k].src && !(cur.p[k].flags & PF_NT_LOAD)) xr = 1;
+        cur.xcd_remap = xr;
         out.launches.push_back(cur);
         out.grid.push_back(blocks);
         out.lds_bytes.push_back(lds_max);
@@ -996,7 +981,7 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
     };
     // groups of pieces that are neighbours along the dst-contiguous dimension
     std::vector<char> grouped(m.kpieces.size(), 0);
-    if ((family < 0 || family == AMAP_K_TILE || family == AMAP_K_WAVE) && env_int("AMAP_GROUPS", 1) && !out.windowed) {
+    if ((family < 0 || family == AMAP_K_TILE || family == AMAP_K_WAVE) && !out.windowed) {
         std::vector<char> in_group;
         for (const auto &g : find_groups(m, in_group)) {
             std::vector<DevPiece> dps;
@@ -1014,11 +999,10 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
     // then the remaining copy pieces, fill pieces last (measured: constant
     // stores at the head of the launch delay the first loads more than they gain)
     std::vector<const KPiece *> order;
-    const bool fill_first = env_int("AMAP_FILL_FIRST", 0) != 0;
     for (size_t i = 0; i < m.kpieces.size(); ++i)
-        if (!grouped[i] && m.kpieces[i].fill == fill_first) order.push_back(&m.kpieces[i]);
+        if (!grouped[i] && !m.kpieces[i].fill) order.push_back(&m.kpieces[i]);
     for (size_t i = 0; i < m.kpieces.size(); ++i)
-        if (!grouped[i] && m.kpieces[i].fill != fill_first) order.push_back(&m.kpieces[i]);
+        if (!grouped[i] && m.kpieces[i].fill) order.push_back(&m.kpieces[i]);
     for (const KPiece *kpp : order) {
         const KPiece &kp = *kpp;
         if ((int)kp.dims.size() > kMaxLoops) return false;
@@ -1152,7 +1136,7 @@ static bool window_pieces(std::vector<KPiece> &ks, int64_t limit) {
 bool plan_strided(const amap &m0, int family, Plan &out) {
     amap m = m0;  // the planner's own piece list: ragged pieces cut into main part + tails
     m.plan.reset();
-    if (m.strided && env_int("AMAP_SPLIT_RAGGED", 1)) {
+    if (m.strided) {
         std::vector<KPiece> ks;
         for (const KPiece &kp : m0.kpieces)
             for (KPiece &p : split_ragged(kp, m.elem)) ks.push_back(std::move(p));
@@ -1206,6 +1190,10 @@ struct Flattener {
     }
 
     void concat_group(const PNode *n, size_t lo, size_t hi) {
+        if (volume_of(n->shape) >= (1ll << 31)) {   // as in emit: 32-bit intermediate indices
+            ok = false;
+            return;
+        }
         // one CONCAT instruction over at most 8 children or groups of children
         int at = alloc();
         if (at < 0) return;
@@ -1236,6 +1224,14 @@ struct Flattener {
         while (ok) {
             if (n->kind == PNode::CONCAT) {
                 concat_group(n, 0, n->kids.size());
+                return;
+            }
+            // the interpreter linearises every intermediate index in 32 bits: a chain that passes
+            // through a tensor of 2^31 elements or more (a repeat or tile that a later slice cuts
+            // down again) has no program form, however small its source and dst are
+            if (volume_of(n->shape) >= (1ll << 31) || std::llabs(n->begin) >= (1ll << 31) || std::llabs(n->step) >= (1ll << 31) ||
+                n->count >= (1ll << 31)) {
+                ok = false;
                 return;
             }
             int at = alloc();

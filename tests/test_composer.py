@@ -336,3 +336,53 @@ def test_empty_tensor():
     assert info.write_bytes == 0 and info.n_pieces == 0
     out = B.amap_eval_host(m, [np.zeros((3, 0, 4), np.uint32)])
     assert out.shape == (0, 7)
+
+
+def test_describe_of_an_upsampling_map_needs_no_walk_over_the_source():
+    """The distinct-element count of a repeat / tile over a huge source is a closed form: describing such a
+    map allocates nothing of the source's size and returns at once."""
+    m = B.amap_source(0, (1 << 20, 1 << 20), 2)
+    m = B.amap_repeat(m, 0, 2)
+    info = B.amap_describe(m)
+    assert info.min_read_bytes == (1 << 40) * 2 and info.write_bytes == (1 << 41) * 2
+    assert B.dst_shape(m) == (1 << 21, 1 << 20)
+    # a source used twice by concat: two pieces read it, so the elements are counted one by one
+    a = B.amap_source(0, (6, 8), 2)
+    c = B.amap_concat([B.amap_slice(a, 0, 0, 4, 1), B.amap_slice(a, 0, 2, 6, 1)], 0)
+    assert B.amap_describe(c).min_read_bytes == 6 * 8 * 2
+    # ... and refused (not a crash) when the marks would not fit
+    big = B.amap_source(0, (1 << 20, 1 << 20), 2)
+    assert B.amap_describe(B.amap_concat([big, big], 0)).min_read_bytes == (1 << 40) * 2   # merged into one piece with a loop that stands still
+    c2 = B.amap_concat([B.amap_slice(big, 0, 0, 1 << 19, 1), B.amap_slice(big, 0, 1 << 18, 1 << 19, 1)], 0)
+    with pytest.raises(B.AmapError) as e:
+        B.amap_describe(c2)
+    assert e.value.status == B.AMAP_E_NOMEM
+
+
+def test_no_program_plan_through_an_intermediate_of_2_to_31_elements():
+    """small source -> tile to 2^32 elements -> reshape -> slice back to a small dst: source and dst fit 32-bit
+    offsets, the intermediate does not, so the interpreter (32-bit intermediate indices) must refuse it."""
+    import ctypes as C
+    m = B.amap_source(0, (1 << 16,), 2)
+    m = B.amap_reshape(m, (1, 1 << 16))
+    m = B.amap_tile(m, 0, 1 << 16)                   # [65536, 65536]
+    m = B.amap_reshape(m, (1 << 32,))
+    m = B.amap_slice(m, 0, (1 << 32) - 4096, 1 << 32, 1)
+    assert B.dst_shape(m) == (4096,)
+    src = (C.c_uint16 * (1 << 16))()
+    dst = (C.c_uint16 * 8192)()
+    sp = (C.addressof(src) + 15) & ~15
+    dp = (C.addressof(dst) + 15) & ~15
+    with pytest.raises(B.AmapError) as e:
+        B.amap_execute([sp], dp, m, 0, kernel_id=B.AMAP_K_PROGRAM)   # refused before anything is launched
+    assert e.value.status == B.AMAP_E_UNSUPPORTED
+    # the same chain at a size where every intermediate fits keeps its program form
+    s2 = B.amap_slice(B.amap_reshape(B.amap_tile(B.amap_reshape(B.amap_source(0, (64,), 2), (1, 64)), 0, 64), (4096,)), 0, 100, 200, 1)
+    assert np.array_equal(B.amap_eval_host(s2, [np.arange(64, dtype=np.uint16)], mode=1), np.arange(100, 200, dtype=np.uint16) % 64)
+
+
+def test_short_source_table_is_refused_by_the_binding():
+    c = B.amap_concat([B.amap_source(0, (4, 8), 2), B.amap_source(1, (4, 8), 2)], 0)
+    with pytest.raises(B.AmapError) as e:
+        B.amap_execute([16], 4096, c, 0)             # source 1 has no pointer: refused before the library reads the table
+    assert e.value.status == B.AMAP_E_INVALID

@@ -440,3 +440,41 @@ def test_one_map_executed_from_several_host_threads(dev):
     for t in range(n_threads):
         for r in (0, reps - 1):
             assert np.array_equal(dev.to_host(dsts[t][r]), want), (t, r)
+
+
+def test_plan_of_large_tensors_on_the_workload_structures(dev):
+    """From 256 MB of dst on, the planner switches to workgroups of 4 wavefronts with tiles staged in LDS
+    (XOR-swizzled slots; cfg3 in the grouped form).  The switches bring that plan to sizes the oracle
+    finishes in seconds: cfg1's border fills, cfg3's four-source groups, cfg2's row copies and cfg0's
+    chain at 64 x its batch, each bit for bit in every kernel family that takes the map."""
+    import os
+    cfg0 = synth.workload("cfg0")
+    cases = [
+        ("cfg1 n=2", synth.workload("cfg1", n=2), None),
+        ("cfg3 n=2", synth.workload("cfg3", n=2), None),
+        ("cfg2_rev b=2", synth.workload("cfg2_rev", b=2), None),
+        ("cfg2_fwd b=2", synth.workload("cfg2_fwd", b=2), None),
+        ("cfg0 x64", None, ((512, 16, 32, 32), 4, [cfg0.ops[0], ("reshape", (512, 1024, 16)), cfg0.ops[2], cfg0.ops[3]])),
+    ]
+    for label, w, raw in cases:
+        if w is not None:
+            shapes, es, ops, srcs = w.src_shapes, w.elem_size, w.ops, w.sources()
+        else:
+            shape, es, ops = raw
+            shapes, srcs = [shape], [synth.random_bits(shape, es, 4242)]
+        oracle.set_threads(8)
+        try:
+            want = oracle.run_chain(srcs, ops)
+        finally:
+            oracle.set_threads(1)
+        for env in ({"AMAP_WAVES_LOG": "2"}, {"AMAP_SMALL_BYTES_MB": "0"}):
+            print(f"[gpu] large-tensor plan on {label} under {env}", flush=True)
+            os.environ.update(env)
+            try:
+                m = B.amap_compose(shapes, es, ops)
+                assert B.amap_plan_selfcheck(m) == 0
+                ran = _run_families(dev, m, srcs, want, min_ran=3)
+                assert None in ran
+            finally:
+                for k in env:
+                    os.environ.pop(k, None)
