@@ -329,8 +329,8 @@ def _ptr_array(ptrs, n_min=0):
 
 
 def _src_array(src_ptrs, maps, what):
-    """Source table sized to the maps it serves; a source id a map reads without a pointer is an error here,
-    before the library sees the table."""
+    """Source table sized to the maps it serves; a table too short for a source id a map reads is an error
+    here, before the library sees it (NULL entries are the library's to judge: an empty map reads none)."""
     n_src = 0
     for m in maps:
         info = amap_describe(m)
@@ -340,7 +340,7 @@ def _src_array(src_ptrs, maps, what):
                 amap_source_shape(m, i)
             except AmapError:
                 continue  # an id the map no longer reads
-            if i >= len(src_ptrs) or not src_ptrs[i]:
+            if i >= len(src_ptrs):
                 raise AmapError(AMAP_E_INVALID, f"{what}: no pointer for source {i}")
     return _ptr_array(src_ptrs, n_src)
 
