@@ -53,6 +53,16 @@ struct Digits {
     FastDiv fmult[kMaxDigits], fext[kMaxDigits];
 };
 
+// A padded operand (Section 2.1: the load of a pad operator composed into the consumer load): the one
+// data piece covers, per dimension, index lo + sum_j i_j * mult[j] with i_j < ext[j]; an index is decoded
+// in the radices rad[j] = mult[j + 1] / mult[j] of the PADDED tensor and lies in the piece iff every
+// digit stays below the piece's extent.  Everything else reads the pad constant.
+struct PadBox {
+    uint32_t lo;
+    uint32_t rad[kMaxDigits];   // rad of the outermost digit: 0 = unbounded
+    FastDiv frad[kMaxDigits];
+};
+
 struct GemmArgs {
     const uint16_t *A_src;
     const uint16_t *W;
@@ -73,6 +83,9 @@ struct GemmArgs {
     // dimension that is never materialised): segment j covers k in [seg_kend[j-1], seg_kend[j])
     // and reads seg_src[j] at seg_sbase[j] + seg_dm[j](m) + seg_dk[j](k - seg_kend[j-1]).
     // n_seg <= 1: the single-source fields above are used instead.
+    // A with padding: padded = 1, the data piece's box per dimension, the pad constant (two bf16 per word)
+    uint32_t padded, pad_word;
+    PadBox pm, pk;
     uint32_t n_seg;
     uint32_t seg_kend[kMaxSeg];
     uint32_t seg_sbase[kMaxSeg];
@@ -100,6 +113,21 @@ __device__ __forceinline__ uint32_t digits_offset(const Digits &d, uint32_t x) {
         off += dig * (uint32_t)d.ss[j];
     }
     return off;
+}
+
+// index x of a padded dimension -> inside the data piece? and its source offset along that dimension
+__device__ __forceinline__ bool padded_offset(const Digits &d, const PadBox &b, uint32_t x, uint32_t &off) {
+    off = 0;
+    if (x < b.lo) return false;
+    const uint32_t y = x - b.lo;
+    bool in = true;
+    for (uint32_t j = 0; j < d.n; ++j) {
+        uint32_t q = fdiv(y, d.fmult[j]);
+        if (b.rad[j]) q -= fdiv(q, b.frad[j]) * b.rad[j];
+        in = in && q < d.ext[j];
+        off += q * (uint32_t)d.ss[j];
+    }
+    return in;
 }
 
 // Byte offset inside an operand tile kept as [row][64 k] bf16 (128 B per row,
@@ -178,7 +206,12 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
         for (int i = 0; i < 8; ++i) {
             uint32_t row = m0 + (tid >> 3) + 32u * i;
             if constexpr (EDGE) row = row < g.M ? row : g.M - 1;
-            a_soff[i] = segmented ? g.seg_sbase[sg] + digits_offset(g.seg_dm[sg], row) : g.sbase + digits_offset(g.dm, row);
+            if (EDGE && !segmented && g.padded) {
+                uint32_t off;   // (a source of < 2^31 elements: no offset reaches the mark of a row outside the data piece)
+                a_soff[i] = padded_offset(g.dm, g.pm, row, off) ? g.sbase + off : 0xFFFFFFFFu;
+            } else {
+                a_soff[i] = segmented ? g.seg_sbase[sg] + digits_offset(g.seg_dm[sg], row) : g.sbase + digits_offset(g.dm, row);
+            }
         }
     };
     if constexpr (AM == A_RUNS_K) {
@@ -221,12 +254,26 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
                     a_rows_of_segment(sg);
                 }
                 koff = digits_offset(g.seg_dk[sg], kc_ok ? kc - seg_klo : 0u);
+            } else if (EDGE && g.padded) {
+                // vectors past K are zero (they meet zero rows of W); vectors outside the data piece hold the pad constant
+                // (every lane loads: one outside the piece reads the piece's first vector and drops it)
+                const bool k_in = padded_offset(g.dk, g.pk, kc_ok ? kc : 0u, koff) && kc_ok;
+                const uint32_t c = kc_ok ? g.pad_word : 0u;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const bool in = k_in && a_soff[i] != 0xFFFFFFFFu;
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(a_base + (size_t)(in ? a_soff[i] + koff : g.sbase));
+                    ra[i] = in ? v : u32x4{c, c, c, c};
+                }
+                koff = 0;
             } else {
                 koff = digits_offset(g.dk, kc_ok ? kc : 0u);
             }
+            if (!(EDGE && !segmented && g.padded)) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                ra[i] = kc_ok ? *reinterpret_cast<const u32x4 *>(a_base + (size_t)(a_soff[i] + koff)) : zero4;
+                for (int i = 0; i < 8; ++i)
+                    ra[i] = kc_ok ? *reinterpret_cast<const u32x4 *>(a_base + (size_t)(a_soff[i] + koff)) : zero4;
+            }
         } else if constexpr (!segmented) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -627,6 +674,48 @@ bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d, int64_t lo 
     return true;
 }
 
+
+// The loops of one dst dimension of a data piece that padding surrounds: digits as in make_digits plus
+// the box (origin and, per digit, the radix of the padded tensor) that tells inside from outside.
+bool make_pad_digits(const Piece &p, int dim, Digits &d, PadBox &b) {
+    std::memset(&d, 0, sizeof(d));
+    std::memset(&b, 0, sizeof(b));
+    std::vector<IterDim> its;
+    for (const IterDim &it : p.it)
+        if (it.dim == dim) its.push_back(it);
+    std::sort(its.begin(), its.end(), [](const IterDim &x, const IterDim &y) { return x.mult < y.mult; });
+    for (size_t i = 0; i + 1 < its.size();) {   // loops that continue one another on both sides are one digit
+        const IterDim &in = its[i], &out = its[i + 1];
+        if (out.mult == in.mult * in.extent && out.sstride == in.sstride * in.extent) {
+            its[i].extent *= out.extent;
+            its.erase(its.begin() + i + 1);
+        } else {
+            ++i;
+        }
+    }
+    if (its.empty()) its.push_back(IterDim{1, dim, 1, 0});   // a single index of this dimension
+    if (its.size() > (size_t)kMaxDigits || its[0].mult != 1 || p.lo[dim] < 0 || p.lo[dim] >= (1ll << 31)) return false;
+    b.lo = (uint32_t)p.lo[dim];
+    for (size_t j = 0; j < its.size(); ++j) {
+        const IterDim &it = its[j];
+        if (it.extent >= (1ll << 31) || it.mult >= (1ll << 31)) return false;
+        d.mult[j] = (uint32_t)it.mult;
+        d.ext[j] = (uint32_t)it.extent;
+        d.ss[j] = (int32_t)it.sstride;
+        d.fmult[j] = make_fastdiv(d.mult[j]);
+        d.fext[j] = make_fastdiv(d.ext[j]);
+        if (j + 1 < its.size()) {
+            if (its[j + 1].mult % it.mult) return false;
+            const int64_t rad = its[j + 1].mult / it.mult;
+            if (rad < it.extent) return false;
+            b.rad[j] = (uint32_t)rad;
+            b.frad[j] = make_fastdiv(b.rad[j]);
+        }
+    }
+    d.n = (uint32_t)its.size();
+    return true;
+}
+
 }  // namespace
 
 namespace {
@@ -678,7 +767,7 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     const int64_t M = A_map->shape[0], K = A_map->shape[1];
     if (M == 0 || K == 0) return unsupported("empty product");
     if (N % 8 || K % 8) return unsupported("N and K must be multiples of 8");
-    const bool edge = M % BM || N % BN || K % BK;
+    bool edge = M % BM || N % BN || K % BK;
     if (!A_map->strided || A_map->pieces.empty()) return unsupported("the A map has no strided form");
     if (M * K >= (1ll << 31) || M * N >= (1ll << 40) || K * N >= (1ll << 31)) return unsupported("operand too large for 32-bit offsets");
     if (out_map && M * N >= (1ll << 31)) return unsupported("product too large for a mapped store");
@@ -688,8 +777,24 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     // ---- the A operand: one piece, or one piece per range of k (segments, sorted by k)
     // A piece whose k indices are not one interval (one source feeding two ranges of k is kept
     // as one piece with an outer loop over the two) is taken apart along that loop.
-    std::vector<Piece> parts(A_map->pieces.begin(), A_map->pieces.end());
-    for (size_t i = 0; i < parts.size() && parts.size() <= (size_t)kMaxSeg; ++i) {
+    // Padding (Section 2.1, a pad operator in front of the product): fill pieces of one constant around
+    // ONE data piece are folded into the operand load; the pieces of a map partition its index space, so
+    // whatever the data piece does not cover reads the constant.
+    std::vector<Piece> parts;
+    bool padded = false;
+    uint32_t pad_bits = 0;
+    for (const Piece &q : A_map->pieces) {
+        if (!q.fill) {
+            parts.push_back(q);
+        } else if (padded && (q.fill_bits & 0xFFFFu) != pad_bits) {
+            return unsupported("the A map pads with more than one constant");
+        } else {
+            padded = true;
+            pad_bits = q.fill_bits & 0xFFFFu;
+        }
+    }
+    if (padded && (parts.size() != 1 || by_id)) return unsupported("padding around an A operand of several pieces");
+    for (size_t i = 0; !padded && i < parts.size() && parts.size() <= (size_t)kMaxSeg; ++i) {
         for (;;) {
             std::vector<IterDim> kl;
             for (const IterDim &it : parts[i].it)
@@ -724,7 +829,6 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     int64_t k_at = 0;
     for (size_t j = 0; j < segs.size(); ++j) {
         const Piece &p = *segs[j];
-        if (p.fill) return unsupported("the A map has a fill piece (padding)");
         const void *src = A_srcs[by_id ? p.src : 0];
         if (!src || ((uintptr_t)src & 15)) return AMAP_E_INVALID;
         const int64_t svol = volume_of(A_map->src_shapes[p.src]);
@@ -732,6 +836,20 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
         if (overlaps(out, cbytes, src, svol * 2)) return AMAP_E_ALIAS;
         const int64_t kext = piece_extent(p, 1);
         Digits dm, dk;
+        if (padded) {
+            if (!make_pad_digits(p, 0, dm, g.pm) || !make_pad_digits(p, 1, dk, g.pk)) return unsupported("the padded A map does not decode into digits");
+            // whole 16-byte vectors along k lie inside or outside the data piece
+            if (!vector_runs(dk, dm, p.sbase) || g.pk.lo % 8 || (g.pk.rad[0] && g.pk.rad[0] % 8)) return unsupported("the padded A map has no 8-element aligned runs along k inside 8-element aligned padding");
+            g.padded = 1;
+            g.pad_word = pad_bits | (pad_bits << 16);
+            amode = A_RUNS_K;
+            g.A_src = static_cast<const uint16_t *>(src);
+            g.sbase = (uint32_t)p.sbase;
+            g.dm = dm;
+            g.dk = dk;
+            k_at = K;
+            break;
+        }
         // every segment spans all of m and continues k where the one before ended
         if (!make_digits(p, 0, M, dm) || !make_digits(p, 1, kext, dk, k_at)) return unsupported("a piece of the A map does not span all of m, or the pieces do not follow one another along k");
         int mode = A_RUNS_K;
@@ -811,7 +929,8 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     // ---- the aligned common case runs on 256 x 256 tiles (see amap_gemm_tile256_kernel)
     const char *t256 = std::getenv("AMAP_GEMM_TILE256");   // 0: always the general kernel (tests compare the two)
     const bool tile256_on = !(t256 && t256[0] == '0');
-    if (tile256_on && amode == A_RUNS_K && segs.size() == 1 && wmode == W_PLAIN && M % T2M == 0 && N % T2N == 0 && K % T2K == 0 &&
+    if (g.padded) edge = true;   // the instances that test every vector also take the padding
+    if (tile256_on && !g.padded && amode == A_RUNS_K && segs.size() == 1 && wmode == W_PLAIN && M % T2M == 0 && N % T2N == 0 && K % T2K == 0 &&
         K >= 2 * T2K && g.dm.mult[0] == 1 && g.dm.ext[0] % T2M == 0 && g.dk.mult[0] == 1 && g.dk.ss[0] == 1 && g.dk.ext[0] % T2K == 0) {
         static thread_local int n_cu = 0;
         if (n_cu == 0) {

@@ -133,7 +133,8 @@ def test_unsupported_and_error_paths(dev):
         (B.amap_compose([(256, 64)], 2, []), 196, B.AMAP_E_UNSUPPORTED),                    # N % 8
         (B.amap_compose([(256, 64)], 4, []), 256, B.AMAP_E_INVALID),                        # not 2-byte
         (B.amap_compose([(4, 256, 64)], 2, []), 256, B.AMAP_E_INVALID),                     # not a matrix
-        (B.amap_compose([(256, 60)], 2, [("pad", (0, 0), (0, 4), 0)]), 256, B.AMAP_E_UNSUPPORTED),  # fill piece
+        (B.amap_compose([(256, 60)], 2, [("pad", (0, 0), (0, 4), 0)]), 256, B.AMAP_E_UNSUPPORTED),  # padding that cuts a 16-byte vector
+        (B.amap_compose([(256, 64)], 2, [("pad", (0, 0), (0, 8), 0), ("pad", (0, 0), (0, 8), 5)]), 256, B.AMAP_E_UNSUPPORTED),  # two pad constants
         (B.amap_compose([(64, 252)], 2, [("transpose", (1, 0))]), 256, B.AMAP_E_UNSUPPORTED),       # runs along m, M % 8
         (B.amap_compose([(64, 512)], 2, [("transpose", (1, 0)), ("slice", 0, 0, 512, 2)]), 256, B.AMAP_E_UNSUPPORTED),  # no runs at all
         (B.amap_compose([(256, 128)], 2, [("slice", 1, 0, 128, 2)]), 256, B.AMAP_E_UNSUPPORTED),    # strided k
@@ -494,3 +495,40 @@ def test_tile256_identity_weight_is_exact(dev, monkeypatch, capfd):
     rest = np.ones(256, dtype=bool)
     rest[cols] = False
     assert not (got[:, rest] & 0x7FFF).any()
+
+
+# ---- padding in front of the product: the pad operator's load composed into the operand load (Section 2.1, eq. 4)
+
+PAD_CASES = [
+    # A source shape, chain -> [M,K] (with fill pieces), N
+    ((200, 120), [("pad", (3, 8), (5, 16), 0)], 128),                                               # rows and columns padded: [208,144]
+    ((2, 6, 6, 32), [("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0), ("reshape", (128, 32))], 72),           # padded image, then flattened: rows inside and outside alternate
+    ((64, 4, 24), [("pad", (0, 0, 0), (0, 0, 8), 0), ("reshape", (64, 128))], 64),                   # padding inside k: 24 of every 32
+    ((100, 64), [("pad", (28, 0), (128, 0), 0x3FC0)], 136),                                          # pad constant 1.5, several row tiles
+    ((3, 40, 64), [("transpose", (1, 0, 2)), ("pad", (4, 0, 0), (4, 0, 8), 0), ("reshape", (48, 216))], 40),  # mapped source under the padding
+]
+
+
+@pytest.mark.parametrize("case", range(len(PAD_CASES)))
+def test_padded_a_operand_vs_oracle(dev, case):
+    shape, ops, N = PAD_CASES[case]
+    print(f"[gpu] padded gemm case {case} {shape} {ops}", flush=True)
+    rng = np.random.default_rng(900 + case)
+    src = synth.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    a = oracle.run_chain([src], ops)                      # pad materialised by the oracle
+    K = a.shape[1]
+    wt = synth.f32_to_bf16_bits((rng.standard_normal((K, N)) * 0.05).astype(np.float32))
+    m = B.amap_compose([shape], 2, ops)
+    assert B.amap_describe(m).n_fill_pieces >= 1
+    got = _gemm(dev, src, shape, ops, wt)
+    _check(got, a, wt)
+
+
+def test_padded_a_identity_weight_is_exact(dev):
+    """W = identity: the product reproduces the padded A bit for bit, pad constant included."""
+    shape, ops = (2, 6, 6, 32), [("pad", (0, 1, 1, 0), (0, 1, 1, 0), 0x4049), ("reshape", (128, 32))]
+    src = synth.f32_to_bf16_bits(np.random.default_rng(5).standard_normal(shape).astype(np.float32))
+    got = _gemm(dev, src, shape, ops, synth.f32_to_bf16_bits(np.eye(32, dtype=np.float32)))
+    a = oracle.run_chain([src], ops)
+    nz = (a & 0x7FFF) != 0
+    assert np.array_equal(got[nz], a[nz]) and not (got[~nz] & 0x7FFF).any()
