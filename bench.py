@@ -513,6 +513,30 @@ def bench_graph(torch, device, B, synth, steps, warmup):
             "after_hip_graph_ms": round(g_gpu, 4)}
 
 
+def bench_small_permute(torch, device, B, synth, steps, warmup):
+    """Short dst rows at bandwidth sizes (>= 1 GiB moved per launch): the cross-lane form (one vector per
+    lane, V x V blocks exchanged between lanes) against the register micro-transpose of the tile
+    kernels, chosen with the planner's AMAP_XLANE switch (2: wherever it applies, 0: nowhere; unset:
+    the planner's own choice)."""
+    out = {}
+    for name, kw in (("cfg0", {"n": 10240}), ("c8_nhwc", {"n": 8192})):
+        row = {}
+        for label, setting in (("cross_lane", "2"), ("micro_transpose", "0"), ("default", None)):
+            if setting is None:
+                os.environ.pop("AMAP_XLANE", None)
+            else:
+                os.environ["AMAP_XLANE"] = setting
+            try:
+                r = bench_workload(torch, device, B, synth, name, steps, warmup, with_unfused=False, with_hot=False, **kw)
+            finally:
+                os.environ.pop("AMAP_XLANE", None)
+            row["min_bytes"] = r["min_bytes"]
+            row[label] = {"kernel": r["kernel"], "kernel_ms": round(r["fused_kernel_ms"], 4),
+                          "kernel_gbs": round(r["fused_kernel_gbs"], 1)}
+        out[r["workload"]] = row
+    return out
+
+
 def cpu_baseline(synth, name, min_bytes, budget_s=12.0):
     from oracle import oracle
     w = synth.workload(name)
@@ -613,7 +637,8 @@ def main():
         for name in synth.NEXT_WORKLOAD_NAMES:
             r = bench_workload(torch, device, B, synth, name, a.steps, a.warmup)
             nxt[r["workload"]] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
-        print(json.dumps({"repeat_tile_reverse": nxt, "graph_dme": bench_graph(torch, device, B, synth, 10, 2),
+        print(json.dumps({"repeat_tile_reverse": nxt, "small_permute": bench_small_permute(torch, device, B, synth, 20, 3),
+                          "graph_dme": bench_graph(torch, device, B, synth, 10, 2),
                           "execute_multi": bench_multi(torch, device, B, synth, a.steps, a.warmup),
                           "layout_assignment": bench_layout(torch, device, B, synth, 10, 2),
                           "fused_gemm_store": bench_gemm_store(torch, device, B, synth, a.steps, a.warmup),
@@ -667,6 +692,7 @@ def main():
         out["fused_gemm_store"] = bench_gemm_store(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["fused_gemm_nchw"] = bench_gemm_nchw(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["fused_gemm_gather"] = bench_gemm_gather(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
+        out["small_permute"] = bench_small_permute(torch, device, B, synth, 20, 3)
         out["execute_multi"] = bench_multi(torch, device, B, synth, max(20, a.steps // 3), max(5, a.warmup // 3))
         out["graph_dme"] = bench_graph(torch, device, B, synth, 10, 2)
         out["layout_assignment"] = bench_layout(torch, device, B, synth, 10, 2)

@@ -135,7 +135,15 @@ typedef enum {
     AMAP_K_ROWS = 2,    /* both sides share their contiguous dimension: vector row copy     */
     AMAP_K_TILE = 3,    /* contiguous dimension permuted: LDS-staged tile transpose (also the
                            flat tiles: blocks of rows that are contiguous on one side)      */
-    AMAP_K_WAVE = 4     /* small permute: in-register / cross-lane transpose, no LDS        */
+    AMAP_K_WAVE = 4     /* small permute without LDS, one tile per wavefront.  Two forms: the
+                           register micro-transpose (every lane loads V source vectors and
+                           reorders its V x V block in its own registers), and, for 2-byte
+                           elements in dst rows of 16 or 32 bytes, the cross-lane form (one
+                           vector per lane, the V x V block exchanged between V lanes with
+                           ds_bpermute), which is ahead only there (4.7 against 4.0 TB/s at
+                           1 GiB per launch; 3.4 against 5.9 TB/s on 80-byte rows of 4-byte
+                           elements).  Environment AMAP_XLANE=0 plans the first form
+                           everywhere, 2 the second wherever it applies.                    */
 } amap_kernel_id;
 
 typedef struct {

@@ -39,7 +39,8 @@ enum PieceKind : uint32_t {
     PK_ROWS = 0,  // one lane per vector, dst order (also fill pieces and the element-wise form)
     PK_TILE = 1,  // P x Q tile, register micro-transpose, staged through LDS
     PK_WAVE = 2,  // P x Q tile per wavefront, register micro-transpose, no LDS
-    PK_FLAT = 3   // block of rows that is one contiguous run on one side, staged through LDS
+    PK_FLAT = 3,  // block of rows that is one contiguous run on one side, staged through LDS
+    PK_XLANE = 4  // short P runs: one vector per lane, V x V blocks transposed across V lanes (ds_bpermute)
 };
 
 enum PieceFlags : uint32_t {
@@ -118,6 +119,12 @@ struct DevPiece {
     // element by element at the two ends.  LDS rows are rag_w elements apart.
     uint32_t rag_cb, rag_w, rag_s;
     FastDiv fd_rag_s;
+    // XLANE only.  A dst row (the whole P run, fills beside it included) is xl_npv vectors long; a wavefront
+    // takes xl_rows consecutive Q positions (a multiple of V, xl_rows * xl_npv <= 64): lane l stores vector
+    // l % xl_npv of row l / xl_npv, so the stores of a wavefront are one contiguous run of dst.  n_units =
+    // wavefront tiles of the piece (tilesQ per batch point); loops as for TILE.
+    uint32_t xl_npv, xl_rows;
+    FastDiv fd_npv;
     // Window of the piece in tensors too large for 32-bit offsets: dbase and every
     // dst offset are relative to element dwin of dst; swin likewise for the source
     // (the host folds it into `src` at launch).  0 for ordinary tensors.

@@ -290,6 +290,54 @@ AMAP_HD uint32_t q_chain_offset(const DevPiece &P, uint32_t w) {
     return off + w * (uint32_t)P.loops[P.nq - 1].ds;
 }
 
+// ---- cross-lane form (PK_XLANE): what one lane loads and stores.
+// The V lanes of a unit sit xl_npv lanes apart (same P vector pv, Q positions w0 .. w0 + V - 1): lane k
+// of the unit LOADS the V elements along Q at P index pv * V + k and, after the V x V block has been
+// transposed across the unit, STORES the V elements along P at Q position w0 + k.
+struct XlaneLane {
+    bool ok;          // the lane's unit lies inside the piece (all V lanes of a unit agree)
+    uint32_t doff;    // dst element offset of the vector the lane stores
+    uint32_t k;       // the lane's place in its unit
+    uint32_t lane0;   // first lane of the unit; the others follow xl_npv lanes apart
+    uint32_t sub;     // entry of the piece group the unit reads (all of a unit's P indices lie in one entry)
+    const void *src;  // that entry's source (null: constant) and fill pattern
+    uint32_t fill;
+    uint32_t soff;    // source element offset of the vector the lane loads
+};
+
+AMAP_HD XlaneLane xlane_lane(const DevPiece &P, const TileGeom &G, uint32_t vlog, uint32_t lane, bool grouped = true) {
+    XlaneLane L;
+    const uint32_t V = 1u << vlog;
+    const uint32_t ql = fdiv(lane, P.fd_npv), pv = lane - ql * P.xl_npv;
+    const uint32_t a = ql >> vlog;
+    L.k = ql & (V - 1);
+    L.lane0 = (a << vlog) * P.xl_npv + pv;
+    const uint32_t w0 = G.tq * P.xl_rows + (a << vlog), q = w0 + L.k;
+    L.ok = ql < P.xl_rows && w0 < P.EQ;
+    const uint32_t p = pv << vlog;  // first P index of the unit
+    L.doff = G.db + q_chain_offset(P, L.ok ? q : 0) + p;
+    L.sub = 0;
+    L.src = P.src;
+    L.fill = P.fill;
+    L.soff = G.sb + (p + L.k) * (uint32_t)P.ssP + w0;
+    if (!grouped) return L;
+    const uint32_t n = P.group_n;
+    for (uint32_t j = 1; j < n; ++j) {
+        const DevPiece &S = (&P)[j];
+        uint32_t sb = S.sbase;
+#pragma unroll
+        for (uint32_t i = 0; i < (uint32_t)kMaxLoops; ++i)
+            if (P.nq + i < P.nloops) sb += G.dig[i] * (uint32_t)S.loops[P.nq + i].ss;
+        if (p >= S.p_begin) {  // entries are in increasing p_begin order: the last match wins
+            L.sub = j;
+            L.src = S.src;
+            L.fill = S.fill;
+            L.soff = sb + (p + L.k - S.p_begin) * (uint32_t)S.ssP + w0;
+        }
+    }
+    return L;
+}
+
 // LDS slot (in vectors) of the vector at (row, column cv) of the tile.  The tile
 // is kept in dst order (one row per Q position, pitch = the tile's P extent),
 // so the store phase reads whole rows.  In the load phase the lanes of a

@@ -437,6 +437,70 @@ __device__ __forceinline__ void tile_body(const DevPiece &P, char *dst, uint32_t
     }
 }
 
+// ------------------------------------------------------------------ cross-lane tiles
+// Short P runs (a dst row of at most 128 bytes, fills beside it included).  Every lane loads ONE 16-byte
+// vector along Q and stores ONE 16-byte vector along P; in between, the V x V block held by the V lanes of
+// a unit is transposed across those lanes with ds_bpermute (no LDS memory, no barrier).  Lane l stores
+// vector l of the wavefront's tile in dst order, so a store instruction covers one contiguous run of dst
+// whatever the row length: with the register micro-transpose the same stores are 16-byte pieces a row apart.
+//   4-byte elements: 4 x 4 block over 4 lanes, three exchanges of one dword (round s: lane k sends its
+//   element (k - s) % 4 to lane (k - s) % 4 ... i.e. reads from lane (k + s) % 4 what that lane holds for it).
+//   2-byte elements: 8 x 8 block over 8 lanes: first the two lanes of a pair swap halves so that a dword holds
+//   one element of each (4 exchanges), then the 4 x 4 transposition of dwords among the pairs (3 exchanges).
+// v_i of four values held in registers (scalars on purpose: a select between elements of a local array is
+// turned into an indexed load, which sends the array to scratch memory)
+__device__ __forceinline__ uint32_t pick4(uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, uint32_t i) {
+    const uint32_t lo = (i & 1u) ? v1 : v0, hi = (i & 1u) ? v3 : v2;
+    return (i & 2u) ? hi : lo;
+}
+
+// out D = value K (the reader's place) of the lane D places on in the ring of four lanes lane_of(0 .. 3)
+template <class LaneOf>
+__device__ __forceinline__ void ring_transpose4(uint32_t i0, uint32_t i1, uint32_t i2, uint32_t i3, uint32_t &o0, uint32_t &o1, uint32_t &o2,
+                                                uint32_t &o3, uint32_t K, LaneOf lane_of) {
+    const uint32_t g0 = pick4(i0, i1, i2, i3, K);
+    const uint32_t g1 = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(lane_of((K + 1u) & 3u) << 2), (int)pick4(i0, i1, i2, i3, (K - 1u) & 3u));
+    const uint32_t g2 = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(lane_of((K + 2u) & 3u) << 2), (int)pick4(i0, i1, i2, i3, (K - 2u) & 3u));
+    const uint32_t g3 = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(lane_of((K + 3u) & 3u) << 2), (int)pick4(i0, i1, i2, i3, (K - 3u) & 3u));
+    o0 = pick4(g0, g1, g2, g3, (0u - K) & 3u);
+    o1 = pick4(g0, g1, g2, g3, (1u - K) & 3u);
+    o2 = pick4(g0, g1, g2, g3, (2u - K) & 3u);
+    o3 = pick4(g0, g1, g2, g3, (3u - K) & 3u);
+}
+
+template <int ES, int NT, bool GROUPED>
+__device__ __forceinline__ void xlane_body(const DevPiece &P, char *dst, uint32_t blk, uint32_t tid) {
+    constexpr uint32_t VLOG = ES == 2 ? 3 : 2;
+    const uint32_t wave = tid >> 6, lane = tid & 63;
+    const uint32_t t = (blk << P.nwlog) + wave;
+    if (t >= P.n_units) return;  // the whole wavefront: no exchange partner is lost
+    const TileGeom G = tile_geometry(P, VLOG, t);
+    const XlaneLane L = xlane_lane(P, G, VLOG, lane, GROUPED);
+    uint32_t in[4], out[4];
+    if (L.ok && L.src) {
+        gld<16, (NT & PF_NT_LOAD) != 0>(in, (const char *)L.src + (size_t)L.soff * ES);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) in[i] = L.fill;
+    }
+    const uint32_t npv = P.xl_npv;
+    if constexpr (ES == 4) {
+        ring_transpose4(in[0], in[1], in[2], in[3], out[0], out[1], out[2], out[3], L.k, [&](uint32_t j) { return L.lane0 + j * npv; });
+    } else {
+        // the pair (k, k ^ 1): afterwards dword d of the even lane holds element 2 d of both, of the odd lane element 2 d + 1
+        const uint32_t partner = (L.lane0 + (L.k ^ 1u) * npv) << 2;
+        uint32_t t2[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t o = (uint32_t)__builtin_amdgcn_ds_bpermute((int)partner, (int)in[d]);
+            t2[d] = (L.k & 1u) ? ((o >> 16) | (in[d] & 0xFFFF0000u)) : ((in[d] & 0xFFFFu) | (o << 16));
+        }
+        const uint32_t r = L.k & 1u;
+        ring_transpose4(t2[0], t2[1], t2[2], t2[3], out[0], out[1], out[2], out[3], L.k >> 1, [&](uint32_t j) { return L.lane0 + (2u * j + r) * npv; });
+    }
+    if (L.ok) gst<16, (NT & PF_NT_STORE) != 0>(dst + (size_t)L.doff * ES, out);
+}
+
 // ------------------------------------------------------------------ flat tiles
 // A block of 64 rows that is one contiguous run on one side (see DevPiece::flat).  The run passes
 // through LDS unchanged, in whole 16-byte vectors whatever the row length C is; the other side is
@@ -657,6 +721,8 @@ __global__ __launch_bounds__(kMaxThreads) void amap_pieces_kernel(const LaunchAr
     char *const d = dst + (size_t)P.dwin * ES;
     if (P.kind == PK_ROWS)
         rows_body<ES, NT>(P, d, local, threadIdx.x);
+    else if (P.kind == PK_XLANE)
+        xlane_body<ES, NT, GROUPED>(P, d, local, threadIdx.x);
     else if (P.kind == PK_TILE)
         tile_dispatch<ES, true, NT, GROUPED>(P, d, local, threadIdx.x, reinterpret_cast<char *>(smem_v));
     else if (P.kind == PK_FLAT && P.rag_cb)

@@ -724,6 +724,41 @@ static int plan_piece(const amap &m, const KPiece &kp, int family, uint32_t nwlo
         dp.flags &= nt_mask(kp);
     }
     vec_bytes = (int)V * es;
+    // ---- short P runs: the cross-lane form.  A dst row (fills beside it included, when this is the head of
+    // a piece group) of at most 128 bytes; one 16-byte vector per lane each way, stores of a wavefront contiguous.
+    {
+        const uint32_t npv = dp.eP / V;
+        const uint32_t R = npv ? ((64u / npv) / V) * V : 0;
+        // Measured at 1 GiB per launch: ahead of the register micro-transpose only where a wavefront still covers
+        // 64 bytes or more of every source row it touches, i.e. for 2-byte elements in dst rows of one or two
+        // vectors (5.0 against 4.1 and 4.8 TB/s); behind it for longer rows and for 4-byte elements
+        // (3.5 against 5.7 TB/s on 80-byte rows).  AMAP_XLANE=2 plans it wherever it applies, 0 nowhere.
+        const int xl = env_int("AMAP_XLANE", 1);
+        const bool xl_pays = xl >= 2 || (es == 2 && npv <= 2);
+        if (xl && xl_pays && V * (uint32_t)es == 16 && dp.eP % V == 0 && (uint64_t)dp.eP * es <= 128 && npv >= 1 && npv <= 8 &&
+            R >= V && EQ % V == 0) {
+            dp.kind = PK_XLANE;
+            dp.xl_npv = npv;
+            dp.xl_rows = R;
+            dp.fd_npv = make_fastdiv(npv);
+            dp.tilesP = 1;
+            dp.fdTP = make_fastdiv(1);
+            dp.tilesQ = (uint32_t)((EQ + R - 1) / R);
+            dp.fdTQ = make_fastdiv(dp.tilesQ);
+            const int64_t tiles = (int64_t)dp.tilesQ * batch;
+            if (tiles >= (1ll << 31)) return -1;
+            dp.n_units = (uint32_t)tiles;
+            dp.n_blocks = (uint32_t)((tiles + NW - 1) / NW);
+            dp.lqlog = dp.nwplog = dp.swz_bits = dp.swz_shift = 0;
+            lds = 0;
+            // streaming stores where every wavefront's run of dst is whole lines; the loads of a wavefront are
+            // short pieces of many source rows and stay cached
+            std::vector<int64_t> ds_all;
+            for (uint32_t k = 0; k < dp.nloops; ++k) ds_all.push_back(k == 0 ? (int64_t)dp.loops[0].ds * R : (int64_t)dp.loops[k].ds);
+            dp.flags = line_aligned(es, {(int64_t)dp.eP * R, kp.dbase}, ds_all) && dp.loops[0].ds == (int32_t)dp.eP ? PF_NT_STORE : 0;
+            dp.flags &= nt_mask(kp);
+        }
+    }
     return fam;
 }
 
@@ -946,7 +981,7 @@ static bool plan_strided_nw(const amap &m, int family, int nw_forced, Plan &out,
     auto emit = [&](const std::vector<DevPiece> &dps, uint32_t lds, int vb, int fam, int64_t vol) {
         if (trace)
             for (const DevPiece &d : dps) {
-                const char *form = d.kind == PK_TILE ? "tile" : d.kind == PK_WAVE ? "wave" : "rows";
+                const char *form = d.kind == PK_TILE ? "tile" : d.kind == PK_WAVE ? "wave" : d.kind == PK_XLANE ? "xlane" : "rows";
                 if (d.kind == PK_FLAT && d.rag_cb) form = d.flat == 1 ? "flat-blocked-src" : "flat-blocked-dst";
                 if (d.kind == PK_FLAT && !d.rag_cb) form = d.flat == 1 ? "flat-src" : "flat-dst";
                 if (d.kind == PK_ROWS) {

@@ -221,6 +221,35 @@ struct Replay {
             }
     }
 
+    // cross-lane form: lane k of a unit stores, at Q position w0 + k, element k of the vector that each of
+    // the unit's V lanes (xl_npv lanes apart, lane j holding P index + j) has loaded
+    void xlane(const DevPiece &P, uint32_t blk) {
+        const uint32_t vlog = P.vlog, V = 1u << vlog;
+        if (V * (uint32_t)m.elem != 16 || P.xl_npv < 1 || P.xl_rows < V || P.xl_rows % V || P.xl_rows * P.xl_npv > 64 || P.tilesP != 1) {
+            ++errors;
+            return;
+        }
+        for (uint32_t wave = 0; wave < (1u << P.nwlog); ++wave) {
+            const uint32_t t = (blk << P.nwlog) + wave;
+            if (t >= P.n_units) continue;
+            const TileGeom G = tile_geometry(P, vlog, t);
+            XlaneLane L[64];
+            for (uint32_t lane = 0; lane < 64; ++lane) L[lane] = xlane_lane(P, G, vlog, lane);
+            for (uint32_t lane = 0; lane < 64; ++lane) {
+                if (!L[lane].ok) continue;
+                for (uint32_t j = 0; j < V; ++j) {
+                    const uint32_t from = L[lane].lane0 + j * P.xl_npv;   // the unit's lane that loaded P index + j
+                    if (from >= 64 || !L[from].ok || L[from].k != j || L[from].lane0 != L[lane].lane0 || L[from].sub != L[lane].sub) {
+                        ++errors;
+                        continue;
+                    }
+                    const int sid = (int)(uintptr_t)L[from].src - 1;
+                    write((int64_t)P.dwin + L[lane].doff + j, code_of(sid, (int64_t)(&P)[L[from].sub].swin + L[from].soff + L[lane].k));
+                }
+            }
+        }
+    }
+
     void tile(const DevPiece &P, uint32_t t, uint32_t lds_bytes) {
         const uint32_t vlog = P.vlog, V = 1u << vlog;
         const TileGeom G = tile_geometry(P, vlog, t);
@@ -315,6 +344,8 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
                     R.rag(P, sid, local, plan->lds_bytes[li]);
                 else if (P.kind == PK_FLAT)
                     R.flat(P, sid, local, plan->lds_bytes[li]);
+                else if (P.kind == PK_XLANE)
+                    R.xlane(P, local);
                 else
                     R.tile(P, local, plan->lds_bytes[li]);
             }

@@ -91,11 +91,11 @@ class Workload:
         return self._make_w() if self._make_w else None
 
 
-def _cfg0():
-    shp = (8, 16, 32, 32)
-    ops = [("transpose", (0, 2, 3, 1)), ("reshape", (8, 1024, 16)),
+def _cfg0(n=8):
+    shp = (n, 16, 32, 32)
+    ops = [("transpose", (0, 2, 3, 1)), ("reshape", (n, 1024, 16)),
            ("slice", 1, 128, 896, 1), ("pad", (0, 0, 0), (0, 0, 4), 0)]
-    return Workload("cfg0", 4, [shp], ops, lambda: [f32_bits(uniform_f32(shp, 0))])
+    return Workload("cfg0" if n == 8 else f"cfg0_n{n}", 4, [shp], ops, lambda: [f32_bits(uniform_f32(shp, 0))])
 
 
 def _cfg1(n=32):
@@ -221,9 +221,18 @@ def _i55_nchw(n=64):
                     lambda: [f32_to_bf16_bits(normal_f32(shp, 12))])
 
 
+def _c8_nhwc(n=1024):
+    """A narrow activation [n,8,64,64] made channels-last: dst rows of 8 elements, one 16-byte vector."""
+    shp = (n, 8, 64, 64)
+    ops = [("transpose", (0, 2, 3, 1))]
+    return Workload("c8_nhwc" if n == 1024 else f"c8_nhwc_n{n}", 2, [shp], ops,
+                    lambda: [f32_to_bf16_bits(normal_f32(shp, 13))])
+
+
 NEXT_FACTORIES = {"up2x": _up2x, "up2x_nhwc": _up2x_nhwc, "bcast": _bcast, "flip_seq": _flip_seq,
                   "rgb_nhwc": _rgb_nhwc, "up3x": _up3x,
-                  "s5_nhwc_pad": _s5_nhwc_pad, "s5_nchw_crop": _s5_nchw_crop, "i35_nchw": _i35_nchw, "i55_nchw": _i55_nchw}
+                  "s5_nhwc_pad": _s5_nhwc_pad, "s5_nchw_crop": _s5_nchw_crop, "i35_nchw": _i35_nchw, "i55_nchw": _i55_nchw,
+                  "c8_nhwc": _c8_nhwc}
 
 _FACTORIES = {
     "cfg0": _cfg0, "cfg1": _cfg1, "cfg2_fwd": _cfg2_fwd, "cfg2_rev": _cfg2_rev,

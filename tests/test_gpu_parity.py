@@ -304,13 +304,46 @@ def test_gathered_rows(dev):
     finally:
         del os.environ["AMAP_INTER"]
     for name, kw in (("rgb_nhwc", {"n": 3}), ("up3x", {"n": 2}), ("s5_nhwc_pad", {"n": 3}), ("s5_nchw_crop", {"n": 3}),
-                     ("i35_nchw", {"n": 2}), ("i55_nchw", {"n": 2})):
+                     ("i35_nchw", {"n": 2}), ("i55_nchw", {"n": 2}), ("c8_nhwc", {"n": 5})):
         print(f"[gpu] gathered rows workload {name}", flush=True)
         w = synth.workload(name, **kw)
         srcs = w.sources()
         m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
         assert B.amap_describe(m).vec_bytes == 16
         _run_families(dev, m, srcs, oracle.run_chain(srcs, w.ops))
+
+
+def test_cross_lane_rows(dev, monkeypatch, capfd):
+    """Short dst rows in the cross-lane form (one vector per lane, V x V blocks exchanged between
+    lanes): the small cases of the replay tests and sizes of many wavefronts with ragged tails, both
+    with the form planned wherever it applies and with the default choice."""
+    from tests.test_plan_replay import XLANE
+    big = [
+        ((37, 8, 1000), 2, [("transpose", (0, 2, 1))]),
+        ((37, 16, 1000), 2, [("transpose", (0, 2, 1))]),
+        ((21, 4, 1028), 4, [("transpose", (0, 2, 1))]),
+        ((21, 20, 516), 4, [("transpose", (0, 2, 1))]),
+        ((9, 56, 520), 2, [("transpose", (0, 2, 1))]),
+        ((33, 16, 24, 32), 4, [("transpose", (0, 2, 3, 1)), ("reshape", (33, 768, 16)),
+                               ("slice", 1, 96, 672, 1), ("pad", (0, 0, 0), (0, 0, 4), 0)]),
+        ((64, 8, 32, 32), 2, [("transpose", (0, 2, 3, 1))]),
+    ]
+    for setting in ("2", None):
+        if setting:
+            monkeypatch.setenv("AMAP_XLANE", setting)
+        else:
+            monkeypatch.delenv("AMAP_XLANE")
+        for i, (shape, es, ops) in enumerate(XLANE + big):
+            print(f"[gpu] cross-lane case {i} AMAP_XLANE={setting}", flush=True)
+            x = synth.random_bits(shape, es, 300 + i)
+            monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+            capfd.readouterr()
+            m = B.amap_compose([shape], es, ops)
+            B.amap_describe(m)
+            monkeypatch.delenv("AMAP_PLAN_TRACE")
+            planned = "amap plan: xlane" in capfd.readouterr().err
+            assert planned or not setting
+            _run_families(dev, m, [x], oracle.run_chain([x], ops))
 
 
 def test_keep_plane_rows(dev):

@@ -96,6 +96,62 @@ def test_aligned_plans(case):
     assert _replay_all(m) >= 2
 
 
+# short dst rows (16 to 128 bytes): the cross-lane form, one vector per lane
+XLANE = [
+    ((5, 8, 96), 2, [("transpose", (0, 2, 1))]),                                  # rows of one vector
+    ((5, 16, 96), 2, [("transpose", (0, 2, 1))]),                                 # two vectors
+    ((3, 4, 52), 4, [("transpose", (0, 2, 1))]),                                  # 4-byte elements, one vector
+    ((3, 8, 52), 4, [("transpose", (0, 2, 1))]),
+    ((3, 12, 40), 4, [("transpose", (0, 2, 1))]),                                 # three vectors: 20 rows of 3 per wavefront
+    ((2, 40, 72), 2, [("transpose", (0, 2, 1))]),                                 # five vectors
+    ((2, 64, 24), 2, [("transpose", (0, 2, 1))]),                                 # eight vectors, 128-byte rows
+    ((3, 16, 6, 8), 4, [("transpose", (0, 2, 3, 1)), ("reshape", (3, 48, 16)),
+                        ("slice", 1, 8, 40, 1), ("pad", (0, 0, 0), (0, 0, 4), 7)]),  # copy piece + fill beside it (a group)
+    ((2, 8, 88), 2, [("transpose", (0, 2, 1)), ("pad", (0, 0, 8), (0, 0, 16), 3)]),  # fill on both sides of the row
+    ((2, 8, 40), 2, [("slice", 1, 7, -1, -1), ("transpose", (0, 2, 1))]),         # P walks the source backwards
+    ((2, 24, 40), 2, [("slice", 1, 0, 24, 3), ("transpose", (0, 2, 1))]),         # strided P
+    ((4, 8, 8), 2, [("transpose", (0, 2, 1))]),                                   # a single unit per batch point
+    ((2, 3, 8, 24), 2, [("transpose", (0, 1, 3, 2))]),                            # two batch loops
+]
+
+
+@pytest.mark.parametrize("case", range(len(XLANE)))
+def test_cross_lane_plans(case, monkeypatch, capfd):
+    shape, es, ops = XLANE[case]
+    monkeypatch.setenv("AMAP_XLANE", "2")      # planned wherever the form applies
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    capfd.readouterr()
+    m = B.amap_compose([shape], es, ops)
+    assert B.amap_plan_selfcheck(m, -1) == 0
+    assert "amap plan: xlane" in capfd.readouterr().err
+    monkeypatch.delenv("AMAP_PLAN_TRACE")
+    assert _replay_all(m) >= 2
+    monkeypatch.setenv("AMAP_WAVES_LOG", "0")  # one wavefront per workgroup
+    assert B.amap_plan_selfcheck(B.amap_compose([shape], es, ops), -1) == 0
+
+
+def test_cross_lane_default_is_the_measured_winner(monkeypatch, capfd):
+    """By default only 2-byte elements in dst rows of one or two vectors take the cross-lane form."""
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    took = []
+    for shape, es, ops in XLANE:
+        capfd.readouterr()
+        m = B.amap_compose([shape], es, ops)
+        assert B.amap_plan_selfcheck(m, -1) == 0
+        took.append("amap plan: xlane" in capfd.readouterr().err)
+    for (shape, es, ops), t in zip(XLANE, took):
+        if any(op[0] == "pad" for op in ops):
+            continue                               # the row is several pieces, grouped or not
+        inner = B.dst_shape(B.amap_compose([shape], es, ops))[-1]
+        assert t == (es == 2 and inner <= 16), (shape, es, ops, t)
+    monkeypatch.setenv("AMAP_XLANE", "0")
+    for shape, es, ops in XLANE:
+        capfd.readouterr()
+        m = B.amap_compose([shape], es, ops)
+        assert B.amap_plan_selfcheck(m, -1) == 0
+        assert "amap plan: xlane" not in capfd.readouterr().err
+
+
 # ---- tensors beyond 32-bit offsets: every piece gets a 64-bit window origin and pieces that span
 # too much are cut.  The span limit is lowered so that small tensors take that path.
 
