@@ -173,9 +173,10 @@ def bench_workload(torch, device, B, synth, name, steps, warmup, with_unfused=Tr
     return res
 
 
-def bench_gemm(torch, device, B, synth, steps, warmup):
+def bench_gemm(torch, device, B, synth, steps, warmup, fused_only=False):
     """Fused-prologue GEMM of cfg4 next to: materialise A with the same library, then the
-    same GEMM kernel on the materialised A (identity map)."""
+    same GEMM kernel on the materialised A (identity map).  fused_only: nothing but the fused
+    launches (for profiler runs)."""
     w = synth.workload("cfg4")
     m = B.amap_compose(w.src_shapes, 2, w.ops)
     M, K = B.dst_shape(m)
@@ -218,8 +219,12 @@ def bench_gemm(torch, device, B, synth, steps, warmup):
         # context only: the vendor library's product on the materialised A of the unfused leg
         torch.matmul(s[3].view(torch.bfloat16), s[1].view(torch.bfloat16), out=s[2].view(torch.bfloat16))
 
-    f_gpu, u_gpu, t_gpu, v_gpu = _time_legs(torch, [fused, unfused, fused_wt, vendor], sets, steps, warmup)
     flops = 2.0 * M * N * K
+    if fused_only:
+        f_gpu = _time_launches(torch, fused, sets, steps, warmup)[1]
+        return {"workload": "cfg4", "fused_ms": round(f_gpu, 5), "fused_tflops": round(flops / f_gpu / 1e9, 1),
+                "algorithmic_bytes": src_h.nbytes + w_h.nbytes + M * N * 2}
+    f_gpu, u_gpu, t_gpu, v_gpu = _time_legs(torch, [fused, unfused, fused_wt, vendor], sets, steps, warmup)
     del sets
     torch.cuda.empty_cache()
     return {"workload": "cfg4: C[8192,4096] = A[8192,1024] x W[1024,4096], A read through permute+reshape of [16,16,512,64]",
@@ -572,18 +577,108 @@ def cpu_baseline(synth, name, min_bytes, budget_s=12.0):
     return res
 
 
+TRAFFIC_SOURCES = ["paper_2002_12798_amd/csrc/amap_kernels.hip", "paper_2002_12798_amd/csrc/amap_index.hpp",
+                   "paper_2002_12798_amd/csrc/amap_compose.cpp", "paper_2002_12798_amd/csrc/amap_plan.cpp",
+                   "paper_2002_12798_amd/csrc/amap_device.hpp", "paper_2002_12798_amd/csrc/amap_gemm.hip"]
+COPY_ELEMENTS = 53248000               # 2-byte elements moved by `--copy-only`: 106,496,000 B read and as many written
+
+
+def _sources_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for f in TRAFFIC_SOURCES:
+        h.update(open(os.path.join(ROOT, f), "rb").read())
+    return h.hexdigest()
+
+
 def measured_traffic(workload):
     """HBM bytes per launch from the committed rocprofv3 counter runs, or None if the
     kernel sources have changed since they were taken (or no counters exist for the workload)."""
-    import hashlib
     path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
     if not os.path.exists(path):
         return None
     rec = json.load(open(path))
-    h = hashlib.sha256()
-    for f in rec["sources"]:
-        h.update(open(os.path.join(ROOT, f), "rb").read())
-    return round(rec["traffic_bytes_per_launch"]) if h.hexdigest() == rec["sources_sha256"] else None
+    if rec.get("sources") != TRAFFIC_SOURCES or rec.get("sources_sha256") != _sources_hash():
+        return None
+    return round(rec["traffic_bytes_per_launch"])
+
+
+def record_traffic(d, workload):
+    """Turn rocprofv3 --pmc runs (csv, one counter set per run) into profiles/traffic_<workload>.json.
+    Expected in `d`:  <tag>_<set>_counter_collection.csv  with tag = the workload and "copy"
+    (`bench.py --copy-only`, the plain copy of known size that scales the counters) and set =
+      FETCH_SIZE, WRITE_SIZE            the derived counters (KiB per dispatch)
+      RD  (optional)                    TCC_EA0_RDREQ_sum TCC_EA0_RDREQ_32B_sum TCC_EA0_RDREQ_DRAM_sum TCC_BUBBLE_sum
+      WR  (optional)                    TCC_EA0_WRREQ_sum TCC_EA0_WRREQ_64B_sum TCC_EA0_WRREQ_DRAM_sum
+    RD / WR give a second reading from other counters: requests that went to DRAM, scaled by what the
+    same counter reads per byte of the plain copy."""
+    import csv
+    import statistics
+    kernel = "amap_gemm" if workload == "cfg4" else "amap_pieces"
+    copy_bytes = 2 * COPY_ELEMENTS
+
+    def means(tag, cset, kname):
+        path = os.path.join(d, f"{tag}_{cset}_counter_collection.csv")
+        if not os.path.exists(path):
+            return None
+        per = {}
+        for r in csv.DictReader(open(path)):
+            if kname in r["Kernel_Name"]:
+                per.setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
+        return {k: (statistics.mean(v), len(v)) for k, v in per.items()}
+
+    rec = {"workload": workload, "kernel": kernel, "sources": TRAFFIC_SOURCES, "sources_sha256": _sources_hash()}
+    f, c = means(workload, "FETCH_SIZE", kernel), means("copy", "FETCH_SIZE", "amap_pieces")
+    wf, wc = means(workload, "WRITE_SIZE", kernel), means("copy", "WRITE_SIZE", "amap_pieces")
+    rec["dispatches"] = f["FETCH_SIZE"][1]
+    rec["fetch_kib_fused"], rec["fetch_kib_copy"] = f["FETCH_SIZE"][0], c["FETCH_SIZE"][0]
+    rec["write_kib_fused"], rec["write_kib_copy"] = wf["WRITE_SIZE"][0], wc["WRITE_SIZE"][0]
+    rec["fetch_factor"] = copy_bytes / (rec["fetch_kib_copy"] * 1024)
+    rec["write_factor"] = copy_bytes / (rec["write_kib_copy"] * 1024)
+    rec["read_bytes_per_launch"] = rec["fetch_kib_fused"] * 1024 * rec["fetch_factor"]
+    rec["write_bytes_per_launch"] = rec["write_kib_fused"] * 1024 * rec["write_factor"]
+    rec["traffic_bytes_per_launch"] = rec["read_bytes_per_launch"] + rec["write_bytes_per_launch"]
+    rd, rdc = means(workload, "RD", kernel), means("copy", "RD", "amap_pieces")
+    wr, wrc = means(workload, "WR", kernel), means("copy", "WR", "amap_pieces")
+    if rd and rdc and wr and wrc:
+        second = {"counters_fused": {k: v[0] for k, v in {**rd, **wr}.items()},
+                  "counters_copy": {k: v[0] for k, v in {**rdc, **wrc}.items()}}
+        second["bytes_per_dram_read_request_on_copy"] = copy_bytes / rdc["TCC_EA0_RDREQ_DRAM_sum"][0]
+        second["bytes_per_dram_write_request_on_copy"] = copy_bytes / wrc["TCC_EA0_WRREQ_DRAM_sum"][0]
+        second["read_bytes_per_launch"] = rd["TCC_EA0_RDREQ_DRAM_sum"][0] * second["bytes_per_dram_read_request_on_copy"]
+        second["write_bytes_per_launch"] = wr["TCC_EA0_WRREQ_DRAM_sum"][0] * second["bytes_per_dram_write_request_on_copy"]
+        second["traffic_bytes_per_launch"] = second["read_bytes_per_launch"] + second["write_bytes_per_launch"]
+        rec["dram_request_counters"] = second
+    out = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    json.dump(rec, open(out, "w"), indent=1)
+    print(json.dumps(rec, indent=1))
+
+
+def copy_ceiling(torch, device, B, n_bytes, steps, warmup):
+    """Kernel-side GB/s of a plain copy that moves n_bytes in total (half read, half written) on cold
+    rotating buffers: the identity map through this library and the vendor copy (Tensor.copy_), the
+    better of the two.  What a kernel with no index arithmetic at all reaches at this size."""
+    n = max(8, n_bytes // 4 // 8 * 8)
+    m = B.amap_source(0, (n,), 2)
+    n_sets = max(2, -(-COLD_FOOTPRINT // (4 * n)))
+    sets = [(torch.zeros(n, dtype=torch.int16, device="cuda"), torch.empty(n, dtype=torch.int16, device="cuda"))
+            for _ in range(n_sets)]
+    stream = C.c_void_p(device.current_stream())
+
+    def ours(s):
+        st = B.raw.amap_execute((C.c_void_p * 1)(s[0].data_ptr()), C.c_void_p(s[1].data_ptr()), m.handle, stream)
+        if st != 0:
+            raise RuntimeError(B.amap_status_str(st))
+
+    def vendor(s):
+        s[1].copy_(s[0])
+
+    t_ours = _time_launches(torch, ours, sets, steps, warmup)[1]
+    t_vendor = _time_launches(torch, vendor, sets, steps, warmup)[1]
+    del sets
+    torch.cuda.empty_cache()
+    return {"bytes": 4 * n, "identity_map_gbs": 4 * n / t_ours / 1e6, "vendor_copy_gbs": 4 * n / t_vendor / 1e6,
+            "gbs": 4 * n / min(t_ours, t_vendor) / 1e6}
 
 
 def main():
@@ -602,11 +697,18 @@ def main():
     ap.add_argument("--next-only", action="store_true",
                     help="time only the repeat / tile / reversed-axis workloads and the graph-level elimination")
     ap.add_argument("--fused-only", action="store_true",
-                    help="launch nothing but the fused kernel on cold buffers (for a clean rocprofv3 kernel summary)")
+                    help="launch nothing but the fused kernel on cold buffers (for a clean rocprofv3 kernel summary); "
+                         "with --gemm-only: nothing but the fused-prologue GEMM")
+    ap.add_argument("--record-traffic", metavar="DIR",
+                    help="no GPU work: turn the rocprofv3 --pmc csv files in DIR into profiles/traffic_<workload>.json")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+
+    if a.record_traffic:
+        record_traffic(a.record_traffic, "cfg4" if a.gemm_only else a.workload)
+        return
 
     import torch
     from paper_2002_12798_amd import binding as B
@@ -614,7 +716,7 @@ def main():
     device.require_gpu()
 
     if a.copy_only:
-        n = 53248000
+        n = COPY_ELEMENTS
         m = B.amap_source(0, (n,), 2)
         sets = [(torch.zeros(n, dtype=torch.int16, device="cuda"), torch.empty(n, dtype=torch.int16, device="cuda"))
                 for _ in range(11)]
@@ -630,7 +732,7 @@ def main():
                           "read_bytes": 2 * n, "write_bytes": 2 * n, "kernel_ms": gpu, "gbs": 4 * n / gpu / 1e6}))
         return
     if a.gemm_only:
-        print(json.dumps(bench_gemm(torch, device, B, synth, a.steps, a.warmup)))
+        print(json.dumps(bench_gemm(torch, device, B, synth, a.steps, a.warmup, fused_only=a.fused_only)))
         return
     if a.next_only:
         nxt = {}
@@ -652,6 +754,7 @@ def main():
         scale_kw = {"b" if a.workload.startswith("cfg2") else "n": a.scale}
     main_res = bench_workload(torch, device, B, synth, a.workload, a.steps, a.warmup,
                               with_unfused=not a.fused_only, with_hot=not a.fused_only, **scale_kw)
+    ceiling = None if a.fused_only else copy_ceiling(torch, device, B, main_res["min_bytes"], a.steps, a.warmup)
     extras = {}
     if not a.no_extras:
         for name, kw in [("cfg0", {}), ("cfg2_fwd", {}), ("cfg2_rev", {}), ("cfg3", {}),
@@ -680,6 +783,11 @@ def main():
                      "unit": "GB/s", "frac": round(main_res["fused_kernel_gbs"] / HBM_PEAK_GBS, 4),
                      "traffic": measured_traffic(a.workload), "algorithmic_bytes": main_res["min_bytes"]},
     }
+    if ceiling:
+        # the same number of bytes moved by a plain copy: what the memory system gives a kernel of this size
+        out["copy_ceiling_gbs"] = round(ceiling["gbs"], 2)
+        out["copy_ceiling"] = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in ceiling.items()}
+        out["roofline"]["frac_of_copy_ceiling"] = round(main_res["fused_kernel_gbs"] / ceiling["gbs"], 4)
     if not a.no_extras:
         out["cpu_baseline"] = cpu_baseline(synth, a.workload, main_res["min_bytes"])
         out["other_workloads"] = extras
