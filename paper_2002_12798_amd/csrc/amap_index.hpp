@@ -66,6 +66,28 @@ AMAP_HD void rows_offsets(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_
     soff = s;
 }
 
+// ---- a launch of one plain row piece (16-byte vectors copied or filled, nothing reshuffled in registers) runs
+// in a kernel of its own, which decodes through all kMaxLoops descriptors with a fixed trip count: they are
+// read once, side by side, and a descriptor past nloops is all zero (it hands r on and adds nothing).
+AMAP_HD bool rows_is_plain(const DevPiece &P, int es) {
+    return P.kind == PK_ROWS && !P.rep_log && !P.rev && !P.gather && !P.inter && (es << P.vlog) == 16;
+}
+AMAP_HD void rows_offsets_fixed(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_t &soff) {
+    uint32_t d = P.dbase, s = P.sbase;
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+#endif
+    for (uint32_t k = 0; k < (uint32_t)kMaxLoops; ++k) {
+        const uint32_t q = fdiv(r, P.loops[k].fd);
+        const uint32_t dig = r - q * P.loops[k].extent;
+        d += dig * (uint32_t)P.loops[k].ds;
+        s += dig * (uint32_t)P.loops[k].ss;
+        r = q;
+    }
+    doff = d;
+    soff = s;
+}
+
 // ---- flat tiles (see DevPiece::flat): workgroup t -> element offsets of its block on both sides
 // (of row r0, c = 0), and the number of rows in the block
 // rows per block = 1 << P.lqlog (16, 32 or 64: as many as fit LDS)

@@ -733,6 +733,26 @@ __global__ __launch_bounds__(kMaxThreads) void amap_pieces_kernel(const LaunchAr
         tile_dispatch<ES, false, NT, GROUPED>(P, d, local, threadIdx.x, nullptr);
 }
 
+// ------------------------------------------------------------------ one plain row piece
+// The launch that most row maps come down to (a head split or merge, a permutation of outer
+// dimensions, a broadcast, a plain copy): one piece, 16-byte vectors, nothing to reshuffle.  Same
+// schedule as rows_body (one lane per vector in dst order, kRowsUnroll vectors per lane), without the
+// piece search and the dispatch over forms in front of it.
+template <int ES, int NT>
+__global__ __launch_bounds__(kMaxThreads) void amap_rows_kernel(const DevPiece P, char *dst) {
+    uint32_t doff[kRowsUnroll], soff[kRowsUnroll];
+    bool ok[kRowsUnroll];
+    const uint32_t threads = blockDim.x;
+    const uint32_t base = blockIdx.x * (threads * kRowsUnroll) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) {
+        const uint32_t r = base + u * threads;
+        ok[u] = r < P.n_units;
+        rows_offsets_fixed(P, r, doff[u], soff[u]);
+    }
+    rows_move<16, NT>(P, dst + (size_t)P.dwin * ES, ES, doff, soff, ok);
+}
+
 // ------------------------------------------------------------------ program
 // Element-wise interpreter of the operator program: applies the index
 // function of every operator of the chain in turn (eq. 4 evaluated lazily).
@@ -850,6 +870,22 @@ amap_status launch_pieces(const LaunchArgs &args, uint32_t blocks, size_t lds, i
         grouped = grouped || (args.p[k].kind != PK_ROWS && args.p[k].group_n > 1);
     const dim3 grid(blocks), block(64u << args.nwlog);
     clear_stale_error();
+    if (args.n_pieces == 1 && rows_is_plain(args.p[0], es)) {
+        const DevPiece &P = args.p[0];
+#define AMAP_LAUNCH_ROWS(ES, NT) hipLaunchKernelGGL((amap_rows_kernel<ES, NT>), grid, block, 0, stream, P, d)
+        switch ((es == 2 ? 0 : 4) + (int)(args.nt & 3)) {
+        case 0: AMAP_LAUNCH_ROWS(2, 0); break;
+        case 1: AMAP_LAUNCH_ROWS(2, 1); break;
+        case 2: AMAP_LAUNCH_ROWS(2, 2); break;
+        case 3: AMAP_LAUNCH_ROWS(2, 3); break;
+        case 4: AMAP_LAUNCH_ROWS(4, 0); break;
+        case 5: AMAP_LAUNCH_ROWS(4, 1); break;
+        case 6: AMAP_LAUNCH_ROWS(4, 2); break;
+        default: AMAP_LAUNCH_ROWS(4, 3); break;
+        }
+#undef AMAP_LAUNCH_ROWS
+        return launch_failed("amap_rows_kernel") ? AMAP_E_HIP : AMAP_OK;
+    }
 #define AMAP_LAUNCH(ES, NT)                                                                                  \
     do {                                                                                                     \
         if (grouped)                                                                                         \

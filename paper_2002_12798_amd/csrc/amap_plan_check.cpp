@@ -45,7 +45,8 @@ struct Replay {
         return ((int64_t)sid << 40) + soff;
     }
 
-    void rows(const DevPiece &P, int sid, uint32_t blk) {
+    // alone: the piece is the only one of its launch
+    void rows(const DevPiece &P, int sid, uint32_t blk, bool alone) {
         // the expanding, reversing, gathered and interleaving forms are written for 16-byte vectors whatever
         // vlog says: replay what the kernel does, so that a plan with another width shows up as errors
         const bool fixed16 = P.rev || P.rep_log || P.gather || P.inter;
@@ -54,9 +55,14 @@ struct Replay {
         for (uint32_t tid = 0; tid < threads; ++tid)
             for (int u = 0; u < kRowsUnroll; ++u) {
                 const uint32_t r = blk * (threads * kRowsUnroll) + tid + u * threads;
-                if (r >= P.n_units) continue;
                 uint32_t d, s;
-                rows_offsets(P, r, d, s);
+                {
+                    if (r >= P.n_units) continue;
+                    if (alone && rows_is_plain(P, m.elem))
+                        rows_offsets_fixed(P, r, d, s);
+                    else
+                        rows_offsets(P, r, d, s);
+                }
                 if (P.inter >= 3) {
                     // one plane kept: position q reads element q * eP (+ eP - 1 for the last-of-group form)
                     for (uint32_t q = 0; q < V; ++q) {
@@ -339,7 +345,7 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
                     continue;
                 }
                 if (P.kind == PK_ROWS)
-                    R.rows(P, sid, local);
+                    R.rows(P, sid, local, A.n_pieces == 1);
                 else if (P.kind == PK_FLAT && P.rag_cb)
                     R.rag(P, sid, local, plan->lds_bytes[li]);
                 else if (P.kind == PK_FLAT)

@@ -346,6 +346,26 @@ def test_cross_lane_rows(dev, monkeypatch, capfd):
             _run_families(dev, m, [x], oracle.run_chain([x], ops))
 
 
+def test_blocked_row_order(dev, monkeypatch):
+    """Short rows in the blocked order (planned from 2^21 vectors up; the floor is lowered so that the
+    small cases take it too), then a head split of the planned size as it is."""
+    from tests.test_plan_replay import BLOCKED_ROWS
+    big = [
+        ((6, 200, 3, 4, 64), 2, [("transpose", (2, 0, 3, 1, 4))]),
+        ((5, 12, 333, 32), 4, [("transpose", (0, 2, 1, 3))]),
+    ]
+    monkeypatch.setenv("AMAP_ROWS_BLOCK_MIN_LOG2", "0")
+    for i, (shape, es, ops) in enumerate(BLOCKED_ROWS + big):
+        print(f"[gpu] blocked rows case {i}", flush=True)
+        x = synth.random_bits(shape, es, 500 + i)
+        _run_families(dev, B.amap_compose([shape], es, ops), [x], oracle.run_chain([x], ops))
+    monkeypatch.delenv("AMAP_ROWS_BLOCK_MIN_LOG2")
+    print("[gpu] blocked rows at the planned size", flush=True)
+    shape, ops = (20, 512, 3, 4, 64), [("transpose", (2, 0, 3, 1, 4))]      # 2^21.3 vectors
+    x = synth.random_bits(shape, 2, 77)
+    _run_families(dev, B.amap_compose([shape], 2, ops), [x], oracle.run_chain([x], ops), families=[None, B.AMAP_K_ROWS])
+
+
 def test_keep_plane_rows(dev):
     """A slice with a small step along the contiguous dimension (step 2 on 2-byte elements keeps one
     plane of an interleaved source in registers, the rest is gathered):

@@ -152,6 +152,44 @@ def test_cross_lane_default_is_the_measured_winner(monkeypatch, capfd):
         assert "amap plan: xlane" not in capfd.readouterr().err
 
 
+# rows shorter than 1 KiB whose next loop differs between dst and source: planned in a blocked order
+# from 2^21 vectors up; the floor is lowered here so that small tensors take that order
+BLOCKED_ROWS = [
+    ((4, 24, 3, 6, 64), 2, [("transpose", (2, 0, 3, 1, 4))]),                     # head split: [b,s,3,h,64] -> [3,b,h,s,64]
+    ((4, 6, 24, 64), 2, [("transpose", (0, 2, 1, 3)), ("reshape", (4, 24, 384))]),  # head merge
+    ((3, 10, 7, 32), 4, [("transpose", (0, 2, 1, 3))]),                           # 128-byte rows of 4-byte elements, odd extents
+    ((2, 9, 5, 3, 16), 2, [("transpose", (0, 3, 2, 1, 4))]),                      # 32-byte rows, three outer loops permuted
+    ((5, 12, 20, 8), 2, [("transpose", (0, 2, 1, 3)), ("pad", (0, 1, 0, 0), (0, 2, 0, 0), 4)]),
+    ((2, 16, 64, 64), 2, [("transpose", (0, 2, 1, 3)), ("slice", 1, 8, 40, 1)]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(BLOCKED_ROWS)))
+def test_blocked_row_order_plans(case, monkeypatch):
+    shape, es, ops = BLOCKED_ROWS[case]
+    for run in ("256", "1024", "4096"):
+        monkeypatch.setenv("AMAP_ROWS_BLOCK_MIN_LOG2", "0")
+        monkeypatch.setenv("AMAP_ROWS_RUN", run)
+        m = B.amap_compose([shape], es, ops)
+        assert B.amap_describe(m).kernel_id == B.AMAP_K_ROWS
+        assert _replay_all(m) >= 2
+        for nw in ("0", "2"):
+            monkeypatch.setenv("AMAP_WAVES_LOG", nw)
+            assert B.amap_plan_selfcheck(B.amap_compose([shape], es, ops), -1) == 0
+        monkeypatch.delenv("AMAP_WAVES_LOG")
+
+
+def test_blocked_row_order_of_random_chains(monkeypatch):
+    monkeypatch.setenv("AMAP_ROWS_BLOCK_MIN_LOG2", "0")
+    for seed in range(0, 200, 2):
+        src_shapes, ops = chains.random_chain(seed, extended=seed % 4 == 0)
+        m = B.amap_compose(src_shapes, 2 if seed % 3 else 4, ops)
+        if B.amap_describe(m).strided:
+            assert B.amap_plan_selfcheck(m, -1) == 0
+    for shape, es, ops in ALIGNED:
+        assert B.amap_plan_selfcheck(B.amap_compose([shape], es, ops), -1) == 0
+
+
 # ---- tensors beyond 32-bit offsets: every piece gets a 64-bit window origin and pieces that span
 # too much are cut.  The span limit is lowered so that small tensors take that path.
 
