@@ -72,6 +72,18 @@ AMAP_HD void rows_offsets(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_
 AMAP_HD bool rows_is_plain(const DevPiece &P, int es) {
     return P.kind == PK_ROWS && !P.rep_log && !P.rev && !P.gather && !P.inter && (es << P.vlog) == 16;
 }
+// ---- a launch whose first piece is an LDS-staged tile piece (or group) of 16-byte vectors and whose other
+// pieces are plain row pieces (the fills around a padded tensor) runs in a kernel of its own as well
+AMAP_HD bool launch_is_tile16(const LaunchArgs &a, int es) {
+    if (a.n_pieces == 0) return false;
+    const DevPiece &H = a.p[0];
+    if (H.kind != PK_TILE || (es << H.vlog) != 16 || H.group_n < 1 || H.group_n > a.n_pieces || H.n_blocks == 0) return false;
+    for (uint32_t k = 1; k < H.group_n; ++k)
+        if (a.p[k].n_blocks) return false;
+    for (uint32_t k = H.group_n; k < a.n_pieces; ++k)
+        if (!rows_is_plain(a.p[k], es)) return false;
+    return true;
+}
 AMAP_HD void rows_offsets_fixed(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_t &soff) {
     uint32_t d = P.dbase, s = P.sbase;
 #if defined(__HIP_DEVICE_COMPILE__)

@@ -753,6 +753,36 @@ __global__ __launch_bounds__(kMaxThreads) void amap_rows_kernel(const DevPiece P
     rows_move<16, NT>(P, dst + (size_t)P.dwin * ES, ES, doff, soff, ok);
 }
 
+// ------------------------------------------------------------------ one tile piece + plain rows
+// The launch of a transposing map (NCHW -> NHWC with or without padding, a concat in front of it):
+// piece 0 is known without a search and its fields sit at fixed places of the argument block; only
+// the workgroups behind it (constant borders) look their piece up.
+template <int ES, int NT, bool GROUPED>
+__global__ __launch_bounds__(kMaxThreads) void amap_tile16_kernel(const LaunchArgs args, char *dst) {
+    extern __shared__ uint4 smem_v[];
+    const uint32_t b = logical_block(args, blockIdx.x, gridDim.x);
+    if (b < args.p[0].n_blocks) {
+        tile_body<ES, 16 / ES, true, NT, GROUPED>(args.p[0], dst + (size_t)args.p[0].dwin * ES, b, threadIdx.x,
+                                                   reinterpret_cast<char *>(smem_v));
+        return;
+    }
+    uint32_t pi = args.p[0].group_n;
+    for (uint32_t k = pi + 1; k < args.n_pieces; ++k)
+        if (b >= args.p[k].first_block) pi = k;
+    const DevPiece &P = args.p[pi];
+    uint32_t doff[kRowsUnroll], soff[kRowsUnroll];
+    bool ok[kRowsUnroll];
+    const uint32_t threads = blockDim.x;
+    const uint32_t base = (b - P.first_block) * (threads * kRowsUnroll) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) {
+        const uint32_t r = base + u * threads;
+        ok[u] = r < P.n_units;
+        rows_offsets_fixed(P, r, doff[u], soff[u]);
+    }
+    rows_move<16, NT>(P, dst + (size_t)P.dwin * ES, ES, doff, soff, ok);
+}
+
 // ------------------------------------------------------------------ program
 // Element-wise interpreter of the operator program: applies the index
 // function of every operator of the chain in turn (eq. 4 evaluated lazily).
@@ -885,6 +915,27 @@ amap_status launch_pieces(const LaunchArgs &args, uint32_t blocks, size_t lds, i
         }
 #undef AMAP_LAUNCH_ROWS
         return launch_failed("amap_rows_kernel") ? AMAP_E_HIP : AMAP_OK;
+    }
+    if (launch_is_tile16(args, es)) {
+#define AMAP_LAUNCH_T16(ES, NT)                                                                              \
+    do {                                                                                                     \
+        if (grouped)                                                                                         \
+            hipLaunchKernelGGL((amap_tile16_kernel<ES, NT, true>), grid, block, lds, stream, args, d);       \
+        else                                                                                                 \
+            hipLaunchKernelGGL((amap_tile16_kernel<ES, NT, false>), grid, block, lds, stream, args, d);      \
+    } while (0)
+        switch ((es == 2 ? 0 : 4) + (int)(args.nt & 3)) {
+        case 0: AMAP_LAUNCH_T16(2, 0); break;
+        case 1: AMAP_LAUNCH_T16(2, 1); break;
+        case 2: AMAP_LAUNCH_T16(2, 2); break;
+        case 3: AMAP_LAUNCH_T16(2, 3); break;
+        case 4: AMAP_LAUNCH_T16(4, 0); break;
+        case 5: AMAP_LAUNCH_T16(4, 1); break;
+        case 6: AMAP_LAUNCH_T16(4, 2); break;
+        default: AMAP_LAUNCH_T16(4, 3); break;
+        }
+#undef AMAP_LAUNCH_T16
+        return launch_failed("amap_tile16_kernel") ? AMAP_E_HIP : AMAP_OK;
     }
 #define AMAP_LAUNCH(ES, NT)                                                                                  \
     do {                                                                                                     \

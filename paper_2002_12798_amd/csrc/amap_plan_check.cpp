@@ -45,7 +45,7 @@ struct Replay {
         return ((int64_t)sid << 40) + soff;
     }
 
-    // alone: the piece is the only one of its launch
+    // alone: the launch runs in one of the kernels that decode plain row pieces through all loop slots
     void rows(const DevPiece &P, int sid, uint32_t blk, bool alone) {
         // the expanding, reversing, gathered and interleaving forms are written for 16-byte vectors whatever
         // vlog says: replay what the kernel does, so that a plan with another width shows up as errors
@@ -345,7 +345,7 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
                     continue;
                 }
                 if (P.kind == PK_ROWS)
-                    R.rows(P, sid, local, A.n_pieces == 1);
+                    R.rows(P, sid, local, A.n_pieces == 1 || launch_is_tile16(A, m->elem));
                 else if (P.kind == PK_FLAT && P.rag_cb)
                     R.rag(P, sid, local, plan->lds_bytes[li]);
                 else if (P.kind == PK_FLAT)
