@@ -613,23 +613,32 @@ def record_traffic(d, workload):
     RD / WR give a second reading from other counters: requests that went to DRAM, scaled by what the
     same counter reads per byte of the plain copy."""
     import csv
+    import re
     import statistics
-    kernel = "amap_gemm" if workload == "cfg4" else "amap_pieces"
+    # the map kernels (amap_pieces_kernel, amap_rows_kernel, amap_tile16_kernel) or the GEMM kernels
+    kernel = "amap_gemm" if workload == "cfg4" else "amap_map"
     copy_bytes = 2 * COPY_ELEMENTS
 
     def means(tag, cset, kname):
         path = os.path.join(d, f"{tag}_{cset}_counter_collection.csv")
         if not os.path.exists(path):
             return None
-        per = {}
+        per, names = {}, set()
         for r in csv.DictReader(open(path)):
-            if kname in r["Kernel_Name"]:
+            n = r["Kernel_Name"]
+            hit = ("amap_gemm" in n) if kname == "amap_gemm" else ("amap_" in n and "amap_gemm" not in n)
+            if hit:
+                names.add(re.search(r"amap_\w+", n).group(0))
                 per.setdefault(r["Counter_Name"], []).append(float(r["Counter_Value"]))
-        return {k: (statistics.mean(v), len(v)) for k, v in per.items()}
+        out = {k: (statistics.mean(v), len(v)) for k, v in per.items()}
+        out["_kernels"] = sorted(names)
+        return out
 
     rec = {"workload": workload, "kernel": kernel, "sources": TRAFFIC_SOURCES, "sources_sha256": _sources_hash()}
-    f, c = means(workload, "FETCH_SIZE", kernel), means("copy", "FETCH_SIZE", "amap_pieces")
-    wf, wc = means(workload, "WRITE_SIZE", kernel), means("copy", "WRITE_SIZE", "amap_pieces")
+    f, c = means(workload, "FETCH_SIZE", kernel), means("copy", "FETCH_SIZE", "amap_map")
+    wf, wc = means(workload, "WRITE_SIZE", kernel), means("copy", "WRITE_SIZE", "amap_map")
+    rec["kernel"] = f["_kernels"]
+    rec["copy_kernel"] = c["_kernels"]
     rec["dispatches"] = f["FETCH_SIZE"][1]
     rec["fetch_kib_fused"], rec["fetch_kib_copy"] = f["FETCH_SIZE"][0], c["FETCH_SIZE"][0]
     rec["write_kib_fused"], rec["write_kib_copy"] = wf["WRITE_SIZE"][0], wc["WRITE_SIZE"][0]
@@ -638,11 +647,11 @@ def record_traffic(d, workload):
     rec["read_bytes_per_launch"] = rec["fetch_kib_fused"] * 1024 * rec["fetch_factor"]
     rec["write_bytes_per_launch"] = rec["write_kib_fused"] * 1024 * rec["write_factor"]
     rec["traffic_bytes_per_launch"] = rec["read_bytes_per_launch"] + rec["write_bytes_per_launch"]
-    rd, rdc = means(workload, "RD", kernel), means("copy", "RD", "amap_pieces")
-    wr, wrc = means(workload, "WR", kernel), means("copy", "WR", "amap_pieces")
+    rd, rdc = means(workload, "RD", kernel), means("copy", "RD", "amap_map")
+    wr, wrc = means(workload, "WR", kernel), means("copy", "WR", "amap_map")
     if rd and rdc and wr and wrc:
-        second = {"counters_fused": {k: v[0] for k, v in {**rd, **wr}.items()},
-                  "counters_copy": {k: v[0] for k, v in {**rdc, **wrc}.items()}}
+        second = {"counters_fused": {k: v[0] for k, v in {**rd, **wr}.items() if k != "_kernels"},
+                  "counters_copy": {k: v[0] for k, v in {**rdc, **wrc}.items() if k != "_kernels"}}
         second["bytes_per_dram_read_request_on_copy"] = copy_bytes / rdc["TCC_EA0_RDREQ_DRAM_sum"][0]
         second["bytes_per_dram_write_request_on_copy"] = copy_bytes / wrc["TCC_EA0_WRREQ_DRAM_sum"][0]
         second["read_bytes_per_launch"] = rd["TCC_EA0_RDREQ_DRAM_sum"][0] * second["bytes_per_dram_read_request_on_copy"]

@@ -84,6 +84,12 @@ AMAP_HD bool launch_is_tile16(const LaunchArgs &a, int es) {
         if (!rows_is_plain(a.p[k], es)) return false;
     return true;
 }
+// ---- a launch of several plain row pieces (the outputs of one multi-output call, a copy with its fills)
+AMAP_HD bool launch_is_plain_rows(const LaunchArgs &a, int es) {
+    for (uint32_t k = 0; k < a.n_pieces; ++k)
+        if (!rows_is_plain(a.p[k], es) || a.p[k].n_blocks == 0) return false;
+    return a.n_pieces > 0 && !a.xcd_remap;
+}
 AMAP_HD void rows_offsets_fixed(const DevPiece &P, uint32_t r, uint32_t &doff, uint32_t &soff) {
     uint32_t d = P.dbase, s = P.sbase;
 #if defined(__HIP_DEVICE_COMPILE__)

@@ -753,6 +753,27 @@ __global__ __launch_bounds__(kMaxThreads) void amap_rows_kernel(const DevPiece P
     rows_move<16, NT>(P, dst + (size_t)P.dwin * ES, ES, doff, soff, ok);
 }
 
+// The same for a launch of several plain row pieces: the piece is looked up, the rest is alike.
+template <int ES, int NT>
+__global__ __launch_bounds__(kMaxThreads) void amap_rows_multi_kernel(const LaunchArgs args, char *dst) {
+    const uint32_t b = blockIdx.x;
+    uint32_t pi = 0;
+    for (uint32_t k = 1; k < args.n_pieces; ++k)
+        if (b >= args.p[k].first_block) pi = k;
+    const DevPiece &P = args.p[pi];
+    uint32_t doff[kRowsUnroll], soff[kRowsUnroll];
+    bool ok[kRowsUnroll];
+    const uint32_t threads = blockDim.x;
+    const uint32_t base = (b - P.first_block) * (threads * kRowsUnroll) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < kRowsUnroll; ++u) {
+        const uint32_t r = base + u * threads;
+        ok[u] = r < P.n_units;
+        rows_offsets_fixed(P, r, doff[u], soff[u]);
+    }
+    rows_move<16, NT>(P, dst + (size_t)P.dwin * ES, ES, doff, soff, ok);
+}
+
 // ------------------------------------------------------------------ one tile piece + plain rows
 // The launch of a transposing map (NCHW -> NHWC with or without padding, a concat in front of it):
 // piece 0 is known without a search and its fields sit at fixed places of the argument block; only
@@ -915,6 +936,21 @@ amap_status launch_pieces(const LaunchArgs &args, uint32_t blocks, size_t lds, i
         }
 #undef AMAP_LAUNCH_ROWS
         return launch_failed("amap_rows_kernel") ? AMAP_E_HIP : AMAP_OK;
+    }
+    if (launch_is_plain_rows(args, es)) {
+#define AMAP_LAUNCH_ROWSM(ES, NT) hipLaunchKernelGGL((amap_rows_multi_kernel<ES, NT>), grid, block, 0, stream, args, d)
+        switch ((es == 2 ? 0 : 4) + (int)(args.nt & 3)) {
+        case 0: AMAP_LAUNCH_ROWSM(2, 0); break;
+        case 1: AMAP_LAUNCH_ROWSM(2, 1); break;
+        case 2: AMAP_LAUNCH_ROWSM(2, 2); break;
+        case 3: AMAP_LAUNCH_ROWSM(2, 3); break;
+        case 4: AMAP_LAUNCH_ROWSM(4, 0); break;
+        case 5: AMAP_LAUNCH_ROWSM(4, 1); break;
+        case 6: AMAP_LAUNCH_ROWSM(4, 2); break;
+        default: AMAP_LAUNCH_ROWSM(4, 3); break;
+        }
+#undef AMAP_LAUNCH_ROWSM
+        return launch_failed("amap_rows_multi_kernel") ? AMAP_E_HIP : AMAP_OK;
     }
     if (launch_is_tile16(args, es)) {
 #define AMAP_LAUNCH_T16(ES, NT)                                                                              \

@@ -345,7 +345,7 @@ extern "C" amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64
                     continue;
                 }
                 if (P.kind == PK_ROWS)
-                    R.rows(P, sid, local, A.n_pieces == 1 || launch_is_tile16(A, m->elem));
+                    R.rows(P, sid, local, A.n_pieces == 1 || launch_is_tile16(A, m->elem) || launch_is_plain_rows(A, m->elem));
                 else if (P.kind == PK_FLAT && P.rag_cb)
                     R.rag(P, sid, local, plan->lds_bytes[li]);
                 else if (P.kind == PK_FLAT)
