@@ -339,8 +339,11 @@ amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t 
 
 /* out[M,N] = bf16( A[M,K] x W[K,N] ) with A[m,k] = A_src[g(m,k)] loaded through
  * the map in the operand-load prologue (the consumer load of eq. 4); A is never
- * materialised.  A_map: dst shape [M,K], 2-byte elements (bf16), one source,
- * no fill pieces.  W: [K,N] row-major bf16.  out: [M,N] row-major bf16,
+ * materialised.  A_map: dst shape [M,K], 2-byte elements (bf16), one source;
+ * either no fill pieces, or fill pieces of ONE constant around ONE data piece
+ * (A padded along m and / or k, e.g. a zero-padded activation; along k in
+ * multiples of 8 elements): the constant is supplied in the operand load.
+ * W: [K,N] row-major bf16.  out: [M,N] row-major bf16,
  * fp32 accumulation, round-to-nearest-even on output.
  * Needs N % 8 == 0, K % 8 == 0 and 8-element aligned contiguous source runs in
  * the map, either along k (a row-major operand behind permutes and reshapes) or,
@@ -348,7 +351,12 @@ amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t 
  * read as the [N*H*W, C] matrix of a pointwise convolution: 4 k x 8 m blocks are
  * transposed on their way to the matrix cores), else AMAP_E_UNSUPPORTED; M, N and K
  * need not be whole numbers of the 256 x 128 x 64 tiles (edge tiles are clamped on
- * load, masked on store). */
+ * load, masked on store).  Shapes with M % 256 == N % 256 == 0, K % 64 == 0,
+ * K >= 128, no padding and source runs of 64 elements and more along k that do
+ * not straddle a block of 256 rows run a kernel with 256 x 256 x 64 tiles whose
+ * operands go straight from L2 into LDS (environment AMAP_GEMM_TILE256=0: the
+ * general kernel for these too); both add the same products in the same order,
+ * so their results are bit-identical. */
 amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
                             void *out, void *stream);
 
