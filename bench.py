@@ -577,16 +577,22 @@ def cpu_baseline(synth, name, min_bytes, budget_s=12.0):
     return res
 
 
-TRAFFIC_SOURCES = ["paper_2002_12798_amd/csrc/amap_kernels.hip", "paper_2002_12798_amd/csrc/amap_index.hpp",
-                   "paper_2002_12798_amd/csrc/amap_compose.cpp", "paper_2002_12798_amd/csrc/amap_plan.cpp",
-                   "paper_2002_12798_amd/csrc/amap_device.hpp", "paper_2002_12798_amd/csrc/amap_gemm.hip"]
+MAP_SOURCES = ["paper_2002_12798_amd/csrc/amap_kernels.hip", "paper_2002_12798_amd/csrc/amap_index.hpp",
+               "paper_2002_12798_amd/csrc/amap_compose.cpp", "paper_2002_12798_amd/csrc/amap_plan.cpp",
+               "paper_2002_12798_amd/csrc/amap_device.hpp"]
+GEMM_SOURCES = ["paper_2002_12798_amd/csrc/amap_gemm.hip", "paper_2002_12798_amd/csrc/amap_compose.cpp"]
 COPY_ELEMENTS = 53248000               # 2-byte elements moved by `--copy-only`: 106,496,000 B read and as many written
 
 
-def _sources_hash():
+def _traffic_sources(workload):
+    """The sources whose change invalidates a traffic record: those of the kernel that ran."""
+    return GEMM_SOURCES if workload == "cfg4" else MAP_SOURCES
+
+
+def _sources_hash(files):
     import hashlib
     h = hashlib.sha256()
-    for f in TRAFFIC_SOURCES:
+    for f in files:
         h.update(open(os.path.join(ROOT, f), "rb").read())
     return h.hexdigest()
 
@@ -598,7 +604,8 @@ def measured_traffic(workload):
     if not os.path.exists(path):
         return None
     rec = json.load(open(path))
-    if rec.get("sources") != TRAFFIC_SOURCES or rec.get("sources_sha256") != _sources_hash():
+    files = _traffic_sources(workload)
+    if rec.get("sources") != files or rec.get("sources_sha256") != _sources_hash(files):
         return None
     return round(rec["traffic_bytes_per_launch"])
 
@@ -634,7 +641,8 @@ def record_traffic(d, workload):
         out["_kernels"] = sorted(names)
         return out
 
-    rec = {"workload": workload, "kernel": kernel, "sources": TRAFFIC_SOURCES, "sources_sha256": _sources_hash()}
+    files = _traffic_sources(workload)
+    rec = {"workload": workload, "kernel": kernel, "sources": files, "sources_sha256": _sources_hash(files)}
     f, c = means(workload, "FETCH_SIZE", kernel), means("copy", "FETCH_SIZE", "amap_map")
     wf, wc = means(workload, "WRITE_SIZE", kernel), means("copy", "WRITE_SIZE", "amap_map")
     rec["kernel"] = f["_kernels"]

@@ -558,6 +558,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
             for (int s = 0; s < 16; ++s) load_one(p * kT2Stage, s >> 1, s & 1);
             ld_k0 += T2K;
         }
+        // with K = 2 k-steps the cursor now stands behind the tile: move it to the workgroup's next tile, as
+        // the loop does after every k-step it fetches (a cursor left at k = K would fetch past the row)
+        if (ld_k0 >= g.K) {
+            ld_k0 = 0;
+            ld_tile += gridDim.x;
+            if (ld_tile < ntiles) cursor_tile();
+        }
         asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // the first step is there, the second may still be on its way
         __builtin_amdgcn_s_barrier();
 #pragma unroll

@@ -434,6 +434,12 @@ T256_CASES = [
     (((512, 128), []), 768, [("reshape", (2, 256, 3, 4, 64)), ("transpose", (2, 0, 3, 1, 4))]),    # QKV head split on the store side
     (((2, 2, 256, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (512, 128))]), 256,
      [("reshape", (2, 256, 4, 64)), ("transpose", (2, 0, 1, 3))]),                                 # both sides mapped
+    # two k-steps and more tiles than workgroups (272 tiles): once both k-steps of its first tile are fetched, a
+    # workgroup's load cursor must stand on its NEXT tile (it once stayed at k = K: weight rows past the end of W
+    # were fetched, and the second tile of a workgroup was computed on the wrong stage)
+    (((4352, 128), []), 4096, None),
+    (((2, 2, 512, 64), [("transpose", (1, 2, 0, 3)), ("reshape", (1024, 128))]), 512, None),       # K = 128 over two digits of k
+    (((4352, 192), []), 4096, [("reshape", (4352, 64, 64)), ("transpose", (1, 0, 2))]),            # three k-steps, two tiles per workgroup, mapped store
 ]
 
 
