@@ -188,6 +188,17 @@ amap_status amap_check_cover(const amap_t *m, int64_t *unwritten, int64_t *overw
  * lets the device indexing be verified on a machine without a GPU. */
 amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64_t *n_errors);
 
+/* Diagnostic: the same for the 256 x 256-tile kernel of amap_gemm_fused / amap_gemm_fused_store
+ * (see amap_gemm_fused for the shapes it takes): replays on the host, with the kernel's own address
+ * functions, the loads of every workgroup (n_workgroups of them: the number of compute units on the
+ * device, or any smaller number to make workgroups walk several tiles) and the stores of every tile
+ * for the product A_map x W[K,N] (stored through out_map when it is not NULL), and counts loads
+ * outside A's source or W, k-steps that fetch anything but their own block of A and W, fetches out
+ * of the order of use, stores outside out and elements of out written never or twice.
+ * AMAP_E_UNSUPPORTED when the product would run in the general kernel (no replay for that one). */
+amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const amap_t *out_map, int n_workgroups,
+                                int64_t *n_errors);
+
 /* ---- data-movement elimination over an operator graph (host only) ---------
  * Section 2.1 applied to a whole program: tensors are either materialised
  * (graph inputs, results of compute operators) or defined by a layout operator,

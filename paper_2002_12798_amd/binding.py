@@ -28,7 +28,7 @@ EXPORTS = [
     "amap_source", "amap_transpose", "amap_reshape", "amap_slice", "amap_repeat", "amap_tile", "amap_pad",
     "amap_concat",
     "amap_inverse", "amap_compose", "amap_free", "amap_describe", "amap_source_shape",
-    "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_execute", "amap_execute_multi", "amap_execute_kernel",
+    "amap_eval_host", "amap_check_cover", "amap_plan_selfcheck", "amap_gemm_selfcheck", "amap_execute", "amap_execute_multi", "amap_execute_kernel",
     "amap_gemm_fused", "amap_gemm_fused_store", "amap_gemm_mapped", "amap_gemm_gather", "amap_status_str", "amap_last_error",
     "amap_graph_create", "amap_graph_free", "amap_graph_input", "amap_graph_op", "amap_graph_map", "amap_graph_store",
     "amap_graph_compute",
@@ -89,6 +89,7 @@ _L.amap_source_shape.argtypes = [_vp, C.c_int, C.POINTER(C.c_int), _i64p]
 _L.amap_eval_host.argtypes = [_vp, _pp, _vp, C.c_int]
 _L.amap_check_cover.argtypes = [_vp, _i64p, _i64p]
 _L.amap_plan_selfcheck.argtypes = [_vp, C.c_int, _i64p]
+_L.amap_gemm_selfcheck.argtypes = [_vp, C.c_int64, _vp, C.c_int, _i64p]
 _L.amap_execute.argtypes = [_pp, _vp, _vp, _vp]
 _L.amap_execute_kernel.argtypes = [_pp, _vp, _vp, _vp, C.c_int]
 _L.amap_execute_multi.argtypes = [_pp, _pp, _pp, C.c_int, _vp]
@@ -297,6 +298,14 @@ def amap_plan_selfcheck(m, kernel_id=-1):
     n = C.c_int64()
     _check(_L.amap_plan_selfcheck(m.handle, int(kernel_id), C.byref(n)), "amap_plan_selfcheck")
     return n.value
+
+
+def amap_gemm_selfcheck(a_map, n, out_map=None, n_workgroups=256):
+    """Errors found by the host replay of the 256 x 256-tile GEMM kernel's loads and stores."""
+    e = C.c_int64()
+    _check(_L.amap_gemm_selfcheck(a_map.handle, int(n), out_map.handle if out_map is not None else None, int(n_workgroups),
+                                  C.byref(e)), "amap_gemm_selfcheck")
+    return e.value
 
 
 def amap_eval_host(m, srcs, mode=0):

@@ -161,7 +161,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // Workgroup index -> output tile.  Workgroups go to the 8 XCDs round-robin;
 // each XCD gets a compact 2-D block of tiles so that the A rows and W columns
 // its workgroups share are fetched into that XCD's L2 once.
-__device__ __forceinline__ void tile_of_block(uint32_t b, uint32_t tiles_m, uint32_t tiles_n, uint32_t &tm, uint32_t &tn) {
+__host__ __device__ __forceinline__ void tile_of_block(uint32_t b, uint32_t tiles_m, uint32_t tiles_n, uint32_t &tm, uint32_t &tn) {
     if ((tiles_m & 3u) == 0 && (tiles_n & 1u) == 0) {
         const uint32_t xcd = b & 7u, j = b >> 3;        // j-th tile of this XCD
         const uint32_t rm = tiles_m >> 2, rn = tiles_n >> 1;  // region extents: 4 x 2 regions
@@ -444,9 +444,11 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) const u32x4 lds_u32x4;
 
 // all digits of one dimension, fixed trip count (unused digits have extent 1 and stride 0)
-__device__ __forceinline__ uint32_t digits_offset4(const Digits &d, uint32_t x) {
+__host__ __device__ __forceinline__ uint32_t digits_offset4(const Digits &d, uint32_t x) {
     uint32_t off = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
 #pragma unroll
+#endif
     for (uint32_t j = 0; j < (uint32_t)kMaxDigits; ++j) {
         const uint32_t q = fdiv(x, d.fmult[j]);
         const uint32_t dig = q - fdiv(q, d.fext[j]) * d.ext[j];
@@ -462,6 +464,62 @@ __device__ __forceinline__ void load_to_lds16(const void *base, uint32_t byte_of
 
 #define AMAP_PIN() __builtin_amdgcn_sched_barrier(0)
 
+// ---- global addressing of amap_gemm_tile256_kernel, shared with its host replay (amap_gemm_selfcheck)
+// The load cursor: the (tile, k-step) the next batch of 16 loads per wavefront fetches.  It runs two k-steps
+// ahead of the MFMAs and crosses into the workgroup's next tile (tile + number of workgroups) on its own.
+struct T2Cursor {
+    uint32_t tile, k0;
+};
+__host__ __device__ __forceinline__ bool t2_cursor_advance(T2Cursor &c, uint32_t K, uint32_t n_workgroups) {
+    c.k0 += (uint32_t)T2K;
+    if (c.k0 < K) return false;
+    c.k0 = 0;
+    c.tile += n_workgroups;
+    return true;  // a new tile: its bases must be recomputed (if it exists)
+}
+// Per-lane byte offsets inside a tile and k-step, for the load blocks of even / odd index (par).
+// A stage: 1 KiB block b = rows 8 b .. 8 b + 7, 128 B each; lane i of the load holds row 8 b + i / 8,
+// physical chunk i % 8 = logical chunk ^ ((row >> 1) & 7).  W stage: block b = k rows 2 b, 2 b + 1,
+// 512 B each; lane i holds row 2 b + i / 32, physical chunk i % 32 = logical chunk ^ ((k & 3) << 2).
+// Wavefront w issues blocks 8 w .. 8 w + 7 of both.
+__host__ __device__ __forceinline__ uint32_t t2_a_lane(const GemmArgs &g, uint32_t wave, uint32_t lane, uint32_t par) {
+    const uint32_t a_chunk0 = (lane & 7u) ^ (lane >> 4);
+    return 2u * ((64u * wave + (lane >> 3)) * g.a_row_ss + 8u * (a_chunk0 ^ (par << 2)));
+}
+__host__ __device__ __forceinline__ uint32_t t2_w_lane(const GemmArgs &g, uint32_t wave, uint32_t lane, uint32_t par) {
+    const uint32_t w_kr = lane >> 5;
+    return 2u * ((16u * wave + w_kr) * g.N + 8u * ((lane & 31u) ^ (w_kr << 2) ^ (par << 3)));
+}
+// wave-uniform byte offsets of a tile, and of a k-step inside it
+__host__ __device__ __forceinline__ void t2_tile_bases(const GemmArgs &g, uint32_t tile, uint32_t &a_tile, uint32_t &w_tile) {
+    uint32_t tm, tn;
+    tile_of_block(tile, g.tiles_m, g.tiles_n, tm, tn);
+    a_tile = 2u * (g.sbase + digits_offset4(g.dm, tm * (uint32_t)T2M));
+    w_tile = 2u * (tn * (uint32_t)T2N);
+}
+__host__ __device__ __forceinline__ uint32_t t2_a_step(const GemmArgs &g, uint32_t a_tile, uint32_t k0) {
+    return a_tile + 2u * digits_offset4(g.dk, k0);
+}
+__host__ __device__ __forceinline__ uint32_t t2_w_step(const GemmArgs &g, uint32_t w_tile, uint32_t k0) { return w_tile + 2u * k0 * g.N; }
+// byte offset of load block j (0 .. 7) of a wavefront
+__host__ __device__ __forceinline__ uint32_t t2_a_load(const GemmArgs &g, uint32_t a_lane_par, uint32_t ka, uint32_t j) {
+    return a_lane_par + ka + 16u * j * g.a_row_ss;
+}
+__host__ __device__ __forceinline__ uint32_t t2_w_load(const GemmArgs &g, uint32_t w_lane_par, uint32_t wk, uint32_t j) {
+    return w_lane_par + wk + 4u * j * g.N;
+}
+// epilogue: element offset in out of the 8 values a lane stores for row m, first column n_lane
+template <bool MAPPED>
+__host__ __device__ __forceinline__ size_t t2_store_col(const GemmArgs &g, uint32_t n_lane) {
+    if constexpr (MAPPED) return (size_t)(g.obase + digits_offset4(g.on, n_lane));
+    return (size_t)n_lane;
+}
+template <bool MAPPED>
+__host__ __device__ __forceinline__ size_t t2_store_off(const GemmArgs &g, size_t col_off, uint32_t m) {
+    if constexpr (MAPPED) return col_off + digits_offset4(g.om, m);
+    return (size_t)m * g.N + col_off;
+}
+
 template <bool STORE_MAPPED>
 __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(const GemmArgs g) {
     const uint32_t tid = threadIdx.x, lane = tid & 63;
@@ -470,37 +528,30 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
     const uint32_t steps = g.K / T2K;  // >= 2
     const uint32_t ntiles = g.tiles_m * g.tiles_n;
 
-    // ---- load cursor: the k-step the next batch of loads fetches.
-    // A stage: 1 KiB block b = rows 8 b .. 8 b + 7, 128 B each; lane i of the load holds row 8 b + i / 8,
-    // physical chunk i % 8 = logical chunk ^ ((row >> 1) & 7).  W stage: block b = k rows 2 b, 2 b + 1,
-    // 512 B each; lane i holds row 2 b + i / 32, physical chunk i % 32 = logical chunk ^ ((k & 3) << 2).
-    // Wavefront w issues blocks 8 w .. 8 w + 7 of both.
-    uint32_t ld_tile = blockIdx.x, ld_k0 = 0;
-    const uint32_t a_chunk0 = (lane & 7u) ^ (lane >> 4);
-    const uint32_t w_kr = lane >> 5;
+    // ---- load cursor (see T2Cursor) and the per-lane parts of the load addresses
+    T2Cursor ld = {blockIdx.x, 0};
     uint32_t a_lane[2], w_lane[2];   // per-lane byte offsets, block parity 0 / 1
 #pragma unroll
     for (uint32_t par = 0; par < 2; ++par) {
-        a_lane[par] = 2u * ((64u * wave + (lane >> 3)) * g.a_row_ss + 8u * (a_chunk0 ^ (par << 2)));
-        w_lane[par] = 2u * ((16u * wave + w_kr) * g.N + 8u * ((lane & 31u) ^ (w_kr << 2) ^ (par << 3)));
+        a_lane[par] = t2_a_lane(g, wave, lane, par);
+        w_lane[par] = t2_w_lane(g, wave, lane, par);
     }
     uint32_t a_tile = 0, w_tile = 0;   // wave-uniform byte offsets of the cursor's tile
-    auto cursor_tile = [&]() __attribute__((always_inline)) {
-        uint32_t tm, tn;
-        tile_of_block(ld_tile, g.tiles_m, g.tiles_n, tm, tn);
-        a_tile = 2u * (g.sbase + digits_offset4(g.dm, tm * T2M));
-        w_tile = 2u * (tn * T2N);
-    };
+    auto cursor_tile = [&]() __attribute__((always_inline)) { t2_tile_bases(g, ld.tile, a_tile, w_tile); };
     uint32_t ka = 0, wk = 0;
     auto loads_begin = [&]() __attribute__((always_inline)) {
-        ka = a_tile + 2u * digits_offset4(g.dk, ld_k0);
-        wk = w_tile + 2u * ld_k0 * g.N;
+        ka = t2_a_step(g, a_tile, ld.k0);
+        wk = t2_w_step(g, w_tile, ld.k0);
     };
     auto load_one = [&](uint32_t stage_base, int j, int which) __attribute__((always_inline)) {
         if (which == 0)
-            load_to_lds16(g.A_src, a_lane[j & 1] + ka + 16u * j * g.a_row_ss, stage_base + (wave * 8u + j) * 1024u);
+            load_to_lds16(g.A_src, t2_a_load(g, a_lane[j & 1], ka, (uint32_t)j), stage_base + (wave * 8u + j) * 1024u);
         else
-            load_to_lds16(g.W, w_lane[j & 1] + wk + 4u * j * g.N, stage_base + kT2WOff + (wave * 8u + j) * 1024u);
+            load_to_lds16(g.W, t2_w_load(g, w_lane[j & 1], wk, (uint32_t)j), stage_base + kT2WOff + (wave * 8u + j) * 1024u);
+    };
+    // the cursor moves on by one k-step; in a new tile that exists its bases are recomputed
+    auto cursor_next = [&]() __attribute__((always_inline)) {
+        if (t2_cursor_advance(ld, g.K, gridDim.x) && ld.tile < ntiles) cursor_tile();
     };
 
     // ---- fragment addresses (bytes from the start of a stage)
@@ -546,24 +597,18 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
             if (loads) load_one(ld_stage, s >> 1, s & 1);
             AMAP_PIN();
         }
-        if (loads) ld_k0 += T2K;
     };
     uint32_t cur = 0;
-    if (ld_tile < ntiles) {
+    if (ld.tile < ntiles) {
         cursor_tile();
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             loads_begin();
 #pragma unroll
             for (int s = 0; s < 16; ++s) load_one(p * kT2Stage, s >> 1, s & 1);
-            ld_k0 += T2K;
-        }
-        // with K = 2 k-steps the cursor now stands behind the tile: move it to the workgroup's next tile, as
-        // the loop does after every k-step it fetches (a cursor left at k = K would fetch past the row)
-        if (ld_k0 >= g.K) {
-            ld_k0 = 0;
-            ld_tile += gridDim.x;
-            if (ld_tile < ntiles) cursor_tile();
+            // (with K = 2 k-steps the second advance already moves the cursor to the workgroup's next tile;
+            // a cursor left at k = K would fetch weight rows past the end of W)
+            cursor_next();
         }
         asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // the first step is there, the second may still be on its way
         __builtin_amdgcn_s_barrier();
@@ -591,13 +636,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
             // last quarter: the fragments of the next step's first quarter come from the other stage (after
             // the workgroup's last step they are stale and unused), and the cursor's k-step, two ahead of
             // this one and possibly in the workgroup's next tile, is fetched into the stage just released
-            const bool issue = ld_tile < ntiles;
+            const bool issue = ld.tile < ntiles;
             phase(1, kT2Stage - cur, 0, true, cur, issue);
-            if (issue && ld_k0 >= g.K) {
-                ld_k0 = 0;
-                ld_tile += gridDim.x;
-                if (ld_tile < ntiles) cursor_tile();
-            }
+            if (issue) cursor_next();
             cur = kT2Stage - cur;
         }
 
@@ -610,8 +651,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
         const uint32_t scr = kT2Scratch + wave * 8192u;
         const uint32_t row_w = lane & 31u, half_w = lane >> 5;
         const uint32_t m_base = tm * T2M + wm * 128u, n_lane = tn * T2N + wn * 128u + (lane & 15u) * 8u;
-        size_t col_off = n_lane;
-        if constexpr (STORE_MAPPED) col_off = g.obase + digits_offset4(g.on, n_lane);
+        const size_t col_off = t2_store_col<STORE_MAPPED>(g, n_lane);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -630,11 +670,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
                 u32x4 x = *reinterpret_cast<lds_u32x4 *>(scr + row * 256u + ((chunk ^ (row & 15u)) << 4));
                 if (p >= 4) x = u32x4{x.z, x.w, x.x, x.y};
                 const uint32_t m = m_base + i * 32u + row;
-                size_t off;
-                if constexpr (STORE_MAPPED)
-                    off = col_off + digits_offset4(g.om, m);
-                else
-                    off = (size_t)m * g.N + col_off;
+                const size_t off = t2_store_off<STORE_MAPPED>(g, col_off, m);
                 __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + off));
             }
         }
@@ -762,8 +798,11 @@ int64_t piece_extent(const Piece &p, int dim) {
 }
 
 // A_srcs: by source id of A_map when `by_id`, else the one source of a single-piece map
+// dry / dry_kernel: plan only, for the host replay: the kernel arguments and which kernel would run
+// (1: 256 x 256 tiles, 0: the general kernel); nothing is launched and no HIP call is made.
 amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_map, const void *W, int64_t N,
-                        const amap_t *W_map, const amap_t *out_map, void *out, void *stream) {
+                        const amap_t *W_map, const amap_t *out_map, void *out, void *stream, GemmArgs *dry = nullptr,
+                        int *dry_kernel = nullptr) {
     if (W_map) {
         if (W_map->shape.size() != 2) return AMAP_E_INVALID;
         N = W_map->shape[1];
@@ -939,6 +978,14 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     if (g.padded) edge = true;   // the instances that test every vector also take the padding
     if (tile256_on && !g.padded && amode == A_RUNS_K && segs.size() == 1 && wmode == W_PLAIN && M % T2M == 0 && N % T2N == 0 && K % T2K == 0 &&
         K >= 2 * T2K && g.dm.mult[0] == 1 && g.dm.ext[0] % T2M == 0 && g.dk.mult[0] == 1 && g.dk.ss[0] == 1 && g.dk.ext[0] % T2K == 0) {
+        if (dry) {
+            g.a_row_ss = (uint32_t)g.dm.ss[0];
+            g.tiles_m = (uint32_t)(M / T2M);
+            g.tiles_n = (uint32_t)(N / T2N);
+            *dry = g;
+            *dry_kernel = 1;
+            return AMAP_OK;
+        }
         static thread_local int n_cu = 0;
         if (n_cu == 0) {
             int dev = 0;
@@ -973,6 +1020,11 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
             set_last_error("amap_gemm_tile256_kernel", hipGetErrorString(e2));
             return AMAP_E_HIP;
         }
+        return AMAP_OK;
+    }
+    if (dry) {
+        *dry = g;
+        *dry_kernel = 0;
         return AMAP_OK;
     }
     if (const char *tr = std::getenv("AMAP_PLAN_TRACE"); tr && tr[0] != '0')
@@ -1073,6 +1125,118 @@ extern "C" amap_status amap_gemm_gather(const void *const *A_srcs, const amap_t 
         if (!q.fill && (q.src < 0 || (size_t)q.src >= A_map->src_shapes.size())) return AMAP_E_INVALID;
     try {
         return gemm_launch(A_srcs, true, A_map, W_src, W_map ? 0 : N, W_map, out_map, out, stream);
+    } catch (...) {
+        return AMAP_E_NOMEM;
+    }
+}
+
+// Host replay of the global accesses of amap_gemm_tile256_kernel for the product A_map x W[K,N] (-> out_map):
+// every workgroup's load cursor is walked through its prologue and its k-loop exactly as the kernel walks it,
+// with the kernel's own address functions, and every store of the epilogue is enumerated.  Counted as errors:
+// a load outside the A source or outside W; a k-step that does not fetch exactly the 256 x 64 block of A and the
+// 64 x 256 block of W it is for; fetches that are not in the order the MFMAs consume them; a store outside out,
+// and elements of out written never or twice.  AMAP_E_UNSUPPORTED if the product would run in the general kernel.
+extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const amap_t *out_map, int n_workgroups,
+                                           int64_t *n_errors) {
+    if (!A_map || !n_errors || n_workgroups < 1) return AMAP_E_INVALID;
+    try {
+        GemmArgs g;
+        int kernel = 0;
+        const void *fake_a = reinterpret_cast<const void *>((uintptr_t)1 << 40);
+        amap_status st = gemm_launch(&fake_a, false, A_map, reinterpret_cast<const void *>((uintptr_t)2 << 40), N, nullptr, out_map,
+                                     reinterpret_cast<void *>((uintptr_t)3 << 40), nullptr, &g, &kernel);
+        if (st != AMAP_OK) return st;
+        if (kernel != 1) return unsupported("no host replay for the general GEMM kernel");
+        int src = -1;
+        for (const Piece &q : A_map->pieces)
+            if (!q.fill) src = q.src;
+        if (src < 0 || (size_t)src >= A_map->src_shapes.size()) return AMAP_E_INVALID;
+        const int64_t a_bytes = volume_of(A_map->src_shapes[(size_t)src]) * 2, w_bytes = (int64_t)g.K * g.N * 2;
+        const int64_t c_elems = (int64_t)g.M * g.N;
+        int64_t errors = 0;
+        const uint32_t ntiles = g.tiles_m * g.tiles_n, steps = g.K / (uint32_t)T2K;
+        const uint32_t nwg = std::min<uint32_t>((uint32_t)n_workgroups, ntiles);
+        std::vector<uint8_t> written((size_t)(c_elems / 8), 0);   // per 8-element vector of out
+        std::vector<uint32_t> got_a, got_w, want_a, want_w;
+        for (uint32_t blk = 0; blk < nwg; ++blk) {
+            std::vector<T2Cursor> fetched, consumed;
+            // one batch of loads of all four wavefronts for the cursor's k-step
+            auto fetch = [&](const T2Cursor &c) {
+                fetched.push_back(c);
+                if (c.tile >= ntiles || c.k0 + (uint32_t)T2K > g.K) {
+                    ++errors;
+                    return;
+                }
+                uint32_t a_tile, w_tile;
+                t2_tile_bases(g, c.tile, a_tile, w_tile);
+                const uint32_t ka = t2_a_step(g, a_tile, c.k0), wk = t2_w_step(g, w_tile, c.k0);
+                got_a.clear(), got_w.clear(), want_a.clear(), want_w.clear();
+                for (uint32_t wave = 0; wave < 4; ++wave)
+                    for (uint32_t j = 0; j < 8; ++j)
+                        for (uint32_t lane = 0; lane < 64; ++lane) {
+                            const uint32_t ao = t2_a_load(g, t2_a_lane(g, wave, lane, j & 1u), ka, j);
+                            const uint32_t wo = t2_w_load(g, t2_w_lane(g, wave, lane, j & 1u), wk, j);
+                            if ((int64_t)ao + 16 > a_bytes) ++errors;
+                            if ((int64_t)wo + 16 > w_bytes) ++errors;
+                            got_a.push_back(ao);
+                            got_w.push_back(wo);
+                        }
+                uint32_t tm, tn;
+                tile_of_block(c.tile, g.tiles_m, g.tiles_n, tm, tn);
+                for (uint32_t r = 0; r < (uint32_t)T2M; ++r)
+                    for (uint32_t ch = 0; ch < 8; ++ch)
+                        want_a.push_back(2u * (g.sbase + digits_offset4(g.dm, tm * (uint32_t)T2M + r) + digits_offset4(g.dk, c.k0 + 8u * ch)));
+                for (uint32_t kr = 0; kr < (uint32_t)T2K; ++kr)
+                    for (uint32_t ch = 0; ch < 32; ++ch)
+                        want_w.push_back(2u * ((c.k0 + kr) * g.N + tn * (uint32_t)T2N + 8u * ch));
+                std::sort(got_a.begin(), got_a.end()), std::sort(want_a.begin(), want_a.end());
+                std::sort(got_w.begin(), got_w.end()), std::sort(want_w.begin(), want_w.end());
+                if (got_a != want_a) ++errors;
+                if (got_w != want_w) ++errors;
+            };
+            T2Cursor ld = {blk, 0};
+            if (ld.tile < ntiles)
+                for (int p = 0; p < 2; ++p) {
+                    fetch(ld);
+                    t2_cursor_advance(ld, g.K, nwg);
+                }
+            for (uint32_t c_tile = blk; c_tile < ntiles; c_tile += nwg) {
+                for (uint32_t ks = 0; ks < steps; ++ks) {
+                    consumed.push_back(T2Cursor{c_tile, ks * (uint32_t)T2K});
+                    if (ld.tile < ntiles) {
+                        fetch(ld);
+                        t2_cursor_advance(ld, g.K, nwg);
+                    }
+                }
+                // epilogue of this tile
+                uint32_t tm, tn;
+                tile_of_block(c_tile, g.tiles_m, g.tiles_n, tm, tn);
+                for (uint32_t wave = 0; wave < 4; ++wave) {
+                    const uint32_t wm = wave >> 1, wn = wave & 1u;
+                    for (uint32_t lane = 0; lane < 64; ++lane) {
+                        const uint32_t m_base = tm * (uint32_t)T2M + wm * 128u, n_lane = tn * (uint32_t)T2N + wn * 128u + (lane & 15u) * 8u;
+                        const size_t col_off = g.store_mapped ? t2_store_col<true>(g, n_lane) : t2_store_col<false>(g, n_lane);
+                        for (uint32_t i = 0; i < 4; ++i)
+                            for (uint32_t pp = 0; pp < 8; ++pp) {
+                                const uint32_t m = m_base + i * 32u + 4u * pp + (lane >> 4);
+                                const size_t off = g.store_mapped ? t2_store_off<true>(g, col_off, m) : t2_store_off<false>(g, col_off, m);
+                                if (off % 8 || (int64_t)off + 8 > c_elems) {
+                                    ++errors;
+                                    continue;
+                                }
+                                if (written[off / 8]++) ++errors;
+                            }
+                    }
+                }
+            }
+            if (fetched.size() != consumed.size()) ++errors;
+            for (size_t i = 0; i < std::min(fetched.size(), consumed.size()); ++i)
+                if (fetched[i].tile != consumed[i].tile || fetched[i].k0 != consumed[i].k0) ++errors;
+        }
+        for (uint8_t w : written)
+            if (w != 1) ++errors;
+        *n_errors = errors;
+        return AMAP_OK;
     } catch (...) {
         return AMAP_E_NOMEM;
     }

@@ -1,0 +1,77 @@
+"""Host replay of the 256 x 256-tile GEMM kernel's global accesses (CPU only): every workgroup's load
+cursor and every store of every tile, walked with the kernel's own address functions.  All loads must
+stay inside A's source and W, every k-step must fetch exactly its own block of both operands, in the
+order of use, and every element of out must be written once."""
+import numpy as np
+import pytest
+
+from paper_2002_12798_amd import binding as B
+from paper_2002_12798_amd import synth
+
+SHAPES = [
+    # (A source shape, chain -> [M,K]), N, chain on the product or None
+    (((512, 128), []), 256, None),                                                                  # two k-steps
+    (((256, 192), []), 256, None),
+    (((2, 4, 256, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (512, 256))]), 512, None),
+    (((2, 2, 512, 64), [("transpose", (1, 2, 0, 3)), ("reshape", (1024, 128))]), 512, None),         # K = 128 over two digits of k
+    (((2, 1024, 2, 64), [("transpose", (0, 2, 1, 3)), ("slice", 2, 256, 768, 1), ("transpose", (0, 2, 1, 3)),
+                         ("reshape", (1024, 128))]), 256, None),                                    # base offset
+    (((512, 128), []), 768, [("reshape", (2, 256, 3, 4, 64)), ("transpose", (2, 0, 3, 1, 4))]),     # mapped store
+    (((4352, 128), []), 4096, None),                                                                # more tiles than workgroups
+    (((4352, 192), []), 4096, [("reshape", (4352, 64, 64)), ("transpose", (1, 0, 2))]),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SHAPES)))
+def test_replay_of_fixed_shapes(case):
+    (shape, ops), n, c_ops = SHAPES[case]
+    a = B.amap_compose([shape], 2, ops)
+    m, _ = B.dst_shape(a)
+    out_map = B.amap_compose([(m, n)], 2, c_ops) if c_ops else None
+    for nwg in (256, 3, 1):          # 3 and 1: every workgroup walks many tiles
+        assert B.amap_gemm_selfcheck(a, n, out_map, nwg) == 0, nwg
+
+
+def test_replay_of_the_headline_product():
+    w = synth.workload("cfg4")
+    a = B.amap_compose(w.src_shapes, 2, w.ops)
+    assert B.amap_gemm_selfcheck(a, w.gemm_n, None, 256) == 0
+    # the QKV projection stored in the head-split layout
+    a2 = B.amap_compose([(8192, 768)], 2, [])
+    store = B.amap_compose([(8192, 2304)], 2, synth.workload("cfg2_fwd").ops)
+    assert B.amap_gemm_selfcheck(a2, 2304, store, 256) == 0
+
+
+def test_replay_of_random_aligned_shapes():
+    rng = np.random.default_rng(5)
+    ran = 0
+    for _ in range(60):
+        b, h = int(rng.integers(1, 3)), int(rng.integers(1, 5))
+        s, d = 256 * int(rng.integers(1, 3)), 64 * int(rng.integers(1, 3))
+        if h * d < 128:
+            h = 2
+        n = 256 * int(rng.integers(1, 4))
+        form = int(rng.integers(3))
+        if form == 0:
+            shape, ops = (b, h, s, d), [("transpose", (0, 2, 1, 3)), ("reshape", (b * s, h * d))]
+        elif form == 1:
+            shape, ops = (b * s, h * d), []
+        else:
+            shape, ops = (h, b, s, d), [("transpose", (1, 2, 0, 3)), ("reshape", (b * s, h * d))]
+        a = B.amap_compose([shape], 2, ops)
+        m = b * s
+        out_map = B.amap_compose([(m, n)], 2, [("reshape", (m, n // 64, 64)), ("transpose", (1, 0, 2))]) if rng.random() < 0.5 else None
+        assert B.amap_gemm_selfcheck(a, n, out_map, int(rng.choice([1, 2, 5, 256]))) == 0, (shape, ops, n)
+        ran += 1
+    assert ran == 60
+
+
+def test_products_of_the_general_kernel_have_no_replay():
+    for shape, ops, n in [((200, 64), [], 128),                                   # M is no multiple of 256
+                          ((512, 64), [], 256),                                   # one k-step
+                          ((256, 136), [("pad", (0, 0), (0, 56), 0)], 256),       # padded
+                          ((128, 512), [("transpose", (1, 0))], 256)]:            # runs along m
+        a = B.amap_compose([shape], 2, ops)
+        with pytest.raises(B.AmapError) as e:
+            B.amap_gemm_selfcheck(a, n)
+        assert e.value.status == B.AMAP_E_UNSUPPORTED
