@@ -367,7 +367,9 @@ amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t 
  * not straddle a block of 256 rows run a kernel with 256 x 256 x 64 tiles whose
  * operands go straight from L2 into LDS (environment AMAP_GEMM_TILE256=0: the
  * general kernel for these too); both add the same products in the same order,
- * so their results are bit-identical. */
+ * so their results are bit-identical.  Operands and sources of 2^31 elements and
+ * more (an A of [1048832, 2048], 4.3 GB) are taken for these aligned shapes only,
+ * with a plain store; every other product over such tensors is AMAP_E_UNSUPPORTED. */
 amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
                             void *out, void *stream);
 

@@ -71,6 +71,7 @@ struct GemmArgs {
     uint32_t sbase;
     uint32_t tiles_m, tiles_n;
     uint32_t a_row_ss;  // tile256 kernel: source elements between consecutive m inside a 256-row tile
+    int64_t a_base;     // tile256 kernel: sbase in 64 bits (its tile and k-step offsets are 64-bit: operands of 2^31 elements and more)
     Digits dm, dk;
     // store side (Section 2, eq. "store"): element (m, n) of the product goes to
     // out[obase + om(m) + on(n)]; store_mapped = 0 means the plain row-major C
@@ -490,24 +491,36 @@ __host__ __device__ __forceinline__ uint32_t t2_w_lane(const GemmArgs &g, uint32
     const uint32_t w_kr = lane >> 5;
     return 2u * ((16u * wave + w_kr) * g.N + 8u * ((lane & 31u) ^ (w_kr << 2) ^ (par << 3)));
 }
-// wave-uniform byte offsets of a tile, and of a k-step inside it
-__host__ __device__ __forceinline__ void t2_tile_bases(const GemmArgs &g, uint32_t tile, uint32_t &a_tile, uint32_t &w_tile) {
+// Wave-uniform byte offsets of a tile, and of a k-step inside it: 64-bit, added to the operand's pointer in
+// scalar registers, so that operands of 2^31 elements and more are within reach; what a lane adds (below) is a
+// non-negative 32-bit offset inside the tile's rows of one k-step.
+__host__ __device__ __forceinline__ int64_t digits_offset4_wide(const Digits &d, uint32_t x) {
+    int64_t off = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+#endif
+    for (uint32_t j = 0; j < (uint32_t)kMaxDigits; ++j) {
+        const uint32_t q = fdiv(x, d.fmult[j]);
+        const uint32_t dig = q - fdiv(q, d.fext[j]) * d.ext[j];
+        off += (int64_t)dig * (int64_t)d.ss[j];
+    }
+    return off;
+}
+__host__ __device__ __forceinline__ void t2_tile_bases(const GemmArgs &g, uint32_t tile, int64_t &a_tile, int64_t &w_tile) {
     uint32_t tm, tn;
     tile_of_block(tile, g.tiles_m, g.tiles_n, tm, tn);
-    a_tile = 2u * (g.sbase + digits_offset4(g.dm, tm * (uint32_t)T2M));
-    w_tile = 2u * (tn * (uint32_t)T2N);
+    a_tile = 2 * (g.a_base + digits_offset4_wide(g.dm, tm * (uint32_t)T2M));
+    w_tile = 2 * (int64_t)(tn * (uint32_t)T2N);
 }
-__host__ __device__ __forceinline__ uint32_t t2_a_step(const GemmArgs &g, uint32_t a_tile, uint32_t k0) {
-    return a_tile + 2u * digits_offset4(g.dk, k0);
+__host__ __device__ __forceinline__ int64_t t2_a_step(const GemmArgs &g, int64_t a_tile, uint32_t k0) {
+    return a_tile + 2 * digits_offset4_wide(g.dk, k0);
 }
-__host__ __device__ __forceinline__ uint32_t t2_w_step(const GemmArgs &g, uint32_t w_tile, uint32_t k0) { return w_tile + 2u * k0 * g.N; }
-// byte offset of load block j (0 .. 7) of a wavefront
-__host__ __device__ __forceinline__ uint32_t t2_a_load(const GemmArgs &g, uint32_t a_lane_par, uint32_t ka, uint32_t j) {
-    return a_lane_par + ka + 16u * j * g.a_row_ss;
+__host__ __device__ __forceinline__ int64_t t2_w_step(const GemmArgs &g, int64_t w_tile, uint32_t k0) { return w_tile + 2 * (int64_t)k0 * (int64_t)g.N; }
+// a lane's byte offset for load block j (0 .. 7) of its wavefront, from the k-step's base
+__host__ __device__ __forceinline__ uint32_t t2_a_load(const GemmArgs &g, uint32_t a_lane_par, uint32_t j) {
+    return a_lane_par + 16u * j * g.a_row_ss;
 }
-__host__ __device__ __forceinline__ uint32_t t2_w_load(const GemmArgs &g, uint32_t w_lane_par, uint32_t wk, uint32_t j) {
-    return w_lane_par + wk + 4u * j * g.N;
-}
+__host__ __device__ __forceinline__ uint32_t t2_w_load(const GemmArgs &g, uint32_t w_lane_par, uint32_t j) { return w_lane_par + 4u * j * g.N; }
 // epilogue: element offset in out of the 8 values a lane stores for row m, first column n_lane
 template <bool MAPPED>
 __host__ __device__ __forceinline__ size_t t2_store_col(const GemmArgs &g, uint32_t n_lane) {
@@ -536,18 +549,18 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
         a_lane[par] = t2_a_lane(g, wave, lane, par);
         w_lane[par] = t2_w_lane(g, wave, lane, par);
     }
-    uint32_t a_tile = 0, w_tile = 0;   // wave-uniform byte offsets of the cursor's tile
+    int64_t a_tile = 0, w_tile = 0;   // wave-uniform byte offsets of the cursor's tile
     auto cursor_tile = [&]() __attribute__((always_inline)) { t2_tile_bases(g, ld.tile, a_tile, w_tile); };
-    uint32_t ka = 0, wk = 0;
+    const char *ka = nullptr, *wk = nullptr;   // the operands at the cursor's tile and k-step
     auto loads_begin = [&]() __attribute__((always_inline)) {
-        ka = t2_a_step(g, a_tile, ld.k0);
-        wk = t2_w_step(g, w_tile, ld.k0);
+        ka = reinterpret_cast<const char *>(g.A_src) + t2_a_step(g, a_tile, ld.k0);
+        wk = reinterpret_cast<const char *>(g.W) + t2_w_step(g, w_tile, ld.k0);
     };
     auto load_one = [&](uint32_t stage_base, int j, int which) __attribute__((always_inline)) {
         if (which == 0)
-            load_to_lds16(g.A_src, t2_a_load(g, a_lane[j & 1], ka, (uint32_t)j), stage_base + (wave * 8u + j) * 1024u);
+            load_to_lds16(ka, t2_a_load(g, a_lane[j & 1], (uint32_t)j), stage_base + (wave * 8u + j) * 1024u);
         else
-            load_to_lds16(g.W, t2_w_load(g, w_lane[j & 1], wk, (uint32_t)j), stage_base + kT2WOff + (wave * 8u + j) * 1024u);
+            load_to_lds16(wk, t2_w_load(g, w_lane[j & 1], (uint32_t)j), stage_base + kT2WOff + (wave * 8u + j) * 1024u);
     };
     // the cursor moves on by one k-step; in a new tile that exists its bases are recomputed
     auto cursor_next = [&]() __attribute__((always_inline)) {
@@ -700,6 +713,8 @@ bool make_digits(const Piece &p, int dim, int64_t extent, Digits &d, int64_t lo 
     int64_t covered = 1;
     for (const IterDim &it : its) covered *= it.extent;
     if (covered != extent || p.lo[dim] != lo) return false;
+    for (const IterDim &it : its)   // what the 32-bit fields below (and the dividers, good below 2^31) hold
+        if (it.mult >= (1ll << 31) || it.extent >= (1ll << 31) || it.sstride >= (1ll << 31) || it.sstride <= -(1ll << 31)) return false;
     for (const IterDim &it : its) {
         const uint32_t j = d.n++;
         d.mult[j] = (uint32_t)it.mult;
@@ -815,7 +830,10 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     if (N % 8 || K % 8) return unsupported("N and K must be multiples of 8");
     bool edge = M % BM || N % BN || K % BK;
     if (!A_map->strided || A_map->pieces.empty()) return unsupported("the A map has no strided form");
-    if (M * K >= (1ll << 31) || M * N >= (1ll << 40) || K * N >= (1ll << 31)) return unsupported("operand too large for 32-bit offsets");
+    if (M >= (1ll << 31) || N >= (1ll << 24) || K >= (1ll << 31) || M * N >= (1ll << 40)) return unsupported("operand too large");
+    // Operands or sources of 2^31 elements and more: only the aligned-shape kernel reaches them (64-bit tile bases);
+    // every other product is refused further down, once it is known which kernel it would take.
+    bool wide = M * K >= (1ll << 31) || K * N >= (1ll << 31);
     if (out_map && M * N >= (1ll << 31)) return unsupported("product too large for a mapped store");
     const int64_t cbytes = M * N * 2;
     GemmArgs g;
@@ -878,7 +896,7 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
         const void *src = A_srcs[by_id ? p.src : 0];
         if (!src || ((uintptr_t)src & 15)) return AMAP_E_INVALID;
         const int64_t svol = volume_of(A_map->src_shapes[p.src]);
-        if (svol >= (1ll << 31)) return unsupported("A source too large for 32-bit offsets");
+        if (svol >= (1ll << 31) || p.sbase >= (1ll << 31)) wide = true;
         if (overlaps(out, cbytes, src, svol * 2)) return AMAP_E_ALIAS;
         const int64_t kext = piece_extent(p, 1);
         Digits dm, dk;
@@ -911,6 +929,7 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
         if (segs.size() == 1) {
             g.A_src = static_cast<const uint16_t *>(src);
             g.sbase = (uint32_t)p.sbase;
+            g.a_base = p.sbase;
             g.dm = dm;
             g.dk = dk;
         } else {
@@ -977,7 +996,8 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     const bool tile256_on = !(t256 && t256[0] == '0');
     if (g.padded) edge = true;   // the instances that test every vector also take the padding
     if (tile256_on && !g.padded && amode == A_RUNS_K && segs.size() == 1 && wmode == W_PLAIN && M % T2M == 0 && N % T2N == 0 && K % T2K == 0 &&
-        K >= 2 * T2K && g.dm.mult[0] == 1 && g.dm.ext[0] % T2M == 0 && g.dk.mult[0] == 1 && g.dk.ss[0] == 1 && g.dk.ext[0] % T2K == 0) {
+        K >= 2 * T2K && g.dm.mult[0] == 1 && g.dm.ext[0] % T2M == 0 && g.dm.ss[0] >= 0 && g.dm.ss[0] < (1 << 23) && g.dk.mult[0] == 1 &&
+        g.dk.ss[0] == 1 && g.dk.ext[0] % T2K == 0 && (!wide || !out_map)) {
         if (dry) {
             g.a_row_ss = (uint32_t)g.dm.ss[0];
             g.tiles_m = (uint32_t)(M / T2M);
@@ -1022,6 +1042,7 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
         }
         return AMAP_OK;
     }
+    if (wide) return unsupported("an operand or source of 2^31 elements and more: only aligned shapes (see amap_gemm_fused) with a plain store reach it");
     if (dry) {
         *dry = g;
         *dry_kernel = 0;
@@ -1157,7 +1178,7 @@ extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const
         const uint32_t ntiles = g.tiles_m * g.tiles_n, steps = g.K / (uint32_t)T2K;
         const uint32_t nwg = std::min<uint32_t>((uint32_t)n_workgroups, ntiles);
         std::vector<uint8_t> written((size_t)(c_elems / 8), 0);   // per 8-element vector of out
-        std::vector<uint32_t> got_a, got_w, want_a, want_w;
+        std::vector<int64_t> got_a, got_w, want_a, want_w;
         for (uint32_t blk = 0; blk < nwg; ++blk) {
             std::vector<T2Cursor> fetched, consumed;
             // one batch of loads of all four wavefronts for the cursor's k-step
@@ -1167,17 +1188,17 @@ extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const
                     ++errors;
                     return;
                 }
-                uint32_t a_tile, w_tile;
+                int64_t a_tile, w_tile;
                 t2_tile_bases(g, c.tile, a_tile, w_tile);
-                const uint32_t ka = t2_a_step(g, a_tile, c.k0), wk = t2_w_step(g, w_tile, c.k0);
+                const int64_t ka = t2_a_step(g, a_tile, c.k0), wk = t2_w_step(g, w_tile, c.k0);
                 got_a.clear(), got_w.clear(), want_a.clear(), want_w.clear();
                 for (uint32_t wave = 0; wave < 4; ++wave)
                     for (uint32_t j = 0; j < 8; ++j)
                         for (uint32_t lane = 0; lane < 64; ++lane) {
-                            const uint32_t ao = t2_a_load(g, t2_a_lane(g, wave, lane, j & 1u), ka, j);
-                            const uint32_t wo = t2_w_load(g, t2_w_lane(g, wave, lane, j & 1u), wk, j);
-                            if ((int64_t)ao + 16 > a_bytes) ++errors;
-                            if ((int64_t)wo + 16 > w_bytes) ++errors;
+                            const int64_t ao = ka + (int64_t)t2_a_load(g, t2_a_lane(g, wave, lane, j & 1u), j);
+                            const int64_t wo = wk + (int64_t)t2_w_load(g, t2_w_lane(g, wave, lane, j & 1u), j);
+                            if (ao < 0 || ao + 16 > a_bytes) ++errors;
+                            if (wo < 0 || wo + 16 > w_bytes) ++errors;
                             got_a.push_back(ao);
                             got_w.push_back(wo);
                         }
@@ -1185,10 +1206,10 @@ extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const
                 tile_of_block(c.tile, g.tiles_m, g.tiles_n, tm, tn);
                 for (uint32_t r = 0; r < (uint32_t)T2M; ++r)
                     for (uint32_t ch = 0; ch < 8; ++ch)
-                        want_a.push_back(2u * (g.sbase + digits_offset4(g.dm, tm * (uint32_t)T2M + r) + digits_offset4(g.dk, c.k0 + 8u * ch)));
+                        want_a.push_back(2 * (g.a_base + digits_offset4_wide(g.dm, tm * (uint32_t)T2M + r) + digits_offset4_wide(g.dk, c.k0 + 8u * ch)));
                 for (uint32_t kr = 0; kr < (uint32_t)T2K; ++kr)
                     for (uint32_t ch = 0; ch < 32; ++ch)
-                        want_w.push_back(2u * ((c.k0 + kr) * g.N + tn * (uint32_t)T2N + 8u * ch));
+                        want_w.push_back(2 * ((int64_t)(c.k0 + kr) * (int64_t)g.N + (int64_t)(tn * (uint32_t)T2N + 8u * ch)));
                 std::sort(got_a.begin(), got_a.end()), std::sort(want_a.begin(), want_a.end());
                 std::sort(got_w.begin(), got_w.end()), std::sort(want_w.begin(), want_w.end());
                 if (got_a != want_a) ++errors;

@@ -75,3 +75,17 @@ def test_products_of_the_general_kernel_have_no_replay():
         with pytest.raises(B.AmapError) as e:
             B.amap_gemm_selfcheck(a, n)
         assert e.value.status == B.AMAP_E_UNSUPPORTED
+
+
+def test_replay_of_an_operand_of_more_than_2_31_elements():
+    """Tile and k-step bases are 64-bit: A[1048832, 2048] (4.3 GB) read plainly and through a head merge."""
+    m, k, n = 4097 * 256, 2048, 256
+    assert B.amap_gemm_selfcheck(B.amap_compose([(m, k)], 2, []), n, None, 256) == 0
+    merged = B.amap_compose([(4097, 16, 256, 128)], 2, [("transpose", (0, 2, 1, 3)), ("reshape", (m, k))])
+    assert B.amap_gemm_selfcheck(merged, n, None, 64) == 0
+    # not for the general kernel, and not with a mapped store
+    for a, out_map in [(B.amap_compose([(m + 8, k)], 2, []), None),
+                       (B.amap_compose([(m, k)], 2, []), B.amap_compose([(m, n)], 2, [("reshape", (m, 4, 64)), ("transpose", (1, 0, 2))]))]:
+        with pytest.raises(B.AmapError) as e:
+            B.amap_gemm_selfcheck(a, n, out_map, 256)
+        assert e.value.status == B.AMAP_E_UNSUPPORTED

@@ -105,3 +105,57 @@ def test_more_than_2_31_elements(dev, ops):
     # compare in slabs to keep the temporaries small
     for r in range(0, want.shape[0], 4096):
         assert np.array_equal(got[r:r + 4096], want[r:r + 4096]), r
+
+
+def test_gemm_operand_of_more_than_2_31_elements(dev, monkeypatch, capfd):
+    """A[1048832, 2048] (2.15e9 elements, 4.3 GB) x W[2048, 256] on the 256 x 256-tile kernel, whose tile and k-step
+    bases are 64-bit: whole 512-row blocks at the start, in the middle and at the end (the last one holds element
+    2^31 of A) against the oracle's product of those rows, and sampled outputs recomputed one by one."""
+    import torch
+    M, K, N = 4097 * 256, 2048, 256
+    free, _ = torch.cuda.mem_get_info()
+    if free < 16 * 2 ** 30:
+        pytest.skip("needs 16 GiB of device memory")
+    print(f"[gpu] wide gemm operand {M} x {K}", flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2024)
+    a = torch.empty((M, K), dtype=torch.int16, device="cuda")
+    for r in range(0, M, 65536):
+        rows = min(65536, M - r)
+        a[r:r + rows] = torch.randn((rows, K), generator=gen, device="cuda").bfloat16().view(torch.int16)
+    w = synth.f32_to_bf16_bits((np.random.default_rng(9).standard_normal((K, N)) * 0.02).astype(np.float32))
+    d_w = dev.to_device(w)
+    out = torch.empty((M, N), dtype=torch.int16, device="cuda")
+    a_map = B.amap_compose([(M, K)], 2, [])
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    capfd.readouterr()
+    B.amap_gemm_fused(a.data_ptr(), a_map, d_w.data_ptr(), N, out.data_ptr(), 0)
+    torch.cuda.synchronize()
+    assert "256 x 256 tiles" in capfd.readouterr().err
+    monkeypatch.delenv("AMAP_PLAN_TRACE")
+    oracle.set_threads(8)
+    try:
+        for r0 in (0, 524288, M - 512):
+            a_rows = a[r0:r0 + 512].cpu().numpy().view(np.uint16)
+            got = out[r0:r0 + 512].cpu().numpy().view(np.uint16)
+            want = oracle.gemm_bf16(a_rows, w)
+            g, r = synth.bf16_bits_to_f32(got).astype(np.float64), synth.bf16_bits_to_f32(want).astype(np.float64)
+            assert np.abs(g - r).max() <= 1e-2 * np.abs(r).max(), r0
+            ulp = np.maximum(np.abs(r), 2.0 ** -126) * 2.0 ** -7
+            assert np.mean(np.abs(g - r) <= ulp) > 0.999, r0
+    finally:
+        oracle.set_threads(1)
+    rng = np.random.default_rng(3)
+    for m, n in zip(rng.integers(0, M, 48), rng.integers(0, N, 48)):
+        row = a[int(m):int(m) + 1].cpu().numpy().view(np.uint16)
+        ref = oracle.gemm_bf16_point(row, w, 0, int(n))
+        gv = float(synth.bf16_bits_to_f32(out[int(m), int(n)].cpu().numpy().view(np.uint16).reshape(1))[0])
+        assert abs(gv - ref) <= 2.0 ** -7 * abs(ref) + 1e-6, (m, n)
+    del a, out
+    torch.cuda.empty_cache()
+    # what only the aligned-shape kernel reaches is refused elsewhere, not run with wrapped offsets
+    x = torch.zeros(1 << 20, dtype=torch.int16, device="cuda")
+    wide_general = B.amap_compose([(M + 8, K)], 2, [])          # M is no multiple of 256
+    with pytest.raises(B.AmapError) as e:
+        B.amap_gemm_fused(x.data_ptr(), wide_general, d_w.data_ptr(), N, x.data_ptr() + 2 * (1 << 19), 0)
+    assert e.value.status in (B.AMAP_E_UNSUPPORTED, B.AMAP_E_ALIAS)
