@@ -192,12 +192,13 @@ amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64_t *n_error
  * (see amap_gemm_fused for the shapes it takes): replays on the host, with the kernel's own address
  * functions, the loads of every workgroup (n_workgroups of them: the number of compute units on the
  * device, or any smaller number to make workgroups walk several tiles) and the stores of every tile
- * for the product A_map x W[K,N] (stored through out_map when it is not NULL), and counts loads
+ * for the product A_map x W (W row-major [K,N] when W_map is NULL, else read through W_map as in
+ * amap_gemm_mapped; stored through out_map when it is not NULL), and counts loads
  * outside A's source or W, k-steps that fetch anything but their own block of A and W, fetches out
  * of the order of use, stores outside out and elements of out written never or twice.
  * AMAP_E_UNSUPPORTED when the product would run in the general kernel (no replay for that one). */
-amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const amap_t *out_map, int n_workgroups,
-                                int64_t *n_errors);
+amap_status amap_gemm_selfcheck(const amap_t *A_map, const amap_t *W_map, int64_t N, const amap_t *out_map,
+                                int n_workgroups, int64_t *n_errors);
 
 /* ---- data-movement elimination over an operator graph (host only) ---------
  * Section 2.1 applied to a whole program: tensors are either materialised
@@ -387,7 +388,9 @@ amap_status amap_gemm_fused_store(const void *A_src, const amap_t *A_map, const 
  * (dst shape [K,N], bf16, one source, no fill; its contiguous runs of a multiple of 8
  * elements may lie along n, as in a row-major weight, or along k, as in a transposed
  * [N,K] weight, which then needs no transposition on its way to the matrix cores), and
- * the product stored through out_map if that is not NULL (as in amap_gemm_fused_store). */
+ * the product stored through out_map if that is not NULL (as in amap_gemm_fused_store).
+ * A [N,K] weight with whole 64-element runs along k and evenly spaced rows also runs in
+ * the 256 x 256-tile kernel when the shape is aligned as described for amap_gemm_fused. */
 amap_status amap_gemm_mapped(const void *A_src, const amap_t *A_map, const void *W_src, const amap_t *W_map,
                              const amap_t *out_map, void *out, void *stream);
 

@@ -89,7 +89,7 @@ _L.amap_source_shape.argtypes = [_vp, C.c_int, C.POINTER(C.c_int), _i64p]
 _L.amap_eval_host.argtypes = [_vp, _pp, _vp, C.c_int]
 _L.amap_check_cover.argtypes = [_vp, _i64p, _i64p]
 _L.amap_plan_selfcheck.argtypes = [_vp, C.c_int, _i64p]
-_L.amap_gemm_selfcheck.argtypes = [_vp, C.c_int64, _vp, C.c_int, _i64p]
+_L.amap_gemm_selfcheck.argtypes = [_vp, _vp, C.c_int64, _vp, C.c_int, _i64p]
 _L.amap_execute.argtypes = [_pp, _vp, _vp, _vp]
 _L.amap_execute_kernel.argtypes = [_pp, _vp, _vp, _vp, C.c_int]
 _L.amap_execute_multi.argtypes = [_pp, _pp, _pp, C.c_int, _vp]
@@ -300,10 +300,11 @@ def amap_plan_selfcheck(m, kernel_id=-1):
     return n.value
 
 
-def amap_gemm_selfcheck(a_map, n, out_map=None, n_workgroups=256):
+def amap_gemm_selfcheck(a_map, n, out_map=None, n_workgroups=256, w_map=None):
     """Errors found by the host replay of the 256 x 256-tile GEMM kernel's loads and stores."""
     e = C.c_int64()
-    _check(_L.amap_gemm_selfcheck(a_map.handle, int(n), out_map.handle if out_map is not None else None, int(n_workgroups),
+    _check(_L.amap_gemm_selfcheck(a_map.handle, w_map.handle if w_map is not None else None, int(n),
+                                  out_map.handle if out_map is not None else None, int(n_workgroups),
                                   C.byref(e)), "amap_gemm_selfcheck")
     return e.value
 

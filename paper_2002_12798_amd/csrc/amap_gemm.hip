@@ -72,6 +72,7 @@ struct GemmArgs {
     uint32_t tiles_m, tiles_n;
     uint32_t a_row_ss;  // tile256 kernel: source elements between consecutive m inside a 256-row tile
     int64_t a_base;     // tile256 kernel: sbase in 64 bits (its tile and k-step offsets are 64-bit: operands of 2^31 elements and more)
+    uint32_t w_row_ss;  // tile256 kernel, W with runs along k (a weight kept as [N,K]): source elements between consecutive n
     Digits dm, dk;
     // store side (Section 2, eq. "store"): element (m, n) of the product goes to
     // out[obase + om(m) + on(n)]; store_mapped = 0 means the plain row-major C
@@ -487,7 +488,13 @@ __host__ __device__ __forceinline__ uint32_t t2_a_lane(const GemmArgs &g, uint32
     const uint32_t a_chunk0 = (lane & 7u) ^ (lane >> 4);
     return 2u * ((64u * wave + (lane >> 3)) * g.a_row_ss + 8u * (a_chunk0 ^ (par << 2)));
 }
+// (W_KM: W's runs lie along k, a weight kept as [N,K] read through a transpose map: its stage is laid out like A's, rows = n)
+template <bool W_KM>
 __host__ __device__ __forceinline__ uint32_t t2_w_lane(const GemmArgs &g, uint32_t wave, uint32_t lane, uint32_t par) {
+    if constexpr (W_KM) {
+        const uint32_t chunk0 = (lane & 7u) ^ (lane >> 4);
+        return 2u * ((64u * wave + (lane >> 3)) * g.w_row_ss + 8u * (chunk0 ^ (par << 2)));
+    }
     const uint32_t w_kr = lane >> 5;
     return 2u * ((16u * wave + w_kr) * g.N + 8u * ((lane & 31u) ^ (w_kr << 2) ^ (par << 3)));
 }
@@ -506,21 +513,33 @@ __host__ __device__ __forceinline__ int64_t digits_offset4_wide(const Digits &d,
     }
     return off;
 }
+template <bool W_KM>
 __host__ __device__ __forceinline__ void t2_tile_bases(const GemmArgs &g, uint32_t tile, int64_t &a_tile, int64_t &w_tile) {
     uint32_t tm, tn;
     tile_of_block(tile, g.tiles_m, g.tiles_n, tm, tn);
     a_tile = 2 * (g.a_base + digits_offset4_wide(g.dm, tm * (uint32_t)T2M));
-    w_tile = 2 * (int64_t)(tn * (uint32_t)T2N);
+    if constexpr (W_KM)
+        w_tile = 2 * ((int64_t)g.wbase + digits_offset4_wide(g.wn, tn * (uint32_t)T2N));
+    else
+        w_tile = 2 * (int64_t)(tn * (uint32_t)T2N);
 }
 __host__ __device__ __forceinline__ int64_t t2_a_step(const GemmArgs &g, int64_t a_tile, uint32_t k0) {
     return a_tile + 2 * digits_offset4_wide(g.dk, k0);
 }
-__host__ __device__ __forceinline__ int64_t t2_w_step(const GemmArgs &g, int64_t w_tile, uint32_t k0) { return w_tile + 2 * (int64_t)k0 * (int64_t)g.N; }
+template <bool W_KM>
+__host__ __device__ __forceinline__ int64_t t2_w_step(const GemmArgs &g, int64_t w_tile, uint32_t k0) {
+    if constexpr (W_KM) return w_tile + 2 * digits_offset4_wide(g.wk, k0);
+    return w_tile + 2 * (int64_t)k0 * (int64_t)g.N;
+}
 // a lane's byte offset for load block j (0 .. 7) of its wavefront, from the k-step's base
 __host__ __device__ __forceinline__ uint32_t t2_a_load(const GemmArgs &g, uint32_t a_lane_par, uint32_t j) {
     return a_lane_par + 16u * j * g.a_row_ss;
 }
-__host__ __device__ __forceinline__ uint32_t t2_w_load(const GemmArgs &g, uint32_t w_lane_par, uint32_t j) { return w_lane_par + 4u * j * g.N; }
+template <bool W_KM>
+__host__ __device__ __forceinline__ uint32_t t2_w_load(const GemmArgs &g, uint32_t w_lane_par, uint32_t j) {
+    if constexpr (W_KM) return w_lane_par + 16u * j * g.w_row_ss;
+    return w_lane_par + 4u * j * g.N;
+}
 // epilogue: element offset in out of the 8 values a lane stores for row m, first column n_lane
 template <bool MAPPED>
 __host__ __device__ __forceinline__ size_t t2_store_col(const GemmArgs &g, uint32_t n_lane) {
@@ -533,7 +552,7 @@ __host__ __device__ __forceinline__ size_t t2_store_off(const GemmArgs &g, size_
     return (size_t)m * g.N + col_off;
 }
 
-template <bool STORE_MAPPED>
+template <bool STORE_MAPPED, bool W_KM>
 __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(const GemmArgs g) {
     const uint32_t tid = threadIdx.x, lane = tid & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -547,20 +566,20 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
 #pragma unroll
     for (uint32_t par = 0; par < 2; ++par) {
         a_lane[par] = t2_a_lane(g, wave, lane, par);
-        w_lane[par] = t2_w_lane(g, wave, lane, par);
+        w_lane[par] = t2_w_lane<W_KM>(g, wave, lane, par);
     }
     int64_t a_tile = 0, w_tile = 0;   // wave-uniform byte offsets of the cursor's tile
-    auto cursor_tile = [&]() __attribute__((always_inline)) { t2_tile_bases(g, ld.tile, a_tile, w_tile); };
+    auto cursor_tile = [&]() __attribute__((always_inline)) { t2_tile_bases<W_KM>(g, ld.tile, a_tile, w_tile); };
     const char *ka = nullptr, *wk = nullptr;   // the operands at the cursor's tile and k-step
     auto loads_begin = [&]() __attribute__((always_inline)) {
         ka = reinterpret_cast<const char *>(g.A_src) + t2_a_step(g, a_tile, ld.k0);
-        wk = reinterpret_cast<const char *>(g.W) + t2_w_step(g, w_tile, ld.k0);
+        wk = reinterpret_cast<const char *>(g.W) + t2_w_step<W_KM>(g, w_tile, ld.k0);
     };
     auto load_one = [&](uint32_t stage_base, int j, int which) __attribute__((always_inline)) {
         if (which == 0)
             load_to_lds16(ka, t2_a_load(g, a_lane[j & 1], (uint32_t)j), stage_base + (wave * 8u + j) * 1024u);
         else
-            load_to_lds16(wk, t2_w_load(g, w_lane[j & 1], (uint32_t)j), stage_base + kT2WOff + (wave * 8u + j) * 1024u);
+            load_to_lds16(wk, t2_w_load<W_KM>(g, w_lane[j & 1], (uint32_t)j), stage_base + kT2WOff + (wave * 8u + j) * 1024u);
     };
     // the cursor moves on by one k-step; in a new tile that exists its bases are recomputed
     auto cursor_next = [&]() __attribute__((always_inline)) {
@@ -578,18 +597,30 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
 #pragma unroll
     for (int jn = 0; jn < 4; ++jn) fw_addr[jn] = fw_base + (((uint32_t)jn ^ ((sq >> 2) & 3u)) << 6);
 
+    // W with runs along k: its stage is laid out like A's (row = n), and so are its fragments:
+    // row 128 wn + 32 jn + lane % 32, logical chunk 2 kk + lane / 32
+    const uint32_t fb_addr0 = kT2WOff + wn * 16384u + (lane & 31u) * 128u + (((lane >> 5) ^ ((lane >> 1) & 7u)) << 4);
+
     f32x16 acc[4][4];
     bf16x8 fa[2][4];
     bf16x4 fbl[2][4], fbh[2][4];
+    bf16x8 fbk[2][4];
     auto mf = [&](int set, int i, int jn) __attribute__((always_inline)) {
-        const bf16x8 b = __builtin_shufflevector(fbl[set][jn], fbh[set][jn], 0, 1, 2, 3, 4, 5, 6, 7);
+        bf16x8 b;
+        if constexpr (W_KM)
+            b = fbk[set][jn];
+        else
+            b = __builtin_shufflevector(fbl[set][jn], fbh[set][jn], 0, 1, 2, 3, 4, 5, 6, 7);
         // W fragment as the row operand: the 32 x 32 result is C^T, a lane holds four consecutive n of one row m
         acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, fa[set][i], acc[i][jn], 0, 0, 0);
     };
-    // one of the 12 fragment reads of a k sub-step (4 of A, 8 of W)
+    // one of the 12 fragment reads of a k sub-step (4 of A, 8 of W; 4 of W when its runs lie along k)
     auto rd = [&](int set, uint32_t stage_base, int kk, int r) __attribute__((always_inline)) {
         if (r < 4) {
             fa[set][r] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u32x4 *>(stage_base + (fa_addr0 ^ ((uint32_t)kk << 5)) + r * 4096u));
+        } else if constexpr (W_KM) {
+            if (r < 8)
+                fbk[set][r - 4] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u32x4 *>(stage_base + (fb_addr0 ^ ((uint32_t)kk << 5)) + (r - 4) * 4096u));
         } else {
             const uint32_t a = stage_base + fw_addr[(r - 4) >> 1] + kk * 8192u + ((r & 1) ? 2048u : 0u);
             const bf16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(reinterpret_cast<__attribute__((address_space(3))) bf16x4 *>(a));
@@ -995,15 +1026,19 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     const char *t256 = std::getenv("AMAP_GEMM_TILE256");   // 0: always the general kernel (tests compare the two)
     const bool tile256_on = !(t256 && t256[0] == '0');
     if (g.padded) edge = true;   // the instances that test every vector also take the padding
-    if (tile256_on && !g.padded && amode == A_RUNS_K && segs.size() == 1 && wmode == W_PLAIN && M % T2M == 0 && N % T2N == 0 && K % T2K == 0 &&
+    // W: row-major [K,N], or kept as [N,K] and read through a transpose map (whole 64-element runs along k, 256-row blocks of n evenly spaced)
+    const bool w_km = wmode == W_MAPPED_K && g.wk.mult[0] == 1 && g.wk.ss[0] == 1 && g.wk.ext[0] % T2K == 0 && g.wn.mult[0] == 1 &&
+                      g.wn.ext[0] % T2N == 0 && g.wn.ss[0] >= 0 && g.wn.ss[0] < (1 << 23);
+    if (tile256_on && !g.padded && amode == A_RUNS_K && segs.size() == 1 && (wmode == W_PLAIN || w_km) && M % T2M == 0 && N % T2N == 0 && K % T2K == 0 &&
         K >= 2 * T2K && g.dm.mult[0] == 1 && g.dm.ext[0] % T2M == 0 && g.dm.ss[0] >= 0 && g.dm.ss[0] < (1 << 23) && g.dk.mult[0] == 1 &&
         g.dk.ss[0] == 1 && g.dk.ext[0] % T2K == 0 && (!wide || !out_map)) {
+        g.w_row_ss = w_km ? (uint32_t)g.wn.ss[0] : 0u;
         if (dry) {
             g.a_row_ss = (uint32_t)g.dm.ss[0];
             g.tiles_m = (uint32_t)(M / T2M);
             g.tiles_n = (uint32_t)(N / T2N);
             *dry = g;
-            *dry_kernel = 1;
+            *dry_kernel = w_km ? 2 : 1;
             return AMAP_OK;
         }
         static thread_local int n_cu = 0;
@@ -1015,7 +1050,8 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
                 set_last_error("amap_gemm_tile256_kernel: cannot query the device");
                 return AMAP_E_HIP;
             }
-            for (const void *fn : {reinterpret_cast<const void *>(amap_gemm_tile256_kernel<false>), reinterpret_cast<const void *>(amap_gemm_tile256_kernel<true>)})
+            for (const void *fn : {reinterpret_cast<const void *>(amap_gemm_tile256_kernel<false, false>), reinterpret_cast<const void *>(amap_gemm_tile256_kernel<true, false>),
+                                   reinterpret_cast<const void *>(amap_gemm_tile256_kernel<false, true>), reinterpret_cast<const void *>(amap_gemm_tile256_kernel<true, true>)})
                 if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kT2Lds) != hipSuccess) {
                     (void)hipGetLastError();
                     n_cu = 0;
@@ -1024,17 +1060,21 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
                 }
         }
         if (const char *tr = std::getenv("AMAP_PLAN_TRACE"); tr && tr[0] != '0')
-            std::fprintf(stderr, "amap gemm: 256 x 256 tiles, %lld x %lld x %lld\n", (long long)M, (long long)N, (long long)K);
+            std::fprintf(stderr, "amap gemm: 256 x 256 tiles%s, %lld x %lld x %lld\n", w_km ? " (W runs along k)" : "", (long long)M, (long long)N, (long long)K);
         g.a_row_ss = (uint32_t)g.dm.ss[0];
         g.tiles_m = (uint32_t)(M / T2M);
         g.tiles_n = (uint32_t)(N / T2N);
         const uint32_t ntiles = g.tiles_m * g.tiles_n;
         const dim3 grid2(std::min<uint32_t>(ntiles, (uint32_t)n_cu)), block2(kGemmThreads);
         (void)hipGetLastError();   // an earlier, unrelated error on this thread is not this launch's
-        if (g.store_mapped)
-            hipLaunchKernelGGL(amap_gemm_tile256_kernel<true>, grid2, block2, kT2Lds, hs, g);
+        if (g.store_mapped && w_km)
+            hipLaunchKernelGGL((amap_gemm_tile256_kernel<true, true>), grid2, block2, kT2Lds, hs, g);
+        else if (g.store_mapped)
+            hipLaunchKernelGGL((amap_gemm_tile256_kernel<true, false>), grid2, block2, kT2Lds, hs, g);
+        else if (w_km)
+            hipLaunchKernelGGL((amap_gemm_tile256_kernel<false, true>), grid2, block2, kT2Lds, hs, g);
         else
-            hipLaunchKernelGGL(amap_gemm_tile256_kernel<false>, grid2, block2, kT2Lds, hs, g);
+            hipLaunchKernelGGL((amap_gemm_tile256_kernel<false, false>), grid2, block2, kT2Lds, hs, g);
         const hipError_t e2 = hipGetLastError();
         if (e2 != hipSuccess) {
             set_last_error("amap_gemm_tile256_kernel", hipGetErrorString(e2));
@@ -1157,22 +1197,39 @@ extern "C" amap_status amap_gemm_gather(const void *const *A_srcs, const amap_t 
 // a load outside the A source or outside W; a k-step that does not fetch exactly the 256 x 64 block of A and the
 // 64 x 256 block of W it is for; fetches that are not in the order the MFMAs consume them; a store outside out,
 // and elements of out written never or twice.  AMAP_E_UNSUPPORTED if the product would run in the general kernel.
-extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const amap_t *out_map, int n_workgroups,
-                                           int64_t *n_errors) {
+namespace {
+template <bool W_KM>
+amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, int n_workgroups, int64_t *n_errors);
+}
+
+extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, const amap_t *W_map, int64_t N, const amap_t *out_map,
+                                           int n_workgroups, int64_t *n_errors) {
     if (!A_map || !n_errors || n_workgroups < 1) return AMAP_E_INVALID;
     try {
         GemmArgs g;
         int kernel = 0;
         const void *fake_a = reinterpret_cast<const void *>((uintptr_t)1 << 40);
-        amap_status st = gemm_launch(&fake_a, false, A_map, reinterpret_cast<const void *>((uintptr_t)2 << 40), N, nullptr, out_map,
+        amap_status st = gemm_launch(&fake_a, false, A_map, reinterpret_cast<const void *>((uintptr_t)2 << 40), N, W_map, out_map,
                                      reinterpret_cast<void *>((uintptr_t)3 << 40), nullptr, &g, &kernel);
         if (st != AMAP_OK) return st;
-        if (kernel != 1) return unsupported("no host replay for the general GEMM kernel");
+        if (kernel == 0) return unsupported("no host replay for the general GEMM kernel");
         int src = -1;
         for (const Piece &q : A_map->pieces)
             if (!q.fill) src = q.src;
         if (src < 0 || (size_t)src >= A_map->src_shapes.size()) return AMAP_E_INVALID;
-        const int64_t a_bytes = volume_of(A_map->src_shapes[(size_t)src]) * 2, w_bytes = (int64_t)g.K * g.N * 2;
+        const int64_t a_bytes = volume_of(A_map->src_shapes[(size_t)src]) * 2;
+        const int64_t w_bytes = (W_map ? volume_of(W_map->src_shapes[(size_t)W_map->pieces[0].src]) : (int64_t)g.K * g.N) * 2;
+        return kernel == 2 ? replay_tile256<true>(g, a_bytes, w_bytes, n_workgroups, n_errors)
+                           : replay_tile256<false>(g, a_bytes, w_bytes, n_workgroups, n_errors);
+    } catch (...) {
+        return AMAP_E_NOMEM;
+    }
+}
+
+namespace {
+template <bool W_KM>
+amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, int n_workgroups, int64_t *n_errors) {
+    {
         const int64_t c_elems = (int64_t)g.M * g.N;
         int64_t errors = 0;
         const uint32_t ntiles = g.tiles_m * g.tiles_n, steps = g.K / (uint32_t)T2K;
@@ -1189,14 +1246,14 @@ extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const
                     return;
                 }
                 int64_t a_tile, w_tile;
-                t2_tile_bases(g, c.tile, a_tile, w_tile);
-                const int64_t ka = t2_a_step(g, a_tile, c.k0), wk = t2_w_step(g, w_tile, c.k0);
+                t2_tile_bases<W_KM>(g, c.tile, a_tile, w_tile);
+                const int64_t ka = t2_a_step(g, a_tile, c.k0), wk = t2_w_step<W_KM>(g, w_tile, c.k0);
                 got_a.clear(), got_w.clear(), want_a.clear(), want_w.clear();
                 for (uint32_t wave = 0; wave < 4; ++wave)
                     for (uint32_t j = 0; j < 8; ++j)
                         for (uint32_t lane = 0; lane < 64; ++lane) {
                             const int64_t ao = ka + (int64_t)t2_a_load(g, t2_a_lane(g, wave, lane, j & 1u), j);
-                            const int64_t wo = wk + (int64_t)t2_w_load(g, t2_w_lane(g, wave, lane, j & 1u), j);
+                            const int64_t wo = wk + (int64_t)t2_w_load<W_KM>(g, t2_w_lane<W_KM>(g, wave, lane, j & 1u), j);
                             if (ao < 0 || ao + 16 > a_bytes) ++errors;
                             if (wo < 0 || wo + 16 > w_bytes) ++errors;
                             got_a.push_back(ao);
@@ -1207,9 +1264,15 @@ extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const
                 for (uint32_t r = 0; r < (uint32_t)T2M; ++r)
                     for (uint32_t ch = 0; ch < 8; ++ch)
                         want_a.push_back(2 * (g.a_base + digits_offset4_wide(g.dm, tm * (uint32_t)T2M + r) + digits_offset4_wide(g.dk, c.k0 + 8u * ch)));
-                for (uint32_t kr = 0; kr < (uint32_t)T2K; ++kr)
-                    for (uint32_t ch = 0; ch < 32; ++ch)
-                        want_w.push_back(2 * ((int64_t)(c.k0 + kr) * (int64_t)g.N + (int64_t)(tn * (uint32_t)T2N + 8u * ch)));
+                if constexpr (W_KM) {
+                    for (uint32_t r = 0; r < (uint32_t)T2N; ++r)
+                        for (uint32_t ch = 0; ch < 8; ++ch)
+                            want_w.push_back(2 * ((int64_t)g.wbase + digits_offset4_wide(g.wn, tn * (uint32_t)T2N + r) + digits_offset4_wide(g.wk, c.k0 + 8u * ch)));
+                } else {
+                    for (uint32_t kr = 0; kr < (uint32_t)T2K; ++kr)
+                        for (uint32_t ch = 0; ch < 32; ++ch)
+                            want_w.push_back(2 * ((int64_t)(c.k0 + kr) * (int64_t)g.N + (int64_t)(tn * (uint32_t)T2N + 8u * ch)));
+                }
                 std::sort(got_a.begin(), got_a.end()), std::sort(want_a.begin(), want_a.end());
                 std::sort(got_w.begin(), got_w.end()), std::sort(want_w.begin(), want_w.end());
                 if (got_a != want_a) ++errors;
@@ -1258,7 +1321,6 @@ extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, int64_t N, const
             if (w != 1) ++errors;
         *n_errors = errors;
         return AMAP_OK;
-    } catch (...) {
-        return AMAP_E_NOMEM;
     }
 }
+}  // namespace

@@ -12,5 +12,5 @@ amap_status amap_gemm_fused(const void *, const amap_t *, const void *, int64_t,
 amap_status amap_gemm_fused_store(const void *, const amap_t *, const void *, int64_t, const amap_t *, void *, void *) { return AMAP_E_HIP; }
 amap_status amap_gemm_mapped(const void *, const amap_t *, const void *, const amap_t *, const amap_t *, void *, void *) { return AMAP_E_HIP; }
 amap_status amap_gemm_gather(const void *const *, const amap_t *, const void *, const amap_t *, int64_t, const amap_t *, void *, void *) { return AMAP_E_HIP; }
-amap_status amap_gemm_selfcheck(const amap_t *, int64_t, const amap_t *, int, int64_t *) { return AMAP_E_HIP; }
+amap_status amap_gemm_selfcheck(const amap_t *, const amap_t *, int64_t, const amap_t *, int, int64_t *) { return AMAP_E_HIP; }
 }

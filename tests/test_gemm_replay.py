@@ -89,3 +89,30 @@ def test_replay_of_an_operand_of_more_than_2_31_elements():
         with pytest.raises(B.AmapError) as e:
             B.amap_gemm_selfcheck(a, n, out_map, 256)
         assert e.value.status == B.AMAP_E_UNSUPPORTED
+
+
+WT_SHAPES = [
+    # (A source shape, chain), (W source shape, chain -> [K,N]), chain on the product or None
+    (((512, 128), []), ((256, 128), [("transpose", (1, 0))]), None),
+    (((512, 256), []), ((768, 320), [("slice", 1, 64, 320, 1), ("transpose", (1, 0))]), [("reshape", (512, 12, 64)), ("transpose", (1, 0, 2))]),
+    (((4352, 128), []), ((4096, 128), [("transpose", (1, 0))]), None),
+    (((512, 192), []), ((2, 256, 192), [("transpose", (2, 0, 1)), ("reshape", (192, 512))]), None),
+    (((16, 16, 512, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (8192, 1024))]), ((4096, 1024), [("transpose", (1, 0))]), None),
+]
+
+
+@pytest.mark.parametrize("case", range(len(WT_SHAPES)))
+def test_replay_with_the_weight_kept_transposed(case):
+    (shape, ops), (w_shape, w_ops), c_ops = WT_SHAPES[case]
+    a, w = B.amap_compose([shape], 2, ops), B.amap_compose([w_shape], 2, w_ops)
+    (m, _), (_, n) = B.dst_shape(a), B.dst_shape(w)
+    out_map = B.amap_compose([(m, n)], 2, c_ops) if c_ops else None
+    for nwg in (256, 2):
+        assert B.amap_gemm_selfcheck(a, n, out_map, nwg, w) == 0, nwg
+
+
+def test_a_weight_with_runs_along_n_through_a_map_has_no_replay():
+    a, w = B.amap_compose([(512, 128)], 2, []), B.amap_compose([(128, 256)], 2, [])
+    with pytest.raises(B.AmapError) as e:
+        B.amap_gemm_selfcheck(a, 256, None, 256, w)
+    assert e.value.status == B.AMAP_E_UNSUPPORTED

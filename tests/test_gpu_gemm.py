@@ -503,6 +503,89 @@ def test_tile256_identity_weight_is_exact(dev, monkeypatch, capfd):
     assert not (got[:, rest] & 0x7FFF).any()
 
 
+T256_WT_CASES = [
+    # (A source shape, A chain -> [M,K]), (W source shape, W chain -> [K,N]), chain on the product or None
+    (((512, 128), []), ((256, 128), [("transpose", (1, 0))]), None),                                # a weight kept as [N,K]
+    (((2, 4, 256, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (512, 256))]), ((512, 256), [("transpose", (1, 0))]), None),
+    (((512, 256), []), ((768, 320), [("slice", 1, 64, 320, 1), ("transpose", (1, 0))]),
+     [("reshape", (512, 12, 64)), ("transpose", (1, 0, 2))]),                                       # rows 320 apart, base offset, mapped store
+    (((4352, 128), []), ((4096, 128), [("transpose", (1, 0))]), None),                              # two k-steps, two tiles per workgroup
+    (((512, 192), []), ((2, 256, 192), [("transpose", (2, 0, 1)), ("reshape", (192, 512))]), None),  # n over two digits
+]
+
+
+@pytest.mark.parametrize("case", range(len(T256_WT_CASES)))
+def test_tile256_kernel_with_the_weight_kept_transposed(dev, case, monkeypatch, capfd):
+    """W with its runs along k (nn.Linear's [out_features, in_features]) on the 256 x 256 kernel: its stage is laid out
+    like A's.  Against the oracle and, bit for bit, against the general kernel."""
+    import torch
+    (shape, a_ops), (w_shape, w_ops), c_ops = T256_WT_CASES[case]
+    print(f"[gpu] tile256 gemm, W along k, case {case} {shape} {w_shape}", flush=True)
+    rng = np.random.default_rng(900 + case)
+    src = synth.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    w_src = synth.f32_to_bf16_bits((rng.standard_normal(w_shape) * 0.05).astype(np.float32))
+    a_map, w_map = B.amap_compose([shape], 2, a_ops), B.amap_compose([w_shape], 2, w_ops)
+    (M, K), (K2, N) = B.dst_shape(a_map), B.dst_shape(w_map)
+    assert K == K2
+    out_map = B.amap_compose([(M, N)], 2, c_ops) if c_ops else None
+    d_src, d_w = dev.to_device(src), dev.to_device(w_src)
+
+    def run():
+        out = torch.empty(B.dst_shape(out_map) if out_map else (M, N), dtype=torch.int16, device="cuda")
+        B.amap_gemm_mapped(d_src.data_ptr(), a_map, d_w.data_ptr(), w_map, out_map, out.data_ptr(), 0)
+        torch.cuda.synchronize()
+        return dev.to_host(out)
+
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    capfd.readouterr()
+    got = run()
+    assert "256 x 256 tiles (W runs along k)" in capfd.readouterr().err
+    monkeypatch.setenv("AMAP_GEMM_TILE256", "0")
+    general = run()
+    assert "256 x 128 tiles" in capfd.readouterr().err
+    monkeypatch.delenv("AMAP_GEMM_TILE256")
+    monkeypatch.delenv("AMAP_PLAN_TRACE")
+    a_bits = oracle.run_chain([src], a_ops) if a_ops else src
+    w_bits = oracle.run_chain([w_src], w_ops)
+    oracle.set_threads(8)
+    try:
+        want = oracle.gemm_bf16(a_bits, w_bits)
+    finally:
+        oracle.set_threads(1)
+    if c_ops:
+        want = oracle.run_chain([want], c_ops)
+    assert got.shape == want.shape
+    g, r = synth.bf16_bits_to_f32(got).astype(np.float64), synth.bf16_bits_to_f32(want).astype(np.float64)
+    assert np.abs(g - r).max() <= TOL * np.abs(r).max()
+    ulp = np.maximum(np.abs(r), 2.0 ** -126) * 2.0 ** -7
+    assert np.mean(np.abs(g - r) <= ulp) > 0.999
+    assert np.array_equal(got, general)
+
+
+def test_tile256_transposed_identity_weight_is_exact(dev, monkeypatch, capfd):
+    """W^T = shifted identity, kept as [N,K]: C reproduces A bit for bit (a wrong chunk or row in W's stage shows)."""
+    import torch
+    shape = (512, 128)
+    src = synth.f32_to_bf16_bits(np.random.default_rng(33).standard_normal(shape).astype(np.float32))
+    cols = (np.arange(128) * 5 + 3) % 256
+    wt = np.zeros((256, 128), dtype=np.float32)
+    wt[cols, np.arange(128)] = 1.0
+    a_map, w_map = B.amap_compose([shape], 2, []), B.amap_compose([(256, 128)], 2, [("transpose", (1, 0))])
+    out = torch.empty((512, 256), dtype=torch.int16, device="cuda")
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    capfd.readouterr()
+    d_src, d_wt = dev.to_device(src), dev.to_device(synth.f32_to_bf16_bits(wt))    # (kept alive until the product has run)
+    B.amap_gemm_mapped(d_src.data_ptr(), a_map, d_wt.data_ptr(), w_map, None, out.data_ptr(), 0)
+    torch.cuda.synchronize()
+    assert "256 x 256 tiles (W runs along k)" in capfd.readouterr().err
+    got = dev.to_host(out)
+    nz = (src & 0x7FFF) != 0
+    assert np.array_equal(got[:, cols][nz], src[nz])
+    rest = np.ones(256, dtype=bool)
+    rest[cols] = False
+    assert not (got[:, rest] & 0x7FFF).any()
+
+
 # ---- padding in front of the product: the pad operator's load composed into the operand load (Section 2.1, eq. 4)
 
 PAD_CASES = [
