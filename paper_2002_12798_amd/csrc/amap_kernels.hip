@@ -921,7 +921,13 @@ amap_status launch_pieces(const LaunchArgs &args, uint32_t blocks, size_t lds, i
         grouped = grouped || (args.p[k].kind != PK_ROWS && args.p[k].group_n > 1);
     const dim3 grid(blocks), block(64u << args.nwlog);
     clear_stale_error();
+    const char *tr = std::getenv("AMAP_PLAN_TRACE");
+    const bool trace = tr && tr[0] && tr[0] != '0';   // one line per launch on stderr: the kernel that takes it
+    auto say = [&](const char *kernel) {
+        if (trace) std::fprintf(stderr, "amap launch: %s, %u workgroups of %u lanes, %u pieces\n", kernel, blocks, 64u << args.nwlog, args.n_pieces);
+    };
     if (args.n_pieces == 1 && rows_is_plain(args.p[0], es)) {
+        say("amap_rows_kernel");
         const DevPiece &P = args.p[0];
 #define AMAP_LAUNCH_ROWS(ES, NT) hipLaunchKernelGGL((amap_rows_kernel<ES, NT>), grid, block, 0, stream, P, d)
         switch ((es == 2 ? 0 : 4) + (int)(args.nt & 3)) {
@@ -938,6 +944,7 @@ amap_status launch_pieces(const LaunchArgs &args, uint32_t blocks, size_t lds, i
         return launch_failed("amap_rows_kernel") ? AMAP_E_HIP : AMAP_OK;
     }
     if (launch_is_plain_rows(args, es)) {
+        say("amap_rows_multi_kernel");
 #define AMAP_LAUNCH_ROWSM(ES, NT) hipLaunchKernelGGL((amap_rows_multi_kernel<ES, NT>), grid, block, 0, stream, args, d)
         switch ((es == 2 ? 0 : 4) + (int)(args.nt & 3)) {
         case 0: AMAP_LAUNCH_ROWSM(2, 0); break;
@@ -953,6 +960,7 @@ amap_status launch_pieces(const LaunchArgs &args, uint32_t blocks, size_t lds, i
         return launch_failed("amap_rows_multi_kernel") ? AMAP_E_HIP : AMAP_OK;
     }
     if (launch_is_tile16(args, es)) {
+        say("amap_tile16_kernel");
 #define AMAP_LAUNCH_T16(ES, NT)                                                                              \
     do {                                                                                                     \
         if (grouped)                                                                                         \
@@ -973,6 +981,7 @@ amap_status launch_pieces(const LaunchArgs &args, uint32_t blocks, size_t lds, i
 #undef AMAP_LAUNCH_T16
         return launch_failed("amap_tile16_kernel") ? AMAP_E_HIP : AMAP_OK;
     }
+    say("amap_pieces_kernel");
 #define AMAP_LAUNCH(ES, NT)                                                                                  \
     do {                                                                                                     \
         if (grouped)                                                                                         \

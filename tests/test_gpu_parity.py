@@ -60,6 +60,27 @@ def test_workloads_all_families(dev, name):
     assert None in ran and B.AMAP_K_PROGRAM in ran and B.AMAP_K_ELEMENT in ran
 
 
+def test_named_workloads_run_in_the_kernels_built_for_their_launch_shape(dev, monkeypatch, capfd):
+    """cfg0, cfg1 and cfg3 (one tile piece or group, plus fill rows) in amap_tile16_kernel, cfg2 and the GEMM's
+    materialising copy (one plain row piece) in amap_rows_kernel; a silent fall-back to the general kernel would
+    keep every parity test green and lose the speed."""
+    import torch
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    for name, kernel in (("cfg0", "amap_tile16_kernel"), ("cfg1", "amap_tile16_kernel"), ("cfg3", "amap_tile16_kernel"),
+                         ("cfg2_fwd", "amap_rows_kernel"), ("cfg2_rev", "amap_rows_kernel"), ("cfg4", "amap_rows_kernel"),
+                         ("up3x", "amap_pieces_kernel")):
+        kw = {"n": 2} if name in ("cfg1", "cfg3", "up3x") else {}
+        w = synth.workload(name, **kw)
+        m = B.amap_compose(w.src_shapes, w.elem_size, w.ops)
+        srcs = [dev.to_device(s) for s in w.sources()]
+        capfd.readouterr()
+        dst = dev.execute(m, srcs)
+        torch.cuda.synchronize()
+        lines = [l for l in capfd.readouterr().err.splitlines() if l.startswith("amap launch:")]
+        assert len(lines) == 1 and lines[0].startswith(f"amap launch: {kernel},"), (name, lines)
+        assert np.array_equal(dev.to_host(dst), oracle.run_chain(w.sources(), w.ops)), name
+
+
 def test_secondary_readings(dev):
     """cfg0 with exclusive slice end / symmetric pad, and one chain per Q/K/V output."""
     w = synth.workload("cfg0")
