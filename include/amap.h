@@ -363,14 +363,16 @@ amap_status amap_execute_kernel(const void *const *src, void *dst, const amap_t 
  * read as the [N*H*W, C] matrix of a pointwise convolution: 4 k x 8 m blocks are
  * transposed on their way to the matrix cores), else AMAP_E_UNSUPPORTED; M, N and K
  * need not be whole numbers of the 256 x 128 x 64 tiles (edge tiles are clamped on
- * load, masked on store).  Shapes with M % 256 == N % 256 == 0, K % 64 == 0,
- * K >= 128, no padding and source runs of 64 elements and more along k that do
- * not straddle a block of 256 rows run a kernel with 256 x 256 x 64 tiles whose
- * operands go straight from L2 into LDS (environment AMAP_GEMM_TILE256=0: the
- * general kernel for these too); both add the same products in the same order,
- * so their results are bit-identical.  Operands and sources of 2^31 elements and
- * more (an A of [1048832, 2048], 4.3 GB) are taken for these aligned shapes only,
- * with a plain store; every other product over such tensors is AMAP_E_UNSUPPORTED. */
+ * load, masked on store).  Shapes with K % 64 == 0, K >= 128, no padding and
+ * source runs of 64 elements and more along k that do not straddle a block of
+ * 256 rows (the rows of A one run of evenly spaced source rows, or split into
+ * blocks that are multiples of 256) run a kernel with 256 x 256 x 64 tiles whose
+ * operands go straight from L2 into LDS, M and N being whole numbers of tiles
+ * or not (environment AMAP_GEMM_TILE256=0: the general kernel for these too);
+ * both add the same products in the same order, so their results are
+ * bit-identical.  Operands and sources of 2^31 elements and more (an A of
+ * [1048832, 2048], 4.3 GB) are taken by that kernel only, with a plain store;
+ * every other product over such tensors is AMAP_E_UNSUPPORTED. */
 amap_status amap_gemm_fused(const void *A_src, const amap_t *A_map, const void *W, int64_t N,
                             void *out, void *stream);
 
@@ -390,7 +392,7 @@ amap_status amap_gemm_fused_store(const void *A_src, const amap_t *A_map, const 
  * [N,K] weight, which then needs no transposition on its way to the matrix cores), and
  * the product stored through out_map if that is not NULL (as in amap_gemm_fused_store).
  * A [N,K] weight with whole 64-element runs along k and evenly spaced rows also runs in
- * the 256 x 256-tile kernel when the shape is aligned as described for amap_gemm_fused. */
+ * the 256 x 256-tile kernel when A and K are as described for amap_gemm_fused. */
 amap_status amap_gemm_mapped(const void *A_src, const amap_t *A_map, const void *W_src, const amap_t *W_map,
                              const amap_t *out_map, void *out, void *stream);
 

@@ -540,6 +540,39 @@ __host__ __device__ __forceinline__ uint32_t t2_w_load(const GemmArgs &g, uint32
     if constexpr (W_KM) return w_lane_par + 16u * j * g.w_row_ss;
     return w_lane_par + 4u * j * g.N;
 }
+// EDGE instances (M or N no multiple of 256): the rows / columns of a tile that exist; a lane whose row or column
+// lies past them loads the last existing one instead (its LDS slot then holds a copy of valid data, which only
+// reaches accumulators of rows / columns that are never stored), so no load leaves the operands.
+__host__ __device__ __forceinline__ uint32_t t2_rows_valid(const GemmArgs &g, uint32_t tm) {
+    const uint32_t left = g.M - tm * (uint32_t)T2M;
+    return left < (uint32_t)T2M ? left : (uint32_t)T2M;
+}
+__host__ __device__ __forceinline__ uint32_t t2_cols_valid(const GemmArgs &g, uint32_t tn) {
+    const uint32_t left = g.N - tn * (uint32_t)T2N;
+    return left < (uint32_t)T2N ? left : (uint32_t)T2N;
+}
+// rv: t2_rows_valid of the tile
+__host__ __device__ __forceinline__ uint32_t t2_a_load_edge(const GemmArgs &g, uint32_t wave, uint32_t lane, uint32_t j, uint32_t rv) {
+    uint32_t row = 64u * wave + (lane >> 3) + 8u * j;
+    row = row < rv ? row : rv - 1u;
+    const uint32_t chunk = (lane & 7u) ^ (lane >> 4) ^ ((j & 1u) << 2);
+    return 2u * (row * g.a_row_ss + 8u * chunk);
+}
+// cv: t2_cols_valid of the tile (a multiple of 8)
+template <bool W_KM>
+__host__ __device__ __forceinline__ uint32_t t2_w_load_edge(const GemmArgs &g, uint32_t wave, uint32_t lane, uint32_t j, uint32_t cv) {
+    if constexpr (W_KM) {
+        uint32_t row = 64u * wave + (lane >> 3) + 8u * j;
+        row = row < cv ? row : cv - 1u;
+        const uint32_t chunk = (lane & 7u) ^ (lane >> 4) ^ ((j & 1u) << 2);
+        return 2u * (row * g.w_row_ss + 8u * chunk);
+    }
+    const uint32_t w_kr = lane >> 5;
+    uint32_t chunk = (lane & 31u) ^ (w_kr << 2) ^ ((j & 1u) << 3);
+    const uint32_t last = (cv >> 3) - 1u;
+    chunk = chunk < last ? chunk : last;
+    return 2u * ((16u * wave + w_kr + 2u * j) * g.N + 8u * chunk);
+}
 // epilogue: element offset in out of the 8 values a lane stores for row m, first column n_lane
 template <bool MAPPED>
 __host__ __device__ __forceinline__ size_t t2_store_col(const GemmArgs &g, uint32_t n_lane) {
@@ -552,7 +585,7 @@ __host__ __device__ __forceinline__ size_t t2_store_off(const GemmArgs &g, size_
     return (size_t)m * g.N + col_off;
 }
 
-template <bool STORE_MAPPED, bool W_KM>
+template <bool STORE_MAPPED, bool W_KM, bool EDGE>
 __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(const GemmArgs g) {
     const uint32_t tid = threadIdx.x, lane = tid & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -569,7 +602,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
         w_lane[par] = t2_w_lane<W_KM>(g, wave, lane, par);
     }
     int64_t a_tile = 0, w_tile = 0;   // wave-uniform byte offsets of the cursor's tile
-    auto cursor_tile = [&]() __attribute__((always_inline)) { t2_tile_bases<W_KM>(g, ld.tile, a_tile, w_tile); };
+    uint32_t ld_rv = (uint32_t)T2M, ld_cv = (uint32_t)T2N;   // EDGE: existing rows / columns of the cursor's tile
+    auto cursor_tile = [&]() __attribute__((always_inline)) {
+        t2_tile_bases<W_KM>(g, ld.tile, a_tile, w_tile);
+        if constexpr (EDGE) {
+            uint32_t tm, tn;
+            tile_of_block(ld.tile, g.tiles_m, g.tiles_n, tm, tn);
+            ld_rv = t2_rows_valid(g, tm);
+            ld_cv = t2_cols_valid(g, tn);
+        }
+    };
     const char *ka = nullptr, *wk = nullptr;   // the operands at the cursor's tile and k-step
     auto loads_begin = [&]() __attribute__((always_inline)) {
         ka = reinterpret_cast<const char *>(g.A_src) + t2_a_step(g, a_tile, ld.k0);
@@ -577,9 +619,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
     };
     auto load_one = [&](uint32_t stage_base, int j, int which) __attribute__((always_inline)) {
         if (which == 0)
-            load_to_lds16(ka, t2_a_load(g, a_lane[j & 1], (uint32_t)j), stage_base + (wave * 8u + j) * 1024u);
+            load_to_lds16(ka, EDGE ? t2_a_load_edge(g, wave, lane, (uint32_t)j, ld_rv) : t2_a_load(g, a_lane[j & 1], (uint32_t)j),
+                          stage_base + (wave * 8u + j) * 1024u);
         else
-            load_to_lds16(wk, t2_w_load<W_KM>(g, w_lane[j & 1], (uint32_t)j), stage_base + kT2WOff + (wave * 8u + j) * 1024u);
+            load_to_lds16(wk, EDGE ? t2_w_load_edge<W_KM>(g, wave, lane, (uint32_t)j, ld_cv) : t2_w_load<W_KM>(g, w_lane[j & 1], (uint32_t)j),
+                          stage_base + kT2WOff + (wave * 8u + j) * 1024u);
     };
     // the cursor moves on by one k-step; in a new tile that exists its bases are recomputed
     auto cursor_next = [&]() __attribute__((always_inline)) {
@@ -715,7 +759,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
                 if (p >= 4) x = u32x4{x.z, x.w, x.x, x.y};
                 const uint32_t m = m_base + i * 32u + row;
                 const size_t off = t2_store_off<STORE_MAPPED>(g, col_off, m);
-                __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + off));
+                if (!EDGE || (m < g.M && n_lane < g.N)) __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + off));
             }
         }
     }
@@ -1026,19 +1070,21 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     const char *t256 = std::getenv("AMAP_GEMM_TILE256");   // 0: always the general kernel (tests compare the two)
     const bool tile256_on = !(t256 && t256[0] == '0');
     if (g.padded) edge = true;   // the instances that test every vector also take the padding
-    // W: row-major [K,N], or kept as [N,K] and read through a transpose map (whole 64-element runs along k, 256-row blocks of n evenly spaced)
+    // W: row-major [K,N], or kept as [N,K] and read through a transpose map (whole 64-element runs along k, rows of n evenly
+    // spaced inside every 256-row block: blocks that never straddle a digit, or one digit for all of n)
+    const bool edge256 = M % T2M != 0 || N % T2N != 0;   // partial last tiles: the EDGE instances
     const bool w_km = wmode == W_MAPPED_K && g.wk.mult[0] == 1 && g.wk.ss[0] == 1 && g.wk.ext[0] % T2K == 0 && g.wn.mult[0] == 1 &&
-                      g.wn.ext[0] % T2N == 0 && g.wn.ss[0] >= 0 && g.wn.ss[0] < (1 << 23);
-    if (tile256_on && !g.padded && amode == A_RUNS_K && segs.size() == 1 && (wmode == W_PLAIN || w_km) && M % T2M == 0 && N % T2N == 0 && K % T2K == 0 &&
-        K >= 2 * T2K && g.dm.mult[0] == 1 && g.dm.ext[0] % T2M == 0 && g.dm.ss[0] >= 0 && g.dm.ss[0] < (1 << 23) && g.dk.mult[0] == 1 &&
+                      (g.wn.ext[0] % T2N == 0 || g.wn.n == 1) && g.wn.ss[0] >= 0 && g.wn.ss[0] < (1 << 23);
+    if (tile256_on && !g.padded && amode == A_RUNS_K && segs.size() == 1 && (wmode == W_PLAIN || w_km) && K % T2K == 0 &&
+        K >= 2 * T2K && g.dm.mult[0] == 1 && (g.dm.ext[0] % T2M == 0 || g.dm.n == 1) && g.dm.ss[0] >= 0 && g.dm.ss[0] < (1 << 23) && g.dk.mult[0] == 1 &&
         g.dk.ss[0] == 1 && g.dk.ext[0] % T2K == 0 && (!wide || !out_map)) {
         g.w_row_ss = w_km ? (uint32_t)g.wn.ss[0] : 0u;
         if (dry) {
             g.a_row_ss = (uint32_t)g.dm.ss[0];
-            g.tiles_m = (uint32_t)(M / T2M);
-            g.tiles_n = (uint32_t)(N / T2N);
+            g.tiles_m = (uint32_t)((M + T2M - 1) / T2M);
+            g.tiles_n = (uint32_t)((N + T2N - 1) / T2N);
             *dry = g;
-            *dry_kernel = w_km ? 2 : 1;
+            *dry_kernel = (w_km ? 2 : 1) + (edge256 ? 2 : 0);
             return AMAP_OK;
         }
         static thread_local int n_cu = 0;
@@ -1050,8 +1096,10 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
                 set_last_error("amap_gemm_tile256_kernel: cannot query the device");
                 return AMAP_E_HIP;
             }
-            for (const void *fn : {reinterpret_cast<const void *>(amap_gemm_tile256_kernel<false, false>), reinterpret_cast<const void *>(amap_gemm_tile256_kernel<true, false>),
-                                   reinterpret_cast<const void *>(amap_gemm_tile256_kernel<false, true>), reinterpret_cast<const void *>(amap_gemm_tile256_kernel<true, true>)})
+#define AMAP_T2_FNS(E)                                                                                                                                     \
+    reinterpret_cast<const void *>(amap_gemm_tile256_kernel<false, false, E>), reinterpret_cast<const void *>(amap_gemm_tile256_kernel<true, false, E>), \
+        reinterpret_cast<const void *>(amap_gemm_tile256_kernel<false, true, E>), reinterpret_cast<const void *>(amap_gemm_tile256_kernel<true, true, E>)
+            for (const void *fn : {AMAP_T2_FNS(false), AMAP_T2_FNS(true)})
                 if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kT2Lds) != hipSuccess) {
                     (void)hipGetLastError();
                     n_cu = 0;
@@ -1060,21 +1108,30 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
                 }
         }
         if (const char *tr = std::getenv("AMAP_PLAN_TRACE"); tr && tr[0] != '0')
-            std::fprintf(stderr, "amap gemm: 256 x 256 tiles%s, %lld x %lld x %lld\n", w_km ? " (W runs along k)" : "", (long long)M, (long long)N, (long long)K);
+            std::fprintf(stderr, "amap gemm: 256 x 256 tiles%s%s, %lld x %lld x %lld\n", w_km ? " (W runs along k)" : "", edge256 ? " (partial last tiles)" : "",
+                         (long long)M, (long long)N, (long long)K);
         g.a_row_ss = (uint32_t)g.dm.ss[0];
-        g.tiles_m = (uint32_t)(M / T2M);
-        g.tiles_n = (uint32_t)(N / T2N);
+        g.tiles_m = (uint32_t)((M + T2M - 1) / T2M);
+        g.tiles_n = (uint32_t)((N + T2N - 1) / T2N);
         const uint32_t ntiles = g.tiles_m * g.tiles_n;
         const dim3 grid2(std::min<uint32_t>(ntiles, (uint32_t)n_cu)), block2(kGemmThreads);
         (void)hipGetLastError();   // an earlier, unrelated error on this thread is not this launch's
-        if (g.store_mapped && w_km)
-            hipLaunchKernelGGL((amap_gemm_tile256_kernel<true, true>), grid2, block2, kT2Lds, hs, g);
-        else if (g.store_mapped)
-            hipLaunchKernelGGL((amap_gemm_tile256_kernel<true, false>), grid2, block2, kT2Lds, hs, g);
-        else if (w_km)
-            hipLaunchKernelGGL((amap_gemm_tile256_kernel<false, true>), grid2, block2, kT2Lds, hs, g);
+#define AMAP_T2_LAUNCH(E)                                                                                   \
+    do {                                                                                                    \
+        if (g.store_mapped && w_km)                                                                         \
+            hipLaunchKernelGGL((amap_gemm_tile256_kernel<true, true, E>), grid2, block2, kT2Lds, hs, g);    \
+        else if (g.store_mapped)                                                                            \
+            hipLaunchKernelGGL((amap_gemm_tile256_kernel<true, false, E>), grid2, block2, kT2Lds, hs, g);   \
+        else if (w_km)                                                                                      \
+            hipLaunchKernelGGL((amap_gemm_tile256_kernel<false, true, E>), grid2, block2, kT2Lds, hs, g);   \
+        else                                                                                                \
+            hipLaunchKernelGGL((amap_gemm_tile256_kernel<false, false, E>), grid2, block2, kT2Lds, hs, g);  \
+    } while (0)
+        if (edge256)
+            AMAP_T2_LAUNCH(true);
         else
-            hipLaunchKernelGGL((amap_gemm_tile256_kernel<false, false>), grid2, block2, kT2Lds, hs, g);
+            AMAP_T2_LAUNCH(false);
+#undef AMAP_T2_LAUNCH
         const hipError_t e2 = hipGetLastError();
         if (e2 != hipSuccess) {
             set_last_error("amap_gemm_tile256_kernel", hipGetErrorString(e2));
@@ -1198,7 +1255,7 @@ extern "C" amap_status amap_gemm_gather(const void *const *A_srcs, const amap_t 
 // 64 x 256 block of W it is for; fetches that are not in the order the MFMAs consume them; a store outside out,
 // and elements of out written never or twice.  AMAP_E_UNSUPPORTED if the product would run in the general kernel.
 namespace {
-template <bool W_KM>
+template <bool W_KM, bool EDGE>
 amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, int n_workgroups, int64_t *n_errors);
 }
 
@@ -1219,15 +1276,19 @@ extern "C" amap_status amap_gemm_selfcheck(const amap_t *A_map, const amap_t *W_
         if (src < 0 || (size_t)src >= A_map->src_shapes.size()) return AMAP_E_INVALID;
         const int64_t a_bytes = volume_of(A_map->src_shapes[(size_t)src]) * 2;
         const int64_t w_bytes = (W_map ? volume_of(W_map->src_shapes[(size_t)W_map->pieces[0].src]) : (int64_t)g.K * g.N) * 2;
-        return kernel == 2 ? replay_tile256<true>(g, a_bytes, w_bytes, n_workgroups, n_errors)
-                           : replay_tile256<false>(g, a_bytes, w_bytes, n_workgroups, n_errors);
+        switch (kernel) {
+        case 1: return replay_tile256<false, false>(g, a_bytes, w_bytes, n_workgroups, n_errors);
+        case 2: return replay_tile256<true, false>(g, a_bytes, w_bytes, n_workgroups, n_errors);
+        case 3: return replay_tile256<false, true>(g, a_bytes, w_bytes, n_workgroups, n_errors);
+        default: return replay_tile256<true, true>(g, a_bytes, w_bytes, n_workgroups, n_errors);
+        }
     } catch (...) {
         return AMAP_E_NOMEM;
     }
 }
 
 namespace {
-template <bool W_KM>
+template <bool W_KM, bool EDGE>
 amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, int n_workgroups, int64_t *n_errors) {
     {
         const int64_t c_elems = (int64_t)g.M * g.N;
@@ -1249,32 +1310,39 @@ amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, 
                 t2_tile_bases<W_KM>(g, c.tile, a_tile, w_tile);
                 const int64_t ka = t2_a_step(g, a_tile, c.k0), wk = t2_w_step<W_KM>(g, w_tile, c.k0);
                 got_a.clear(), got_w.clear(), want_a.clear(), want_w.clear();
+                uint32_t tm, tn;
+                tile_of_block(c.tile, g.tiles_m, g.tiles_n, tm, tn);
+                const uint32_t rv = EDGE ? t2_rows_valid(g, tm) : (uint32_t)T2M, cv = EDGE ? t2_cols_valid(g, tn) : (uint32_t)T2N;
                 for (uint32_t wave = 0; wave < 4; ++wave)
                     for (uint32_t j = 0; j < 8; ++j)
                         for (uint32_t lane = 0; lane < 64; ++lane) {
-                            const int64_t ao = ka + (int64_t)t2_a_load(g, t2_a_lane(g, wave, lane, j & 1u), j);
-                            const int64_t wo = wk + (int64_t)t2_w_load<W_KM>(g, t2_w_lane<W_KM>(g, wave, lane, j & 1u), j);
+                            const int64_t ao = ka + (int64_t)(EDGE ? t2_a_load_edge(g, wave, lane, j, rv) : t2_a_load(g, t2_a_lane(g, wave, lane, j & 1u), j));
+                            const int64_t wo = wk + (int64_t)(EDGE ? t2_w_load_edge<W_KM>(g, wave, lane, j, cv)
+                                                                   : t2_w_load<W_KM>(g, t2_w_lane<W_KM>(g, wave, lane, j & 1u), j));
                             if (ao < 0 || ao + 16 > a_bytes) ++errors;
                             if (wo < 0 || wo + 16 > w_bytes) ++errors;
                             got_a.push_back(ao);
                             got_w.push_back(wo);
                         }
-                uint32_t tm, tn;
-                tile_of_block(c.tile, g.tiles_m, g.tiles_n, tm, tn);
-                for (uint32_t r = 0; r < (uint32_t)T2M; ++r)
+                // what the k-step is for: the existing rows (columns) of the tile, every 16-byte vector of them once
+                for (uint32_t r = 0; r < rv; ++r)
                     for (uint32_t ch = 0; ch < 8; ++ch)
                         want_a.push_back(2 * (g.a_base + digits_offset4_wide(g.dm, tm * (uint32_t)T2M + r) + digits_offset4_wide(g.dk, c.k0 + 8u * ch)));
                 if constexpr (W_KM) {
-                    for (uint32_t r = 0; r < (uint32_t)T2N; ++r)
+                    for (uint32_t r = 0; r < cv; ++r)
                         for (uint32_t ch = 0; ch < 8; ++ch)
                             want_w.push_back(2 * ((int64_t)g.wbase + digits_offset4_wide(g.wn, tn * (uint32_t)T2N + r) + digits_offset4_wide(g.wk, c.k0 + 8u * ch)));
                 } else {
                     for (uint32_t kr = 0; kr < (uint32_t)T2K; ++kr)
-                        for (uint32_t ch = 0; ch < 32; ++ch)
+                        for (uint32_t ch = 0; ch < cv / 8; ++ch)
                             want_w.push_back(2 * ((int64_t)(c.k0 + kr) * (int64_t)g.N + (int64_t)(tn * (uint32_t)T2N + 8u * ch)));
                 }
                 std::sort(got_a.begin(), got_a.end()), std::sort(want_a.begin(), want_a.end());
                 std::sort(got_w.begin(), got_w.end()), std::sort(want_w.begin(), want_w.end());
+                if (EDGE) {  // lanes past the last row / column repeat existing vectors: compare the sets
+                    got_a.erase(std::unique(got_a.begin(), got_a.end()), got_a.end());
+                    got_w.erase(std::unique(got_w.begin(), got_w.end()), got_w.end());
+                }
                 if (got_a != want_a) ++errors;
                 if (got_w != want_w) ++errors;
             };
@@ -1303,6 +1371,7 @@ amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, 
                         for (uint32_t i = 0; i < 4; ++i)
                             for (uint32_t pp = 0; pp < 8; ++pp) {
                                 const uint32_t m = m_base + i * 32u + 4u * pp + (lane >> 4);
+                                if (EDGE && !(m < g.M && n_lane < g.N)) continue;   // the kernel's store mask
                                 const size_t off = g.store_mapped ? t2_store_off<true>(g, col_off, m) : t2_store_off<false>(g, col_off, m);
                                 if (off % 8 || (int64_t)off + 8 > c_elems) {
                                     ++errors;

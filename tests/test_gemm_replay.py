@@ -67,8 +67,9 @@ def test_replay_of_random_aligned_shapes():
 
 
 def test_products_of_the_general_kernel_have_no_replay():
-    for shape, ops, n in [((200, 64), [], 128),                                   # M is no multiple of 256
+    for shape, ops, n in [((200, 72), [], 128),                                   # K is no multiple of 64
                           ((512, 64), [], 256),                                   # one k-step
+                          ((2, 4, 250, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (500, 256))], 512),   # tiles would straddle the two digits of m
                           ((256, 136), [("pad", (0, 0), (0, 56), 0)], 256),       # padded
                           ((128, 512), [("transpose", (1, 0))], 256)]:            # runs along m
         a = B.amap_compose([shape], 2, ops)
@@ -84,7 +85,8 @@ def test_replay_of_an_operand_of_more_than_2_31_elements():
     merged = B.amap_compose([(4097, 16, 256, 128)], 2, [("transpose", (0, 2, 1, 3)), ("reshape", (m, k))])
     assert B.amap_gemm_selfcheck(merged, n, None, 64) == 0
     # not for the general kernel, and not with a mapped store
-    for a, out_map in [(B.amap_compose([(m + 8, k)], 2, []), None),
+    assert B.amap_gemm_selfcheck(B.amap_compose([(m + 8, k)], 2, []), n, None, 256) == 0        # a partial last tile
+    for a, out_map in [(B.amap_compose([(m, k + 8)], 2, []), None),                             # K is no multiple of 64
                        (B.amap_compose([(m, k)], 2, []), B.amap_compose([(m, n)], 2, [("reshape", (m, 4, 64)), ("transpose", (1, 0, 2))]))]:
         with pytest.raises(B.AmapError) as e:
             B.amap_gemm_selfcheck(a, n, out_map, 256)
@@ -116,3 +118,29 @@ def test_a_weight_with_runs_along_n_through_a_map_has_no_replay():
     with pytest.raises(B.AmapError) as e:
         B.amap_gemm_selfcheck(a, 256, None, 256, w)
     assert e.value.status == B.AMAP_E_UNSUPPORTED
+
+
+EDGE_SHAPES = [
+    # M, K, N, workgroups: partial last tiles in M and / or N
+    (200, 128, 136, 256), (300, 192, 264, 256), (1000, 256, 1000, 3), (8, 128, 8, 256), (257, 128, 8, 1), (256, 128, 264, 2),
+]
+
+
+@pytest.mark.parametrize("case", range(len(EDGE_SHAPES)))
+def test_replay_of_partial_last_tiles(case):
+    m, k, n, nwg = EDGE_SHAPES[case]
+    a = B.amap_compose([(m, k)], 2, [])
+    assert B.amap_gemm_selfcheck(a, n, None, nwg) == 0
+    wt = B.amap_compose([(n, k)], 2, [("transpose", (1, 0))])          # the weight kept as [N,K]
+    assert B.amap_gemm_selfcheck(a, n, None, nwg, wt) == 0
+    if n % 8 == 0 and n >= 16:
+        store = B.amap_compose([(m, n)], 2, [("reshape", (m, n // 8, 8)), ("transpose", (1, 0, 2))])
+        assert B.amap_gemm_selfcheck(a, n, store, nwg) == 0
+
+
+def test_replay_of_random_partial_shapes():
+    rng = np.random.default_rng(17)
+    for _ in range(60):
+        m, k, n = int(rng.integers(1, 1200)), 64 * int(rng.integers(2, 6)), 8 * int(rng.integers(1, 150))
+        a = B.amap_compose([(m + 3, k + 64)], 2, [("slice", 0, 3, m + 3, 1), ("slice", 1, 64, k + 64, 1)])   # base offset, longer rows
+        assert B.amap_gemm_selfcheck(a, n, None, int(rng.choice([1, 4, 256]))) == 0, (m, k, n)

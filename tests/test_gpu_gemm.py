@@ -586,6 +586,67 @@ def test_tile256_transposed_identity_weight_is_exact(dev, monkeypatch, capfd):
     assert not (got[:, rest] & 0x7FFF).any()
 
 
+T256_EDGE_CASES = [
+    # M, K, N, weight kept as [N,K]?, chain on the product or None: partial last tiles of 256 in M and / or N
+    (200, 128, 136, False, None),
+    (300, 192, 264, False, None),
+    (1000, 256, 1000, False, None),
+    (8, 128, 8, False, None),
+    (1000, 256, 1000, True, None),
+    (257, 128, 520, True, None),
+    (520, 256, 200, False, [("reshape", (520, 25, 8)), ("transpose", (1, 0, 2))]),
+    (4352 + 40, 128, 4096 + 8, False, None),                  # partial tiles, two k-steps, two tiles per workgroup
+]
+
+
+@pytest.mark.parametrize("case", range(len(T256_EDGE_CASES)))
+def test_tile256_kernel_with_partial_last_tiles(dev, case, monkeypatch, capfd):
+    """M and N that are no multiples of 256 on the 256 x 256 kernel (lanes past the last row / column load the last
+    existing one, stores are masked): against the oracle and, bit for bit, against the general kernel."""
+    import torch
+    M, K, N, w_t, c_ops = T256_EDGE_CASES[case]
+    print(f"[gpu] tile256 gemm, partial tiles, case {case}: {M} x {K} x {N}", flush=True)
+    rng = np.random.default_rng(1100 + case)
+    src = synth.f32_to_bf16_bits(rng.standard_normal((M + 3, K + 64)).astype(np.float32))
+    a_ops = [("slice", 0, 3, M + 3, 1), ("slice", 1, 64, K + 64, 1)]          # base offset, rows longer than K
+    w = synth.f32_to_bf16_bits((rng.standard_normal((K, N)) * 0.05).astype(np.float32))
+    a_map = B.amap_compose([(M + 3, K + 64)], 2, a_ops)
+    w_map = B.amap_compose([(N, K)], 2, [("transpose", (1, 0))]) if w_t else None
+    out_map = B.amap_compose([(M, N)], 2, c_ops) if c_ops else None
+    d_src = dev.to_device(src)
+    d_w = dev.to_device(np.ascontiguousarray(w.T) if w_t else w)
+
+    def run():
+        out = torch.full(B.dst_shape(out_map) if out_map else (M, N), 0x5A5A, dtype=torch.int16, device="cuda")
+        B.amap_gemm_gather([d_src.data_ptr()], a_map, d_w.data_ptr(), w_map, N, out_map, out.data_ptr(), 0)
+        torch.cuda.synchronize()
+        return dev.to_host(out)
+
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    capfd.readouterr()
+    got = run()
+    err = capfd.readouterr().err
+    assert "256 x 256 tiles" in err and "(partial last tiles)" in err
+    monkeypatch.setenv("AMAP_GEMM_TILE256", "0")
+    general = run()
+    assert "256 x 128 tiles" in capfd.readouterr().err
+    monkeypatch.delenv("AMAP_GEMM_TILE256")
+    monkeypatch.delenv("AMAP_PLAN_TRACE")
+    oracle.set_threads(8)
+    try:
+        want = oracle.gemm_bf16(oracle.run_chain([src], a_ops), w)
+    finally:
+        oracle.set_threads(1)
+    if c_ops:
+        want = oracle.run_chain([want], c_ops)
+    assert got.shape == want.shape
+    g, r = synth.bf16_bits_to_f32(got).astype(np.float64), synth.bf16_bits_to_f32(want).astype(np.float64)
+    assert np.abs(g - r).max() <= TOL * np.abs(r).max()
+    ulp = np.maximum(np.abs(r), 2.0 ** -126) * 2.0 ** -7
+    assert np.mean(np.abs(g - r) <= ulp) > 0.999
+    assert np.array_equal(got, general)
+
+
 # ---- padding in front of the product: the pad operator's load composed into the operand load (Section 2.1, eq. 4)
 
 PAD_CASES = [

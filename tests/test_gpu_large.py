@@ -155,7 +155,7 @@ def test_gemm_operand_of_more_than_2_31_elements(dev, monkeypatch, capfd):
     torch.cuda.empty_cache()
     # what only the aligned-shape kernel reaches is refused elsewhere, not run with wrapped offsets
     x = torch.zeros(1 << 20, dtype=torch.int16, device="cuda")
-    wide_general = B.amap_compose([(M + 8, K)], 2, [])          # M is no multiple of 256
+    wide_general = B.amap_compose([(M, K + 8)], 2, [])          # K is no multiple of 64: the general kernel's
     with pytest.raises(B.AmapError) as e:
         B.amap_gemm_fused(x.data_ptr(), wide_general, d_w.data_ptr(), N, x.data_ptr() + 2 * (1 << 19), 0)
     assert e.value.status in (B.AMAP_E_UNSUPPORTED, B.AMAP_E_ALIAS)
