@@ -53,6 +53,15 @@ struct Digits {
     FastDiv fmult[kMaxDigits], fext[kMaxDigits];
 };
 
+// The k-steps of an operand of the 256 x 256-tile kernel as an odometer over the digits of k, so that the kernel
+// moves from one step to the next with a few scalar additions instead of decoding k: level 0 counts the
+// 64-element blocks of the contiguous lowest digit, level j >= 1 is digit j.  A step that carries into level j
+// (levels below j return to 0, level j goes up by one) moves the operand's address by dl[j] bytes.
+struct T2Steps {
+    uint32_t e[kMaxDigits - 1];   // extents of levels 0 .. 2 (the top level ends with K)
+    int64_t dl[kMaxDigits];
+};
+
 // A padded operand (Section 2.1: the load of a pad operator composed into the consumer load): the one
 // data piece covers, per dimension, index lo + sum_j i_j * mult[j] with i_j < ext[j]; an index is decoded
 // in the radices rad[j] = mult[j + 1] / mult[j] of the PADDED tensor and lies in the piece iff every
@@ -73,6 +82,7 @@ struct GemmArgs {
     uint32_t a_row_ss;  // tile256 kernel: source elements between consecutive m inside a 256-row tile
     int64_t a_base;     // tile256 kernel: sbase in 64 bits (its tile and k-step offsets are 64-bit: operands of 2^31 elements and more)
     uint32_t w_row_ss;  // tile256 kernel, W with runs along k (a weight kept as [N,K]): source elements between consecutive n
+    T2Steps a_steps, w_steps;   // tile256 kernel: the k-steps of A (and of a W with runs along k) as odometers over the digits of k
     Digits dm, dk;
     // store side (Section 2, eq. "store"): element (m, n) of the product goes to
     // out[obase + om(m) + on(n)]; store_mapped = 0 means the plain row-major C
@@ -523,13 +533,66 @@ __host__ __device__ __forceinline__ void t2_tile_bases(const GemmArgs &g, uint32
     else
         w_tile = 2 * (int64_t)(tn * (uint32_t)T2N);
 }
-__host__ __device__ __forceinline__ int64_t t2_a_step(const GemmArgs &g, int64_t a_tile, uint32_t k0) {
-    return a_tile + 2 * digits_offset4_wide(g.dk, k0);
+// the odometer of an operand whose lowest digit of k is contiguous and a whole number of 64-element steps
+__host__ inline T2Steps t2_steps_of(const Digits &d) {
+    T2Steps s;
+    const int64_t st[kMaxDigits] = {(int64_t)T2K, d.ss[1], d.ss[2], d.ss[3]};
+    const uint32_t e[kMaxDigits] = {d.ext[0] / (uint32_t)T2K, d.ext[1], d.ext[2], d.ext[3]};
+    int64_t back = 0;   // from the last step of the levels below to their first one
+    for (int j = 0; j < kMaxDigits; ++j) {
+        s.dl[j] = 2 * (st[j] - back);
+        back += (int64_t)(e[j] - 1u) * st[j];
+        if (j + 1 < kMaxDigits) s.e[j] = e[j];
+    }
+    return s;
 }
+// plain row-major W[K,N]: one level, 64 rows of N elements per step
+__host__ inline T2Steps t2_steps_plain_w(uint32_t K, uint32_t N) {
+    T2Steps s;
+    s.e[0] = K / (uint32_t)T2K;
+    s.e[1] = s.e[2] = 1;
+    for (int j = 0; j < kMaxDigits; ++j) s.dl[j] = 2 * (int64_t)T2K * (int64_t)N;
+    return s;
+}
+// counters of levels 0 .. 2 of one operand's odometer; all 0 at the first k-step of a tile
+struct T2Odo {
+    uint32_t c0, c1, c2;
+};
+// one k-step on: the byte delta to the next step's base (not called at the last step of a tile)
+__host__ __device__ __forceinline__ int64_t t2_odo_advance(T2Odo &o, const T2Steps &s) {
+    if (++o.c0 < s.e[0]) return s.dl[0];
+    o.c0 = 0;
+    if (++o.c1 < s.e[1]) return s.dl[1];
+    o.c1 = 0;
+    if (++o.c2 < s.e[2]) return s.dl[2];
+    o.c2 = 0;
+    return s.dl[3];
+}
+// The load stream of a workgroup: its cursor, the byte offsets of the cursor's tile in both operands and of the
+// cursor's k-step inside the tile's rows, and the odometers that move the latter.
+struct T2Stream {
+    T2Cursor c;
+    int64_t a_tile, w_tile, a_step, w_step;
+    T2Odo ao, wo;
+};
+// the cursor's tile has changed (and exists): its bases, first k-step
 template <bool W_KM>
-__host__ __device__ __forceinline__ int64_t t2_w_step(const GemmArgs &g, int64_t w_tile, uint32_t k0) {
-    if constexpr (W_KM) return w_tile + 2 * digits_offset4_wide(g.wk, k0);
-    return w_tile + 2 * (int64_t)k0 * (int64_t)g.N;
+__host__ __device__ __forceinline__ void t2_stream_tile(const GemmArgs &g, T2Stream &st) {
+    t2_tile_bases<W_KM>(g, st.c.tile, st.a_tile, st.w_tile);
+    st.a_step = st.w_step = 0;
+    st.ao = st.wo = T2Odo{0, 0, 0};
+}
+// one k-step on, into the workgroup's next tile after the last step of a tile; true if that was a tile change.
+// (g_tile: the same arguments as g, for what only the start of a tile reads; see t2_args_again)
+template <bool W_KM>
+__host__ __device__ __forceinline__ bool t2_stream_next(const GemmArgs &g, const GemmArgs &g_tile, T2Stream &st, uint32_t n_workgroups, uint32_t ntiles) {
+    if (t2_cursor_advance(st.c, g.K, n_workgroups)) {
+        if (st.c.tile < ntiles) t2_stream_tile<W_KM>(g_tile, st);
+        return true;
+    }
+    st.a_step += t2_odo_advance(st.ao, g.a_steps);
+    st.w_step += t2_odo_advance(st.wo, g.w_steps);
+    return false;
 }
 // a lane's byte offset for load block j (0 .. 7) of its wavefront, from the k-step's base
 __host__ __device__ __forceinline__ uint32_t t2_a_load(const GemmArgs &g, uint32_t a_lane_par, uint32_t j) {
@@ -585,6 +648,16 @@ __host__ __device__ __forceinline__ size_t t2_store_off(const GemmArgs &g, size_
     return (size_t)m * g.N + col_off;
 }
 
+// The kernel's argument block, read from the argument segment again at the place of use: what only the start of a
+// tile or its epilogue needs (the digits of m and n of both operands and of the store) then occupies no scalar
+// registers during the k-loop.  Left to itself the compiler loads every field once at the top of the kernel and
+// keeps it, and spills scalar registers inside the loop.  (The block is the kernel's only argument: offset 0.)
+__device__ __forceinline__ const GemmArgs &t2_args_again() {
+    auto p = (const __attribute__((address_space(4))) GemmArgs *)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(p));
+    return *(const GemmArgs *)p;
+}
+
 template <bool STORE_MAPPED, bool W_KM, bool EDGE>
 __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(const GemmArgs g) {
     const uint32_t tid = threadIdx.x, lane = tid & 63;
@@ -593,29 +666,28 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
     const uint32_t steps = g.K / T2K;  // >= 2
     const uint32_t ntiles = g.tiles_m * g.tiles_n;
 
-    // ---- load cursor (see T2Cursor) and the per-lane parts of the load addresses
-    T2Cursor ld = {blockIdx.x, 0};
+    // ---- load stream (see T2Stream) and the per-lane parts of the load addresses
+    T2Stream ld = {};
+    ld.c = T2Cursor{blockIdx.x, 0};
     uint32_t a_lane[2], w_lane[2];   // per-lane byte offsets, block parity 0 / 1
 #pragma unroll
     for (uint32_t par = 0; par < 2; ++par) {
         a_lane[par] = t2_a_lane(g, wave, lane, par);
         w_lane[par] = t2_w_lane<W_KM>(g, wave, lane, par);
     }
-    int64_t a_tile = 0, w_tile = 0;   // wave-uniform byte offsets of the cursor's tile
     uint32_t ld_rv = (uint32_t)T2M, ld_cv = (uint32_t)T2N;   // EDGE: existing rows / columns of the cursor's tile
-    auto cursor_tile = [&]() __attribute__((always_inline)) {
-        t2_tile_bases<W_KM>(g, ld.tile, a_tile, w_tile);
+    auto cursor_edges = [&]() __attribute__((always_inline)) {
         if constexpr (EDGE) {
             uint32_t tm, tn;
-            tile_of_block(ld.tile, g.tiles_m, g.tiles_n, tm, tn);
+            tile_of_block(ld.c.tile, g.tiles_m, g.tiles_n, tm, tn);
             ld_rv = t2_rows_valid(g, tm);
             ld_cv = t2_cols_valid(g, tn);
         }
     };
     const char *ka = nullptr, *wk = nullptr;   // the operands at the cursor's tile and k-step
     auto loads_begin = [&]() __attribute__((always_inline)) {
-        ka = reinterpret_cast<const char *>(g.A_src) + t2_a_step(g, a_tile, ld.k0);
-        wk = reinterpret_cast<const char *>(g.W) + t2_w_step<W_KM>(g, w_tile, ld.k0);
+        ka = reinterpret_cast<const char *>(g.A_src) + (ld.a_tile + ld.a_step);
+        wk = reinterpret_cast<const char *>(g.W) + (ld.w_tile + ld.w_step);
     };
     auto load_one = [&](uint32_t stage_base, int j, int which) __attribute__((always_inline)) {
         if (which == 0)
@@ -625,9 +697,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
             load_to_lds16(wk, EDGE ? t2_w_load_edge<W_KM>(g, wave, lane, (uint32_t)j, ld_cv) : t2_w_load<W_KM>(g, w_lane[j & 1], (uint32_t)j),
                           stage_base + kT2WOff + (wave * 8u + j) * 1024u);
     };
-    // the cursor moves on by one k-step; in a new tile that exists its bases are recomputed
+    // the stream moves on by one k-step (a few scalar additions); in a new tile that exists its bases are recomputed
     auto cursor_next = [&]() __attribute__((always_inline)) {
-        if (t2_cursor_advance(ld, g.K, gridDim.x) && ld.tile < ntiles) cursor_tile();
+        if (t2_stream_next<W_KM>(g, t2_args_again(), ld, gridDim.x, ntiles) && ld.c.tile < ntiles) cursor_edges();
     };
 
     // ---- fragment addresses (bytes from the start of a stage)
@@ -687,8 +759,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
         }
     };
     uint32_t cur = 0;
-    if (ld.tile < ntiles) {
-        cursor_tile();
+    if (ld.c.tile < ntiles) {
+        t2_stream_tile<W_KM>(t2_args_again(), ld);
+        cursor_edges();
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             loads_begin();
@@ -724,7 +797,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
             // last quarter: the fragments of the next step's first quarter come from the other stage (after
             // the workgroup's last step they are stale and unused), and the cursor's k-step, two ahead of
             // this one and possibly in the workgroup's next tile, is fetched into the stage just released
-            const bool issue = ld.tile < ntiles;
+            const bool issue = ld.c.tile < ntiles;
             phase(1, kT2Stage - cur, 0, true, cur, issue);
             if (issue) cursor_next();
             cur = kT2Stage - cur;
@@ -739,7 +812,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
         const uint32_t scr = kT2Scratch + wave * 8192u;
         const uint32_t row_w = lane & 31u, half_w = lane >> 5;
         const uint32_t m_base = tm * T2M + wm * 128u, n_lane = tn * T2N + wn * 128u + (lane & 15u) * 8u;
-        const size_t col_off = t2_store_col<STORE_MAPPED>(g, n_lane);
+        const GemmArgs &gs = t2_args_again();   // the store map's digits
+        const size_t col_off = t2_store_col<STORE_MAPPED>(gs, n_lane);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -758,7 +832,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
                 u32x4 x = *reinterpret_cast<lds_u32x4 *>(scr + row * 256u + ((chunk ^ (row & 15u)) << 4));
                 if (p >= 4) x = u32x4{x.z, x.w, x.x, x.y};
                 const uint32_t m = m_base + i * 32u + row;
-                const size_t off = t2_store_off<STORE_MAPPED>(g, col_off, m);
+                const size_t off = t2_store_off<STORE_MAPPED>(gs, col_off, m);
                 if (!EDGE || (m < g.M && n_lane < g.N)) __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(g.C + off));
             }
         }
@@ -1079,6 +1153,8 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
         K >= 2 * T2K && g.dm.mult[0] == 1 && (g.dm.ext[0] % T2M == 0 || g.dm.n == 1) && g.dm.ss[0] >= 0 && g.dm.ss[0] < (1 << 23) && g.dk.mult[0] == 1 &&
         g.dk.ss[0] == 1 && g.dk.ext[0] % T2K == 0 && (!wide || !out_map)) {
         g.w_row_ss = w_km ? (uint32_t)g.wn.ss[0] : 0u;
+        g.a_steps = t2_steps_of(g.dk);
+        g.w_steps = w_km ? t2_steps_of(g.wk) : t2_steps_plain_w(g.K, g.N);
         if (dry) {
             g.a_row_ss = (uint32_t)g.dm.ss[0];
             g.tiles_m = (uint32_t)((M + T2M - 1) / T2M);
@@ -1300,15 +1376,14 @@ amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, 
         for (uint32_t blk = 0; blk < nwg; ++blk) {
             std::vector<T2Cursor> fetched, consumed;
             // one batch of loads of all four wavefronts for the cursor's k-step
-            auto fetch = [&](const T2Cursor &c) {
+            auto fetch = [&](const T2Stream &st) {
+                const T2Cursor &c = st.c;
                 fetched.push_back(c);
                 if (c.tile >= ntiles || c.k0 + (uint32_t)T2K > g.K) {
                     ++errors;
                     return;
                 }
-                int64_t a_tile, w_tile;
-                t2_tile_bases<W_KM>(g, c.tile, a_tile, w_tile);
-                const int64_t ka = t2_a_step(g, a_tile, c.k0), wk = t2_w_step<W_KM>(g, w_tile, c.k0);
+                const int64_t ka = st.a_tile + st.a_step, wk = st.w_tile + st.w_step;
                 got_a.clear(), got_w.clear(), want_a.clear(), want_w.clear();
                 uint32_t tm, tn;
                 tile_of_block(c.tile, g.tiles_m, g.tiles_n, tm, tn);
@@ -1346,18 +1421,21 @@ amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, 
                 if (got_a != want_a) ++errors;
                 if (got_w != want_w) ++errors;
             };
-            T2Cursor ld = {blk, 0};
-            if (ld.tile < ntiles)
+            T2Stream ld = {};
+            ld.c = T2Cursor{blk, 0};
+            if (ld.c.tile < ntiles) {
+                t2_stream_tile<W_KM>(g, ld);
                 for (int p = 0; p < 2; ++p) {
                     fetch(ld);
-                    t2_cursor_advance(ld, g.K, nwg);
+                    t2_stream_next<W_KM>(g, g, ld, nwg, ntiles);
                 }
+            }
             for (uint32_t c_tile = blk; c_tile < ntiles; c_tile += nwg) {
                 for (uint32_t ks = 0; ks < steps; ++ks) {
                     consumed.push_back(T2Cursor{c_tile, ks * (uint32_t)T2K});
-                    if (ld.tile < ntiles) {
+                    if (ld.c.tile < ntiles) {
                         fetch(ld);
-                        t2_cursor_advance(ld, g.K, nwg);
+                        t2_stream_next<W_KM>(g, g, ld, nwg, ntiles);
                     }
                 }
                 // epilogue of this tile
