@@ -647,6 +647,61 @@ def test_tile256_kernel_with_partial_last_tiles(dev, case, monkeypatch, capfd):
     assert np.array_equal(got, general)
 
 
+def _random_product(rng):
+    """A random product the 256 x 256 kernel takes: (A source shape, chain), N, weight kept [N,K]?, chain on the product."""
+    k = 64 * int(rng.integers(2, 6))
+    form = int(rng.integers(3))
+    if form == 0:                                            # plain rows, any M
+        m = 8 * int(rng.integers(1, 100))
+        shape, ops = (m, k), []
+    elif form == 1:                                          # rows longer than K, behind an offset
+        m = 8 * int(rng.integers(1, 100))
+        shape, ops = (m + 5, k + 64), [("slice", 0, 5, m + 5, 1), ("slice", 1, 64, k + 64, 1)]
+    else:                                                    # head merge: blocks of 256 rows, k over two digits
+        b, h = int(rng.integers(1, 3)), int(rng.integers(2, 4))
+        m, k = b * 256, h * 64
+        shape, ops = (b, h, 256, 64), [("transpose", (0, 2, 1, 3)), ("reshape", (m, k))]
+    n = 8 * int(rng.integers(1, 100))
+    c_ops = [("reshape", (m, n // 8, 8)), ("transpose", (1, 0, 2))] if rng.random() < 0.4 else None
+    return (shape, ops), n, bool(rng.random() < 0.5), c_ops
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_products_on_the_tile256_kernel(dev, seed, monkeypatch, capfd):
+    """Random shapes (partial tiles, offsets, a mapped store, the weight either way round): the kernel's addressing is
+    replayed on the host first, then the product is compared with the oracle."""
+    import torch
+    rng = np.random.default_rng(4200 + seed)
+    (shape, a_ops), N, w_t, c_ops = _random_product(rng)
+    print(f"[gpu] random tile256 product, seed {seed}: {shape} {a_ops} N={N} w_t={w_t} store={c_ops}", flush=True)
+    a_map = B.amap_compose([shape], 2, a_ops)
+    M, K = B.dst_shape(a_map)
+    w_map = B.amap_compose([(N, K)], 2, [("transpose", (1, 0))]) if w_t else None
+    out_map = B.amap_compose([(M, N)], 2, c_ops) if c_ops else None
+    assert B.amap_gemm_selfcheck(a_map, N, out_map, 256, w_map) == 0
+    assert B.amap_gemm_selfcheck(a_map, N, out_map, 3, w_map) == 0
+    src = synth.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    w = synth.f32_to_bf16_bits((rng.standard_normal((K, N)) * 0.05).astype(np.float32))
+    d_src = dev.to_device(src)
+    d_w = dev.to_device(np.ascontiguousarray(w.T) if w_t else w)
+    out = torch.full(B.dst_shape(out_map) if out_map else (M, N), 0x5A5A, dtype=torch.int16, device="cuda")
+    monkeypatch.setenv("AMAP_PLAN_TRACE", "1")
+    capfd.readouterr()
+    B.amap_gemm_gather([d_src.data_ptr()], a_map, d_w.data_ptr(), w_map, N, out_map, out.data_ptr(), 0)
+    torch.cuda.synchronize()
+    assert "256 x 256 tiles" in capfd.readouterr().err
+    monkeypatch.delenv("AMAP_PLAN_TRACE")
+    got = dev.to_host(out)
+    want = oracle.gemm_bf16(oracle.run_chain([src], a_ops) if a_ops else src, w)
+    if c_ops:
+        want = oracle.run_chain([want], c_ops)
+    assert got.shape == want.shape
+    g, r = synth.bf16_bits_to_f32(got).astype(np.float64), synth.bf16_bits_to_f32(want).astype(np.float64)
+    assert np.abs(g - r).max() <= TOL * np.abs(r).max()
+    ulp = np.maximum(np.abs(r), 2.0 ** -126) * 2.0 ** -7
+    assert np.mean(np.abs(g - r) <= ulp) > 0.999
+
+
 # ---- padding in front of the product: the pad operator's load composed into the operand load (Section 2.1, eq. 4)
 
 PAD_CASES = [
