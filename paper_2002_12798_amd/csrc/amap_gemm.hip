@@ -4,7 +4,8 @@
 // used to read the materialised chain output t_s reads the chain's source t_l
 // through g' instead, in its operand-load prologue, and t_s never exists.
 //
-// Two kernels.  amap_gemm_tile256_kernel (further down) takes the aligned common case; the general one:
+// Two kernels.  amap_gemm_tile256_kernel (further down) takes the common case of whole 64-element runs along k;
+// the general one:
 // Kernel shape (gfx950): 256 x 128 output tile per workgroup of 4 wavefronts,
 // each wavefront 128 x 64 = 4 x 2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (fp32
 // accumulate in 128 AGPRs), K stepped by 64 through one LDS stage with the
@@ -431,8 +432,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
 }
 
 // ---------------------------------------------------------------------------------------------
-// The aligned case (M % 256 = N % 256 = 0, K % 64 = 0, K >= 128, row-major W, one source with its
-// runs along k, a tile's 256 rows inside one digit of m and a k-step inside one digit of k).
+// The common case: K % 64 = 0, K >= 128, one source with its runs along k, a tile's 256 rows inside one
+// digit of m and a k-step inside one digit of k, W row-major or kept as [N,K] with the same properties
+// (W_KM); M and N whole numbers of tiles or not (EDGE).
 // Same consumer load of eq. 4, different machine mapping:
 //   * 256 x 256 output tile per workgroup of 4 wavefronts (128 x 128 each: 16 MFMA tiles, 256
 //     accumulator registers), one workgroup per compute unit, persistent over its tiles;
@@ -980,7 +982,7 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     bool edge = M % BM || N % BN || K % BK;
     if (!A_map->strided || A_map->pieces.empty()) return unsupported("the A map has no strided form");
     if (M >= (1ll << 31) || N >= (1ll << 24) || K >= (1ll << 31) || M * N >= (1ll << 40)) return unsupported("operand too large");
-    // Operands or sources of 2^31 elements and more: only the aligned-shape kernel reaches them (64-bit tile bases);
+    // Operands or sources of 2^31 elements and more: only the 256 x 256-tile kernel reaches them (64-bit tile bases);
     // every other product is refused further down, once it is known which kernel it would take.
     bool wide = M * K >= (1ll << 31) || K * N >= (1ll << 31);
     if (out_map && M * N >= (1ll << 31)) return unsupported("product too large for a mapped store");
@@ -1140,7 +1142,7 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
     g.tiles_m = (uint32_t)((M + BM - 1) / BM);
     g.tiles_n = (uint32_t)((N + BN - 1) / BN);
     hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
-    // ---- the aligned common case runs on 256 x 256 tiles (see amap_gemm_tile256_kernel)
+    // ---- the common case runs on 256 x 256 tiles (see amap_gemm_tile256_kernel)
     const char *t256 = std::getenv("AMAP_GEMM_TILE256");   // 0: always the general kernel (tests compare the two)
     const bool tile256_on = !(t256 && t256[0] == '0');
     if (g.padded) edge = true;   // the instances that test every vector also take the padding
@@ -1215,7 +1217,7 @@ amap_status gemm_launch(const void *const *A_srcs, bool by_id, const amap_t *A_m
         }
         return AMAP_OK;
     }
-    if (wide) return unsupported("an operand or source of 2^31 elements and more: only aligned shapes (see amap_gemm_fused) with a plain store reach it");
+    if (wide) return unsupported("an operand or source of 2^31 elements and more: only the 256 x 256-tile kernel (see amap_gemm_fused) with a plain store reaches it");
     if (dry) {
         *dry = g;
         *dry_kernel = 0;

@@ -421,7 +421,7 @@ def test_gather_one_source_twice_and_error_paths(dev):
     torch.cuda.synchronize()
 
 
-# ---- the aligned case: 256 x 256 tiles, operands loaded straight into LDS (its own kernel)
+# ---- 256 x 256 tiles, operands loaded straight into LDS (a kernel of its own)
 
 T256_CASES = [
     # (A source shape, A chain -> [M,K]), N, chain on the product or None

@@ -153,7 +153,7 @@ def test_gemm_operand_of_more_than_2_31_elements(dev, monkeypatch, capfd):
         assert abs(gv - ref) <= 2.0 ** -7 * abs(ref) + 1e-6, (m, n)
     del a, out
     torch.cuda.empty_cache()
-    # what only the aligned-shape kernel reaches is refused elsewhere, not run with wrapped offsets
+    # what only the 256 x 256-tile kernel reaches is refused elsewhere, not run with wrapped offsets
     x = torch.zeros(1 << 20, dtype=torch.int16, device="cuda")
     wide_general = B.amap_compose([(M, K + 8)], 2, [])          # K is no multiple of 64: the general kernel's
     with pytest.raises(B.AmapError) as e:
