@@ -190,8 +190,9 @@ amap_status amap_plan_selfcheck(const amap_t *m, int kernel_id, int64_t *n_error
 
 /* Diagnostic: the same for the 256 x 256-tile kernel of amap_gemm_fused / amap_gemm_fused_store
  * (see amap_gemm_fused for the shapes it takes): replays on the host, with the kernel's own address
- * functions, the loads of every workgroup (n_workgroups of them: the number of compute units on the
- * device, or any smaller number to make workgroups walk several tiles) and the stores of every tile
+ * functions, the loads of every workgroup (for a device of n_workgroups compute units: the kernel
+ * launches as many workgroups, at most one per compute unit, as give every one the same number of
+ * tiles; a small number makes workgroups walk many tiles) and the stores of every tile
  * for the product A_map x W (W row-major [K,N] when W_map is NULL, else read through W_map as in
  * amap_gemm_mapped; stored through out_map when it is not NULL), and counts loads
  * outside A's source or W, k-steps that fetch anything but their own block of A and W, fetches out
