@@ -728,43 +728,49 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
     const uint32_t fb_addr0 = kT2WOff + wn * 16384u + (lane & 31u) * 128u + (((lane >> 5) ^ ((lane >> 1) & 7u)) << 4);
 
     f32x16 acc[4][4];
-    bf16x8 fa[2][4];
-    bf16x4 fbl[2][4], fbh[2][4];
-    bf16x8 fbk[2][4];
-    auto mf = [&](int set, int i, int jn) __attribute__((always_inline)) {
+    bf16x8 fa[2][4];                      // A fragments: two sets, read one k sub-step ahead
+    bf16x4 fbl[4][4], fbh[4][4];          // W fragments: four sets, read three sub-steps ahead (see the k-loop)
+    bf16x8 fbk[4][4];
+    auto mf = [&](int aset, int wset, int i, int jn) __attribute__((always_inline)) {
         bf16x8 b;
         if constexpr (W_KM)
-            b = fbk[set][jn];
+            b = fbk[wset][jn];
         else
-            b = __builtin_shufflevector(fbl[set][jn], fbh[set][jn], 0, 1, 2, 3, 4, 5, 6, 7);
+            b = __builtin_shufflevector(fbl[wset][jn], fbh[wset][jn], 0, 1, 2, 3, 4, 5, 6, 7);
         // W fragment as the row operand: the 32 x 32 result is C^T, a lane holds four consecutive n of one row m
-        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, fa[set][i], acc[i][jn], 0, 0, 0);
+        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, fa[aset][i], acc[i][jn], 0, 0, 0);
     };
-    // one of the 12 fragment reads of a k sub-step (4 of A, 8 of W; 4 of W when its runs lie along k)
-    auto rd = [&](int set, uint32_t stage_base, int kk, int r) __attribute__((always_inline)) {
-        if (r < 4) {
-            fa[set][r] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u32x4 *>(stage_base + (fa_addr0 ^ ((uint32_t)kk << 5)) + r * 4096u));
-        } else if constexpr (W_KM) {
-            if (r < 8)
-                fbk[set][r - 4] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u32x4 *>(stage_base + (fb_addr0 ^ ((uint32_t)kk << 5)) + (r - 4) * 4096u));
+    // the fragment reads of a k sub-step: 4 of A, 8 of W (4 of W when its runs lie along k)
+    auto rd_a = [&](int set, uint32_t stage_base, int kk, int r) __attribute__((always_inline)) {
+        fa[set][r] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u32x4 *>(stage_base + (fa_addr0 ^ ((uint32_t)kk << 5)) + r * 4096u));
+    };
+    auto rd_w = [&](int set, uint32_t stage_base, int kk, int r) __attribute__((always_inline)) {
+        if constexpr (W_KM) {
+            if (r < 4)
+                fbk[set][r] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u32x4 *>(stage_base + (fb_addr0 ^ ((uint32_t)kk << 5)) + r * 4096u));
         } else {
-            const uint32_t a = stage_base + fw_addr[(r - 4) >> 1] + kk * 8192u + ((r & 1) ? 2048u : 0u);
+            const uint32_t a = stage_base + fw_addr[r >> 1] + kk * 8192u + ((r & 1) ? 2048u : 0u);
             const bf16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(reinterpret_cast<__attribute__((address_space(3))) bf16x4 *>(a));
             if (r & 1)
-                fbh[set][(r - 4) >> 1] = v;
+                fbh[set][r >> 1] = v;
             else
-                fbl[set][(r - 4) >> 1] = v;
+                fbl[set][r >> 1] = v;
         }
     };
-    // 16 MFMAs on fragment set `set`; the 12 reads of the next sub-step go into the other set, one per MFMA;
-    // with `loads` the 16 loads of the cursor's k-step go out as well, one per MFMA
-    auto phase = [&](int set, uint32_t rd_stage, int rd_kk, bool reads, uint32_t ld_stage, bool loads) __attribute__((always_inline)) {
-        if (loads) loads_begin();
+    // 16 MFMAs of one k sub-step on A set `aset` and W set `wset`.  Under them, one per MFMA: the 4 reads of A's
+    // next sub-step (into the other A set), the 8 reads of the W sub-step three ahead (into the W set before
+    // `wset`), and, with `which` = 1 / 2, the 8 loads per wavefront of the stream's k-step of W / of A.
+    // (One code path for all cases: an MFMA sequence in two arms of a branch makes the compiler copy the
+    // accumulators; and no branch around a load: 16 branches per k-step cost more than the loads.)
+    auto phase = [&](int aset, int wset, uint32_t a_stage, int a_kk, uint32_t w_stage, int w_kk, uint32_t ld_stage, int which) __attribute__((always_inline)) {
+        if (which == 1) wk = reinterpret_cast<const char *>(g.W) + (ld.w_tile + ld.w_step);
+        if (which == 2) ka = reinterpret_cast<const char *>(g.A_src) + (ld.a_tile + ld.a_step);
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-            mf(set, s >> 2, s & 3);
-            if (reads && s < 12) rd(set ^ 1, rd_stage, rd_kk, s);
-            if (loads) load_one(ld_stage, s >> 1, s & 1);
+            mf(aset, wset, s >> 2, s & 3);
+            if (s < 4) rd_a(aset ^ 1, a_stage, a_kk, s);
+            if (s >= 4 && s < 12) rd_w((wset + 3) & 3, w_stage, w_kk, s - 4);
+            if (which != 0 && (s & 1) == 0) load_one(ld_stage, s >> 1, which == 1 ? 1 : 0);
             AMAP_PIN();
         }
     };
@@ -772,19 +778,28 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
     if (ld.c.tile < ntiles) {
         t2_stream_tile<W_KM>(t2_args_again(), ld);
         cursor_edges();
+        // the first two k-steps (K >= 2 steps: both lie in the first tile); of the second one W first, then A:
+        // the order in which the k-loop waits for them
+        loads_begin();
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            loads_begin();
+        for (int s = 0; s < 16; ++s) load_one(0, s >> 1, s & 1);
+        // (with K = 2 k-steps the second advance already moves the cursor to the workgroup's next tile;
+        // a cursor left at k = K would fetch weight rows past the end of W)
+        cursor_next();
+        loads_begin();
 #pragma unroll
-            for (int s = 0; s < 16; ++s) load_one(p * kT2Stage, s >> 1, s & 1);
-            // (with K = 2 k-steps the second advance already moves the cursor to the workgroup's next tile;
-            // a cursor left at k = K would fetch weight rows past the end of W)
-            cursor_next();
-        }
+        for (int j = 0; j < 8; ++j) load_one(kT2Stage, j, 1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) load_one(kT2Stage, j, 0);
+        cursor_next();
         asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // the first step is there, the second may still be on its way
         __builtin_amdgcn_s_barrier();
 #pragma unroll
-        for (int r = 0; r < 12; ++r) rd(0, 0, 0, r);
+        for (int r = 0; r < 4; ++r) rd_a(0, 0, 0, r);
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) rd_w(kk, 0, kk, r);
     }
     for (uint32_t c_tile = blockIdx.x; c_tile < ntiles; c_tile += gridDim.x) {
 #pragma unroll
@@ -794,23 +809,34 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
         for (uint32_t ks = 0; ks < steps; ++ks) {
-            // one k-step on stage `cur`
+            // One k-step (four sub-steps of 16 k) on stage `cur`; `oth` holds the next step.  The two operands of a
+            // stage are released, refilled and waited for half a step apart, so that two batches of loads are in
+            // flight at any time (one batch at a time left the step waiting for the latency of its loads plus
+            // their transfer): A's fragments are read one sub-step ahead, W's three sub-steps ahead, hence
+            //   sub-step 0: last reads of W in `cur`                     -> W of the stream's step goes into `cur`
+            //   sub-step 2: last reads of A in `cur`                     -> A of the stream's step goes into `cur`
+            // The stream's step is two ahead of this one, possibly in the workgroup's next tile.  Each wavefront
+            // has 8 loads per operand and step; vmcnt(8) therefore waits for the older of the two batches in flight.
+            // Once the stream has passed the workgroup's last tile it stands still: the loads of the last two
+            // k-steps fetch that tile's last step again, into stages nobody reads any more.
+            const uint32_t oth = kT2Stage - cur;
             AMAP_PIN();
-            phase(0, cur, 1, true, 0, false);
-            phase(1, cur, 2, true, 0, false);
-            phase(0, cur, 3, true, 0, false);
-            // every wavefront's reads of this stage are complete, and everyone's loads of the other stage
-            // have landed, before anyone goes on (the loads only count in vmcnt; the compiler does not know of them)
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            phase(0, 0, cur, 1, cur, 3, 0, 0);
+            // W of the next step has landed (A of it may still be on its way), and every wavefront is done with W in `cur`
+            // (the loads only count in vmcnt; the compiler does not know of them)
+            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();
             AMAP_PIN();
-            // last quarter: the fragments of the next step's first quarter come from the other stage (after
-            // the workgroup's last step they are stale and unused), and the cursor's k-step, two ahead of
-            // this one and possibly in the workgroup's next tile, is fetched into the stage just released
-            const bool issue = ld.c.tile < ntiles;
-            phase(1, kT2Stage - cur, 0, true, cur, issue);
-            if (issue) cursor_next();
-            cur = kT2Stage - cur;
+            phase(1, 1, cur, 2, oth, 0, cur, 1);
+            phase(0, 2, cur, 3, oth, 1, 0, 0);
+            // A of the next step has landed, and every wavefront is done with A in `cur`
+            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            AMAP_PIN();
+            // (after the workgroup's last step the fragments read ahead are stale and unused)
+            phase(1, 3, oth, 0, oth, 2, cur, 2);
+            if (ld.c.tile < ntiles) cursor_next();
+            cur = oth;
         }
 
         // ---- epilogue: this wavefront's 128 x 128 block, 32 rows at a time: rounded to bf16, through its
@@ -847,6 +873,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void amap_gemm_tile256_kernel(cons
             }
         }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the loads of the last two k-steps land in LDS before the wavefront ends
 }
 
 // Split the loops of one dst dimension of a piece into digits.  The piece must start at
@@ -1431,6 +1458,22 @@ amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, 
                 if (got_a != want_a) ++errors;
                 if (got_w != want_w) ++errors;
             };
+            // loads issued after the stream has passed the workgroup's last tile: bounds only (nobody reads them)
+            auto stale = [&](const T2Stream &st) {
+                const int64_t ka = st.a_tile + st.a_step, wk = st.w_tile + st.w_step;
+                uint32_t tm, tn;
+                tile_of_block(st.c.tile - nwg, g.tiles_m, g.tiles_n, tm, tn);   // the tile whose state the stream kept
+                const uint32_t rv = EDGE ? t2_rows_valid(g, tm) : (uint32_t)T2M, cv = EDGE ? t2_cols_valid(g, tn) : (uint32_t)T2N;
+                for (uint32_t wave = 0; wave < 4; ++wave)
+                    for (uint32_t j = 0; j < 8; ++j)
+                        for (uint32_t lane = 0; lane < 64; ++lane) {
+                            const int64_t ao = ka + (int64_t)(EDGE ? t2_a_load_edge(g, wave, lane, j, rv) : t2_a_load(g, t2_a_lane(g, wave, lane, j & 1u), j));
+                            const int64_t wo = wk + (int64_t)(EDGE ? t2_w_load_edge<W_KM>(g, wave, lane, j, cv)
+                                                                   : t2_w_load<W_KM>(g, t2_w_lane<W_KM>(g, wave, lane, j & 1u), j));
+                            if (ao < 0 || ao + 16 > a_bytes) ++errors;
+                            if (wo < 0 || wo + 16 > w_bytes) ++errors;
+                        }
+            };
             T2Stream ld = {};
             ld.c = T2Cursor{blk, 0};
             if (ld.c.tile < ntiles) {
@@ -1446,6 +1489,8 @@ amap_status replay_tile256(const GemmArgs &g, int64_t a_bytes, int64_t w_bytes, 
                     if (ld.c.tile < ntiles) {
                         fetch(ld);
                         t2_stream_next<W_KM>(g, g, ld, nwg, ntiles);
+                    } else {
+                        stale(ld);   // the stream stands still past the last tile; its loads are issued all the same
                     }
                 }
                 // epilogue of this tile
