@@ -443,9 +443,10 @@ __global__ __launch_bounds__(kGemmThreads, 2) void amap_gemm_kernel(const GemmAr
 //     bank swizzle on the global side because such a load always fills 1 KiB of LDS in lane order;
 //   * W stays [k][n] in LDS and is read with the transposing LDS read (ds_read_b64_tr_b16), which
 //     hands every lane four consecutive k of one n: the MFMA operand layout without a register transpose;
-//   * two LDS stages of 64 k; the batch for step s + 2 is issued right after the barrier that frees
-//     its stage, laid between the MFMAs of the last quarter of step s, and the first loads of the
-//     workgroup's next tile are in flight while the current tile is written out;
+//   * two LDS stages of 64 k whose halves (A, W) are refilled half a step apart: W's fragments are read
+//     three quarters of a step ahead of the MFMAs, A's one quarter, so W of step s + 2 goes out after the
+//     first quarter of step s and A of step s + 2 after the third, two batches are in flight at any time,
+//     and the first loads of the workgroup's next tile are in flight while the current tile is written out;
 //   * every memory instruction sits at a fixed place between two MFMAs (scheduling barriers pin the
 //     order): one LDS read, or one LDS read and one load, per MFMA.
 constexpr int T2M = 256, T2N = 256, T2K = 64;
